@@ -1,0 +1,360 @@
+"""ctypes access to the CPU oracle (test infrastructure only; see gan_oracle.h).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this.
+Nothing here computes: it marshals numpy arrays to the C functions.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = os.path.join(_HERE, "liboracle_f64.so")
+MAX_LAYERS = 8
+
+
+def build(force=False):
+    """Compile gan_oracle.c (double precision, OpenMP) next to its source."""
+    src = os.path.join(_HERE, "gan_oracle.c")
+    hdr = os.path.join(_HERE, "gan_oracle.h")
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= max(os.path.getmtime(src), os.path.getmtime(hdr))):
+        return _LIB
+    cmd = ["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", _LIB, src, "-lm"]
+    subprocess.check_call(cmd)
+    return _LIB
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("n_models", C.c_int32), ("n_labels", C.c_int32),
+        ("cond_g", C.c_int32), ("cond_d", C.c_int32), ("z_dim", C.c_int32),
+        ("img_c", C.c_int32), ("img_hw", C.c_int32), ("g_h0", C.c_int32),
+        ("n_g", C.c_int32), ("g_ch", C.c_int32 * MAX_LAYERS),
+        ("n_d", C.c_int32), ("d_ch", C.c_int32 * MAX_LAYERS),
+        ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("adam_eps", C.c_double),
+        ("bn_eps", C.c_double), ("bn_momentum", C.c_double), ("leaky_slope", C.c_double),
+        ("d_loss_scale", C.c_double), ("g_loss_scale", C.c_double),
+    ]
+
+
+_lib = None
+_D = C.POINTER(C.c_double)
+_I = C.POINTER(C.c_int32)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_param_count.restype = C.c_int64
+        _lib.oracle_bn_count.restype = C.c_int64
+        _lib.oracle_logistic_loss.restype = C.c_double
+        _lib.oracle_logistic_loss.argtypes = [_D, C.c_int, C.c_int, C.c_double, _D]
+        _lib.oracle_adam.argtypes = [_D, _D, _D, _D, C.c_int64, C.c_int64] + [C.c_double] * 4
+        _lib.oracle_bn_train.argtypes = [_D, _D, _D, C.c_double, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_bn_eval.argtypes = [_D, _D, _D, C.c_double, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_bn_bwd.argtypes = [_D, _D, _D, _D, C.c_double, _D, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_bn_running_update.argtypes = [_D, _D, _D, _D, C.c_double, C.c_int, C.c_int64]
+        _lib.oracle_leaky_relu.argtypes = [_D, _D, C.c_int64, C.c_double]
+        _lib.oracle_leaky_relu_bwd.argtypes = [_D, _D, _D, C.c_int64, C.c_double]
+        _lib.oracle_tanh.argtypes = [_D, _D, C.c_int64]
+        _lib.oracle_tanh_bwd.argtypes = [_D, _D, _D, C.c_int64]
+        conv_args = [_D, _D, _D, _D] + [C.c_int] * 8
+        bwd_args = [_D, _D, _D, _D, _D, _D] + [C.c_int] * 8
+        _lib.oracle_conv2d.argtypes = conv_args
+        _lib.oracle_conv_transpose2d.argtypes = conv_args
+        _lib.oracle_conv2d_bwd.argtypes = bwd_args
+        _lib.oracle_conv_transpose2d_bwd.argtypes = bwd_args
+        _lib.oracle_linear.argtypes = [_D, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_linear_bwd.argtypes = [_D, _D, _D, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_route.argtypes = [_I, C.c_int, C.c_int, C.c_int, _I, _I, _I]
+        _lib.oracle_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
+        _lib.oracle_destroy.argtypes = [C.c_void_p]
+        _lib.oracle_param_count.argtypes = [C.c_void_p, C.c_int]
+        _lib.oracle_bn_count.argtypes = [C.c_void_p, C.c_int]
+        _lib.oracle_get_params.argtypes = [C.c_void_p, C.c_int, C.c_int, _D]
+        _lib.oracle_set_params.argtypes = [C.c_void_p, C.c_int, C.c_int, _D]
+        _lib.oracle_get_grads.argtypes = [C.c_void_p, C.c_int, C.c_int, _D]
+        _lib.oracle_get_opt_state.argtypes = [C.c_void_p, C.c_int, C.c_int, _D, _D, C.POINTER(C.c_int64)]
+        _lib.oracle_get_bn_running.argtypes = [C.c_void_p, C.c_int, C.c_int, _D, _D]
+        _lib.oracle_train_step.argtypes = [C.c_void_p, _I, _D, _D, C.c_int32, C.c_int32]
+        _lib.oracle_generate.argtypes = [C.c_void_p, _I, _D, C.c_int32, _D, C.c_int32, C.c_int32]
+        _lib.oracle_get_losses.argtypes = [C.c_void_p, _D, _D, _I]
+        _lib.oracle_get_routing.argtypes = [C.c_void_p, _I, _I]
+        _lib.oracle_eval_losses.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
+        _lib.oracle_eval_grads.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
+    return _lib
+
+
+def _d(a):
+    return None if a is None else a.ctypes.data_as(_D)
+
+
+def _i(a):
+    return None if a is None else a.ctypes.data_as(_I)
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def make_config(spec, n_models, n_labels, hyper=None):
+    """spec: dict with cond_g, cond_d, z_dim, img_c, img_hw, g_h0, g_ch, d_ch."""
+    h = dict(lr=2e-4, beta1=0.5, beta2=0.999, adam_eps=1e-8, bn_eps=1e-5, bn_momentum=0.1,
+             leaky_slope=0.2, d_loss_scale=0.5, g_loss_scale=0.5)
+    h.update(hyper or {})
+    c = Config()
+    c.struct_size = C.sizeof(Config)
+    c.n_models, c.n_labels = n_models, n_labels
+    c.cond_g, c.cond_d, c.z_dim = spec["cond_g"], spec["cond_d"], spec["z_dim"]
+    c.img_c, c.img_hw, c.g_h0 = spec["img_c"], spec["img_hw"], spec["g_h0"]
+    c.n_g = len(spec["g_ch"])
+    for i, v in enumerate(spec["g_ch"]):
+        c.g_ch[i] = v
+    c.n_d = len(spec["d_ch"])
+    for i, v in enumerate(spec["d_ch"]):
+        c.d_ch[i] = v
+    for k, v in h.items():
+        setattr(c, k, v)
+    return c
+
+
+class Oracle:
+    def __init__(self, spec, n_models, n_labels, hyper=None):
+        self.cfg = make_config(spec, n_models, n_labels, hyper)
+        self.h = C.c_void_p()
+        rc = lib().oracle_create(C.byref(self.cfg), C.byref(self.h))
+        if rc != 0:
+            raise ValueError("oracle_create failed: %d" % rc)
+        self.n_models = n_models
+        self.img_shape = (spec["img_c"], spec["img_hw"], spec["img_hw"])
+
+    def close(self):
+        if self.h:
+            lib().oracle_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def param_count(self, which):
+        return int(lib().oracle_param_count(self.h, which))
+
+    def bn_count(self, which):
+        return int(lib().oracle_bn_count(self.h, which))
+
+    def get_params(self, which, model):
+        out = np.empty(self.param_count(which), np.float64)
+        assert lib().oracle_get_params(self.h, which, model, _d(out)) == 0
+        return out
+
+    def set_params(self, which, model, src):
+        src = _f64(src)
+        assert src.size == self.param_count(which)
+        assert lib().oracle_set_params(self.h, which, model, _d(src)) == 0
+
+    def get_grads(self, which, model):
+        out = np.empty(self.param_count(which), np.float64)
+        assert lib().oracle_get_grads(self.h, which, model, _d(out)) == 0
+        return out
+
+    def get_opt_state(self, which, model):
+        P = self.param_count(which)
+        m, v, t = np.empty(P), np.empty(P), C.c_int64()
+        assert lib().oracle_get_opt_state(self.h, which, model, _d(m), _d(v), C.byref(t)) == 0
+        return m, v, t.value
+
+    def get_bn_running(self, which, model):
+        B = self.bn_count(which)
+        m, v = np.empty(B), np.empty(B)
+        assert lib().oracle_get_bn_running(self.h, which, model, _d(m), _d(v)) == 0
+        return m, v
+
+    def train_step(self, label_ids, noise, real, only_model=-1):
+        label_ids = np.ascontiguousarray(label_ids, np.int32)
+        noise, real = _f64(noise), _f64(real)
+        n = label_ids.size
+        return lib().oracle_train_step(self.h, _i(label_ids), _d(noise), _d(real), n, only_model)
+
+    def generate(self, label_ids, noise, use_running_stats=0, only_model=-1):
+        label_ids = np.ascontiguousarray(label_ids, np.int32)
+        noise = _f64(noise)
+        n = label_ids.size
+        out = np.zeros((n,) + self.img_shape, np.float64)
+        rc = lib().oracle_generate(self.h, _i(label_ids), _d(noise), n, _d(out), use_running_stats, only_model)
+        return rc, out
+
+    def get_losses(self):
+        K = self.n_models
+        jd, jg, cnt = np.empty(K), np.empty(K), np.empty(K, np.int32)
+        lib().oracle_get_losses(self.h, _d(jd), _d(jg), _i(cnt))
+        return jd, jg, cnt
+
+    def get_routing(self, n):
+        perm, offs = np.empty(n, np.int32), np.empty(self.n_models + 1, np.int32)
+        lib().oracle_get_routing(self.h, _i(perm), _i(offs))
+        return perm, offs
+
+    def eval_losses(self, model, label_ids, noise, real):
+        label_ids = np.ascontiguousarray(label_ids, np.int32)
+        noise, real = _f64(noise), _f64(real)
+        jd, jg = C.c_double(), C.c_double()
+        lib().oracle_eval_losses(self.h, model, _i(label_ids), _d(noise), _d(real), label_ids.size,
+                                 C.byref(jd), C.byref(jg))
+        return jd.value, jg.value
+
+    def eval_grads(self, model, label_ids, noise, real):
+        label_ids = np.ascontiguousarray(label_ids, np.int32)
+        noise, real = _f64(noise), _f64(real)
+        gD, gG = np.empty(self.param_count(1)), np.empty(self.param_count(0))
+        lib().oracle_eval_grads(self.h, model, _i(label_ids), _d(noise), _d(real), label_ids.size, _d(gD), _d(gG))
+        return gD, gG
+
+
+# ---- single operations on numpy arrays (NCHW) ------------------------------
+
+def conv2d(X, W, bias=None, k=4, s=2, p=1):
+    X, W, bias = _f64(X), _f64(W), _f64(bias)
+    N, Cin, H, Wd = X.shape
+    Cout = W.shape[0]
+    Y = np.empty((N, Cout, (H + 2 * p - k) // s + 1, (Wd + 2 * p - k) // s + 1))
+    lib().oracle_conv2d(_d(X), _d(W), _d(bias), _d(Y), N, Cin, H, Wd, Cout, k, s, p)
+    return Y
+
+
+def conv2d_bwd(X, W, dY, k=4, s=2, p=1, need_dx=True):
+    X, W, dY = _f64(X), _f64(W), _f64(dY)
+    N, Cin, H, Wd = X.shape
+    Cout = W.shape[0]
+    dX = np.empty_like(X) if need_dx else None
+    dW, db = np.empty_like(W), np.empty(Cout)
+    lib().oracle_conv2d_bwd(_d(X), _d(W), _d(dY), _d(dX), _d(dW), _d(db), N, Cin, H, Wd, Cout, k, s, p)
+    return dX, dW, db
+
+
+def conv_transpose2d(X, W, bias=None, k=4, s=2, p=1):
+    X, W, bias = _f64(X), _f64(W), _f64(bias)
+    N, Cin, H, Wd = X.shape
+    Cout = W.shape[1]
+    Y = np.empty((N, Cout, (H - 1) * s - 2 * p + k, (Wd - 1) * s - 2 * p + k))
+    lib().oracle_conv_transpose2d(_d(X), _d(W), _d(bias), _d(Y), N, Cin, H, Wd, Cout, k, s, p)
+    return Y
+
+
+def conv_transpose2d_bwd(X, W, dY, k=4, s=2, p=1, need_dx=True):
+    X, W, dY = _f64(X), _f64(W), _f64(dY)
+    N, Cin, H, Wd = X.shape
+    Cout = W.shape[1]
+    dX = np.empty_like(X) if need_dx else None
+    dW, db = np.empty_like(W), np.empty(Cout)
+    lib().oracle_conv_transpose2d_bwd(_d(X), _d(W), _d(dY), _d(dX), _d(dW), _d(db), N, Cin, H, Wd, Cout, k, s, p)
+    return dX, dW, db
+
+
+def linear(X, W, bias=None):
+    X, W, bias = _f64(X), _f64(W), _f64(bias)
+    Y = np.empty((X.shape[0], W.shape[0]))
+    lib().oracle_linear(_d(X), _d(W), _d(bias), _d(Y), X.shape[0], X.shape[1], W.shape[0])
+    return Y
+
+
+def linear_bwd(X, W, dY):
+    X, W, dY = _f64(X), _f64(W), _f64(dY)
+    dX, dW, db = np.empty_like(X), np.empty_like(W), np.empty(W.shape[0])
+    lib().oracle_linear_bwd(_d(X), _d(W), _d(dY), _d(dX), _d(dW), _d(db), X.shape[0], X.shape[1], W.shape[0])
+    return dX, dW, db
+
+
+def bn_train(X, gamma, beta, eps):
+    X, gamma, beta = _f64(X), _f64(gamma), _f64(beta)
+    N, Cn = X.shape[:2]
+    HW = int(np.prod(X.shape[2:]))
+    Y, mean, var = np.empty_like(X), np.empty(Cn), np.empty(Cn)
+    lib().oracle_bn_train(_d(X), _d(gamma), _d(beta), eps, _d(Y), _d(mean), _d(var), N, Cn, HW)
+    return Y, mean, var
+
+
+def bn_eval(X, gamma, beta, eps, mean, var):
+    X, gamma, beta, mean, var = _f64(X), _f64(gamma), _f64(beta), _f64(mean), _f64(var)
+    N, Cn = X.shape[:2]
+    HW = int(np.prod(X.shape[2:]))
+    Y = np.empty_like(X)
+    lib().oracle_bn_eval(_d(X), _d(gamma), _d(beta), eps, _d(mean), _d(var), _d(Y), N, Cn, HW)
+    return Y
+
+
+def bn_bwd(X, gamma, mean, var, eps, dY):
+    X, gamma, mean, var, dY = _f64(X), _f64(gamma), _f64(mean), _f64(var), _f64(dY)
+    N, Cn = X.shape[:2]
+    HW = int(np.prod(X.shape[2:]))
+    dX, dg, db = np.empty_like(X), np.empty(Cn), np.empty(Cn)
+    lib().oracle_bn_bwd(_d(X), _d(gamma), _d(mean), _d(var), eps, _d(dY), _d(dX), _d(dg), _d(db), N, Cn, HW)
+    return dX, dg, db
+
+
+def bn_running_update(rmean, rvar, mean, var, momentum, count):
+    rmean, rvar = _f64(rmean).copy(), _f64(rvar).copy()
+    mean, var = _f64(mean), _f64(var)
+    lib().oracle_bn_running_update(_d(rmean), _d(rvar), _d(mean), _d(var), momentum, rmean.size, count)
+    return rmean, rvar
+
+
+def leaky_relu(X, slope):
+    X = _f64(X)
+    Y = np.empty_like(X)
+    lib().oracle_leaky_relu(_d(X), _d(Y), X.size, slope)
+    return Y
+
+
+def leaky_relu_bwd(X, dY, slope):
+    X, dY = _f64(X), _f64(dY)
+    dX = np.empty_like(X)
+    lib().oracle_leaky_relu_bwd(_d(X), _d(dY), _d(dX), X.size, slope)
+    return dX
+
+
+def tanh(X):
+    X = _f64(X)
+    Y = np.empty_like(X)
+    lib().oracle_tanh(_d(X), _d(Y), X.size)
+    return Y
+
+
+def tanh_bwd(Y, dY):
+    Y, dY = _f64(Y), _f64(dY)
+    dX = np.empty_like(Y)
+    lib().oracle_tanh_bwd(_d(Y), _d(dY), _d(dX), Y.size)
+    return dX
+
+
+def logistic_loss(s, sign, scale):
+    s = _f64(s)
+    ds = np.empty_like(s)
+    val = lib().oracle_logistic_loss(_d(s), s.size, sign, scale, _d(ds))
+    return val, ds
+
+
+def adam(theta, m, v, g, t, lr=2e-4, beta1=0.5, beta2=0.999, eps=1e-8):
+    theta, m, v, g = _f64(theta).copy(), _f64(m).copy(), _f64(v).copy(), _f64(g)
+    lib().oracle_adam(_d(theta), _d(m), _d(v), _d(g), theta.size, t, lr, beta1, beta2, eps)
+    return theta, m, v
+
+
+def route(label_ids, n_models, n_labels):
+    label_ids = np.ascontiguousarray(label_ids, np.int32)
+    n = label_ids.size
+    perm, offs, bad = np.empty(max(n, 1), np.int32), np.empty(n_models + 1, np.int32), C.c_int32()
+    lib().oracle_route(_i(label_ids), n, n_models, n_labels, _i(perm), _i(offs), C.byref(bad))
+    return perm[:n], offs, bad.value
+
+
+def threads():
+    return int(lib().oracle_threads())
