@@ -1,0 +1,164 @@
+/*
+ * C ABI of the grouped per-label DC-CGAN training library for gfx950.
+ *
+ * The paper (Section 2) factorises the data distribution over the K labels
+ * (Eq. 5) and trains K independent conditional GANs, pair k seeing only the
+ * samples of label k.  This library holds all K (generator, discriminator)
+ * pairs on one GPU and advances all of them by one iteration per call:
+ * route the minibatch by label, run G and D forward, the discriminator cost
+ * (Eq. 3) and its backward pass, Adam on theta_D, the generator cost (Eq. 4)
+ * through the updated D, its backward pass, Adam on theta_G.
+ *
+ * Conventions
+ *  - Every function returns a gan_status and never throws or aborts.
+ *  - "DEVICE" pointers are HIP device pointers owned by the caller (for
+ *    example a torch tensor's data_ptr()); "HOST" pointers are ordinary host
+ *    memory.  The context owns parameters, Adam moments, BatchNorm running
+ *    statistics and all workspace; the caller owns every argument buffer.
+ *  - gan_train_step and gan_generate enqueue work on the stream given to
+ *    gan_create and return without waiting; the caller may reuse the input
+ *    buffers for stream-ordered work as soon as the call returns.  The
+ *    gan_get_* / gan_set_* functions synchronise that stream.
+ *  - Argument errors detectable on the host (null pointer, n < 0,
+ *    n > max_total_batch) fail immediately with no side effects.  A label id
+ *    outside [0, n_labels) is only visible on the device: that sample is
+ *    dropped from every model, a sticky flag is raised, and the next
+ *    gan_get_losses returns GAN_E_LABEL (and clears the flag).
+ *  - Image tensors are [n, C, H, W] fp32 with values in [-1, 1] (the generator
+ *    ends in tanh); noise is [n, z_dim] fp32; row i of each array describes
+ *    sample i, in any label order.
+ *
+ * Network family (one shape for all K pairs; widths per configuration):
+ *   G: [z ; onehot_cond_g(y)] -> linear -> [g_ch[0], g_h0, g_h0] -> BN -> ReLU
+ *      -> { convT k4 s2 p1 -> BN -> ReLU } x (n_g - 1) -> convT k4 s2 p1 (+bias) -> tanh
+ *   D: [x ; cond_d one-hot label maps] -> conv k4 s2 p1 (+bias) -> LeakyReLU
+ *      -> { conv k4 s2 p1 -> BN -> LeakyReLU } x (n_d - 1) -> flatten -> linear (+bias) -> logit
+ * (layer types as in the paper's Tables 1-4: linear input stage, BatchNorm with momentum 0.1,
+ *  LeakyReLU slope 0.2, tanh output; D returns a logit and the sigmoid lives in the cost.)
+ *
+ * Flat parameter order seen by gan_get_params / gan_set_params (fp32 master values):
+ *   G: fc.w [g_ch[0]*g_h0*g_h0, z_dim+cond_g] (rows in (c,h,w) order), bn0.gamma, bn0.beta,
+ *      then per transposed conv i: w [Cin, Cout, 4, 4], and (gamma, beta) [Cout] or, for the last, bias [img_c].
+ *   D: c1.w [d_ch[0], img_c+cond_d, 4, 4], c1.b, then per conv j: w [Cout, Cin, 4, 4], gamma, beta,
+ *      then fc.w [d_ch[last]*h*h] (in (c,h,w) order), fc.b.
+ */
+#ifndef GAN_H
+#define GAN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gan_ctx gan_ctx;
+
+typedef enum {
+  GAN_OK = 0,
+  GAN_E_ARG = -1,     /* null pointer, negative size, bad index                       */
+  GAN_E_SHAPE = -2,   /* configuration the kernels do not support (see gan_create)    */
+  GAN_E_OOM = -3,     /* device allocation failed                                     */
+  GAN_E_HIP = -4,     /* a HIP call or kernel launch failed; see gan_last_error       */
+  GAN_E_LABEL = -5,   /* an out-of-range label id was seen since the last query       */
+  GAN_E_STATE = -6    /* call not valid in the current state (e.g. no step taken yet) */
+} gan_status;
+
+typedef enum { GAN_FP32 = 0, GAN_BF16_FP32MASTER = 1 } gan_precision;
+
+#define GAN_MAX_LAYERS 8
+
+typedef struct {
+  uint32_t struct_size;     /* sizeof(gan_config), for versioning                                     */
+  int32_t  precision;       /* gan_precision: storage/contraction type of activations and weights     */
+  int32_t  n_models;        /* K of Eq. 5: number of independent (G, D) pairs                         */
+  int32_t  n_labels;        /* label ids lie in [0, n_labels); model(label) = label, or 0 if K == 1   */
+  int32_t  cond_g;          /* one-hot width concatenated to z (0: unconditional generator)           */
+  int32_t  cond_d;          /* number of one-hot label maps appended to D's input (0: none)           */
+  int32_t  z_dim;           /* d_Z                                                                    */
+  int32_t  img_c, img_hw;   /* image channels (1..4) and side                                         */
+  int32_t  g_h0;            /* side of G's first feature map; img_hw = g_h0 * 2^n_g                   */
+  int32_t  n_g;             /* number of transposed convolutions in G                                 */
+  int32_t  g_ch[GAN_MAX_LAYERS]; /* input channels of each transposed conv (multiples of 64)          */
+  int32_t  n_d;             /* number of strided convolutions in D                                    */
+  int32_t  d_ch[GAN_MAX_LAYERS]; /* output channels of each conv (multiples of 64)                    */
+  int32_t  max_total_batch; /* largest n any call will pass; sizes the workspace                      */
+  float    lr, beta1, beta2, adam_eps;        /* Adam (the paper: lr 2e-4)                            */
+  float    bn_eps, bn_momentum, leaky_slope;  /* the paper's tables: momentum 0.1, slope 0.2          */
+  float    d_loss_scale, g_loss_scale;        /* the factors 1/2 in Eq. 3 and Eq. 4                   */
+  float    init_std;        /* built-in initialiser: weights ~ N(0, init_std^2), gamma 1, the rest 0  */
+  uint64_t seed;            /* seed of the built-in initialiser                                       */
+} gan_config;
+
+/* Allocate a context on the current device.  hip_stream is a hipStream_t (0 = the null stream).
+   Fails with GAN_E_SHAPE when a channel count is not a multiple of 64, img_c > 4, the sides do not
+   match (img_hw = g_h0 * 2^n_g, img_hw divisible by 2^n_d), or n_models is neither 1 nor n_labels. */
+gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out);
+gan_status gan_destroy(gan_ctx* ctx);
+
+/* One training iteration for every model that receives at least one sample (Section 2: Eq. 3, Eq. 4, Adam).
+   label_ids: DEVICE int32 [n]; noise: DEVICE fp32 [n, z_dim]; real_batch: DEVICE fp32 [n, img_c, img_hw, img_hw].
+   A model with no sample in this call is left untouched (parameters, moments, step count, statistics). */
+gan_status gan_train_step(gan_ctx* ctx, const int32_t* label_ids, const float* noise,
+                          const float* real_batch, int32_t n);
+
+/* x = G_k(z) for each sample, k = model(label) (the sampling half of Eq. 5's mixture).
+   out_images: DEVICE fp32 [n, img_c, img_hw, img_hw], rows in the caller's order.
+   use_running_stats = 0: BatchNorm uses the statistics of the generated batch, per model (as during training);
+   1: the running statistics. */
+gan_status gan_generate(gan_ctx* ctx, const int32_t* label_ids, const float* noise, int32_t n,
+                        float* out_images, int32_t use_running_stats);
+
+/* Costs of the last step: d_loss[k] = J_D of Eq. 3, g_loss[k] = -J_G of Eq. 4 (the quantity G minimises),
+   counts[k] = samples model k received (0 => both losses are reported as 0).  HOST arrays [n_models];
+   any of them may be NULL. */
+gan_status gan_get_losses(gan_ctx* ctx, float* d_loss, float* g_loss, int32_t* counts);
+
+/* ---- parity / checkpoint surface ---------------------------------------------------------------- */
+/* which: 0 = generator, 1 = discriminator.  All buffers HOST, fp32, in the flat order documented above. */
+gan_status gan_param_count(const gan_ctx* ctx, int32_t which, int64_t* per_model);
+gan_status gan_get_params(gan_ctx* ctx, int32_t which, int32_t model, float* dst, int64_t n);
+gan_status gan_set_params(gan_ctx* ctx, int32_t which, int32_t model, const float* src, int64_t n);
+/* Adam first / second moments (may be NULL) and step count of one model. */
+gan_status gan_get_opt_state(gan_ctx* ctx, int32_t which, int32_t model, float* m, float* v, int64_t* t);
+/* Gradients used by the last update of this model (same order as the parameters). */
+gan_status gan_get_grads(gan_ctx* ctx, int32_t which, int32_t model, float* dst, int64_t n);
+/* BatchNorm running statistics, concatenated over the network's BN layers. */
+gan_status gan_bn_count(const gan_ctx* ctx, int32_t which, int64_t* per_model);
+gan_status gan_get_bn_running(gan_ctx* ctx, int32_t which, int32_t model, float* mean, float* var, int64_t n);
+/* Routing of the last step: perm[j] = caller index of the j-th sample in model-major order (stable within a
+   model), offs[k]..offs[k+1] = model k's rows.  HOST int32 [n of that step] and [n_models + 1]. */
+gan_status gan_get_routing(gan_ctx* ctx, int32_t* perm, int32_t* offs);
+/* Text of the last error on this context (never NULL). */
+const char* gan_last_error(const gan_ctx* ctx);
+
+/* ---- profiling ------------------------------------------------------------------------------------ */
+/* Time every kernel launch of the next steps with HIP events on the context's stream (enable = 1), or stop
+   (enable = 0).  Costs two events per launch; off by default. */
+gan_status gan_profile_enable(gan_ctx* ctx, int32_t enable);
+/* Accumulated since enabling: for each of up to `cap` kernel families, its name (pointer to a static string),
+   launch count, total milliseconds, and the algorithmic flops and bytes those launches stood for.
+   HOST arrays; *n_out receives the number of families.  Synchronises the stream. */
+gan_status gan_profile_read(gan_ctx* ctx, int32_t cap, const char** names, int64_t* launches, double* ms,
+                            double* flops, double* bytes, int32_t* n_out);
+
+/* ---- single operations, for per-kernel parity tests ---------------------------------------------- */
+/* All pointers DEVICE.  Activations are NHWC in the context's storage type (fp32, or bf16 as uint16),
+   rows model-major; offs is DEVICE int32 [n_groups + 1] of sample offsets.  Weights are in the library's
+   internal layout [tap = ky*4+kx][c_big][c_small] ("up" form) or [tap][c_small][c_big] ("down" form), one
+   block per model, in the storage type; gradients of weights are fp32 in the "up" form.
+   "big" is the tensor with the larger spatial side (2*hs), "small" the one with side hs:
+     down : small[n,y,x,cs]  = sum_{ky,kx,cb} big[n,2y-1+ky,2x-1+kx,cb] * w[ky,kx,cb,cs]      (conv forward, convT dgrad)
+     up   : big[n,Y,X,cb]    = sum_{ky,kx,cs : Y=2y-1+ky, X=2x-1+kx} small[n,y,x,cs] * w[ky,kx,cb,cs]  (convT forward, conv dgrad)
+     wgrad: dw[ky,kx,cb,cs]  = sum_{n,y,x} big[n,2y-1+ky,2x-1+kx,cb] * small[n,y,x,cs]
+   n_groups models, group g uses weight block g.  n_samples = offs[n_groups] must be given by the caller. */
+gan_status gan_op_conv_down(gan_ctx* ctx, const void* big, const void* w_down, void* small_out, const int32_t* offs,
+                            int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs);
+gan_status gan_op_conv_up(gan_ctx* ctx, const void* small_in, const void* w_up, void* big_out, const int32_t* offs,
+                          int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs);
+gan_status gan_op_conv_wgrad(gan_ctx* ctx, const void* big, const void* small_in, float* dw, const int32_t* offs,
+                             int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

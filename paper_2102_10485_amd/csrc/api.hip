@@ -1,0 +1,952 @@
+// Host side of the library: context, arenas, parameter layout, and the launch sequence of one training step
+// (Section 2 of the paper: cost of Eq. 3 and Adam on theta_D, then cost of Eq. 4 through the updated D and Adam on
+// theta_G, for all label models of Eq. 5 at once).
+#include "../../include/gan.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace gan;
+
+namespace {
+
+inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
+
+// A (transposed) convolution between a "big" tensor (Cb channels, side 2*Hs) and a "small" one (Cs, side Hs).
+// Internal weight layout [tap][Cb (or CBT)][Cs].
+struct ConvLayer {
+  int Cb = 0, CBT = 0, Cs = 0, Hs = 0;
+  long long w = -1, bias = -1, gamma = -1, beta = -1;   // offsets into the per-model parameter block
+  long long rs = -1;                                    // offset into the running-statistics block
+  int bnC = 0;                                          // channels normalised after this layer (0: none)
+  int nbias = 0;
+};
+
+struct Net {
+  std::vector<ConvLayer> conv;     // G: transposed convs 1..n_g ; D: convs 1..n_d
+  // linear layer: G's input stage (J outputs, Kp padded inputs, followed by BN over C0) / D's head (K inputs)
+  long long fc_w = -1, fc_b = -1, fc_gamma = -1, fc_beta = -1, fc_rs = -1;
+  int J = 0, Kz = 0, Kp = 0, C0 = 0, h0 = 0, K = 0;
+  long long P = 0;                 // internal parameters per model (multiple of 64: keeps 16-byte alignment)
+  long long Pext = 0;              // parameters per model in the documented order
+  long long nbn = 0;
+  std::vector<long long> ext2int;  // documented index -> internal index
+  float *theta = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
+  void *shadow_u = nullptr, *shadow_d = nullptr;   // storage-type copies: [tap][cb][cs] and [tap][cs][cb]
+  float *run_mean = nullptr, *run_var = nullptr;
+  int* t = nullptr;
+  float* bc = nullptr;
+};
+
+struct ProfEntry { const char* name; hipEvent_t e0, e1; double flops, bytes; };
+
+}  // namespace
+
+struct gan_ctx {
+  gan_config cfg;
+  hipStream_t st = nullptr;
+  bool bf16 = false;
+  int L = 0, NB = 0;
+  Net G, D;
+  GeomTable geoms;
+  RouteBuffers rb;
+  // workspace (storage type unless noted)
+  void *zin = nullptr, *xd = nullptr, *dimg = nullptr, *bufA = nullptr, *bufB = nullptr;
+  std::vector<void*> gpre, gact, dpre, dact;
+  std::vector<float*> g_mean, g_var, g_rstd, g_sums, d_mean, d_var, d_rstd, d_sums;
+  float *logits = nullptr, *dlogits = nullptr, *loss_d = nullptr, *loss_g = nullptr;
+  float *lm_table = nullptr, *lm_rsum = nullptr, *partial = nullptr;
+  int nslot = 1;
+  int last_n = -1;
+  bool shadows_dirty = true;
+  std::string err;
+  std::vector<void*> allocs;
+  // profiling
+  bool prof = false;
+  std::vector<ProfEntry> prof_entries;
+  std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+size_t esize(const gan_ctx* c) { return c->bf16 ? 2 : 4; }
+
+gan_status fail(gan_ctx* c, gan_status s, const std::string& msg) {
+  if (c) c->err = msg;
+  return s;
+}
+
+bool dev_alloc(gan_ctx* c, void** p, size_t bytes) {
+  if (bytes == 0) bytes = 16;
+  if (hipMalloc(p, bytes) != hipSuccess) { (void)hipGetLastError(); return false; }
+  c->allocs.push_back(*p);
+  return true;
+}
+
+int geom_id(gan_ctx* c, int rps, int tile_rows) {
+  for (int i = 0; i < c->geoms.n; ++i)
+    if (c->geoms.rps[i] == rps && c->geoms.tile_rows[i] == tile_rows) return i;
+  if (c->geoms.n >= MAX_GEOMS) return -1;
+  c->geoms.rps[c->geoms.n] = rps;
+  c->geoms.tile_rows[c->geoms.n] = tile_rows;
+  return c->geoms.n++;
+}
+const int* tpre_of(gan_ctx* c, int rps, int tile_rows) {
+  const int g = geom_id(c, rps, tile_rows);
+  return c->rb.tpre + (long long)g * (c->L + 1);
+}
+int ub_tiles(const gan_ctx* c, int n, int rps, int tile_rows) {
+  return (int)(((long long)n * rps) / tile_rows) + (n < c->L ? n : c->L);
+}
+
+// ---- profiling: two events around a launch ------------------------------------------------------------
+struct Scope {
+  gan_ctx* c; int idx = -1;
+  Scope(gan_ctx* c_, const char* name, double flops, double bytes) : c(c_) {
+    if (!c->prof) return;
+    ProfEntry e; e.name = name; e.flops = flops; e.bytes = bytes;
+    hipEventCreate(&e.e0); hipEventCreate(&e.e1);
+    hipEventRecord(e.e0, c->st);
+    c->prof_entries.push_back(e);
+    idx = (int)c->prof_entries.size() - 1;
+  }
+  ~Scope() { if (idx >= 0) hipEventRecord(c->prof_entries[idx].e1, c->st); }
+};
+
+double valid_tap_fraction(int Hs) {   // k4 s2 p1: per axis 2 of the 4*Hs (row, tap) pairs fall outside
+  const double f = (4.0 * Hs - 2.0) / (4.0 * Hs);
+  return f * f;
+}
+
+// ---- parameter layout ----------------------------------------------------------------------------------
+void build_layout(gan_ctx* c) {
+  const gan_config& f = c->cfg;
+  {
+    Net& G = c->G;
+    long long o = 0, ext = 0, r = 0;
+    G.Kz = f.z_dim + f.cond_g;
+    G.Kp = (int)round_up(G.Kz, 64);
+    G.C0 = f.g_ch[0]; G.h0 = f.g_h0; G.J = G.C0 * G.h0 * G.h0;
+    G.fc_w = o; o += (long long)G.J * G.Kp;
+    G.fc_gamma = o; o += G.C0; G.fc_beta = o; o += G.C0; G.fc_rs = r; r += G.C0;
+    o = round_up(o, 8);
+    // documented order: fc.w [(c,h,w)][Kz]
+    G.ext2int.reserve(1 << 20);
+    for (int ch = 0; ch < G.C0; ++ch)
+      for (int y = 0; y < G.h0; ++y)
+        for (int x = 0; x < G.h0; ++x)
+          for (int i = 0; i < G.Kz; ++i)
+            G.ext2int.push_back(G.fc_w + ((long long)((y * G.h0 + x) * G.C0 + ch)) * G.Kp + i);
+    for (int ch = 0; ch < G.C0; ++ch) G.ext2int.push_back(G.fc_gamma + ch);
+    for (int ch = 0; ch < G.C0; ++ch) G.ext2int.push_back(G.fc_beta + ch);
+    int h = f.g_h0;
+    for (int i = 1; i <= f.n_g; ++i) {
+      ConvLayer l;
+      l.Cs = f.g_ch[i - 1]; l.Cb = (i < f.n_g) ? f.g_ch[i] : f.img_c; l.CBT = l.Cb; l.Hs = h;
+      l.w = o; o += (long long)16 * l.CBT * l.Cs;
+      for (int cs = 0; cs < l.Cs; ++cs)
+        for (int cb = 0; cb < l.Cb; ++cb)
+          for (int tap = 0; tap < 16; ++tap) G.ext2int.push_back(l.w + ((long long)tap * l.CBT + cb) * l.Cs + cs);
+      if (i < f.n_g) {
+        l.gamma = o; o += l.Cb; l.beta = o; o += l.Cb; l.rs = r; r += l.Cb; l.bnC = l.Cb;
+        for (int ch = 0; ch < l.Cb; ++ch) G.ext2int.push_back(l.gamma + ch);
+        for (int ch = 0; ch < l.Cb; ++ch) G.ext2int.push_back(l.beta + ch);
+      } else {
+        l.bias = o; l.nbias = l.Cb; o += l.Cb;
+        for (int ch = 0; ch < l.Cb; ++ch) G.ext2int.push_back(l.bias + ch);
+      }
+      o = round_up(o, 8);
+      G.conv.push_back(l);
+      h *= 2;
+    }
+    G.P = round_up(o, 64); G.Pext = (long long)G.ext2int.size(); G.nbn = r; (void)ext;
+  }
+  {
+    Net& D = c->D;
+    long long o = 0, r = 0;
+    int h = f.img_hw;
+    for (int j = 0; j < f.n_d; ++j) {
+      ConvLayer l;
+      l.Cb = (j == 0) ? f.img_c : f.d_ch[j - 1];
+      l.CBT = (j == 0) ? f.img_c + f.cond_d : l.Cb;
+      l.Cs = f.d_ch[j]; l.Hs = h / 2;
+      l.w = o; o += (long long)16 * l.CBT * l.Cs;
+      for (int cs = 0; cs < l.Cs; ++cs)
+        for (int cb = 0; cb < l.CBT; ++cb)
+          for (int tap = 0; tap < 16; ++tap) D.ext2int.push_back(l.w + ((long long)tap * l.CBT + cb) * l.Cs + cs);
+      if (j == 0) {
+        l.bias = o; l.nbias = l.Cs; o += l.Cs;
+        for (int ch = 0; ch < l.Cs; ++ch) D.ext2int.push_back(l.bias + ch);
+      } else {
+        l.gamma = o; o += l.Cs; l.beta = o; o += l.Cs; l.rs = r; r += l.Cs; l.bnC = l.Cs;
+        for (int ch = 0; ch < l.Cs; ++ch) D.ext2int.push_back(l.gamma + ch);
+        for (int ch = 0; ch < l.Cs; ++ch) D.ext2int.push_back(l.beta + ch);
+      }
+      o = round_up(o, 8);
+      D.conv.push_back(l);
+      h /= 2;
+    }
+    const int Cl = f.d_ch[f.n_d - 1];
+    D.K = Cl * h * h; D.h0 = h; D.C0 = Cl;
+    D.fc_w = o; o += D.K;
+    for (int ch = 0; ch < Cl; ++ch)
+      for (int y = 0; y < h; ++y)
+        for (int x = 0; x < h; ++x) D.ext2int.push_back(D.fc_w + (long long)(y * h + x) * Cl + ch);
+    D.fc_b = o; o += 1;
+    D.ext2int.push_back(D.fc_b);
+    D.P = round_up(o, 64); D.Pext = (long long)D.ext2int.size(); D.nbn = r;
+  }
+}
+
+bool alloc_net(gan_ctx* c, Net& n) {
+  const size_t tot = (size_t)c->L * n.P;
+  bool ok = dev_alloc(c, (void**)&n.theta, tot * 4) && dev_alloc(c, (void**)&n.m, tot * 4) &&
+            dev_alloc(c, (void**)&n.v, tot * 4) && dev_alloc(c, (void**)&n.g, tot * 4) &&
+            dev_alloc(c, &n.shadow_d, tot * esize(c)) &&
+            dev_alloc(c, (void**)&n.run_mean, (size_t)c->L * n.nbn * 4) &&
+            dev_alloc(c, (void**)&n.run_var, (size_t)c->L * n.nbn * 4) &&
+            dev_alloc(c, (void**)&n.t, (size_t)c->L * 4) && dev_alloc(c, (void**)&n.bc, (size_t)c->L * 8);
+  if (!ok) return false;
+  if (c->bf16) { if (!dev_alloc(c, &n.shadow_u, tot * 2)) return false; }
+  else n.shadow_u = n.theta;
+  hipMemsetAsync(n.theta, 0, tot * 4, c->st);
+  hipMemsetAsync(n.m, 0, tot * 4, c->st);
+  hipMemsetAsync(n.v, 0, tot * 4, c->st);
+  hipMemsetAsync(n.g, 0, tot * 4, c->st);
+  hipMemsetAsync(n.shadow_d, 0, tot * esize(c), c->st);
+  hipMemsetAsync(n.run_mean, 0, (size_t)c->L * n.nbn * 4, c->st);
+  hipMemsetAsync(n.t, 0, (size_t)c->L * 4, c->st);
+  hipMemsetAsync(n.bc, 0, (size_t)c->L * 8, c->st);
+  return true;
+}
+
+// ---- built-in initialiser (host side, documented order; tests overwrite it through gan_set_params) ------
+__global__ void init_normal_kernel(float* p, long long count, float std, unsigned long long seed, int inner, int inner_valid) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  if ((int)(i % inner) >= inner_valid) { p[i] = 0.f; return; }
+  unsigned long long z = seed + 0x9E3779B97F4A7C15ull * (unsigned long long)(i + 1);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  const float u1 = ((float)(unsigned)(z >> 40) + 1.0f) * (1.0f / 16777217.0f);
+  const float u2 = (float)(unsigned)((z >> 8) & 0xffffffu) * (1.0f / 16777216.0f);
+  p[i] = std * sqrtf(-2.0f * logf(u1)) * cosf(6.2831853f * u2);
+}
+__global__ void fill_kernel(float* p, long long count, float v) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) p[i] = v;
+}
+void init_normal(gan_ctx* c, float* p, long long count, int inner, int inner_valid, unsigned long long salt) {
+  hipLaunchKernelGGL(init_normal_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, c->st, p, count,
+                     c->cfg.init_std, c->cfg.seed * 0x100000001B3ull + salt, inner, inner_valid);
+}
+void fill(gan_ctx* c, float* p, long long count, float v) {
+  if (count == 0) return;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, c->st, p, count, v);
+}
+
+void builtin_init(gan_ctx* c) {
+  unsigned long long salt = 1;
+  for (int l = 0; l < c->L; ++l) {
+    Net& G = c->G;
+    float* th = G.theta + (long long)l * G.P;
+    init_normal(c, th + G.fc_w, (long long)G.J * G.Kp, G.Kp, G.Kz, salt++);
+    fill(c, th + G.fc_gamma, G.C0, 1.f);
+    for (auto& cl : G.conv) {
+      init_normal(c, th + cl.w, (long long)16 * cl.CBT * cl.Cs, 1, 1, salt++);
+      if (cl.bnC) fill(c, th + cl.gamma, cl.bnC, 1.f);
+    }
+    Net& D = c->D;
+    th = D.theta + (long long)l * D.P;
+    for (auto& cl : D.conv) {
+      init_normal(c, th + cl.w, (long long)16 * cl.CBT * cl.Cs, 1, 1, salt++);
+      if (cl.bnC) fill(c, th + cl.gamma, cl.bnC, 1.f);
+    }
+    init_normal(c, th + D.fc_w, D.K, 1, 1, salt++);
+  }
+  fill(c, c->G.run_var, (long long)c->L * c->G.nbn, 1.f);
+  fill(c, c->D.run_var, (long long)c->L * c->D.nbn, 1.f);
+}
+
+// ---- storage-type copies of the weights ------------------------------------------------------------------
+template <typename T>
+void refresh_transposes(gan_ctx* c, Net& n, bool isG) {
+  // layers run by the GEMM engine in "down" form need [tap][cs][cb]
+  for (size_t i = 0; i < n.conv.size(); ++i) {
+    const ConvLayer& cl = n.conv[i];
+    const bool gemm = isG ? (i + 1 < n.conv.size()) : (i > 0);
+    if (!gemm) continue;
+    Scope s(c, "transpose_w", 0, (double)c->L * 16 * cl.Cb * cl.Cs * 2 * sizeof(T));
+    if (c->bf16)
+      launch_transpose_w<bf16_t, bf16_t>((const bf16_t*)n.shadow_u + cl.w, (bf16_t*)n.shadow_d + cl.w, n.P, c->L, cl.Cb, cl.Cs, c->st);
+    else
+      launch_transpose_w<float, float>((const float*)n.theta + cl.w, (float*)n.shadow_d + cl.w, n.P, c->L, cl.Cb, cl.Cs, c->st);
+  }
+}
+void refresh_shadows(gan_ctx* c) {
+  for (Net* n : {&c->G, &c->D}) {
+    if (c->bf16) launch_cast_shadow<bf16_t>(n->theta, (bf16_t*)n->shadow_u, (long long)c->L * n->P, c->st);
+    if (c->bf16) refresh_transposes<bf16_t>(c, *n, n == &c->G); else refresh_transposes<float>(c, *n, n == &c->G);
+  }
+  c->shadows_dirty = false;
+}
+
+// ---- launch helpers ---------------------------------------------------------------------------------------
+template <typename T>
+void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, const void* W, long long wstride, void* Out,
+               const void* Aux, int C, int N, int Hin, int Hr, int seg_first, int nseg, int n) {
+  ConvArgs a;
+  a.A = A; a.W = W; a.Out = Out; a.Aux = Aux;
+  a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, conv_tile_m());
+  a.w_stride = wstride; a.L = c->L; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n;
+  a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr; a.ub_tiles = ub_tiles(c, n, Hr * Hr, conv_tile_m());
+  a.slope = c->cfg.leaky_slope;
+  const int ntaps = mode == MODE_DOWN ? 16 : (mode == MODE_UP ? 4 : 1);
+  const int phases = mode == MODE_UP ? 4 : 1;
+  const double rows = (double)n * nseg * Hr * Hr * phases;
+  const double frac = mode == MODE_DENSE ? 1.0 : valid_tap_fraction(Hr);
+  const double flops = 2.0 * rows * N * C * ntaps * frac;
+  const double bytes = sizeof(T) * ((double)n * nseg * Hin * Hin * C + rows * N + (double)c->L * 16 * C * N /
+                                    (mode == MODE_DENSE ? 16 : 1));
+  Scope s(c, name, flops, bytes);
+  launch_conv<T>(mode, epi, a, c->st);
+}
+
+template <typename T>
+void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small, float* dW, long long stride, int Cb, int Cs,
+                int Hs, int ntaps, int nseg, int n) {
+  WgradArgs a;
+  a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.dw_stride = stride;
+  a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps;
+  const double rows = (double)n * nseg * Hs * Hs;
+  const double frac = ntaps == 1 ? 1.0 : valid_tap_fraction(Hs);
+  const int Hb = ntaps == 1 ? 1 : 2 * Hs;
+  const double bytes = sizeof(T) * ((double)n * nseg * Hb * Hb * Cb + rows * Cs) + 4.0 * c->L * ntaps * Cb * Cs;
+  Scope s(c, name, 2.0 * rows * Cb * Cs * ntaps * frac, bytes);
+  launch_wgrad<T>(a, c->st);
+}
+
+template <typename T>
+NormArgs norm_args(gan_ctx* c, Net& net, int C, int rps, long long gamma, long long beta, long long rs, float* mean, float* var,
+                   float* rstd, float* sums, int seg_first, int nseg, int n, float slope) {
+  NormArgs a;
+  memset(&a, 0, sizeof(a));
+  a.mean = mean; a.var = var; a.rstd = rstd; a.sums = sums;
+  a.gamma = net.theta + gamma; a.beta = net.theta + beta; a.dgamma = net.g + gamma; a.dbeta = net.g + beta;
+  a.pstride = net.P;
+  a.run_mean = net.run_mean + rs; a.run_var = net.run_var + rs; a.rstride = net.nbn;
+  a.offs = c->rb.offs; a.counts = c->rb.counts; a.sample_model = c->rb.sample_model;
+  a.L = c->L; a.C = C; a.rps = rps; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n; a.n = n;
+  a.slope = slope; a.eps = c->cfg.bn_eps; a.momentum = c->cfg.bn_momentum;
+  return a;
+}
+
+// BatchNorm (batch statistics, or the running ones) + activation: x -> y
+template <typename T>
+void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running, bool update_running) {
+  a.x = x; a.y = y;
+  const double elems = (double)a.n * a.nseg * a.rps * a.C;
+  if (use_running) {
+    launch_bn_from_running(a, c->st);
+  } else {
+    { Scope s(c, "bn_stats", 0, elems * sizeof(T)); launch_bn_stats<T>(a, c->st); }
+    if (update_running) launch_bn_running(a, c->st);
+  }
+  Scope s(c, "bn_apply", 0, 2 * elems * sizeof(T));
+  launch_bn_apply<T>(a, c->st);
+}
+
+// dy (w.r.t. the activated output) -> dx (w.r.t. the pre-normalisation tensor), plus dgamma / dbeta
+template <typename T>
+void bn_backward(gan_ctx* c, NormArgs a, const void* x, const void* dy, void* dx, bool param_grads) {
+  a.x = x; a.dy = dy; a.y = dx;
+  const double elems = (double)a.n * a.nseg * a.rps * a.C;
+  { Scope s(c, "bn_bwd_reduce", 0, 2 * elems * sizeof(T)); launch_bn_bwd_reduce<T>(a, c->st); }
+  if (param_grads) launch_bn_param_grad(a, c->st);
+  Scope s(c, "bn_bwd_apply", 0, 3 * elems * sizeof(T));
+  launch_bn_bwd_apply<T>(a, c->st);
+}
+
+SkinnyArgs skinny_args(gan_ctx* c, Net& net, const ConvLayer& cl, int tile_rows, int seg_first, int nseg, int n) {
+  SkinnyArgs a;
+  memset(&a, 0, sizeof(a));
+  a.w = net.theta + cl.w; a.pstride = net.P;
+  a.offs = c->rb.offs; a.tpre = tpre_of(c, cl.Hs * cl.Hs, tile_rows);
+  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Hs = cl.Hs;
+  a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n; a.ub_tiles = ub_tiles(c, n, cl.Hs * cl.Hs, tile_rows);
+  a.slope = c->cfg.leaky_slope; a.sample_slot = c->rb.sample_slot; a.nslot = c->nslot;
+  return a;
+}
+
+double skinny_flops(const ConvLayer& cl, int n, int nseg) {
+  return 2.0 * n * nseg * cl.Hs * cl.Hs * 16 * cl.Cb * cl.Cs * valid_tap_fraction(cl.Hs);
+}
+template <typename T> double skinny_bytes(const ConvLayer& cl, int n, int nseg) {
+  return sizeof(T) * (double)n * nseg * cl.Hs * cl.Hs * (cl.Cs + 4.0 * cl.Cb);
+}
+
+// ---- the networks -------------------------------------------------------------------------------------------
+template <typename T>
+void g_forward(gan_ctx* c, int n, bool use_running, bool update_running) {
+  Net& G = c->G;
+  const float relu = 0.f;
+  conv_call<T>(c, "gemm_dense", MODE_DENSE, EPI_NONE, c->zin, (const T*)G.shadow_u + G.fc_w, G.P, c->gpre[0], nullptr, G.Kp, G.J,
+               1, 1, 0, 1, n);
+  bn_forward<T>(c, norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
+                                c->g_sums[0], 0, 1, n, relu),
+                c->gpre[0], c->gact[0], use_running, update_running);
+  const int nl = (int)G.conv.size();
+  for (int i = 0; i + 1 < nl; ++i) {
+    const ConvLayer& cl = G.conv[i];
+    conv_call<T>(c, "gemm_up", MODE_UP, EPI_NONE, c->gact[i], (const T*)G.shadow_u + cl.w, G.P, c->gpre[i + 1], nullptr, cl.Cs, cl.Cb,
+                 cl.Hs, cl.Hs, 0, 1, n);
+    bn_forward<T>(c, norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
+                                  c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, relu),
+                  c->gpre[i + 1], c->gact[i + 1], use_running, update_running);
+  }
+  const ConvLayer& cl = G.conv[nl - 1];
+  SkinnyArgs a = skinny_args(c, G, cl, SKINNY_UP_ROWS, 0, 1, n);
+  a.feat = c->gact[nl - 1];
+  a.out = (T*)c->xd + (long long)n * 4 * cl.Hs * cl.Hs * cl.Cb;     // the fake half of D's input
+  a.bias = G.theta + cl.bias; a.tanh_out = 1;
+  Scope s(c, "skinny_up", skinny_flops(cl, n, 1), skinny_bytes<T>(cl, n, 1));
+  launch_skinny_up<T>(a, c->st);
+}
+
+template <typename T>
+void d_forward(gan_ctx* c, int n, int seg_first, int nseg, bool update_running) {
+  Net& D = c->D;
+  const float slope = c->cfg.leaky_slope;
+  const ConvLayer& c1 = D.conv[0];
+  LabelMapArgs lm;
+  memset(&lm, 0, sizeof(lm));
+  if (c->cfg.cond_d > 0) {
+    lm.w = D.theta + c1.w; lm.pstride = D.P; lm.table = c->lm_table; lm.L = c->L; lm.nslot = c->nslot;
+    lm.CB = c1.Cb; lm.CBT = c1.CBT; lm.Cs = c1.Cs; lm.Hs = c1.Hs;
+    launch_labelmap_table(lm, c->st);
+  }
+  {
+    SkinnyArgs a = skinny_args(c, D, c1, SKINNY_DOWN_ROWS, seg_first, nseg, n);
+    a.img = c->xd; a.out = c->dact[0]; a.bias = D.theta + c1.bias;
+    a.table = c->cfg.cond_d > 0 ? c->lm_table : nullptr; a.lrelu = 1;
+    Scope s(c, "skinny_down", skinny_flops(c1, n, nseg), skinny_bytes<T>(c1, n, nseg));
+    launch_skinny_down<T>(a, c->st);
+  }
+  const int nl = (int)D.conv.size();
+  for (int j = 1; j < nl; ++j) {
+    const ConvLayer& cl = D.conv[j];
+    conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->dact[j - 1], (const T*)D.shadow_d + cl.w, D.P, c->dpre[j], nullptr, cl.Cb,
+                 cl.Cs, 2 * cl.Hs, cl.Hs, seg_first, nseg, n);
+    bn_forward<T>(c, norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
+                                  c->d_sums[j], seg_first, nseg, n, slope),
+                  c->dpre[j], c->dact[j], false, update_running);
+  }
+  HeadArgs h;
+  memset(&h, 0, sizeof(h));
+  h.feat = c->dact[nl - 1]; h.w = D.theta + D.fc_w; h.b = D.theta + D.fc_b; h.pstride = D.P; h.logits = c->logits;
+  h.offs = c->rb.offs; h.sample_model = c->rb.sample_model; h.L = c->L; h.K = D.K;
+  h.seg_first = seg_first; h.nseg = nseg; h.seg_samples = n; h.n = n;
+  Scope s(c, "head_fwd", 0, sizeof(T) * (double)n * nseg * D.K);
+  launch_head_fwd<T>(h, c->st);
+}
+
+// mode 0: discriminator cost on (real, fake); mode 1: generator cost on the fake segment
+void loss_call(gan_ctx* c, int n, int mode) {
+  HeadArgs h;
+  memset(&h, 0, sizeof(h));
+  h.logits = c->logits; h.dlogits = c->dlogits; h.loss = mode == 0 ? c->loss_d : c->loss_g;
+  h.offs = c->rb.offs; h.L = c->L; h.seg_first = mode == 0 ? 0 : 1; h.nseg = mode == 0 ? 2 : 1; h.seg_samples = n; h.n = n;
+  h.mode = mode; h.scale = mode == 0 ? c->cfg.d_loss_scale : c->cfg.g_loss_scale;
+  launch_loss(h, c->st);
+}
+
+// Backward through D.  param_grads: fill D's gradient block (both segments summed).  to_image: continue down to
+// d cost / d fake, multiplied by the tanh derivative, into dimg.
+template <typename T>
+void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bool to_image) {
+  Net& D = c->D;
+  const float slope = c->cfg.leaky_slope;
+  const int nl = (int)D.conv.size();
+  HeadArgs h;
+  memset(&h, 0, sizeof(h));
+  h.feat = c->dact[nl - 1]; h.dfeat = c->bufA; h.w = D.theta + D.fc_w; h.b = D.theta + D.fc_b;
+  h.dw = D.g + D.fc_w; h.db = D.g + D.fc_b; h.pstride = D.P; h.dlogits = c->dlogits;
+  h.offs = c->rb.offs; h.sample_model = c->rb.sample_model; h.L = c->L; h.K = D.K;
+  h.seg_first = seg_first; h.nseg = nseg; h.seg_samples = n; h.n = n;
+  { Scope s(c, "head_bwd_data", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_data<T>(h, c->st); }
+  if (param_grads) { Scope s(c, "head_bwd_w", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_w<T>(h, c->st); }
+  for (int j = nl - 1; j >= 1; --j) {
+    const ConvLayer& cl = D.conv[j];
+    bn_backward<T>(c, norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
+                                   c->d_sums[j], seg_first, nseg, n, slope),
+                   c->dpre[j], c->bufA, c->bufB, param_grads);
+    if (param_grads)
+      wgrad_call<T>(c, "gemm_wgrad", c->dact[j - 1], c->bufB, D.g + cl.w, D.P, cl.Cb, cl.Cs, cl.Hs, 16, nseg, n);
+    // data gradient; for the first conv's output the LeakyReLU derivative is applied in the epilogue
+    conv_call<T>(c, "gemm_up", MODE_UP, j == 1 ? EPI_ACT_BWD : EPI_NONE, c->bufB, (const T*)D.shadow_u + cl.w, D.P, c->bufA,
+                 j == 1 ? c->dact[0] : nullptr, cl.Cs, cl.Cb, cl.Hs, cl.Hs, seg_first, nseg, n);
+  }
+  const ConvLayer& c1 = D.conv[0];
+  if (param_grads) {
+    {
+      SkinnyArgs a = skinny_args(c, D, c1, SKINNY_WGRAD_ROWS, 0, nseg, n);
+      a.img = c->xd; a.feat = c->bufA; a.partial = c->partial; a.dw = D.g + c1.w;
+      Scope s(c, "skinny_wgrad", skinny_flops(c1, n, nseg), skinny_bytes<T>(c1, n, nseg));
+      launch_skinny_wgrad<T>(a, c->st);
+    }
+    LabelMapArgs lm;
+    memset(&lm, 0, sizeof(lm));
+    lm.w = D.theta + c1.w; lm.dw = D.g + c1.w; lm.dbias = D.g + c1.bias; lm.pstride = D.P; lm.rsum = c->lm_rsum;
+    lm.dfeat = c->bufA; lm.offs = c->rb.offs; lm.sample_slot = c->rb.sample_slot;
+    lm.L = c->L; lm.nslot = c->nslot; lm.CB = c1.Cb; lm.CBT = c1.CBT; lm.Cs = c1.Cs; lm.Hs = c1.Hs; lm.nseg = nseg; lm.seg_samples = n;
+    { Scope s(c, "labelmap_reduce", 0, sizeof(T) * (double)n * nseg * c1.Hs * c1.Hs * c1.Cs); launch_labelmap_reduce<T>(lm, c->st); }
+    launch_labelmap_grads(lm, c->st);
+  }
+  if (to_image) {
+    SkinnyArgs a = skinny_args(c, D, c1, SKINNY_UP_ROWS, seg_first, nseg, n);
+    a.feat = c->bufA; a.out = c->dimg; a.aux = c->xd; a.tanh_out = 2;
+    Scope s(c, "skinny_up", skinny_flops(c1, n, nseg), skinny_bytes<T>(c1, n, nseg));
+    launch_skinny_up<T>(a, c->st);
+  }
+}
+
+// Backward through G from dimg (fake segment) = d cost / d (pre-tanh output).
+template <typename T>
+void g_backward(gan_ctx* c, int n) {
+  Net& G = c->G;
+  const int nl = (int)G.conv.size();
+  const ConvLayer& last = G.conv[nl - 1];
+  const T* dlast = (const T*)c->dimg + (long long)n * 4 * last.Hs * last.Hs * last.Cb;
+  {
+    SkinnyArgs a = skinny_args(c, G, last, SKINNY_WGRAD_ROWS, 0, 1, n);
+    a.img = dlast; a.feat = c->gact[nl - 1]; a.partial = c->partial; a.dw = G.g + last.w; a.dbias = G.g + last.bias;
+    { Scope s(c, "skinny_wgrad", skinny_flops(last, n, 1), skinny_bytes<T>(last, n, 1)); launch_skinny_wgrad<T>(a, c->st); }
+    launch_img_bias_grad<T>(a, c->st);
+    SkinnyArgs d = skinny_args(c, G, last, SKINNY_DOWN_ROWS, 0, 1, n);
+    d.img = dlast; d.out = c->bufA;
+    Scope s(c, "skinny_down", skinny_flops(last, n, 1), skinny_bytes<T>(last, n, 1));
+    launch_skinny_down<T>(d, c->st);
+  }
+  for (int i = nl - 2; i >= 0; --i) {
+    const ConvLayer& cl = G.conv[i];
+    bn_backward<T>(c, norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
+                                   c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, 0.f),
+                   c->gpre[i + 1], c->bufA, c->bufB, true);
+    wgrad_call<T>(c, "gemm_wgrad", c->bufB, c->gact[i], G.g + cl.w, G.P, cl.Cb, cl.Cs, cl.Hs, 16, 1, n);
+    conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->bufB, (const T*)G.shadow_d + cl.w, G.P, c->bufA, nullptr, cl.Cb, cl.Cs,
+                 2 * cl.Hs, cl.Hs, 0, 1, n);
+  }
+  bn_backward<T>(c, norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
+                                 c->g_sums[0], 0, 1, n, 0.f),
+                 c->gpre[0], c->bufA, c->bufB, true);
+  wgrad_call<T>(c, "gemm_wgrad_dense", c->bufB, c->zin, G.g + G.fc_w, G.P, G.J, G.Kp, 1, 1, 1, n);
+}
+
+template <typename T>
+void adam_call(gan_ctx* c, Net& net, bool isG) {
+  AdamArgs a;
+  a.theta = net.theta; a.m = net.m; a.v = net.v; a.g = net.g; a.shadow = c->bf16 ? net.shadow_u : nullptr;
+  a.P = net.P; a.L = c->L; a.counts = c->rb.counts; a.t = net.t; a.bc = net.bc;
+  a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps;
+  { Scope s(c, "adam", 0, (double)c->L * net.P * (28.0 + (c->bf16 ? 2.0 : 0.0))); launch_adam(a, c->st); }
+  refresh_transposes<T>(c, net, isG);
+}
+
+template <typename T>
+void route_and_stage(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real, int n) {
+  launch_route(label_ids, n, c->L, c->cfg.n_labels, c->geoms, c->rb, c->st);
+  Scope s(c, "stage", 0, (double)n * (c->cfg.img_hw * c->cfg.img_hw * c->cfg.img_c * (4.0 + sizeof(T)) + c->cfg.z_dim * 4.0));
+  launch_stage<T>(label_ids, noise, real, n, c->L, c->cfg.z_dim, c->cfg.cond_g, c->G.Kp, c->cfg.img_c, c->cfg.img_hw, c->rb,
+                  (T*)c->zin, (T*)c->xd, c->st);
+}
+
+template <typename T>
+void train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real, int n) {
+  if (c->shadows_dirty) refresh_shadows(c);
+  route_and_stage<T>(c, label_ids, noise, real, n);
+  g_forward<T>(c, n, false, true);                 // fake = G(z), written next to the real batch
+  d_forward<T>(c, n, 0, 2, true);                  // D(real), D(fake): separate batch statistics per segment
+  loss_call(c, n, 0);                              // Eq. 3
+  d_backward<T>(c, n, 0, 2, true, false);
+  adam_call<T>(c, c->D, false);
+  d_forward<T>(c, n, 1, 1, true);                  // updated D on the same fake batch
+  loss_call(c, n, 1);                              // Eq. 4 (negated: minimised)
+  d_backward<T>(c, n, 1, 1, false, true);          // only data gradients: theta_D is not G's to move
+  g_backward<T>(c, n);
+  adam_call<T>(c, c->G, true);
+}
+
+bool check_config(const gan_config* f, std::string& why) {
+  if (f->n_models < 1 || f->n_labels < 1) { why = "n_models and n_labels must be positive"; return false; }
+  if (f->n_models != 1 && f->n_models != f->n_labels) { why = "n_models must be 1 or n_labels"; return false; }
+  if (f->n_g < 2 || f->n_g > GAN_MAX_LAYERS || f->n_d < 2 || f->n_d > GAN_MAX_LAYERS) { why = "n_g, n_d must be in [2, 8]"; return false; }
+  if (f->img_c < 1 || f->img_c > 4) { why = "img_c must be in [1, 4]"; return false; }
+  if ((f->g_h0 << f->n_g) != f->img_hw) { why = "img_hw must equal g_h0 * 2^n_g"; return false; }
+  if (((f->img_hw >> f->n_d) << f->n_d) != f->img_hw || (f->img_hw >> f->n_d) < 1) { why = "img_hw must be divisible by 2^n_d"; return false; }
+  for (int i = 0; i < f->n_g; ++i) if (f->g_ch[i] <= 0 || f->g_ch[i] % 64) { why = "g_ch must be multiples of 64"; return false; }
+  for (int i = 0; i < f->n_d; ++i) if (f->d_ch[i] <= 0 || f->d_ch[i] % 64) { why = "d_ch must be multiples of 64"; return false; }
+  if (f->g_ch[f->n_g - 1] > 128 || f->d_ch[0] > 128) { why = "the layers next to the image support 64 or 128 feature channels"; return false; }
+  if ((f->g_ch[0] * f->g_h0 * f->g_h0) % 128) { why = "g_ch[0]*g_h0^2 must be a multiple of 128"; return false; }
+  if (f->z_dim < 1 || f->cond_g < 0 || f->cond_d < 0 || f->max_total_batch < 1) { why = "bad z_dim / cond / max_total_batch"; return false; }
+  if (f->cond_g > f->n_labels || (f->cond_d != 0 && f->cond_d < f->n_labels)) { why = "cond_d must cover every label"; return false; }
+  if (f->n_models == 1 && f->cond_d > 16) { why = "a single model supports at most 16 label maps"; return false; }
+  if (f->precision != GAN_FP32 && f->precision != GAN_BF16_FP32MASTER) { why = "unknown precision"; return false; }
+  return true;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------------
+extern "C" {
+
+gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
+  if (!cfg || !out || cfg->struct_size != sizeof(gan_config)) return GAN_E_ARG;
+  std::string why;
+  if (!check_config(cfg, why)) return GAN_E_SHAPE;
+  gan_ctx* c = new gan_ctx();
+  c->cfg = *cfg;
+  c->st = (hipStream_t)hip_stream;
+  c->bf16 = cfg->precision == GAN_BF16_FP32MASTER;
+  c->L = cfg->n_models; c->NB = cfg->max_total_batch;
+  c->nslot = (cfg->cond_d > 0 && c->L == 1) ? cfg->cond_d : 1;
+  c->geoms.n = 0;
+  build_layout(c);
+  const int L = c->L, NB = c->NB;
+  const size_t es = esize(c);
+  bool ok = alloc_net(c, c->G) && alloc_net(c, c->D);
+  // geometries used by any launch
+  {
+    const int bm = conv_tile_m();
+    geom_id(c, 1, bm);
+    for (auto& cl : c->G.conv) geom_id(c, cl.Hs * cl.Hs, bm);
+    for (auto& cl : c->D.conv) geom_id(c, cl.Hs * cl.Hs, bm);
+    for (const ConvLayer* cl : {&c->G.conv.back(), &c->D.conv.front()}) {
+      geom_id(c, cl->Hs * cl->Hs, SKINNY_DOWN_ROWS);
+      geom_id(c, cl->Hs * cl->Hs, SKINNY_WGRAD_ROWS);
+    }
+  }
+  RouteBuffers& rb = c->rb;
+  ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&
+       dev_alloc(c, (void**)&rb.offs, (size_t)(L + 1) * 4) && dev_alloc(c, (void**)&rb.perm, (size_t)NB * 4) &&
+       dev_alloc(c, (void**)&rb.sample_model, (size_t)NB * 4) && dev_alloc(c, (void**)&rb.sample_slot, (size_t)NB * 4) &&
+       dev_alloc(c, (void**)&rb.tpre, (size_t)MAX_GEOMS * (L + 1) * 4) && dev_alloc(c, (void**)&rb.flags, 16);
+  const long long img_elems = (long long)cfg->img_hw * cfg->img_hw * cfg->img_c;
+  long long max_act = img_elems;
+  ok = ok && dev_alloc(c, &c->zin, (size_t)NB * c->G.Kp * es) && dev_alloc(c, &c->xd, (size_t)2 * NB * img_elems * es) &&
+       dev_alloc(c, &c->dimg, (size_t)2 * NB * img_elems * es);
+  // G activations (one segment)
+  {
+    const int nl = (int)c->G.conv.size();
+    c->gpre.resize(nl); c->gact.resize(nl); c->g_mean.resize(nl); c->g_var.resize(nl); c->g_rstd.resize(nl); c->g_sums.resize(nl);
+    for (int i = 0; i < nl && ok; ++i) {
+      const long long e = i == 0 ? c->G.J : (long long)4 * c->G.conv[i - 1].Hs * c->G.conv[i - 1].Hs * c->G.conv[i - 1].Cb;
+      const int C = i == 0 ? c->G.C0 : c->G.conv[i - 1].Cb;
+      max_act = e > max_act ? e : max_act;
+      ok = dev_alloc(c, &c->gpre[i], (size_t)NB * e * es) && dev_alloc(c, &c->gact[i], (size_t)NB * e * es) &&
+           dev_alloc(c, (void**)&c->g_mean[i], (size_t)2 * L * C * 4) && dev_alloc(c, (void**)&c->g_var[i], (size_t)2 * L * C * 4) &&
+           dev_alloc(c, (void**)&c->g_rstd[i], (size_t)2 * L * C * 4) && dev_alloc(c, (void**)&c->g_sums[i], (size_t)4 * L * C * 4);
+    }
+  }
+  // D activations (two segments: real, fake)
+  {
+    const int nl = (int)c->D.conv.size();
+    c->dpre.assign(nl, nullptr); c->dact.assign(nl, nullptr);
+    c->d_mean.assign(nl, nullptr); c->d_var.assign(nl, nullptr); c->d_rstd.assign(nl, nullptr); c->d_sums.assign(nl, nullptr);
+    for (int j = 0; j < nl && ok; ++j) {
+      const ConvLayer& cl = c->D.conv[j];
+      const long long e = (long long)cl.Hs * cl.Hs * cl.Cs;
+      max_act = e > max_act ? e : max_act;
+      ok = dev_alloc(c, &c->dact[j], (size_t)2 * NB * e * es);
+      if (j > 0)
+        ok = ok && dev_alloc(c, &c->dpre[j], (size_t)2 * NB * e * es) && dev_alloc(c, (void**)&c->d_mean[j], (size_t)2 * L * cl.Cs * 4) &&
+             dev_alloc(c, (void**)&c->d_var[j], (size_t)2 * L * cl.Cs * 4) && dev_alloc(c, (void**)&c->d_rstd[j], (size_t)2 * L * cl.Cs * 4) &&
+             dev_alloc(c, (void**)&c->d_sums[j], (size_t)4 * L * cl.Cs * 4);
+    }
+  }
+  ok = ok && dev_alloc(c, &c->bufA, (size_t)2 * NB * max_act * es) && dev_alloc(c, &c->bufB, (size_t)2 * NB * max_act * es) &&
+       dev_alloc(c, (void**)&c->logits, (size_t)2 * NB * 4) && dev_alloc(c, (void**)&c->dlogits, (size_t)2 * NB * 4) &&
+       dev_alloc(c, (void**)&c->loss_d, (size_t)L * 4) && dev_alloc(c, (void**)&c->loss_g, (size_t)L * 4);
+  {
+    const ConvLayer& c1 = c->D.conv[0];
+    const ConvLayer& gl = c->G.conv.back();
+    const size_t lm = (size_t)L * c->nslot * 9 * c1.Cs * 4;
+    ok = ok && dev_alloc(c, (void**)&c->lm_table, lm) && dev_alloc(c, (void**)&c->lm_rsum, lm);
+    const size_t p1 = (size_t)2 * ub_tiles(c, NB, c1.Hs * c1.Hs, SKINNY_WGRAD_ROWS) * (256 / c1.Cs) * 16 * c1.Cb * c1.Cs * 4;
+    const size_t p2 = (size_t)ub_tiles(c, NB, gl.Hs * gl.Hs, SKINNY_WGRAD_ROWS) * (256 / gl.Cs) * 16 * gl.Cb * gl.Cs * 4;
+    ok = ok && dev_alloc(c, (void**)&c->partial, p1 > p2 ? p1 : p2);
+  }
+  if (!ok) {
+    for (void* p : c->allocs) (void)hipFree(p);
+    delete c;
+    return GAN_E_OOM;
+  }
+  hipMemsetAsync(rb.flags, 0, 16, c->st);
+  hipMemsetAsync(rb.counts, 0, (size_t)L * 4, c->st);
+  hipMemsetAsync(rb.offs, 0, (size_t)(L + 1) * 4, c->st);
+  hipMemsetAsync(c->loss_d, 0, (size_t)L * 4, c->st);
+  hipMemsetAsync(c->loss_g, 0, (size_t)L * 4, c->st);
+  builtin_init(c);
+  if (hipStreamSynchronize(c->st) != hipSuccess || hipGetLastError() != hipSuccess) {
+    for (void* p : c->allocs) (void)hipFree(p);
+    delete c;
+    return GAN_E_HIP;
+  }
+  c->shadows_dirty = true;
+  *out = c;
+  return GAN_OK;
+}
+
+gan_status gan_destroy(gan_ctx* c) {
+  if (!c) return GAN_E_ARG;
+  (void)hipStreamSynchronize(c->st);
+  for (auto& e : c->prof_entries) { hipEventDestroy(e.e0); hipEventDestroy(e.e1); }
+  for (void* p : c->allocs) (void)hipFree(p);
+  delete c;
+  return GAN_OK;
+}
+
+const char* gan_last_error(const gan_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+gan_status gan_train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real_batch, int32_t n) {
+  if (!c) return GAN_E_ARG;
+  if (n < 0 || n > c->NB) return fail(c, GAN_E_ARG, "n out of range [0, max_total_batch]");
+  if (n > 0 && (!label_ids || !noise || !real_batch)) return fail(c, GAN_E_ARG, "null input pointer");
+  c->last_n = n;
+  if (n == 0) {
+    hipMemsetAsync(c->rb.counts, 0, (size_t)c->L * 4, c->st);
+    hipMemsetAsync(c->rb.offs, 0, (size_t)(c->L + 1) * 4, c->st);
+    hipMemsetAsync(c->loss_d, 0, (size_t)c->L * 4, c->st);
+    hipMemsetAsync(c->loss_g, 0, (size_t)c->L * 4, c->st);
+    return GAN_OK;
+  }
+  if (c->bf16) train_step<bf16_t>(c, label_ids, noise, real_batch, n);
+  else train_step<float>(c, label_ids, noise, real_batch, n);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("launch failed: ") + hipGetErrorString(e));
+  return GAN_OK;
+}
+
+gan_status gan_generate(gan_ctx* c, const int32_t* label_ids, const float* noise, int32_t n, float* out_images,
+                        int32_t use_running_stats) {
+  if (!c) return GAN_E_ARG;
+  if (n < 0 || n > c->NB) return fail(c, GAN_E_ARG, "n out of range [0, max_total_batch]");
+  if (n == 0) return GAN_OK;
+  if (!label_ids || !noise || !out_images) return fail(c, GAN_E_ARG, "null pointer");
+  if (c->shadows_dirty) refresh_shadows(c);
+  c->last_n = n;
+  const gan_config& f = c->cfg;
+  if (c->bf16) {
+    route_and_stage<bf16_t>(c, label_ids, noise, nullptr, n);
+    g_forward<bf16_t>(c, n, use_running_stats != 0, false);
+    launch_unstage<bf16_t>((const bf16_t*)c->xd + (long long)n * f.img_hw * f.img_hw * f.img_c, out_images, n, c->L, f.img_c,
+                           f.img_hw, c->rb, c->st);
+  } else {
+    route_and_stage<float>(c, label_ids, noise, nullptr, n);
+    g_forward<float>(c, n, use_running_stats != 0, false);
+    launch_unstage<float>((const float*)c->xd + (long long)n * f.img_hw * f.img_hw * f.img_c, out_images, n, c->L, f.img_c,
+                          f.img_hw, c->rb, c->st);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("launch failed: ") + hipGetErrorString(e));
+  return GAN_OK;
+}
+
+static gan_status sync(gan_ctx* c) {
+  const hipError_t e = hipStreamSynchronize(c->st);
+  if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("stream failed: ") + hipGetErrorString(e));
+  return GAN_OK;
+}
+
+gan_status gan_get_losses(gan_ctx* c, float* d_loss, float* g_loss, int32_t* counts) {
+  if (!c) return GAN_E_ARG;
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  if (d_loss) hipMemcpy(d_loss, c->loss_d, (size_t)c->L * 4, hipMemcpyDeviceToHost);
+  if (g_loss) hipMemcpy(g_loss, c->loss_g, (size_t)c->L * 4, hipMemcpyDeviceToHost);
+  if (counts) hipMemcpy(counts, c->rb.counts, (size_t)c->L * 4, hipMemcpyDeviceToHost);
+  int flag = 0;
+  hipMemcpy(&flag, c->rb.flags, 4, hipMemcpyDeviceToHost);
+  if (flag) {
+    hipMemset(c->rb.flags, 0, 4);
+    return fail(c, GAN_E_LABEL, "a label id outside [0, n_labels) was dropped");
+  }
+  return GAN_OK;
+}
+
+gan_status gan_param_count(const gan_ctx* c, int32_t which, int64_t* per_model) {
+  if (!c || !per_model || which < 0 || which > 1) return GAN_E_ARG;
+  *per_model = which == 0 ? c->G.Pext : c->D.Pext;
+  return GAN_OK;
+}
+gan_status gan_bn_count(const gan_ctx* c, int32_t which, int64_t* per_model) {
+  if (!c || !per_model || which < 0 || which > 1) return GAN_E_ARG;
+  *per_model = which == 0 ? c->G.nbn : c->D.nbn;
+  return GAN_OK;
+}
+
+static gan_status read_block(gan_ctx* c, int which, int model, const float* dev_base, float* dst, int64_t n) {
+  if (!c || !dst || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
+  Net& net = which == 0 ? c->G : c->D;
+  if (n != net.Pext) return fail(c, GAN_E_ARG, "wrong element count");
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  std::vector<float> tmp((size_t)net.P);
+  if (hipMemcpy(tmp.data(), dev_base + (long long)model * net.P, (size_t)net.P * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(c, GAN_E_HIP, "copy failed");
+  for (long long i = 0; i < net.Pext; ++i) dst[i] = tmp[(size_t)net.ext2int[(size_t)i]];
+  return GAN_OK;
+}
+
+gan_status gan_get_params(gan_ctx* c, int32_t which, int32_t model, float* dst, int64_t n) {
+  if (!c || which < 0 || which > 1) return GAN_E_ARG;
+  return read_block(c, which, model, (which == 0 ? c->G : c->D).theta, dst, n);
+}
+gan_status gan_get_grads(gan_ctx* c, int32_t which, int32_t model, float* dst, int64_t n) {
+  if (!c || which < 0 || which > 1) return GAN_E_ARG;
+  return read_block(c, which, model, (which == 0 ? c->G : c->D).g, dst, n);
+}
+gan_status gan_get_opt_state(gan_ctx* c, int32_t which, int32_t model, float* m, float* v, int64_t* t) {
+  if (!c || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
+  Net& net = which == 0 ? c->G : c->D;
+  gan_status s = GAN_OK;
+  if (m) s = read_block(c, which, model, net.m, m, net.Pext);
+  if (s == GAN_OK && v) s = read_block(c, which, model, net.v, v, net.Pext);
+  if (s == GAN_OK && t) {
+    s = sync(c);
+    int tt = 0;
+    hipMemcpy(&tt, net.t + model, 4, hipMemcpyDeviceToHost);
+    *t = tt;
+  }
+  return s;
+}
+
+gan_status gan_set_params(gan_ctx* c, int32_t which, int32_t model, const float* src, int64_t n) {
+  if (!c || !src || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
+  Net& net = which == 0 ? c->G : c->D;
+  if (n != net.Pext) return fail(c, GAN_E_ARG, "wrong element count");
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  std::vector<float> tmp((size_t)net.P, 0.f);
+  for (long long i = 0; i < net.Pext; ++i) tmp[(size_t)net.ext2int[(size_t)i]] = src[i];
+  if (hipMemcpy(net.theta + (long long)model * net.P, tmp.data(), (size_t)net.P * 4, hipMemcpyHostToDevice) != hipSuccess)
+    return fail(c, GAN_E_HIP, "copy failed");
+  c->shadows_dirty = true;
+  return GAN_OK;
+}
+
+gan_status gan_get_bn_running(gan_ctx* c, int32_t which, int32_t model, float* mean, float* var, int64_t n) {
+  if (!c || !mean || !var || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
+  Net& net = which == 0 ? c->G : c->D;
+  if (n != net.nbn) return fail(c, GAN_E_ARG, "wrong element count");
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  hipMemcpy(mean, net.run_mean + (long long)model * net.nbn, (size_t)n * 4, hipMemcpyDeviceToHost);
+  hipMemcpy(var, net.run_var + (long long)model * net.nbn, (size_t)n * 4, hipMemcpyDeviceToHost);
+  return GAN_OK;
+}
+
+gan_status gan_get_routing(gan_ctx* c, int32_t* perm, int32_t* offs) {
+  if (!c) return GAN_E_ARG;
+  if (c->last_n < 0) return fail(c, GAN_E_STATE, "no step has been taken");
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  if (offs) hipMemcpy(offs, c->rb.offs, (size_t)(c->L + 1) * 4, hipMemcpyDeviceToHost);
+  if (perm && c->last_n > 0) {
+    int nv = 0;
+    hipMemcpy(&nv, c->rb.offs + c->L, 4, hipMemcpyDeviceToHost);
+    for (int i = 0; i < c->last_n; ++i) perm[i] = -1;
+    hipMemcpy(perm, c->rb.perm, (size_t)nv * 4, hipMemcpyDeviceToHost);
+  }
+  return GAN_OK;
+}
+
+gan_status gan_profile_enable(gan_ctx* c, int32_t enable) {
+  if (!c) return GAN_E_ARG;
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  for (auto& e : c->prof_entries) { hipEventDestroy(e.e0); hipEventDestroy(e.e1); }
+  c->prof_entries.clear();
+  c->prof = enable != 0;
+  return GAN_OK;
+}
+
+gan_status gan_profile_read(gan_ctx* c, int32_t cap, const char** names, int64_t* launches, double* ms, double* flops,
+                            double* bytes, int32_t* n_out) {
+  if (!c || !names || !launches || !ms || !flops || !bytes || !n_out || cap < 1) return GAN_E_ARG;
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  int nf = 0;
+  for (auto& e : c->prof_entries) {
+    int k = -1;
+    for (int i = 0; i < nf; ++i) if (strcmp(names[i], e.name) == 0) { k = i; break; }
+    if (k < 0) {
+      if (nf >= cap) continue;
+      k = nf++;
+      names[k] = e.name; launches[k] = 0; ms[k] = 0; flops[k] = 0; bytes[k] = 0;
+    }
+    float t = 0.f;
+    hipEventElapsedTime(&t, e.e0, e.e1);
+    launches[k] += 1; ms[k] += t; flops[k] += e.flops; bytes[k] += e.bytes;
+  }
+  *n_out = nf;
+  return GAN_OK;
+}
+
+// ---- single operations ------------------------------------------------------------------------------------
+static gan_status op_common(gan_ctx* c, const int32_t* offs, int n_groups, int rps, int** tpre_out) {
+  int* tp = nullptr;
+  if (hipMalloc((void**)&tp, (size_t)(n_groups + 1) * 4) != hipSuccess) return fail(c, GAN_E_OOM, "tile prefix alloc");
+  launch_tile_prefix(offs, n_groups, rps, conv_tile_m(), tp, c->st);
+  *tpre_out = tp;
+  return GAN_OK;
+}
+
+static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, void* Out, const int32_t* offs, int n_groups,
+                          int n_samples, int C, int N, int Hin, int Hr, long long wstride) {
+  if (!c || !A || !W || !Out || !offs || n_groups < 1 || n_samples < 0) return GAN_E_ARG;
+  if (C % 64 || N < 1) return fail(c, GAN_E_SHAPE, "channels must be multiples of 64");
+  int* tp = nullptr;
+  gan_status s = op_common(c, offs, n_groups, Hr * Hr, &tp);
+  if (s != GAN_OK) return s;
+  ConvArgs a;
+  a.A = A; a.W = W; a.Out = Out; a.Aux = nullptr; a.offs = offs; a.tpre = tp; a.w_stride = wstride; a.L = n_groups;
+  a.seg_first = 0; a.nseg = 1; a.seg_samples = n_samples; a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr;
+  a.ub_tiles = (int)(((long long)n_samples * Hr * Hr) / conv_tile_m()) + n_groups; a.slope = 0.f;
+  if (c->bf16) launch_conv<bf16_t>(mode, EPI_NONE, a, c->st); else launch_conv<float>(mode, EPI_NONE, a, c->st);
+  s = sync(c);
+  (void)hipFree(tp);
+  const hipError_t e = hipGetLastError();
+  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
+  return s;
+}
+
+gan_status gan_op_conv_down(gan_ctx* c, const void* big, const void* w_down, void* small_out, const int32_t* offs,
+                            int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs) {
+  return op_conv(c, MODE_DOWN, big, w_down, small_out, offs, n_groups, n_samples, cb, cs, 2 * hs, hs, (long long)16 * cb * cs);
+}
+gan_status gan_op_conv_up(gan_ctx* c, const void* small_in, const void* w_up, void* big_out, const int32_t* offs,
+                          int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs) {
+  return op_conv(c, MODE_UP, small_in, w_up, big_out, offs, n_groups, n_samples, cs, cb, hs, hs, (long long)16 * cb * cs);
+}
+gan_status gan_op_conv_wgrad(gan_ctx* c, const void* big, const void* small_in, float* dw, const int32_t* offs,
+                             int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs) {
+  if (!c || !big || !small_in || !dw || !offs || n_groups < 1 || n_samples < 0) return GAN_E_ARG;
+  if ((16 * cb) % 128 || cb % 8 || cs % 8) return fail(c, GAN_E_SHAPE, "unsupported channel counts");
+  WgradArgs a;
+  a.Big = big; a.Small = small_in; a.dW = dw; a.offs = offs; a.dw_stride = (long long)16 * cb * cs;
+  a.L = n_groups; a.nseg = 1; a.seg_samples = n_samples; a.Cb = cb; a.Cs = cs; a.Hs = hs; a.ntaps = 16;
+  if (c->bf16) launch_wgrad<bf16_t>(a, c->st); else launch_wgrad<float>(a, c->st);
+  gan_status s = sync(c);
+  const hipError_t e = hipGetLastError();
+  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
+  return s;
+}
+
+}  // extern "C"

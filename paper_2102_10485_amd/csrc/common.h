@@ -1,0 +1,76 @@
+// Shared declarations of the gfx950 kernels and their host launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gan {
+
+// bf16 storage: upper half of an fp32, round-to-nearest-even on conversion.
+struct bf16_t {
+  unsigned short v;
+};
+
+__host__ __device__ inline float to_float(float x) { return x; }
+__host__ __device__ inline float to_float(bf16_t x) {
+  union { unsigned u; float f; } c;
+  c.u = (unsigned)x.v << 16;
+  return c.f;
+}
+__host__ __device__ inline unsigned short f32_to_bf16_bits(float f) {
+  union { unsigned u; float f; } c;
+  c.f = f;
+  unsigned u = c.u;
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;   // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+template <typename T> __host__ __device__ inline T from_float(float f);
+template <> __host__ __device__ inline float from_float<float>(float f) { return f; }
+template <> __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
+  bf16_t r;
+  r.v = f32_to_bf16_bits(f);
+  return r;
+}
+
+enum ConvMode { MODE_DOWN = 0, MODE_UP = 1, MODE_DENSE = 2 };
+enum Epilogue { EPI_NONE = 0, EPI_ACT_BWD = 1 };
+enum Act { ACT_RELU = 0, ACT_LRELU = 1 };
+
+// Arguments of the grouped implicit-GEMM forward-type kernel (down / up / dense).
+struct ConvArgs {
+  const void* A;         // gathered activations (storage type)
+  const void* W;         // weights of model 0, K-contiguous: [tap][N][C] (storage type)
+  void* Out;             // output activations (storage type)
+  const void* Aux;       // EPI_ACT_BWD: forward activation at the output position (storage type)
+  const int* offs;       // [L+1] sample offsets of the models inside one segment
+  const int* tpre;       // [L+1] prefix of M-tiles per model for this geometry
+  long long w_stride;    // elements between two models' weight blocks
+  int L;                 // models
+  int seg_first, nseg;   // segments to process: rows of segment s start at sample s*seg_samples
+  int seg_samples;
+  int C, N;              // channels per tap of A, output channels
+  int Hin;               // side of the gathered tensor
+  int Hr;                // side of the row space (rows per sample = Hr*Hr)
+  int ub_tiles;          // launched upper bound of M-tiles per (segment, phase)
+  float slope;           // EPI_ACT_BWD: derivative on the non-positive side
+};
+
+// Arguments of the grouped weight-gradient kernel: dW[tap][cb][cs] = sum_rows big(tap)[cb] * small[cs].
+struct WgradArgs {
+  const void* Big;       // tensor gathered through the taps, side 2*Hs (dense: side 1), channels Cb
+  const void* Small;     // tensor indexed directly by row, side Hs, channels Cs
+  float* dW;             // fp32 output of model 0: [ntaps][Cb][Cs]
+  const int* offs;       // [L+1]
+  long long dw_stride;   // elements between two models' blocks
+  int L, nseg, seg_samples;
+  int Cb, Cs, Hs;
+  int ntaps;             // 16 (conv) or 1 (dense)
+};
+
+template <typename T> void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st);
+template <typename T> void launch_wgrad(const WgradArgs& a, hipStream_t st);
+
+int conv_tile_m();   // rows per M-tile of the forward-type kernel (for tile prefix arrays)
+
+}  // namespace gan

@@ -1,0 +1,654 @@
+// Bandwidth-bound kernels of the training step: label routing, staging, BatchNorm statistics / apply / backward
+// fused with the activation, D's linear head and the two logistic costs (Eq. 3, Eq. 4), Adam, layout copies.
+// Every reduction has a fixed order that does not depend on the number of models, so results are deterministic
+// and a model's numbers do not change with what else is in the launch.
+#include "kernels.h"
+
+namespace gan {
+
+// ---------------------------------------------------------------------------------------------------------
+// routing: stable partition of the flat batch by model
+// ---------------------------------------------------------------------------------------------------------
+
+__device__ inline int model_of_label(int y, int L) { return L == 1 ? 0 : y; }
+
+__global__ void route_count_kernel(const int* __restrict__ label_ids, int n, int L, int n_labels, int* cnt, int* flags) {
+  const int t = threadIdx.x;
+  int* row = cnt + (long long)t * L;
+  for (int l = 0; l < L; ++l) row[l] = 0;
+  const int chunk = (n + ROUTE_CHUNKS - 1) / ROUTE_CHUNKS;
+  const int i0 = t * chunk, i1 = min(n, i0 + chunk);
+  bool bad = false;
+  for (int i = i0; i < i1; ++i) {
+    const int y = label_ids[i];
+    if (y < 0 || y >= n_labels) { bad = true; continue; }
+    row[model_of_label(y, L)] += 1;
+  }
+  if (bad) flags[0] = 1;
+}
+
+__global__ void route_scan_chunks_kernel(int* cnt, int* counts, int L) {
+  const int l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= L) return;
+  int run = 0;
+  for (int t = 0; t < ROUTE_CHUNKS; ++t) {
+    const int c = cnt[(long long)t * L + l];
+    cnt[(long long)t * L + l] = run;
+    run += c;
+  }
+  counts[l] = run;
+}
+
+__global__ void route_offsets_kernel(const int* counts, int* offs, int* tpre, int L, GeomTable geoms) {
+  const int t = threadIdx.x;
+  if (t == 0) {
+    int run = 0;
+    for (int l = 0; l < L; ++l) { offs[l] = run; run += counts[l]; }
+    offs[L] = run;
+  } else if (t - 1 < geoms.n) {
+    const int g = t - 1;
+    int* tp = tpre + (long long)g * (L + 1);
+    int run = 0;
+    for (int l = 0; l < L; ++l) {
+      tp[l] = run;
+      run += (counts[l] * geoms.rps[g] + geoms.tile_rows[g] - 1) / geoms.tile_rows[g];
+    }
+    tp[L] = run;
+  }
+}
+
+__global__ void route_scatter_kernel(const int* __restrict__ label_ids, int n, int L, int n_labels, int* cnt,
+                                     const int* offs, int* perm, int* sample_model, int* sample_slot) {
+  const int t = threadIdx.x;
+  int* row = cnt + (long long)t * L;
+  const int chunk = (n + ROUTE_CHUNKS - 1) / ROUTE_CHUNKS;
+  const int i0 = t * chunk, i1 = min(n, i0 + chunk);
+  for (int i = i0; i < i1; ++i) {
+    const int y = label_ids[i];
+    if (y < 0 || y >= n_labels) continue;
+    const int mdl = model_of_label(y, L);
+    const int pos = offs[mdl] + row[mdl];
+    row[mdl] += 1;
+    perm[pos] = i;
+    sample_model[pos] = mdl;
+    sample_slot[pos] = (L == 1) ? y : 0;
+  }
+}
+
+void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTable& geoms, const RouteBuffers& rb,
+                  hipStream_t st) {
+  hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.flags);
+  hipLaunchKernelGGL(route_scan_chunks_kernel, dim3((L + 255) / 256), dim3(256), 0, st, rb.cnt, rb.counts, L);
+  hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(64), 0, st, rb.counts, rb.offs, rb.tpre, L, geoms);
+  hipLaunchKernelGGL(route_scatter_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.offs,
+                     rb.perm, rb.sample_model, rb.sample_slot);
+}
+
+__global__ void tile_prefix_kernel(const int* offs, int L, int rps, int tile_rows, int* tpre) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    int run = 0;
+    for (int l = 0; l < L; ++l) {
+      tpre[l] = run;
+      run += ((offs[l + 1] - offs[l]) * rps + tile_rows - 1) / tile_rows;
+    }
+    tpre[L] = run;
+  }
+}
+void launch_tile_prefix(const int* offs, int L, int rps, int tile_rows, int* tpre, hipStream_t st) {
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(64), 0, st, offs, L, rps, tile_rows, tpre);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// staging: gather through perm, NCHW fp32 -> NHWC storage type; z | one-hot | zero padding
+// ---------------------------------------------------------------------------------------------------------
+
+template <typename T>
+__global__ void stage_images_kernel(const float* __restrict__ real, const int* __restrict__ perm, const int* offs, int L,
+                                    int n, int C, int HW, T* __restrict__ xd) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;   // (j, pixel)
+  if (idx >= (long long)n * HW) return;
+  const int j = (int)(idx / HW), pix = (int)(idx - (long long)j * HW);
+  if (j >= offs[L]) return;
+  const int src = perm[j];
+  for (int c = 0; c < C; ++c) xd[idx * C + c] = from_float<T>(real[((long long)src * C + c) * HW + pix]);
+}
+
+template <typename T>
+__global__ void stage_noise_kernel(const float* __restrict__ noise, const int* __restrict__ label_ids,
+                                   const int* __restrict__ perm, const int* offs, int L, int n, int zdim, int cond_g,
+                                   int kp, T* __restrict__ zin) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;   // (j, k)
+  if (idx >= (long long)n * kp) return;
+  const int j = (int)(idx / kp), k = (int)(idx - (long long)j * kp);
+  if (j >= offs[L]) return;
+  const int src = perm[j];
+  float v = 0.f;
+  if (k < zdim) v = noise[(long long)src * zdim + k];
+  else if (k < zdim + cond_g) v = (k - zdim == label_ids[src]) ? 1.f : 0.f;
+  zin[idx] = from_float<T>(v);
+}
+
+template <typename T>
+void launch_stage(const int* label_ids, const float* noise, const float* real, int n, int L, int zdim, int cond_g, int kp,
+                  int img_c, int img_hw, const RouteBuffers& rb, T* zin, T* xd, hipStream_t st) {
+  if (n == 0) return;
+  const int HW = img_hw * img_hw;
+  if (real) {
+    const long long tot = (long long)n * HW;
+    hipLaunchKernelGGL((stage_images_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, real, rb.perm,
+                       rb.offs, L, n, img_c, HW, xd);
+  }
+  const long long tot = (long long)n * kp;
+  hipLaunchKernelGGL((stage_noise_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, noise, label_ids,
+                     rb.perm, rb.offs, L, n, zdim, cond_g, kp, zin);
+}
+template void launch_stage<float>(const int*, const float*, const float*, int, int, int, int, int, int, int,
+                                  const RouteBuffers&, float*, float*, hipStream_t);
+template void launch_stage<bf16_t>(const int*, const float*, const float*, int, int, int, int, int, int, int,
+                                   const RouteBuffers&, bf16_t*, bf16_t*, hipStream_t);
+
+template <typename T>
+__global__ void unstage_kernel(const T* __restrict__ fake, const int* __restrict__ perm, const int* offs, int L, int n, int C,
+                               int HW, float* __restrict__ out) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)n * HW) return;
+  const int j = (int)(idx / HW), pix = (int)(idx - (long long)j * HW);
+  if (j >= offs[L]) return;
+  const int dst = perm[j];
+  for (int c = 0; c < C; ++c) out[((long long)dst * C + c) * HW + pix] = to_float(fake[idx * C + c]);
+}
+template <typename T>
+void launch_unstage(const T* fake, float* out, int n, int L, int img_c, int img_hw, const RouteBuffers& rb, hipStream_t st) {
+  if (n == 0) return;
+  const int HW = img_hw * img_hw;
+  const long long tot = (long long)n * HW;
+  hipLaunchKernelGGL((unstage_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, fake, rb.perm, rb.offs,
+                     L, n, img_c, HW, out);
+}
+template void launch_unstage<float>(const float*, float*, int, int, int, int, const RouteBuffers&, hipStream_t);
+template void launch_unstage<bf16_t>(const bf16_t*, float*, int, int, int, int, const RouteBuffers&, hipStream_t);
+
+// ---------------------------------------------------------------------------------------------------------
+// BatchNorm
+// ---------------------------------------------------------------------------------------------------------
+
+// Loads 4 consecutive channels as floats.
+__device__ inline void load4(const float* p, float (&v)[4]) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ inline void load4(const bf16_t* p, float (&v)[4]) {
+  const uint2 t = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+__device__ inline void store4(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ inline void store4(bf16_t* p, const float (&v)[4]) {
+  uint2 t;
+  t.x = (unsigned)f32_to_bf16_bits(v[0]) | ((unsigned)f32_to_bf16_bits(v[1]) << 16);
+  t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
+  *reinterpret_cast<uint2*>(p) = t;
+}
+
+// Block (channel chunk of 64, group): 16 row lanes x 16 channel lanes of 4 channels.  Two passes over the
+// group's slab (mean, then centred second moment), the second served from cache.
+template <typename T>
+__global__ __launch_bounds__(256) void bn_stats_kernel(NormArgs a) {
+  __shared__ float red[16][64];
+  __shared__ float smean[64];
+  const int l = blockIdx.y % a.L, sidx = blockIdx.y / a.L;
+  const int seg = a.seg_first + sidx;
+  const int cnt = a.offs[l + 1] - a.offs[l];
+  const int g = seg * a.L + l;
+  const int c0 = blockIdx.x * 64;
+  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const long long rows = (long long)cnt * a.rps;
+  if (rows == 0) return;
+  const T* x = static_cast<const T*>(a.x) + ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * 4;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  for (long long r = rl; r < rows; r += 16) {
+    float v[4];
+    load4(x + r * a.C, v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s[e] += v[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[rl][cl * 4 + e] = s[e];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float t = 0.f;
+    for (int i = 0; i < 16; ++i) t += red[i][threadIdx.x];
+    smean[threadIdx.x] = t / (float)rows;
+  }
+  __syncthreads();
+  float mu[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { mu[e] = smean[cl * 4 + e]; s[e] = 0.f; }
+  for (long long r = rl; r < rows; r += 16) {
+    float v[4];
+    load4(x + r * a.C, v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { const float d = v[e] - mu[e]; s[e] += d * d; }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[rl][cl * 4 + e] = s[e];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float t = 0.f;
+    for (int i = 0; i < 16; ++i) t += red[i][threadIdx.x];
+    const float var = t / (float)rows;
+    const long long o = (long long)g * a.C + c0 + threadIdx.x;
+    a.mean[o] = smean[threadIdx.x];
+    a.var[o] = var;
+    a.rstd[o] = 1.0f / sqrtf(var + a.eps);
+  }
+}
+template <typename T> void launch_bn_stats(const NormArgs& a, hipStream_t st) {
+  if (a.nseg == 0) return;
+  hipLaunchKernelGGL((bn_stats_kernel<T>), dim3(a.C / 64, a.L * a.nseg), dim3(256), 0, st, a);
+}
+template void launch_bn_stats<float>(const NormArgs&, hipStream_t);
+template void launch_bn_stats<bf16_t>(const NormArgs&, hipStream_t);
+
+// running <- (1 - momentum) running + momentum * batch, once per segment in order; unbiased variance stored.
+__global__ void bn_running_kernel(NormArgs a) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= a.L * a.C) return;
+  const int l = idx / a.C, c = idx - l * a.C;
+  const int cnt = a.offs[l + 1] - a.offs[l];
+  if (cnt == 0) return;
+  const long long S = (long long)cnt * a.rps;
+  float rm = a.run_mean[(long long)l * a.rstride + c], rv = a.run_var[(long long)l * a.rstride + c];
+  for (int s = 0; s < a.nseg; ++s) {
+    const long long o = (long long)((a.seg_first + s) * a.L + l) * a.C + c;
+    rm = (1.f - a.momentum) * rm + a.momentum * a.mean[o];
+    if (S > 1) rv = (1.f - a.momentum) * rv + a.momentum * a.var[o] * ((float)S / (float)(S - 1));
+  }
+  a.run_mean[(long long)l * a.rstride + c] = rm;
+  a.run_var[(long long)l * a.rstride + c] = rv;
+}
+void launch_bn_running(const NormArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(bn_running_kernel, dim3((a.L * a.C + 255) / 256), dim3(256), 0, st, a);
+}
+
+__global__ void bn_from_running_kernel(NormArgs a) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= a.L * a.C) return;
+  const int l = idx / a.C, c = idx - l * a.C;
+  const long long o = (long long)(a.seg_first * a.L + l) * a.C + c;
+  const float rv = a.run_var[(long long)l * a.rstride + c];
+  a.mean[o] = a.run_mean[(long long)l * a.rstride + c];
+  a.var[o] = rv;
+  a.rstd[o] = 1.0f / sqrtf(rv + a.eps);
+}
+void launch_bn_from_running(const NormArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(bn_from_running_kernel, dim3((a.L * a.C + 255) / 256), dim3(256), 0, st, a);
+}
+
+// y = act(gamma * (x - mean) * rstd + beta); one thread per 4 channels of one row.
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_kernel(NormArgs a) {
+  const int c4 = a.C / 4;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long rows_seg = (long long)a.n * a.rps;
+  if (idx >= rows_seg * c4 * a.nseg) return;
+  const long long row_all = idx / c4;
+  const int c = (int)(idx - row_all * c4) * 4;
+  const int sidx = (int)(row_all / rows_seg);
+  const long long row = row_all - (long long)sidx * rows_seg;
+  const int j = (int)(row / a.rps);
+  if (j >= a.offs[a.L]) return;
+  const int l = a.sample_model[j];
+  const int seg = a.seg_first + sidx;
+  const long long e = (((long long)seg * a.seg_samples) * a.rps + row) * a.C + c;
+  const long long so = (long long)(seg * a.L + l) * a.C + c;
+  float v[4];
+  load4(static_cast<const T*>(a.x) + e, v);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const float sc = a.gamma[(long long)l * a.pstride + c + k] * a.rstd[so + k];
+    const float u = (v[k] - a.mean[so + k]) * sc + a.beta[(long long)l * a.pstride + c + k];
+    v[k] = u > 0.f ? u : u * a.slope;
+  }
+  store4(static_cast<T*>(a.y) + e, v);
+}
+template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st) {
+  const long long tot = (long long)a.n * a.rps * (a.C / 4) * a.nseg;
+  if (tot == 0) return;
+  hipLaunchKernelGGL((bn_apply_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+}
+template void launch_bn_apply<float>(const NormArgs&, hipStream_t);
+template void launch_bn_apply<bf16_t>(const NormArgs&, hipStream_t);
+
+// sums[g][c] = (sum g, sum g * xhat) with g = dy * act'(u), u = gamma * xhat + beta.
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a) {
+  __shared__ float red[2][16][64];
+  const int l = blockIdx.y % a.L, sidx = blockIdx.y / a.L;
+  const int seg = a.seg_first + sidx;
+  const int cnt = a.offs[l + 1] - a.offs[l];
+  const int g = seg * a.L + l;
+  const int c0 = blockIdx.x * 64;
+  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const long long rows = (long long)cnt * a.rps;
+  if (rows == 0) return;
+  const long long base = ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * 4;
+  const T* x = static_cast<const T*>(a.x) + base;
+  const T* dy = static_cast<const T*>(a.dy) + base;
+  float mu[4], rs[4], ga[4], be[4], sg[4] = {0, 0, 0, 0}, sgx[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int c = c0 + cl * 4 + e;
+    mu[e] = a.mean[(long long)g * a.C + c];
+    rs[e] = a.rstd[(long long)g * a.C + c];
+    ga[e] = a.gamma[(long long)l * a.pstride + c];
+    be[e] = a.beta[(long long)l * a.pstride + c];
+  }
+  for (long long r = rl; r < rows; r += 16) {
+    float v[4], d[4];
+    load4(x + r * a.C, v);
+    load4(dy + r * a.C, d);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float xh = (v[e] - mu[e]) * rs[e];
+      const float u = ga[e] * xh + be[e];
+      const float gg = u > 0.f ? d[e] : d[e] * a.slope;
+      sg[e] += gg;
+      sgx[e] += gg * xh;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { red[0][rl][cl * 4 + e] = sg[e]; red[1][rl][cl * 4 + e] = sgx[e]; }
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    const int w = threadIdx.x >> 6, c = threadIdx.x & 63;
+    float t = 0.f;
+    for (int i = 0; i < 16; ++i) t += red[w][i][c];
+    a.sums[((long long)g * a.C + c0 + c) * 2 + w] = t;
+  }
+}
+template <typename T> void launch_bn_bwd_reduce(const NormArgs& a, hipStream_t st) {
+  if (a.nseg == 0) return;
+  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(a.C / 64, a.L * a.nseg), dim3(256), 0, st, a);
+}
+template void launch_bn_bwd_reduce<float>(const NormArgs&, hipStream_t);
+template void launch_bn_bwd_reduce<bf16_t>(const NormArgs&, hipStream_t);
+
+// dgamma, dbeta: the segments' sums added in order.
+__global__ void bn_param_grad_kernel(NormArgs a) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= a.L * a.C) return;
+  const int l = idx / a.C, c = idx - l * a.C;
+  if (a.offs[l + 1] == a.offs[l]) return;
+  float db = 0.f, dg = 0.f;
+  for (int s = 0; s < a.nseg; ++s) {
+    const long long o = ((long long)((a.seg_first + s) * a.L + l) * a.C + c) * 2;
+    db += a.sums[o];
+    dg += a.sums[o + 1];
+  }
+  a.dbeta[(long long)l * a.pstride + c] = db;
+  a.dgamma[(long long)l * a.pstride + c] = dg;
+}
+void launch_bn_param_grad(const NormArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(bn_param_grad_kernel, dim3((a.L * a.C + 255) / 256), dim3(256), 0, st, a);
+}
+
+// dx = gamma * rstd * (g - sum_g / S - xhat * sum_gx / S)
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(NormArgs a) {
+  const int c4 = a.C / 4;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long rows_seg = (long long)a.n * a.rps;
+  if (idx >= rows_seg * c4 * a.nseg) return;
+  const long long row_all = idx / c4;
+  const int c = (int)(idx - row_all * c4) * 4;
+  const int sidx = (int)(row_all / rows_seg);
+  const long long row = row_all - (long long)sidx * rows_seg;
+  const int j = (int)(row / a.rps);
+  if (j >= a.offs[a.L]) return;
+  const int l = a.sample_model[j];
+  const int seg = a.seg_first + sidx;
+  const float invS = 1.0f / ((float)(a.offs[l + 1] - a.offs[l]) * (float)a.rps);
+  const long long e = (((long long)seg * a.seg_samples) * a.rps + row) * a.C + c;
+  const long long so = (long long)(seg * a.L + l) * a.C + c;
+  float v[4], d[4];
+  load4(static_cast<const T*>(a.x) + e, v);
+  load4(static_cast<const T*>(a.dy) + e, d);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const float rs = a.rstd[so + k];
+    const float ga = a.gamma[(long long)l * a.pstride + c + k];
+    const float xh = (v[k] - a.mean[so + k]) * rs;
+    const float u = ga * xh + a.beta[(long long)l * a.pstride + c + k];
+    const float gg = u > 0.f ? d[k] : d[k] * a.slope;
+    v[k] = ga * rs * (gg - a.sums[(so + k) * 2] * invS - xh * a.sums[(so + k) * 2 + 1] * invS);
+  }
+  store4(static_cast<T*>(a.y) + e, v);
+}
+template <typename T> void launch_bn_bwd_apply(const NormArgs& a, hipStream_t st) {
+  const long long tot = (long long)a.n * a.rps * (a.C / 4) * a.nseg;
+  if (tot == 0) return;
+  hipLaunchKernelGGL((bn_bwd_apply_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+}
+template void launch_bn_bwd_apply<float>(const NormArgs&, hipStream_t);
+template void launch_bn_bwd_apply<bf16_t>(const NormArgs&, hipStream_t);
+
+// ---------------------------------------------------------------------------------------------------------
+// D's linear head, the costs, and their gradients
+// ---------------------------------------------------------------------------------------------------------
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// one wave per row: logit = <feat[row], w[model]> + b[model]
+template <typename T>
+__global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long long wrow = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (wrow >= (long long)a.n * a.nseg) return;
+  const int sidx = (int)(wrow / a.n), j = (int)(wrow - (long long)sidx * a.n);
+  if (j >= a.offs[a.L]) return;
+  const int l = a.sample_model[j];
+  const long long r = (long long)(a.seg_first + sidx) * a.seg_samples + j;
+  const T* f = static_cast<const T*>(a.feat) + r * a.K;
+  const float* w = a.w + (long long)l * a.pstride;
+  float acc = 0.f;
+  for (int k = lane * 4; k < a.K; k += 256) {
+    float v[4];
+    load4(f + k, v);
+    const float4 ww = *reinterpret_cast<const float4*>(w + k);
+    acc += v[0] * ww.x + v[1] * ww.y + v[2] * ww.z + v[3] * ww.w;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) a.logits[r] = acc + a.b[(long long)l * a.pstride];
+}
+template <typename T> void launch_head_fwd(const HeadArgs& a, hipStream_t st) {
+  const long long rows = (long long)a.n * a.nseg;
+  if (rows == 0) return;
+  hipLaunchKernelGGL((head_fwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);
+}
+template void launch_head_fwd<float>(const HeadArgs&, hipStream_t);
+template void launch_head_fwd<bf16_t>(const HeadArgs&, hipStream_t);
+
+__device__ inline float softplus_f(float u) { return fmaxf(u, 0.f) + log1pf(expf(-fabsf(u))); }
+__device__ inline float sigmoid_f(float u) {
+  if (u >= 0.f) return 1.f / (1.f + expf(-u));
+  const float e = expf(u);
+  return e / (1.f + e);
+}
+
+// One block per model.  mode 0 (Eq. 3): J_D = scale*mean softplus(-s_real) + scale*mean softplus(s_fake),
+// segments (0, 1).  mode 1 (Eq. 4, negated): scale*mean softplus(-s_fake') on segment seg_first.
+__global__ __launch_bounds__(256) void loss_kernel(HeadArgs a) {
+  __shared__ float red[256];
+  const int l = blockIdx.x;
+  const int s0 = a.offs[l], cnt = a.offs[l + 1] - s0;
+  if (cnt == 0) { if (threadIdx.x == 0) a.loss[l] = 0.f; return; }
+  const float inv = 1.f / (float)cnt;
+  float acc = 0.f;
+  for (int s = 0; s < a.nseg; ++s) {
+    const int seg = a.seg_first + s;
+    const float sign = (a.mode == 0 && seg == 1) ? 1.f : -1.f;
+    for (int i = threadIdx.x; i < cnt; i += 256) {
+      const long long r = (long long)seg * a.seg_samples + s0 + i;
+      const float u = sign * a.logits[r];
+      acc += softplus_f(u);
+      a.dlogits[r] = a.scale * sign * sigmoid_f(u) * inv;
+    }
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) a.loss[l] = a.scale * red[0] * inv;
+}
+void launch_loss(const HeadArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(loss_kernel, dim3(a.L), dim3(256), 0, st, a);
+}
+
+// dfeat[row][k] = dlogit[row] * w[model][k]
+template <typename T>
+__global__ __launch_bounds__(256) void head_bwd_data_kernel(HeadArgs a) {
+  const int k4 = a.K / 4;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)a.n * a.nseg * k4) return;
+  const long long wrow = idx / k4;
+  const int k = (int)(idx - wrow * k4) * 4;
+  const int sidx = (int)(wrow / a.n), j = (int)(wrow - (long long)sidx * a.n);
+  if (j >= a.offs[a.L]) return;
+  const int l = a.sample_model[j];
+  const long long r = (long long)(a.seg_first + sidx) * a.seg_samples + j;
+  const float d = a.dlogits[r];
+  const float4 ww = *reinterpret_cast<const float4*>(a.w + (long long)l * a.pstride + k);
+  const float v[4] = {d * ww.x, d * ww.y, d * ww.z, d * ww.w};
+  store4(static_cast<T*>(a.dfeat) + r * a.K + k, v);
+}
+template <typename T> void launch_head_bwd_data(const HeadArgs& a, hipStream_t st) {
+  const long long tot = (long long)a.n * a.nseg * (a.K / 4);
+  if (tot == 0) return;
+  hipLaunchKernelGGL((head_bwd_data_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+}
+template void launch_head_bwd_data<float>(const HeadArgs&, hipStream_t);
+template void launch_head_bwd_data<bf16_t>(const HeadArgs&, hipStream_t);
+
+// dw[model][k] = sum_rows dlogit[row] * feat[row][k] ; db = sum_rows dlogit.  Block (k chunk of 1024, model).
+template <typename T>
+__global__ __launch_bounds__(256) void head_bwd_w_kernel(HeadArgs a) {
+  const int l = blockIdx.y;
+  const int s0 = a.offs[l], cnt = a.offs[l + 1] - s0;
+  if (cnt == 0) return;
+  const int k = blockIdx.x * 1024 + threadIdx.x * 4;
+  float acc[4] = {0, 0, 0, 0}, accb = 0.f;
+  for (int s = 0; s < a.nseg; ++s) {
+    const long long r0 = (long long)(a.seg_first + s) * a.seg_samples + s0;
+    for (int i = 0; i < cnt; ++i) {
+      const float d = a.dlogits[r0 + i];
+      accb += d;
+      if (k < a.K) {
+        float v[4];
+        load4(static_cast<const T*>(a.feat) + (r0 + i) * a.K + k, v);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += d * v[e];
+      }
+    }
+  }
+  if (k < a.K) *reinterpret_cast<float4*>(a.dw + (long long)l * a.pstride + k) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  if (blockIdx.x == 0 && threadIdx.x == 0) a.db[(long long)l * a.pstride] = accb;
+}
+template <typename T> void launch_head_bwd_w(const HeadArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((head_bwd_w_kernel<T>), dim3((a.K + 1023) / 1024, a.L), dim3(256), 0, st, a);
+}
+template void launch_head_bwd_w<float>(const HeadArgs&, hipStream_t);
+template void launch_head_bwd_w<bf16_t>(const HeadArgs&, hipStream_t);
+
+// ---------------------------------------------------------------------------------------------------------
+// Adam (bias-corrected, epsilon outside the root), all models and tensors of one network in one sweep
+// ---------------------------------------------------------------------------------------------------------
+
+__global__ void adam_prepare_kernel(AdamArgs a) {
+  const int l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= a.L) return;
+  if (a.counts[l] == 0) return;
+  const int t = a.t[l] + 1;
+  a.t[l] = t;
+  a.bc[2 * l] = (float)(1.0 - pow((double)a.beta1, (double)t));
+  a.bc[2 * l + 1] = (float)(1.0 - pow((double)a.beta2, (double)t));
+}
+
+__global__ __launch_bounds__(256) void adam_kernel(AdamArgs a) {
+  const int l = blockIdx.y;
+  if (a.counts[l] == 0) return;
+  const long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= a.P) return;
+  const long long o = (long long)l * a.P + i;
+  const float bc1 = a.bc[2 * l], bc2 = a.bc[2 * l + 1];
+  const float4 g = *reinterpret_cast<const float4*>(a.g + o);
+  float4 th = *reinterpret_cast<const float4*>(a.theta + o);
+  float4 m = *reinterpret_cast<const float4*>(a.m + o);
+  float4 v = *reinterpret_cast<const float4*>(a.v + o);
+  const float gg[4] = {g.x, g.y, g.z, g.w};
+  float tt[4] = {th.x, th.y, th.z, th.w}, mm[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    mm[e] = a.beta1 * mm[e] + (1.f - a.beta1) * gg[e];
+    vv[e] = a.beta2 * vv[e] + (1.f - a.beta2) * gg[e] * gg[e];
+    const float mh = mm[e] / bc1, vh = vv[e] / bc2;
+    tt[e] -= a.lr * mh / (sqrtf(vh) + a.eps);
+  }
+  *reinterpret_cast<float4*>(a.theta + o) = make_float4(tt[0], tt[1], tt[2], tt[3]);
+  *reinterpret_cast<float4*>(a.m + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+  *reinterpret_cast<float4*>(a.v + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+  if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
+}
+void launch_adam(const AdamArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(adam_prepare_kernel, dim3((a.L + 255) / 256), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((a.P / 4 + 255) / 256), a.L), dim3(256), 0, st, a);
+}
+
+template <typename T>
+__global__ void cast_shadow_kernel(const float* __restrict__ theta, T* __restrict__ shadow, long long total) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) shadow[i] = from_float<T>(theta[i]);
+}
+template <typename T> void launch_cast_shadow(const float* theta, T* shadow, long long total, hipStream_t st) {
+  if (total == 0) return;
+  hipLaunchKernelGGL((cast_shadow_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, theta, shadow, total);
+}
+template void launch_cast_shadow<bf16_t>(const float*, bf16_t*, long long, hipStream_t);
+template void launch_cast_shadow<float>(const float*, float*, long long, hipStream_t);
+
+// dst[tap][cs][cb] <- src[tap][cb][cs]; block = 32 x 32 tile, grid (tiles, 16 taps, L)
+template <typename T, typename S>
+__global__ void transpose_w_kernel(const S* __restrict__ src, T* __restrict__ dst, long long pstride, int Cb, int Cs) {
+  __shared__ float tile[32][33];
+  const int tb = Cb / 32;
+  const int tcs = blockIdx.x / tb, tcb = blockIdx.x - tcs * tb;
+  const long long base = (long long)blockIdx.z * pstride + (long long)blockIdx.y * Cb * Cs;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 256 threads: 8 rows per pass
+  for (int r = ty; r < 32; r += 8) {
+    const int cb = tcb * 32 + r, cs = tcs * 32 + tx;
+    tile[r][tx] = (cs < Cs) ? to_float(src[base + (long long)cb * Cs + cs]) : 0.f;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int cs = tcs * 32 + r, cb = tcb * 32 + tx;
+    if (cs < Cs) dst[base + (long long)cs * Cb + cb] = from_float<T>(tile[tx][r]);
+  }
+}
+template <typename T, typename S>
+void launch_transpose_w(const S* src, T* dst, long long pstride, int L, int Cb, int Cs, hipStream_t st) {
+  dim3 grid((Cb / 32) * ((Cs + 31) / 32), 16, L);
+  hipLaunchKernelGGL((transpose_w_kernel<T, S>), grid, dim3(256), 0, st, src, dst, pstride, Cb, Cs);
+}
+template void launch_transpose_w<float, float>(const float*, float*, long long, int, int, int, hipStream_t);
+template void launch_transpose_w<bf16_t, bf16_t>(const bf16_t*, bf16_t*, long long, int, int, int, hipStream_t);
+
+}  // namespace gan

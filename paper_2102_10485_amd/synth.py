@@ -24,8 +24,9 @@ SPECS = {
     "imagenet": dict(cond_g=0, cond_d=0, z_dim=100, img_c=3, img_hw=64, g_h0=4, g_ch=[512, 256, 128, 64],
                      d_ch=[64, 128, 256, 512]),
     # small nets for unit tests (channel counts that still span MFMA tiles)
-    "tiny": dict(cond_g=4, cond_d=4, z_dim=12, img_c=1, img_hw=8, g_h0=2, g_ch=[32, 32], d_ch=[32, 64]),
-    "tiny3": dict(cond_g=0, cond_d=3, z_dim=20, img_c=3, img_hw=16, g_h0=2, g_ch=[64, 32, 32], d_ch=[32, 64, 32]),
+    "tiny": dict(cond_g=4, cond_d=4, z_dim=12, img_c=1, img_hw=8, g_h0=2, g_ch=[64, 64], d_ch=[64, 128]),
+    "tiny3": dict(cond_g=0, cond_d=3, z_dim=20, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 64], d_ch=[64, 128, 64]),
+    "tiny0": dict(cond_g=0, cond_d=0, z_dim=20, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 128], d_ch=[128, 64, 64]),
     "micro": dict(cond_g=2, cond_d=2, z_dim=3, img_c=1, img_hw=4, g_h0=1, g_ch=[3, 2], d_ch=[2, 3]),
 }
 

@@ -1,0 +1,231 @@
+"""Whole-step parity of the HIP library against the CPU oracle on identical seeded inputs (GPU).
+
+Tolerances: fp32 storage 1e-4 relative, bf16 storage (fp32 master weights) 2e-2 relative, on the per-step costs
+and on the parameters; label routing is compared bit for bit.  Parameters are compared as relative L2 norms, per
+network (strict) and per tensor with the denominator floored at the initialisation scale 0.02 per element
+(tensors that start at zero move by about lr per step, so they carry no relative precision of their own).
+"""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2102_10485_amd import binding, synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+TOL = {binding.FP32: 1e-4, binding.BF16: 2e-2}
+
+
+class Pair:
+    """The HIP context and the oracle with identical parameters."""
+
+    def __init__(self, spec_name, n_models, n_labels, max_n, prec, seed=3, oracle_models=None):
+        torch = U.torch_mod()
+        self.torch = torch
+        self.spec = synth.SPECS[spec_name]
+        self.prec = prec
+        self.K = n_models
+        self.gpu = binding.Gan(binding.make_config(self.spec, n_models, n_labels, max_n, prec),
+                               torch.cuda.current_stream().cuda_stream)
+        self.orc = O.Oracle(self.spec, n_models, n_labels)
+        self.models = list(range(n_models)) if oracle_models is None else list(oracle_models)
+        for l in range(n_models):
+            rng = np.random.default_rng([seed, l])
+            for which in (0, 1):
+                assert self.gpu.param_count(which) == synth.param_count(self.spec, which) == self.orc.param_count(which)
+                p = synth.init_params(self.spec, which, rng)
+                self.gpu.set_params(which, l, p)
+                if l in self.models:
+                    self.orc.set_params(which, l, p)
+
+    def step(self, lab, z, x):
+        t = self.torch
+        self.keep = (t.from_numpy(np.ascontiguousarray(lab, np.int32)).cuda(),
+                     t.from_numpy(np.ascontiguousarray(z, np.float32)).cuda(),
+                     t.from_numpy(np.ascontiguousarray(x, np.float32)).cuda())
+        self.gpu.train_step(self.keep[0].data_ptr(), self.keep[1].data_ptr(), self.keep[2].data_ptr(), len(lab))
+        for l in self.models:
+            self.orc.train_step(lab, z.astype(np.float64), x.astype(np.float64), only_model=l)
+
+    def compare(self, what=""):
+        tol = TOL[self.prec]
+        jd, jg, cnt = self.gpu.get_losses()
+        ojd, ojg, ocnt = self.orc.get_losses()
+        assert np.array_equal(cnt, ocnt)
+        worst = 0.0
+        for l in self.models:
+            if ocnt[l] == 0:
+                assert jd[l] == 0 and jg[l] == 0
+                continue
+            assert abs(jd[l] - ojd[l]) <= tol * abs(ojd[l]), (what, "J_D", l, jd[l], ojd[l])
+            assert abs(jg[l] - ojg[l]) <= tol * abs(ojg[l]), (what, "J_G", l, jg[l], ojg[l])
+            for which in (0, 1):
+                got, ref = self.gpu.get_params(which, l), self.orc.get_params(which, l)
+                e = U.rel_l2(got, ref)
+                worst = max(worst, e)
+                assert e <= tol, (what, "params", which, l, e)
+                per = U.tensor_errors(self.spec, which, got, ref, 0.02)
+                bad = {k: v for k, v in per.items() if v > tol}
+                assert not bad, (what, which, l, bad)
+        return worst
+
+    def close(self):
+        self.gpu.close()
+        self.orc.close()
+
+
+def batch(spec, labels, seed):
+    rng = np.random.default_rng(seed)
+    n = len(labels)
+    z = rng.normal(size=(n, spec["z_dim"])).astype(np.float32)
+    x = np.tanh(rng.normal(size=(n, spec["img_c"], spec["img_hw"], spec["img_hw"]))).astype(np.float32)
+    return np.asarray(labels, np.int32), z, x
+
+
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+def test_first_step_gradients_and_routing(prec):
+    """One step, three ragged models: routing bit-exact, gradients of both networks, costs, parameters."""
+    p = Pair("tiny3", 3, 3, 64, prec)
+    lab = np.array([2, 0, 1, 1, 2, 0, 0, 2, 1, 2, 2, 0, 2, 2, 1, 2, 2, 2, 0, 2, 2], np.int32)
+    lab_, z, x = batch(p.spec, lab, 11)
+    p.step(lab_, z, x)
+    perm, offs = p.gpu.get_routing(len(lab))
+    operm, ooffs = p.orc.get_routing(len(lab))
+    assert np.array_equal(perm, operm) and np.array_equal(offs, ooffs)
+    tol = TOL[prec]
+    for l in range(3):
+        for which in (0, 1):
+            got, ref = p.gpu.get_grads(which, l), p.orc.get_grads(which, l)
+            per = {}
+            for name, (sl, shape) in synth.param_slices(p.spec, which).items():
+                per[name] = U.rel_l2(got[sl], ref[sl], floor=1e-3 * np.linalg.norm(ref))
+            bad = {k: v for k, v in per.items() if v > (10 * tol if prec == binding.FP32 else tol)}
+            assert not bad, (which, l, bad)
+    p.compare("step1")
+    p.close()
+
+
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+@pytest.mark.parametrize("spec_name,K,nlab", [("tiny", 1, 4), ("tiny", 4, 4), ("tiny0", 2, 2)])
+def test_three_steps(prec, spec_name, K, nlab):
+    """Mixed labels in one conditional pair, one pair per label, and an unconditional family; three iterations."""
+    p = Pair(spec_name, K, nlab, 80, prec)
+    rng = np.random.default_rng(5)
+    for s in range(3):
+        n = [37, 80, 52][s]
+        lab = rng.integers(0, nlab, n)
+        p.step(*batch(p.spec, lab, 100 + s))
+        p.compare("step %d" % s)
+    # BatchNorm running statistics after three updates each (three per step in D)
+    for l in range(K):
+        for which in (0, 1):
+            gm, gv = p.gpu.get_bn_running(which, l)
+            om, ov = p.orc.get_bn_running(which, l)
+            assert U.rel_l2(gm, om, floor=1e-2 * np.sqrt(om.size)) <= TOL[prec] * 5
+            assert U.rel_l2(gv, ov) <= TOL[prec] * 5
+        assert p.gpu.get_opt_state(0, l)[2] == p.orc.get_opt_state(0, l)[2] == 3
+    p.close()
+
+
+def test_empty_model_bad_label_and_empty_batch():
+    torch = U.torch_mod()
+    p = Pair("tiny", 4, 4, 32, binding.FP32)
+    before = [p.gpu.get_params(w, 1) for w in (0, 1)]
+    lab = np.array([0, 2, 2, 3, 0, 0, 2, 3, 3, 3], np.int32)     # model 1 receives nothing
+    p.step(*batch(p.spec, lab, 7))
+    p.compare("empty model")
+    for w in (0, 1):
+        assert np.array_equal(before[w], p.gpu.get_params(w, 1))
+        assert p.gpu.get_opt_state(w, 1)[2] == 0 and p.gpu.get_opt_state(w, 0)[2] == 1
+    # n = 0 is a no-op that reports zero counts
+    p.gpu.train_step(0, 0, 0, 0)
+    jd, jg, cnt = p.gpu.get_losses()
+    assert not cnt.any() and not jd.any()
+    # an out-of-range label is dropped, the rest of the step is exact, and the next query reports it once
+    lab2 = lab.copy()
+    lab2[4] = 9
+    lab_, z, x = batch(p.spec, lab2, 8)
+    p.step(lab_, z, x)
+    out = p.gpu.get_losses(check=False)
+    assert out[3] == binding.GAN_E_LABEL
+    assert p.gpu.get_losses(check=False)[3] == binding.GAN_OK
+    perm, offs = p.gpu.get_routing(len(lab2))
+    operm, ooffs = p.orc.get_routing(len(lab2))
+    assert np.array_equal(perm, operm) and np.array_equal(offs, ooffs)
+    p.compare("bad label")
+    # host-detectable argument errors have no side effects
+    with pytest.raises(binding.GanError):
+        p.gpu.train_step(p.keep[0].data_ptr(), p.keep[1].data_ptr(), p.keep[2].data_ptr(), 33)
+    with pytest.raises(binding.GanError):
+        p.gpu.train_step(0, p.keep[1].data_ptr(), p.keep[2].data_ptr(), 4)
+    p.close()
+
+
+def test_models_independent_and_deterministic_bitwise():
+    """Eq. 5: a model's numbers do not depend on what else is in the launch, nor on the run."""
+    torch = U.torch_mod()
+    spec = synth.SPECS["tiny"]
+    K = 4
+    rng = np.random.default_rng(21)
+    lab = rng.integers(0, K, 70).astype(np.int32)
+    steps = [batch(spec, lab, 300 + s) for s in range(2)]
+    results = []
+    for rep in range(2):
+        p = Pair("tiny", K, K, 80, binding.BF16, oracle_models=[])
+        for b in steps:
+            p.step(*b)
+        results.append([p.gpu.get_params(w, l) for l in range(K) for w in (0, 1)])
+        p.close()
+    for a, b in zip(*results):
+        assert np.array_equal(a, b)
+    # model 2 alone, in a context that holds all four models but sees only label 2's samples
+    p = Pair("tiny", K, K, 80, binding.BF16, oracle_models=[])
+    sel = np.flatnonzero(lab == 2)
+    for lab_, z, x in steps:
+        p.step(lab_[sel], z[sel], x[sel])
+    assert np.array_equal(p.gpu.get_params(0, 2), results[0][2 * 2])
+    assert np.array_equal(p.gpu.get_params(1, 2), results[0][2 * 2 + 1])
+    # permuting the flat batch changes only perm
+    q = Pair("tiny", K, K, 80, binding.BF16, oracle_models=[])
+    for lab_, z, x in steps:
+        order = np.concatenate([np.flatnonzero(lab_ == l)[::1] for l in (3, 1, 0, 2)])
+        q.step(lab_[order], z[order], x[order])
+    for l in range(K):
+        assert np.array_equal(q.gpu.get_params(0, l), results[0][2 * l])
+    p.close()
+    q.close()
+
+
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+def test_generate(prec):
+    torch = U.torch_mod()
+    p = Pair("tiny3", 3, 3, 40, prec)
+    lab = np.random.default_rng(2).integers(0, 3, 33).astype(np.int32)
+    lab_, z, x = batch(p.spec, lab, 55)
+    tol = TOL[prec]
+
+    def gen(running):
+        out = torch.zeros((33,) + (3, 16, 16), dtype=torch.float32, device="cuda")
+        dl, dz = torch.from_numpy(lab_).cuda(), torch.from_numpy(z).cuda()
+        p.gpu.generate(dl.data_ptr(), dz.data_ptr(), 33, out.data_ptr(), running)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    rc, ref = p.orc.generate(lab_, z)
+    assert U.rel_l2(gen(0), ref) <= tol
+    p.step(lab_, z, x)
+    rc, ref = p.orc.generate(lab_, z, use_running_stats=1)
+    assert U.rel_l2(gen(1), ref) <= tol * 2
+    p.close()
+
+
+def test_config0_five_steps_fp32():
+    """The 28x28x1 conditional pair, batch 64, one label, five iterations, fp32."""
+    w = synth.Workload(0)
+    p = Pair("mnist", 1, 10, 64, binding.FP32)
+    for s in range(5):
+        lab = w.labels(single_label=3)
+        p.step(lab, w.noise(), w.images(lab))
+        p.compare("config0 step %d" % s)
+    p.close()
