@@ -10,21 +10,25 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB = os.path.join(_HERE, "liboracle_f64.so")
+_LIBS = {np.float64: os.path.join(_HERE, "liboracle_f64.so"), np.float32: os.path.join(_HERE, "liboracle_f32.so")}
 MAX_LAYERS = 8
 
 
-def build(force=False):
-    """Compile gan_oracle.c (double precision, OpenMP) next to its source."""
+def build(force=False, real=None):
+    """Compile gan_oracle.c next to its source: the double-precision oracle, and the same loops in single
+    precision (used only to measure how far plain fp32 arithmetic drifts from the fp64 result)."""
     src = os.path.join(_HERE, "gan_oracle.c")
     hdr = os.path.join(_HERE, "gan_oracle.h")
-    if (not force and os.path.exists(_LIB)
-            and os.path.getmtime(_LIB) >= max(os.path.getmtime(src), os.path.getmtime(hdr))):
-        return _LIB
-    cmd = ["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-o", _LIB, src, "-lm"]
-    subprocess.check_call(cmd)
-    return _LIB
+    for dt, path in _LIBS.items():
+        if real is not None and dt is not real:
+            continue
+        if (not force and os.path.exists(path)
+                and os.path.getmtime(path) >= max(os.path.getmtime(src), os.path.getmtime(hdr))):
+            continue
+        cmd = ["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-DORACLE_REAL=" + ("double" if dt is np.float64 else "float"), "-o", path, src, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIBS[np.float64]
 
 
 class Config(C.Structure):
@@ -41,27 +45,27 @@ class Config(C.Structure):
     ]
 
 
-_lib = None
-_D = C.POINTER(C.c_double)
+_loaded = {}
 _I = C.POINTER(C.c_int32)
 
 
-def lib():
-    global _lib
-    if _lib is None:
-        build()
-        _lib = C.CDLL(_LIB)
+def lib(real=np.float64):
+    if real not in _loaded:
+        build(real=real)
+        _lib = C.CDLL(_LIBS[real])
+        creal = C.c_double if real is np.float64 else C.c_float
+        _D = C.POINTER(creal)
         _lib.oracle_param_count.restype = C.c_int64
         _lib.oracle_bn_count.restype = C.c_int64
-        _lib.oracle_logistic_loss.restype = C.c_double
-        _lib.oracle_logistic_loss.argtypes = [_D, C.c_int, C.c_int, C.c_double, _D]
-        _lib.oracle_adam.argtypes = [_D, _D, _D, _D, C.c_int64, C.c_int64] + [C.c_double] * 4
-        _lib.oracle_bn_train.argtypes = [_D, _D, _D, C.c_double, _D, _D, _D, C.c_int, C.c_int, C.c_int]
-        _lib.oracle_bn_eval.argtypes = [_D, _D, _D, C.c_double, _D, _D, _D, C.c_int, C.c_int, C.c_int]
-        _lib.oracle_bn_bwd.argtypes = [_D, _D, _D, _D, C.c_double, _D, _D, _D, _D, C.c_int, C.c_int, C.c_int]
-        _lib.oracle_bn_running_update.argtypes = [_D, _D, _D, _D, C.c_double, C.c_int, C.c_int64]
-        _lib.oracle_leaky_relu.argtypes = [_D, _D, C.c_int64, C.c_double]
-        _lib.oracle_leaky_relu_bwd.argtypes = [_D, _D, _D, C.c_int64, C.c_double]
+        _lib.oracle_logistic_loss.restype = creal
+        _lib.oracle_logistic_loss.argtypes = [_D, C.c_int, C.c_int, creal, _D]
+        _lib.oracle_adam.argtypes = [_D, _D, _D, _D, C.c_int64, C.c_int64] + [creal] * 4
+        _lib.oracle_bn_train.argtypes = [_D, _D, _D, creal, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_bn_eval.argtypes = [_D, _D, _D, creal, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_bn_bwd.argtypes = [_D, _D, _D, _D, creal, _D, _D, _D, _D, C.c_int, C.c_int, C.c_int]
+        _lib.oracle_bn_running_update.argtypes = [_D, _D, _D, _D, creal, C.c_int, C.c_int64]
+        _lib.oracle_leaky_relu.argtypes = [_D, _D, C.c_int64, creal]
+        _lib.oracle_leaky_relu_bwd.argtypes = [_D, _D, _D, C.c_int64, creal]
         _lib.oracle_tanh.argtypes = [_D, _D, C.c_int64]
         _lib.oracle_tanh_bwd.argtypes = [_D, _D, _D, C.c_int64]
         conv_args = [_D, _D, _D, _D] + [C.c_int] * 8
@@ -88,11 +92,14 @@ def lib():
         _lib.oracle_get_routing.argtypes = [C.c_void_p, _I, _I]
         _lib.oracle_eval_losses.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
         _lib.oracle_eval_grads.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
-    return _lib
+        _loaded[real] = _lib
+    return _loaded[real]
 
 
 def _d(a):
-    return None if a is None else a.ctypes.data_as(_D)
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.POINTER(C.c_double if a.dtype == np.float64 else C.c_float))
 
 
 def _i(a):
@@ -125,10 +132,13 @@ def make_config(spec, n_models, n_labels, hyper=None):
 
 
 class Oracle:
-    def __init__(self, spec, n_models, n_labels, hyper=None):
+    def __init__(self, spec, n_models, n_labels, hyper=None, real=np.float64):
+        """real=np.float64 is the oracle; np.float32 runs the same loops in single precision."""
+        self.real = real
+        self.L = lib(real)
         self.cfg = make_config(spec, n_models, n_labels, hyper)
         self.h = C.c_void_p()
-        rc = lib().oracle_create(C.byref(self.cfg), C.byref(self.h))
+        rc = self.L.oracle_create(C.byref(self.cfg), C.byref(self.h))
         if rc != 0:
             raise ValueError("oracle_create failed: %d" % rc)
         self.n_models = n_models
@@ -136,7 +146,7 @@ class Oracle:
 
     def close(self):
         if self.h:
-            lib().oracle_destroy(self.h)
+            self.L.oracle_destroy(self.h)
             self.h = C.c_void_p()
 
     def __del__(self):
@@ -146,76 +156,76 @@ class Oracle:
             pass
 
     def param_count(self, which):
-        return int(lib().oracle_param_count(self.h, which))
+        return int(self.L.oracle_param_count(self.h, which))
 
     def bn_count(self, which):
-        return int(lib().oracle_bn_count(self.h, which))
+        return int(self.L.oracle_bn_count(self.h, which))
 
     def get_params(self, which, model):
-        out = np.empty(self.param_count(which), np.float64)
-        assert lib().oracle_get_params(self.h, which, model, _d(out)) == 0
+        out = np.empty(self.param_count(which), self.real)
+        assert self.L.oracle_get_params(self.h, which, model, _d(out)) == 0
         return out
 
     def set_params(self, which, model, src):
-        src = _f64(src)
+        src = np.ascontiguousarray(src, self.real)
         assert src.size == self.param_count(which)
-        assert lib().oracle_set_params(self.h, which, model, _d(src)) == 0
+        assert self.L.oracle_set_params(self.h, which, model, _d(src)) == 0
 
     def get_grads(self, which, model):
-        out = np.empty(self.param_count(which), np.float64)
-        assert lib().oracle_get_grads(self.h, which, model, _d(out)) == 0
+        out = np.empty(self.param_count(which), self.real)
+        assert self.L.oracle_get_grads(self.h, which, model, _d(out)) == 0
         return out
 
     def get_opt_state(self, which, model):
         P = self.param_count(which)
-        m, v, t = np.empty(P), np.empty(P), C.c_int64()
-        assert lib().oracle_get_opt_state(self.h, which, model, _d(m), _d(v), C.byref(t)) == 0
+        m, v, t = np.empty(P, self.real), np.empty(P, self.real), C.c_int64()
+        assert self.L.oracle_get_opt_state(self.h, which, model, _d(m), _d(v), C.byref(t)) == 0
         return m, v, t.value
 
     def get_bn_running(self, which, model):
         B = self.bn_count(which)
-        m, v = np.empty(B), np.empty(B)
-        assert lib().oracle_get_bn_running(self.h, which, model, _d(m), _d(v)) == 0
+        m, v = np.empty(B, self.real), np.empty(B, self.real)
+        assert self.L.oracle_get_bn_running(self.h, which, model, _d(m), _d(v)) == 0
         return m, v
 
     def train_step(self, label_ids, noise, real, only_model=-1):
         label_ids = np.ascontiguousarray(label_ids, np.int32)
-        noise, real = _f64(noise), _f64(real)
+        noise, real = np.ascontiguousarray(noise, self.real), np.ascontiguousarray(real, self.real)
         n = label_ids.size
-        return lib().oracle_train_step(self.h, _i(label_ids), _d(noise), _d(real), n, only_model)
+        return self.L.oracle_train_step(self.h, _i(label_ids), _d(noise), _d(real), n, only_model)
 
     def generate(self, label_ids, noise, use_running_stats=0, only_model=-1):
         label_ids = np.ascontiguousarray(label_ids, np.int32)
-        noise = _f64(noise)
+        noise = np.ascontiguousarray(noise, self.real)
         n = label_ids.size
-        out = np.zeros((n,) + self.img_shape, np.float64)
-        rc = lib().oracle_generate(self.h, _i(label_ids), _d(noise), n, _d(out), use_running_stats, only_model)
+        out = np.zeros((n,) + self.img_shape, self.real)
+        rc = self.L.oracle_generate(self.h, _i(label_ids), _d(noise), n, _d(out), use_running_stats, only_model)
         return rc, out
 
     def get_losses(self):
         K = self.n_models
-        jd, jg, cnt = np.empty(K), np.empty(K), np.empty(K, np.int32)
-        lib().oracle_get_losses(self.h, _d(jd), _d(jg), _i(cnt))
+        jd, jg, cnt = np.empty(K, self.real), np.empty(K, self.real), np.empty(K, np.int32)
+        self.L.oracle_get_losses(self.h, _d(jd), _d(jg), _i(cnt))
         return jd, jg, cnt
 
     def get_routing(self, n):
         perm, offs = np.empty(n, np.int32), np.empty(self.n_models + 1, np.int32)
-        lib().oracle_get_routing(self.h, _i(perm), _i(offs))
+        self.L.oracle_get_routing(self.h, _i(perm), _i(offs))
         return perm, offs
 
     def eval_losses(self, model, label_ids, noise, real):
         label_ids = np.ascontiguousarray(label_ids, np.int32)
-        noise, real = _f64(noise), _f64(real)
-        jd, jg = C.c_double(), C.c_double()
-        lib().oracle_eval_losses(self.h, model, _i(label_ids), _d(noise), _d(real), label_ids.size,
-                                 C.byref(jd), C.byref(jg))
-        return jd.value, jg.value
+        noise, real = np.ascontiguousarray(noise, self.real), np.ascontiguousarray(real, self.real)
+        jd, jg = np.empty(1, self.real), np.empty(1, self.real)
+        self.L.oracle_eval_losses(self.h, model, _i(label_ids), _d(noise), _d(real), label_ids.size,
+                                 _d(jd), _d(jg))
+        return float(jd[0]), float(jg[0])
 
     def eval_grads(self, model, label_ids, noise, real):
         label_ids = np.ascontiguousarray(label_ids, np.int32)
-        noise, real = _f64(noise), _f64(real)
-        gD, gG = np.empty(self.param_count(1)), np.empty(self.param_count(0))
-        lib().oracle_eval_grads(self.h, model, _i(label_ids), _d(noise), _d(real), label_ids.size, _d(gD), _d(gG))
+        noise, real = np.ascontiguousarray(noise, self.real), np.ascontiguousarray(real, self.real)
+        gD, gG = np.empty(self.param_count(1), self.real), np.empty(self.param_count(0), self.real)
+        self.L.oracle_eval_grads(self.h, model, _i(label_ids), _d(noise), _d(real), label_ids.size, _d(gD), _d(gG))
         return gD, gG
 
 

@@ -220,3 +220,27 @@ def test_whole_step_against_autograd_library():
         flat = orc.get_params(which, 0)
         for k, (s, shape) in sl.items():
             np.testing.assert_allclose(flat[s].reshape(shape), p[k].detach().numpy(), rtol=1e-7, atol=1e-9, err_msg=k)
+
+
+def test_single_precision_build_runs_the_same_algorithm():
+    """The oracle's loops compiled with a 32-bit real agree with the 64-bit oracle to rounding on the first
+    iteration (same algorithm), and the printed drift of later iterations documents how quickly rounding is
+    amplified by the iteration itself (the reason the fp32 parity bound widens from the second iteration on)."""
+    spec = synth.SPECS["tiny"]
+    a, b = O.Oracle(spec, 1, 4), O.Oracle(spec, 1, 4, real=np.float32)
+    rng = np.random.default_rng(8)
+    for which in (0, 1):
+        p = synth.init_params(spec, which, rng)
+        a.set_params(which, 0, p)
+        b.set_params(which, 0, p)
+    drift = []
+    for s in range(4):
+        lab, z, x = batch(spec, [0, 3, 1, 2, 2, 1, 0, 3] * 4, seed=60 + s)
+        z, x = z.astype(np.float32), x.astype(np.float32)
+        a.train_step(lab, z, x)
+        b.train_step(lab, z, x)
+        e = max(np.linalg.norm(b.get_params(w, 0) - a.get_params(w, 0)) / np.linalg.norm(a.get_params(w, 0)) for w in (0, 1))
+        drift.append(e)
+    assert drift[0] < 1e-5
+    assert abs(b.get_losses()[0][0] - a.get_losses()[0][0]) < 1e-2
+    print("single-precision drift per iteration:", drift)
