@@ -1,0 +1,135 @@
+"""Benchmark of the grouped per-label DC-CGAN training step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: route by label, G forward, D forward on real
+and fake, the discriminator cost and backward, Adam on D, D again on the fake batch, the generator cost, backward
+through D and G, Adam on G -- for every label model at once.  Inputs are resident in HBM before the timed region.
+Prints one JSON line.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+PEAK = {"mfma_bf16": 2500.0, "mfma_fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s (published MI355X figures)
+
+DESCR = {
+    0: "config 0: one conditional pair, 28x28x1, batch 64, fp32",
+    1: "config 1: 10 label models, 28x28x1, batch 128 per label",
+    2: "config 2: 100 label models, 32x32x3, batch 64 per label",
+    3: "config 3: 8 label models (one GPU's share of 1000), 64x64x3, batch 128 per label",
+    4: "config 4: 100 label models, 32x32x3, rank-Zipf batch sizes in [16, 256], 6400 images",
+}
+
+
+def cpu_baseline(work, budget_models=1):
+    """The oracle as it stands, on the host cores, for one step of a bounded sample of the same workload."""
+    import oracle as O
+    spec = work.spec
+    orc = O.Oracle(spec, work.n_models, work.n_labels)
+    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
+    x = work.images(lab)
+    z = work.noise()
+    models = list(range(min(budget_models, work.n_models)))
+    t0 = time.perf_counter()
+    images = 0
+    for l in models:
+        orc.train_step(lab, z, x, only_model=l)
+        images += int(orc.get_losses()[2][l])
+    dt = time.perf_counter() - t0
+    orc.close()
+    return {"value": images / dt, "unit": "images/s", "cores": O.threads(), "kind": "oracle",
+            "sample": "1 step of %d of %d label models (%d images) in %.1f s, fp64 direct loops"
+                      % (len(models), work.n_models, images, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload 0-4 (default: 2, the largest)")
+    ap.add_argument("--precision", choices=["fp32", "bf16"], default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not time individual kernels (no roofline object)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the label models shard with no per-step traffic; "
+                 "see DESIGN.md); run with --gpus 1")
+
+    import torch
+    from paper_2102_10485_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP library has no CPU fallback")
+    torch.cuda.set_device(0)
+    work = synth.Workload(args.config)
+    prec_name = args.precision or work.precision
+    prec = binding.BF16 if prec_name == "bf16" else binding.FP32
+    n = work.n
+    cfg = binding.make_config(work.spec, work.n_models, work.n_labels, n, prec, seed=work.seed)
+    gan = binding.Gan(cfg, torch.cuda.current_stream().cuda_stream)
+
+    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
+    d_lab = torch.from_numpy(lab).cuda()
+    d_real = torch.from_numpy(work.images(lab)).cuda()
+    d_noise = [torch.from_numpy(work.noise()).cuda() for _ in range(4)]
+    torch.cuda.synchronize()
+
+    def step(i):
+        gan.train_step(d_lab.data_ptr(), d_noise[i % 4].data_ptr(), d_real.data_ptr(), n)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        gan.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    jd, jg, cnt = gan.get_losses()
+    assert np.all(np.isfinite(jd)) and np.all(np.isfinite(jg)) and int(cnt.sum()) == n
+
+    out = {
+        "metric": "training images/sec (G+D step, all labels)", "value": n * args.steps / dt, "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": prec_name, "data": "synthetic",
+        "config": {"workload": DESCR[args.config] + (", %s" % prec_name), "n_models": work.n_models, "images_per_step": n,
+                   "batch_sizes": "min %d / median %d / max %d" % (work.batch_sizes.min(), np.median(work.batch_sizes),
+                                                                  work.batch_sizes.max())},
+    }
+    if not args.no_profile:
+        prof = gan.profile_read()
+        gan.profile_enable(False)
+        kern = {}
+        for name, r in prof.items():
+            per = r["ms"] / max(r["launches"], 1)
+            kern[name] = {"launches_per_step": r["launches"] / args.steps, "ms_per_step": r["ms"] / args.steps,
+                          "avg_launch_ms": per,
+                          "tflops": r["flops"] / (r["ms"] * 1e9) if r["ms"] > 0 else 0.0,
+                          "gbps": r["bytes"] / (r["ms"] * 1e6) if r["ms"] > 0 else 0.0}
+        gemm = [k for k in kern if k.startswith("gemm_")]
+        dom = max(gemm, key=lambda k: kern[k]["ms_per_step"])
+        peak = PEAK["mfma_bf16"] if prec_name == "bf16" else PEAK["mfma_fp32"]
+        out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": kern[dom]["tflops"], "peak": peak,
+                           "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / peak, "traffic": None,
+                           "avg_launch_ms": kern[dom]["avg_launch_ms"]}
+        gemm_ms = sum(kern[k]["ms_per_step"] for k in gemm)
+        gemm_fl = sum(prof[k]["flops"] for k in gemm) / args.steps
+        out["conv_mfma"] = {"tflops": gemm_fl / (gemm_ms * 1e9), "frac_of_peak": gemm_fl / (gemm_ms * 1e9) / peak,
+                            "ms_per_step": gemm_ms}
+        out["kernels"] = {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(kern.items(),
+                                                                                        key=lambda kv: -kv[1]["ms_per_step"])}
+        out["kernel_ms_sum"] = sum(v["ms_per_step"] for v in kern.values())
+    gan.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(synth.Workload(args.config))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

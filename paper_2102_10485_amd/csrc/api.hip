@@ -61,7 +61,10 @@ struct gan_ctx {
   std::vector<void*> gpre, gact, dpre, dact;
   std::vector<float*> g_mean, g_var, g_rstd, g_sums, d_mean, d_var, d_rstd, d_sums;
   float *logits = nullptr, *dlogits = nullptr, *loss_d = nullptr, *loss_g = nullptr;
-  float *lm_table = nullptr, *lm_rsum = nullptr, *partial = nullptr;
+  // image-side layers: patch matrices, packed weights, packed weight gradients
+  void *colD = nullptr, *colG = nullptr, *wpD = nullptr, *wpG = nullptr;
+  float *dwp = nullptr, *bias_partial = nullptr;
+  int KcD = 0, KcG = 0;
   int nslot = 1;
   int last_n = -1;
   bool shadows_dirty = true;
@@ -276,8 +279,13 @@ void builtin_init(gan_ctx* c) {
 }
 
 // ---- storage-type copies of the weights ------------------------------------------------------------------
+PackArgs pack_args(gan_ctx* c, Net& net, const ConvLayer& cl, int Kc, int nslot, void* wp);
+
 template <typename T>
 void refresh_transposes(gan_ctx* c, Net& n, bool isG) {
+  // the image-side layer multiplies a patch matrix: [cs][Kc] with the label-map sums and the bias folded in
+  if (isG) launch_pack_w<T>(pack_args(c, n, n.conv.back(), c->KcG, 0, c->wpG), c->st);
+  else launch_pack_w<T>(pack_args(c, n, n.conv.front(), c->KcD, c->nslot, c->wpD), c->st);
   // layers run by the GEMM engine in "down" form need [tap][cs][cb]
   for (size_t i = 0; i < n.conv.size(); ++i) {
     const ConvLayer& cl = n.conv[i];
@@ -301,9 +309,10 @@ void refresh_shadows(gan_ctx* c) {
 // ---- launch helpers ---------------------------------------------------------------------------------------
 template <typename T>
 void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, const void* W, long long wstride, void* Out,
-               const void* Aux, int C, int N, int Hin, int Hr, int seg_first, int nseg, int n) {
-  ConvArgs a;
-  a.A = A; a.W = W; a.Out = Out; a.Aux = Aux;
+               const void* Aux, int C, int N, int Hin, int Hr, int seg_first, int nseg, int n, int w_nstride = 0,
+               const float* bias = nullptr, long long bias_stride = 0, double flops_alg = -1.0) {
+  ConvArgs a = {};
+  a.A = A; a.W = W; a.Out = Out; a.Aux = Aux; a.bias = bias; a.bias_stride = bias_stride; a.w_nstride = w_nstride ? w_nstride : N;
   a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, conv_tile_m());
   a.w_stride = wstride; a.L = c->L; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n;
   a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr; a.ub_tiles = ub_tiles(c, n, Hr * Hr, conv_tile_m());
@@ -312,24 +321,24 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
   const int phases = mode == MODE_UP ? 4 : 1;
   const double rows = (double)n * nseg * Hr * Hr * phases;
   const double frac = mode == MODE_DENSE ? 1.0 : valid_tap_fraction(Hr);
-  const double flops = 2.0 * rows * N * C * ntaps * frac;
-  const double bytes = sizeof(T) * ((double)n * nseg * Hin * Hin * C + rows * N + (double)c->L * 16 * C * N /
-                                    (mode == MODE_DENSE ? 16 : 1));
+  const double flops = flops_alg >= 0 ? flops_alg : 2.0 * rows * N * C * ntaps * frac;
+  const double in_elems = mode == MODE_DENSE ? rows * C : (double)n * nseg * Hin * Hin * C;
+  const double bytes = sizeof(T) * (in_elems + rows * N + (double)c->L * (mode == MODE_DENSE ? 1 : 16) * C * N);
   Scope s(c, name, flops, bytes);
   launch_conv<T>(mode, epi, a, c->st);
 }
 
 template <typename T>
 void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small, float* dW, long long stride, int Cb, int Cs,
-                int Hs, int ntaps, int nseg, int n) {
-  WgradArgs a;
+                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0) {
+  WgradArgs a = {};
   a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.dw_stride = stride;
   a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps;
   const double rows = (double)n * nseg * Hs * Hs;
   const double frac = ntaps == 1 ? 1.0 : valid_tap_fraction(Hs);
-  const int Hb = ntaps == 1 ? 1 : 2 * Hs;
-  const double bytes = sizeof(T) * ((double)n * nseg * Hb * Hb * Cb + rows * Cs) + 4.0 * c->L * ntaps * Cb * Cs;
-  Scope s(c, name, 2.0 * rows * Cb * Cs * ntaps * frac, bytes);
+  const double big_elems = ntaps == 1 ? rows * Cb : (double)n * nseg * 4 * Hs * Hs * Cb;
+  const double bytes = sizeof(T) * (big_elems + rows * Cs) + 4.0 * c->L * ntaps * Cb * Cs;
+  Scope s(c, name, flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes);
   launch_wgrad<T>(a, c->st);
 }
 
@@ -374,22 +383,30 @@ void bn_backward(gan_ctx* c, NormArgs a, const void* x, const void* dy, void* dx
   launch_bn_bwd_apply<T>(a, c->st);
 }
 
-SkinnyArgs skinny_args(gan_ctx* c, Net& net, const ConvLayer& cl, int tile_rows, int seg_first, int nseg, int n) {
-  SkinnyArgs a;
-  memset(&a, 0, sizeof(a));
-  a.w = net.theta + cl.w; a.pstride = net.P;
-  a.offs = c->rb.offs; a.tpre = tpre_of(c, cl.Hs * cl.Hs, tile_rows);
-  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Hs = cl.Hs;
-  a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n; a.ub_tiles = ub_tiles(c, n, cl.Hs * cl.Hs, tile_rows);
-  a.slope = c->cfg.leaky_slope; a.sample_slot = c->rb.sample_slot; a.nslot = c->nslot;
-  return a;
-}
-
-double skinny_flops(const ConvLayer& cl, int n, int nseg) {
+double img_flops(const ConvLayer& cl, int n, int nseg) {
   return 2.0 * n * nseg * cl.Hs * cl.Hs * 16 * cl.Cb * cl.Cs * valid_tap_fraction(cl.Hs);
 }
-template <typename T> double skinny_bytes(const ConvLayer& cl, int n, int nseg) {
-  return sizeof(T) * (double)n * nseg * cl.Hs * cl.Hs * (cl.Cs + 4.0 * cl.Cb);
+
+// Patch matrix of an image-side tensor (or of the caller's real batch when img == NULL).
+template <typename T>
+void im2col_call(gan_ctx* c, const ConvLayer& cl, const void* img, const float* real, void* out, int Kc, int nslot, int seg, int n) {
+  Im2colArgs a;
+  memset(&a, 0, sizeof(a));
+  a.img = img; a.real = real; a.perm = c->rb.perm; a.out = out; a.offs = c->rb.offs; a.sample_slot = c->rb.sample_slot;
+  a.L = c->L; a.n = n; a.CB = cl.Cb; a.Hs = cl.Hs; a.Kc = Kc; a.nslot = nslot; a.seg = seg; a.seg_samples = n;
+  const double rows = (double)n * cl.Hs * cl.Hs;
+  Scope s(c, "im2col", 0, rows * (4.0 * cl.Cb * (real ? 4 : sizeof(T)) + (double)Kc * sizeof(T)));
+  launch_im2col<T>(a, c->st);
+}
+
+PackArgs pack_args(gan_ctx* c, Net& net, const ConvLayer& cl, int Kc, int nslot, void* wp) {
+  PackArgs a;
+  memset(&a, 0, sizeof(a));
+  a.w = net.theta + cl.w; a.bias = (nslot > 0 && cl.bias >= 0) ? net.theta + cl.bias : nullptr;
+  a.dw = net.g + cl.w; a.dbias = (nslot > 0 && cl.bias >= 0) ? net.g + cl.bias : nullptr;
+  a.pstride = net.P; a.wp = wp; a.dwp = c->dwp;
+  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Kc = Kc; a.nslot = nslot;
+  return a;
 }
 
 // ---- the networks -------------------------------------------------------------------------------------------
@@ -411,34 +428,21 @@ void g_forward(gan_ctx* c, int n, bool use_running, bool update_running) {
                                   c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, relu),
                   c->gpre[i + 1], c->gact[i + 1], use_running, update_running);
   }
+  // last transposed conv (+bias, tanh) straight into the fake half of D's image buffer
   const ConvLayer& cl = G.conv[nl - 1];
-  SkinnyArgs a = skinny_args(c, G, cl, SKINNY_UP_ROWS, 0, 1, n);
-  a.feat = c->gact[nl - 1];
-  a.out = (T*)c->xd + (long long)n * 4 * cl.Hs * cl.Hs * cl.Cb;     // the fake half of D's input
-  a.bias = G.theta + cl.bias; a.tanh_out = 1;
-  Scope s(c, "skinny_up", skinny_flops(cl, n, 1), skinny_bytes<T>(cl, n, 1));
-  launch_skinny_up<T>(a, c->st);
+  T* fake = (T*)c->xd + (long long)n * 4 * cl.Hs * cl.Hs * cl.Cb;
+  conv_call<T>(c, "gemm_up_img", MODE_UP, EPI_BIAS_TANH, c->gact[nl - 1], (const T*)G.shadow_u + cl.w, G.P, fake, nullptr, cl.Cs,
+               cl.Cb, cl.Hs, cl.Hs, 0, 1, n, cl.CBT, G.theta + cl.bias, G.P);
 }
 
 template <typename T>
 void d_forward(gan_ctx* c, int n, int seg_first, int nseg, bool update_running) {
   Net& D = c->D;
   const float slope = c->cfg.leaky_slope;
+  // first conv (+label maps, bias, LeakyReLU) as a row-by-row GEMM over the patch matrix
   const ConvLayer& c1 = D.conv[0];
-  LabelMapArgs lm;
-  memset(&lm, 0, sizeof(lm));
-  if (c->cfg.cond_d > 0) {
-    lm.w = D.theta + c1.w; lm.pstride = D.P; lm.table = c->lm_table; lm.L = c->L; lm.nslot = c->nslot;
-    lm.CB = c1.Cb; lm.CBT = c1.CBT; lm.Cs = c1.Cs; lm.Hs = c1.Hs;
-    launch_labelmap_table(lm, c->st);
-  }
-  {
-    SkinnyArgs a = skinny_args(c, D, c1, SKINNY_DOWN_ROWS, seg_first, nseg, n);
-    a.img = c->xd; a.out = c->dact[0]; a.bias = D.theta + c1.bias;
-    a.table = c->cfg.cond_d > 0 ? c->lm_table : nullptr; a.lrelu = 1;
-    Scope s(c, "skinny_down", skinny_flops(c1, n, nseg), skinny_bytes<T>(c1, n, nseg));
-    launch_skinny_down<T>(a, c->st);
-  }
+  conv_call<T>(c, "gemm_dense_img", MODE_DENSE, EPI_LRELU, c->colD, c->wpD, (long long)c1.Cs * c->KcD, c->dact[0], nullptr, c->KcD,
+               c1.Cs, 1, c1.Hs, seg_first, nseg, n, 0, nullptr, 0, img_flops(c1, n, nseg));
   const int nl = (int)D.conv.size();
   for (int j = 1; j < nl; ++j) {
     const ConvLayer& cl = D.conv[j];
@@ -495,26 +499,14 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
   }
   const ConvLayer& c1 = D.conv[0];
   if (param_grads) {
-    {
-      SkinnyArgs a = skinny_args(c, D, c1, SKINNY_WGRAD_ROWS, 0, nseg, n);
-      a.img = c->xd; a.feat = c->bufA; a.partial = c->partial; a.dw = D.g + c1.w;
-      Scope s(c, "skinny_wgrad", skinny_flops(c1, n, nseg), skinny_bytes<T>(c1, n, nseg));
-      launch_skinny_wgrad<T>(a, c->st);
-    }
-    LabelMapArgs lm;
-    memset(&lm, 0, sizeof(lm));
-    lm.w = D.theta + c1.w; lm.dw = D.g + c1.w; lm.dbias = D.g + c1.bias; lm.pstride = D.P; lm.rsum = c->lm_rsum;
-    lm.dfeat = c->bufA; lm.offs = c->rb.offs; lm.sample_slot = c->rb.sample_slot;
-    lm.L = c->L; lm.nslot = c->nslot; lm.CB = c1.Cb; lm.CBT = c1.CBT; lm.Cs = c1.Cs; lm.Hs = c1.Hs; lm.nseg = nseg; lm.seg_samples = n;
-    { Scope s(c, "labelmap_reduce", 0, sizeof(T) * (double)n * nseg * c1.Hs * c1.Hs * c1.Cs); launch_labelmap_reduce<T>(lm, c->st); }
-    launch_labelmap_grads(lm, c->st);
+    // taps, label-map class sums and the bias gradient in one GEMM over the patch matrix
+    wgrad_call<T>(c, "gemm_wgrad_img", c->colD, c->bufA, c->dwp, (long long)c->KcD * c1.Cs, c->KcD, c1.Cs, c1.Hs, 1, nseg, n,
+                  img_flops(c1, n, nseg));
+    launch_unpack_dw(pack_args(c, D, c1, c->KcD, c->nslot, c->wpD), c->st);
   }
-  if (to_image) {
-    SkinnyArgs a = skinny_args(c, D, c1, SKINNY_UP_ROWS, seg_first, nseg, n);
-    a.feat = c->bufA; a.out = c->dimg; a.aux = c->xd; a.tanh_out = 2;
-    Scope s(c, "skinny_up", skinny_flops(c1, n, nseg), skinny_bytes<T>(c1, n, nseg));
-    launch_skinny_up<T>(a, c->st);
-  }
+  if (to_image)   // d cost / d fake, times the tanh derivative
+    conv_call<T>(c, "gemm_up_img", MODE_UP, EPI_TANH_BWD, c->bufA, (const T*)D.shadow_u + c1.w, D.P, c->dimg, c->xd, c1.Cs, c1.Cb,
+                 c1.Hs, c1.Hs, seg_first, nseg, n, c1.CBT);
 }
 
 // Backward through G from dimg (fake segment) = d cost / d (pre-tanh output).
@@ -525,14 +517,16 @@ void g_backward(gan_ctx* c, int n) {
   const ConvLayer& last = G.conv[nl - 1];
   const T* dlast = (const T*)c->dimg + (long long)n * 4 * last.Hs * last.Hs * last.Cb;
   {
-    SkinnyArgs a = skinny_args(c, G, last, SKINNY_WGRAD_ROWS, 0, 1, n);
-    a.img = dlast; a.feat = c->gact[nl - 1]; a.partial = c->partial; a.dw = G.g + last.w; a.dbias = G.g + last.bias;
-    { Scope s(c, "skinny_wgrad", skinny_flops(last, n, 1), skinny_bytes<T>(last, n, 1)); launch_skinny_wgrad<T>(a, c->st); }
-    launch_img_bias_grad<T>(a, c->st);
-    SkinnyArgs d = skinny_args(c, G, last, SKINNY_DOWN_ROWS, 0, 1, n);
-    d.img = dlast; d.out = c->bufA;
-    Scope s(c, "skinny_down", skinny_flops(last, n, 1), skinny_bytes<T>(last, n, 1));
-    launch_skinny_down<T>(d, c->st);
+    im2col_call<T>(c, last, dlast, nullptr, c->colG, c->KcG, 0, 0, n);
+    wgrad_call<T>(c, "gemm_wgrad_img", c->colG, c->gact[nl - 1], c->dwp, (long long)c->KcG * last.Cs, c->KcG, last.Cs, last.Hs, 1, 1, n,
+                  img_flops(last, n, 1));
+    launch_unpack_dw(pack_args(c, G, last, c->KcG, 0, c->wpG), c->st);
+    ImgBiasArgs b;
+    b.img = dlast; b.partial = c->bias_partial; b.dbias = G.g + last.bias; b.pstride = G.P; b.offs = c->rb.offs;
+    b.L = c->L; b.CB = last.Cb; b.HW = 4 * last.Hs * last.Hs;
+    launch_img_bias_grad<T>(b, c->st);
+    conv_call<T>(c, "gemm_dense_img", MODE_DENSE, EPI_NONE, c->colG, c->wpG, (long long)last.Cs * c->KcG, c->bufA, nullptr, c->KcG,
+                 last.Cs, 1, last.Hs, 0, 1, n, 0, nullptr, 0, img_flops(last, n, 1));
   }
   for (int i = nl - 2; i >= 0; --i) {
     const ConvLayer& cl = G.conv[i];
@@ -551,7 +545,7 @@ void g_backward(gan_ctx* c, int n) {
 
 template <typename T>
 void adam_call(gan_ctx* c, Net& net, bool isG) {
-  AdamArgs a;
+  AdamArgs a = {};
   a.theta = net.theta; a.m = net.m; a.v = net.v; a.g = net.g; a.shadow = c->bf16 ? net.shadow_u : nullptr;
   a.P = net.P; a.L = c->L; a.counts = c->rb.counts; a.t = net.t; a.bc = net.bc;
   a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps;
@@ -562,16 +556,20 @@ void adam_call(gan_ctx* c, Net& net, bool isG) {
 template <typename T>
 void route_and_stage(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real, int n) {
   launch_route(label_ids, n, c->L, c->cfg.n_labels, c->geoms, c->rb, c->st);
-  Scope s(c, "stage", 0, (double)n * (c->cfg.img_hw * c->cfg.img_hw * c->cfg.img_c * (4.0 + sizeof(T)) + c->cfg.z_dim * 4.0));
-  launch_stage<T>(label_ids, noise, real, n, c->L, c->cfg.z_dim, c->cfg.cond_g, c->G.Kp, c->cfg.img_c, c->cfg.img_hw, c->rb,
-                  (T*)c->zin, (T*)c->xd, c->st);
+  {
+    Scope s(c, "stage", 0, (double)n * c->cfg.z_dim * (4.0 + sizeof(T)));
+    launch_stage<T>(label_ids, noise, nullptr, n, c->L, c->cfg.z_dim, c->cfg.cond_g, c->G.Kp, c->cfg.img_c, c->cfg.img_hw, c->rb,
+                    (T*)c->zin, (T*)c->xd, c->st);
+  }
+  if (real) im2col_call<T>(c, c->D.conv[0], nullptr, real, c->colD, c->KcD, c->nslot, 0, n);   // the real half of D's input
 }
 
 template <typename T>
 void train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real, int n) {
   if (c->shadows_dirty) refresh_shadows(c);
   route_and_stage<T>(c, label_ids, noise, real, n);
-  g_forward<T>(c, n, false, true);                 // fake = G(z), written next to the real batch
+  g_forward<T>(c, n, false, true);                 // fake = G(z)
+  im2col_call<T>(c, c->D.conv[0], c->xd, nullptr, c->colD, c->KcD, c->nslot, 1, n);   // the fake half of D's input
   d_forward<T>(c, n, 0, 2, true);                  // D(real), D(fake): separate batch statistics per segment
   loss_call(c, n, 0);                              // Eq. 3
   d_backward<T>(c, n, 0, 2, true, false);
@@ -596,7 +594,6 @@ bool check_config(const gan_config* f, std::string& why) {
   if ((f->g_ch[0] * f->g_h0 * f->g_h0) % 128) { why = "g_ch[0]*g_h0^2 must be a multiple of 128"; return false; }
   if (f->z_dim < 1 || f->cond_g < 0 || f->cond_d < 0 || f->max_total_batch < 1) { why = "bad z_dim / cond / max_total_batch"; return false; }
   if (f->cond_g > f->n_labels || (f->cond_d != 0 && f->cond_d < f->n_labels)) { why = "cond_d must cover every label"; return false; }
-  if (f->n_models == 1 && f->cond_d > 16) { why = "a single model supports at most 16 label maps"; return false; }
   if (f->precision != GAN_FP32 && f->precision != GAN_BF16_FP32MASTER) { why = "unknown precision"; return false; }
   return true;
 }
@@ -627,10 +624,6 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     geom_id(c, 1, bm);
     for (auto& cl : c->G.conv) geom_id(c, cl.Hs * cl.Hs, bm);
     for (auto& cl : c->D.conv) geom_id(c, cl.Hs * cl.Hs, bm);
-    for (const ConvLayer* cl : {&c->G.conv.back(), &c->D.conv.front()}) {
-      geom_id(c, cl->Hs * cl->Hs, SKINNY_DOWN_ROWS);
-      geom_id(c, cl->Hs * cl->Hs, SKINNY_WGRAD_ROWS);
-    }
   }
   RouteBuffers& rb = c->rb;
   ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&
@@ -676,11 +669,13 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   {
     const ConvLayer& c1 = c->D.conv[0];
     const ConvLayer& gl = c->G.conv.back();
-    const size_t lm = (size_t)L * c->nslot * 9 * c1.Cs * 4;
-    ok = ok && dev_alloc(c, (void**)&c->lm_table, lm) && dev_alloc(c, (void**)&c->lm_rsum, lm);
-    const size_t p1 = (size_t)2 * ub_tiles(c, NB, c1.Hs * c1.Hs, SKINNY_WGRAD_ROWS) * (256 / c1.Cs) * 16 * c1.Cb * c1.Cs * 4;
-    const size_t p2 = (size_t)ub_tiles(c, NB, gl.Hs * gl.Hs, SKINNY_WGRAD_ROWS) * (256 / gl.Cs) * 16 * gl.Cb * gl.Cs * 4;
-    ok = ok && dev_alloc(c, (void**)&c->partial, p1 > p2 ? p1 : p2);
+    c->KcD = (int)round_up(16 * c1.Cb + 9 * c->nslot + 1, 64);
+    c->KcG = (int)round_up(16 * gl.Cb, 64);
+    const size_t d1 = (size_t)c->KcD * c1.Cs, g1 = (size_t)c->KcG * gl.Cs;
+    ok = ok && dev_alloc(c, &c->colD, (size_t)2 * NB * c1.Hs * c1.Hs * c->KcD * es) &&
+         dev_alloc(c, &c->colG, (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
+         dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)L * (d1 > g1 ? d1 : g1) * 4) &&
+         dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
   }
   if (!ok) {
     for (void* p : c->allocs) (void)hipFree(p);
@@ -915,8 +910,8 @@ static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, vo
   int* tp = nullptr;
   gan_status s = op_common(c, offs, n_groups, Hr * Hr, &tp);
   if (s != GAN_OK) return s;
-  ConvArgs a;
-  a.A = A; a.W = W; a.Out = Out; a.Aux = nullptr; a.offs = offs; a.tpre = tp; a.w_stride = wstride; a.L = n_groups;
+  ConvArgs a = {};
+  a.A = A; a.W = W; a.Out = Out; a.Aux = nullptr; a.w_nstride = N; a.offs = offs; a.tpre = tp; a.w_stride = wstride; a.L = n_groups;
   a.seg_first = 0; a.nseg = 1; a.seg_samples = n_samples; a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr;
   a.ub_tiles = (int)(((long long)n_samples * Hr * Hr) / conv_tile_m()) + n_groups; a.slope = 0.f;
   if (c->bf16) launch_conv<bf16_t>(mode, EPI_NONE, a, c->st); else launch_conv<float>(mode, EPI_NONE, a, c->st);
@@ -939,7 +934,7 @@ gan_status gan_op_conv_wgrad(gan_ctx* c, const void* big, const void* small_in, 
                              int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs) {
   if (!c || !big || !small_in || !dw || !offs || n_groups < 1 || n_samples < 0) return GAN_E_ARG;
   if ((16 * cb) % 128 || cb % 8 || cs % 8) return fail(c, GAN_E_SHAPE, "unsupported channel counts");
-  WgradArgs a;
+  WgradArgs a = {};
   a.Big = big; a.Small = small_in; a.dW = dw; a.offs = offs; a.dw_stride = (long long)16 * cb * cs;
   a.L = n_groups; a.nseg = 1; a.seg_samples = n_samples; a.Cb = cb; a.Cs = cs; a.Hs = hs; a.ntaps = 16;
   if (c->bf16) launch_wgrad<bf16_t>(a, c->st); else launch_wgrad<float>(a, c->st);

@@ -34,7 +34,7 @@ template <> __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
 }
 
 enum ConvMode { MODE_DOWN = 0, MODE_UP = 1, MODE_DENSE = 2 };
-enum Epilogue { EPI_NONE = 0, EPI_ACT_BWD = 1 };
+enum Epilogue { EPI_NONE = 0, EPI_ACT_BWD = 1, EPI_LRELU = 2, EPI_BIAS_TANH = 3, EPI_TANH_BWD = 4 };
 enum Act { ACT_RELU = 0, ACT_LRELU = 1 };
 
 // Arguments of the grouped implicit-GEMM forward-type kernel (down / up / dense).
@@ -42,7 +42,10 @@ struct ConvArgs {
   const void* A;         // gathered activations (storage type)
   const void* W;         // weights of model 0, K-contiguous: [tap][N][C] (storage type)
   void* Out;             // output activations (storage type)
-  const void* Aux;       // EPI_ACT_BWD: forward activation at the output position (storage type)
+  const void* Aux;       // EPI_ACT_BWD / EPI_TANH_BWD: saved forward output at the output position (storage type)
+  const float* bias;     // EPI_BIAS_TANH: per output channel, model 0; bias_stride elements between models
+  long long bias_stride;
+  int w_nstride;         // rows per tap in the weight block (>= N)
   const int* offs;       // [L+1] sample offsets of the models inside one segment
   const int* tpre;       // [L+1] prefix of M-tiles per model for this geometry
   long long w_stride;    // elements between two models' weight blocks
@@ -58,7 +61,7 @@ struct ConvArgs {
 
 // Arguments of the grouped weight-gradient kernel: dW[tap][cb][cs] = sum_rows big(tap)[cb] * small[cs].
 struct WgradArgs {
-  const void* Big;       // tensor gathered through the taps, side 2*Hs (dense: side 1), channels Cb
+  const void* Big;       // tensor gathered through the taps, side 2*Hs, channels Cb (ntaps == 1: read row by row)
   const void* Small;     // tensor indexed directly by row, side Hs, channels Cs
   float* dW;             // fp32 output of model 0: [ntaps][Cb][Cs]
   const int* offs;       // [L+1]

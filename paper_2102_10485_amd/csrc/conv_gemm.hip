@@ -13,6 +13,8 @@
 //
 // Both stage 128-byte K-rows in LDS (row stride 144 bytes) and feed v_mfma_f32_32x32x16_bf16 (bf16 storage) or
 // v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace gan {
@@ -39,37 +41,42 @@ __device__ inline void mma16B(floatx16& acc, const uint4& a, const uint4& b, flo
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 
-// One K-chunk held in LDS: every wave multiplies its 64 x 64 sub-tile.
-template <typename T>
-__device__ inline void tile_mma(floatx16 (&acc)[2][2], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
+// One K-chunk held in LDS: every wave multiplies its (TM*32) x (TN*32) sub-tile.
+template <typename T, int TM, int TN>
+__device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
                                 int lane) {
   const int r = lane & 31, h = lane >> 5;
 #pragma unroll
   for (int vs = 0; vs < BKB / 32; ++vs) {
-    uint4 a[2], b[2];
+    uint4 a[TM], b[TN];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      a[t] = *reinterpret_cast<const uint4*>(As + (wm * 64 + t * 32 + r) * LDS_STRIDE + (vs * 2 + h) * 16);
-      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * 64 + t * 32 + r) * LDS_STRIDE + (vs * 2 + h) * 16);
-    }
+    for (int t = 0; t < TM; ++t)
+      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * LDS_STRIDE + (vs * 2 + h) * 16);
 #pragma unroll
-    for (int tm = 0; tm < 2; ++tm)
+    for (int t = 0; t < TN; ++t)
+      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * LDS_STRIDE + (vs * 2 + h) * 16);
 #pragma unroll
-      for (int tn = 0; tn < 2; ++tn) mma16B(acc[tm][tn], a[tm], b[tn], T());
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) mma16B(acc[tm][tn], a[tm], b[tn], T());
   }
 }
 
 __device__ inline void store_out(float* p, float v) { *p = v; }
 __device__ inline void store_out(bf16_t* p, float v) { *p = from_float<bf16_t>(v); }
 
-template <typename T, int MODE, int EPI>
+// BN_ = 128: waves 2 x 2, each 64 x 64.  BN_ = 32 (image-side outputs, N <= 32): waves 4 x 1, each 32 x 32.
+template <typename T, int MODE, int EPI, int BN_>
 __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
+  constexpr int WN = BN_ == 128 ? 2 : 1, WM = 4 / WN;
+  constexpr int TM = BM / (WM * 32), TN = BN_ / (WN * 32);
   __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN_ * LDS_STRIDE];
   constexpr int BK = BKB / (int)sizeof(T);
   constexpr int EPV = 16 / (int)sizeof(T);
+  constexpr int BN = BN_;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
 
   // ---- which tile: consecutive virtual ids stay on one XCD (block ids are dealt round-robin to the 8 XCDs)
   const int NT = (p.N + BN - 1) / BN;
@@ -109,11 +116,17 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
   for (int i = 0; i < 4; ++i) {
     const int r = m0 + row0 + 32 * i;
     if (r < Mrows) {
-      const int n = r / rps, rem = r - n * rps;
-      const int y = rem / Hr, x = rem - y * Hr;
-      abase[i] = (sample_base + n) * (long long)(Hin * Hin) * C;
-      aby[i] = (MODE == MODE_DOWN) ? 2 * y - 1 : y;
-      abx[i] = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
+      if (MODE == MODE_DENSE) {               // rows are read directly: one "tap" at (0, 0) of a 1 x 1 map
+        abase[i] = (sample_base * rps + r) * (long long)C;
+        aby[i] = 0;
+        abx[i] = 0;
+      } else {
+        const int n = r / rps, rem = r - n * rps;
+        const int y = rem / Hr, x = rem - y * Hr;
+        abase[i] = (sample_base + n) * (long long)(Hin * Hin) * C;
+        aby[i] = (MODE == MODE_DOWN) ? 2 * y - 1 : y;
+        abx[i] = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
+      }
     } else {
       abase[i] = 0;
       aby[i] = -100000;   // never in range
@@ -124,7 +137,8 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
   const int ntaps = (MODE == MODE_DOWN) ? 16 : (MODE == MODE_UP ? 4 : 1);
   const int nk = ntaps * C / BK;
 
-  uint4 ra[4], rb[4];
+  const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
+  uint4 ra[4], rb[BN / 32];
   auto load_chunk = [&](int kc) {
     const int kk = kc * BK;
     const int tap = kk / C;
@@ -150,25 +164,26 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
                  : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < BN / 32; ++i) {
       const int col = nt * BN + row0 + 32 * i;
-      rb[i] = (col < N) ? *reinterpret_cast<const uint4*>(W + ((long long)wtap * N + col) * C + c0)
+      rb[i] = (col < N) ? *reinterpret_cast<const uint4*>(W + ((long long)wtap * wns + col) * C + c0)
                         : make_uint4(0, 0, 0, 0);
     }
   };
   auto store_chunk = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i)
       *reinterpret_cast<uint4*>(As + (row0 + 32 * i) * LDS_STRIDE + chunk * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < BN / 32; ++i)
       *reinterpret_cast<uint4*>(Bs + (row0 + 32 * i) * LDS_STRIDE + chunk * 16) = rb[i];
-    }
   };
 
-  floatx16 acc[2][2];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -177,7 +192,7 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
   __syncthreads();
   for (int kc = 0; kc < nk; ++kc) {
     if (kc + 1 < nk) load_chunk(kc + 1);          // global loads in flight while the MFMAs run
-    tile_mma<T>(acc, As, Bs, wm, wn, lane);
+    tile_mma<T, TM, TN>(acc, As, Bs, wm, wn, lane);
     __syncthreads();
     if (kc + 1 < nk) {
       store_chunk();
@@ -206,41 +221,61 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
   T* __restrict__ Out = static_cast<T*>(p.Out);
   const T* __restrict__ Aux = static_cast<const T*>(p.Aux);
 #pragma unroll
-  for (int tm = 0; tm < 2; ++tm)
+  for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-      const int col = nt * BN + wn * 64 + tn * 32 + (lane & 31);
+    for (int tn = 0; tn < TN; ++tn) {
+      const int col = nt * BN + wn * TN * 32 + tn * 32 + (lane & 31);
       if (col >= N) continue;
+      float bias = 0.f;
+      if (EPI == EPI_BIAS_TANH) bias = p.bias[(long long)l * p.bias_stride + col];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int rr = wm * 64 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int rr = wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
         const long long o = orow[rr];
         if (o < 0) continue;
         float val = acc[tm][tn][e];
-        if (EPI == EPI_ACT_BWD) {
+        if (EPI == EPI_ACT_BWD) {                 // times the activation's derivative, from the saved output
           const float f = to_float(Aux[o * N + col]);
           val = f > 0.f ? val : val * p.slope;
+        } else if (EPI == EPI_LRELU) {
+          val = val > 0.f ? val : val * p.slope;
+        } else if (EPI == EPI_BIAS_TANH) {
+          val = tanhf(val + bias);
+        } else if (EPI == EPI_TANH_BWD) {         // times 1 - y^2, y the saved tanh output
+          const float y = to_float(Aux[o * N + col]);
+          val *= (1.f - y * y);
         }
         store_out(Out + o * N + col, val);
       }
     }
 }
 
+template <typename T, int MODE, int EPI, int BN_>
+static void launch_one(const ConvArgs& a, hipStream_t st) {
+  const int NT = (a.N + BN_ - 1) / BN_;
+  const long long blocks = ((long long)a.ub_tiles * NT + 7) / 8 * 8;
+  if (blocks == 0 || a.nseg == 0) return;
+  dim3 grid((unsigned)blocks, (unsigned)a.nseg, MODE == MODE_UP ? 4 : 1);
+  hipLaunchKernelGGL((conv_gemm_kernel<T, MODE, EPI, BN_>), grid, dim3(NTHREADS), 0, st, a);
+}
+
+// The (mode, epilogue, tile) combinations the networks use.
 template <typename T>
 void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
-  const int NT = (a.N + BN - 1) / BN;
-  const long long blocks = ((long long)a.ub_tiles * NT + 7) / 8 * 8;
-  dim3 grid((unsigned)blocks, (unsigned)a.nseg, mode == MODE_UP ? 4 : 1);
-  if (blocks == 0 || a.nseg == 0) return;
-  if (mode == MODE_DOWN) {
-    if (epi == EPI_NONE) hipLaunchKernelGGL((conv_gemm_kernel<T, MODE_DOWN, EPI_NONE>), grid, dim3(NTHREADS), 0, st, a);
-    else hipLaunchKernelGGL((conv_gemm_kernel<T, MODE_DOWN, EPI_ACT_BWD>), grid, dim3(NTHREADS), 0, st, a);
-  } else if (mode == MODE_UP) {
-    if (epi == EPI_NONE) hipLaunchKernelGGL((conv_gemm_kernel<T, MODE_UP, EPI_NONE>), grid, dim3(NTHREADS), 0, st, a);
-    else hipLaunchKernelGGL((conv_gemm_kernel<T, MODE_UP, EPI_ACT_BWD>), grid, dim3(NTHREADS), 0, st, a);
-  } else {
-    hipLaunchKernelGGL((conv_gemm_kernel<T, MODE_DENSE, EPI_NONE>), grid, dim3(NTHREADS), 0, st, a);
-  }
+  // the kernel's assumptions, checked before anything is launched
+  if (!a.A || !a.W || !a.Out || !a.offs || !a.tpre || a.N < 1 || a.w_nstride < a.N || a.C % (BKB / (int)sizeof(T)) != 0 ||
+      ((epi == EPI_ACT_BWD || epi == EPI_TANH_BWD) && !a.Aux) || (epi == EPI_BIAS_TANH && !a.bias))
+    abort();
+  const bool narrow = a.N <= 32;
+  if (mode == MODE_DOWN && epi == EPI_NONE && !narrow) return launch_one<T, MODE_DOWN, EPI_NONE, 128>(a, st);
+  if (mode == MODE_UP && epi == EPI_NONE && !narrow) return launch_one<T, MODE_UP, EPI_NONE, 128>(a, st);
+  if (mode == MODE_UP && epi == EPI_ACT_BWD && !narrow) return launch_one<T, MODE_UP, EPI_ACT_BWD, 128>(a, st);
+  if (mode == MODE_UP && epi == EPI_NONE && narrow) return launch_one<T, MODE_UP, EPI_NONE, 32>(a, st);
+  if (mode == MODE_UP && epi == EPI_BIAS_TANH && narrow) return launch_one<T, MODE_UP, EPI_BIAS_TANH, 32>(a, st);
+  if (mode == MODE_UP && epi == EPI_TANH_BWD && narrow) return launch_one<T, MODE_UP, EPI_TANH_BWD, 32>(a, st);
+  if (mode == MODE_DENSE && epi == EPI_NONE && !narrow) return launch_one<T, MODE_DENSE, EPI_NONE, 128>(a, st);
+  if (mode == MODE_DENSE && epi == EPI_LRELU && !narrow) return launch_one<T, MODE_DENSE, EPI_LRELU, 128>(a, st);
+  abort();   // a combination no caller uses
 }
 template void launch_conv<float>(int, int, const ConvArgs&, hipStream_t);
 template void launch_conv<bf16_t>(int, int, const ConvArgs&, hipStream_t);
@@ -277,7 +312,8 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradArgs p) {
 
   // ---- tile: all tiles of a model run on one XCD, models are dealt round-robin to XCDs
   const int Cb = p.Cb, Cs = p.Cs, Hs = p.Hs;
-  const int MT = p.ntaps * Cb / BM, NT = (Cs + BN - 1) / BN;
+  const int Mtot = p.ntaps * Cb;
+  const int MT = (Mtot + BM - 1) / BM, NT = (Cs + BN - 1) / BN;
   const int ntiles = MT * NT;
   const int bid = blockIdx.x;
   const int l = (bid / (8 * ntiles)) * 8 + (bid & 7);
@@ -302,6 +338,7 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradArgs p) {
   bool chan_ok = true;
   if (roleA) {
     const int m = mt * BM + cg * EPV;
+    chan_ok = m < Mtot;
     const int tap = m / Cb;
     ch = m - tap * Cb;
     if (p.ntaps != 1) { ky = tap >> 2; kx = tap & 3; }
@@ -327,7 +364,9 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradArgs p) {
         const int r = k0 + (IS16 ? rg * 8 + j : rg + 4 * j);
         uint4 val = make_uint4(0, 0, 0, 0);
         if (r < R && chan_ok) {
-          if (roleA) {
+          if (roleA && p.ntaps == 1) {           // rows of the big tensor are read directly
+            val = *reinterpret_cast<const uint4*>(Big + (sample_base * rps + r) * (long long)Cb + ch);
+          } else if (roleA) {
             const int n = r / rps, rem = r - n * rps;
             const int y = rem / Hs, x = rem - y * Hs;
             const int iy = 2 * y - 1 + ky, ix = 2 * x - 1 + kx;
@@ -358,7 +397,7 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradArgs p) {
         }
       }
       __syncthreads();
-      tile_mma<T>(acc, As, Bs, wm, wn, lane);
+      tile_mma<T, 2, 2>(acc, As, Bs, wm, wn, lane);
     }
   }
 
@@ -372,14 +411,15 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int m = mt * BM + wm * 64 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        dW[(long long)m * Cs + col] = acc[tm][tn][e];
+        if (m < Mtot) dW[(long long)m * Cs + col] = acc[tm][tn][e];
       }
     }
 }
 
 template <typename T>
 void launch_wgrad(const WgradArgs& a, hipStream_t st) {
-  const int MT = a.ntaps * a.Cb / BM, NT = (a.Cs + BN - 1) / BN;
+  if (!a.Big || !a.Small || !a.dW || !a.offs || a.Cb % 8 || a.Cs % 8 || (a.ntaps != 1 && a.ntaps != 16)) abort();
+  const int MT = (a.ntaps * a.Cb + BM - 1) / BM, NT = (a.Cs + BN - 1) / BN;
   const long long blocks = (long long)((a.L + 7) / 8) * 8 * MT * NT;
   if (blocks == 0) return;
   hipLaunchKernelGGL((wgrad_kernel<T>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, a);

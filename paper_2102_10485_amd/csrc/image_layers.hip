@@ -1,0 +1,203 @@
+// The two layers that touch the image (1..4 channels): D's first convolution and G's last transposed
+// convolution.  With so few image channels their implicit-GEMM K (16 taps x channels) is tiny, so the image
+// side is expanded once into an explicit patch matrix ("im2col") of 64-column rows and the layers run on the
+// same MFMA engine as everything else, as plain row-by-row GEMMs:
+//   forward of D's first conv      : feat = patches x Wp^T
+//   its weight gradient            : dWp  = patches^T x dfeat
+//   data gradient of G's last convT: dfeat = patches(d image) x Wp^T ; its weight gradient likewise.
+//
+// A one-hot label map is a constant plane: its contribution to D's first convolution is a per-position bias
+// that only differs at the border (3 x 3 position classes), and its weight gradient is the sum of dfeat over the
+// positions where the tap falls inside the image.  Both are exact.  The patch matrix therefore carries, after the
+// 16*CB tap columns, one indicator column per (label slot, position class) and one constant column: the packed
+// weight holds the summed label-map taps and the bias there, so the forward GEMM adds them and the weight-
+// gradient GEMM returns the class sums and the bias gradient with no extra pass over the feature tensor.
+#include "kernels.h"
+
+namespace gan {
+
+template <typename T> __device__ inline float ldf(const T* p) { return to_float(*p); }
+
+// Position class along one axis: 0 = first output row/col (tap 0 outside), 1 = interior, 2 = last (tap 3 outside).
+__device__ inline bool tap_valid(int cls, int k) { return !((cls == 0 && k == 0) || (cls == 2 && k == 3)); }
+__device__ inline int pos_class(int y, int x, int Hs) {
+  return (y == 0 ? 0 : (y == Hs - 1 ? 2 : 1)) * 3 + (x == 0 ? 0 : (x == Hs - 1 ? 2 : 1));
+}
+
+__device__ inline void store8(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ inline void store8(bf16_t* p, const float (&v)[8]) {
+  uint4 t;
+  t.x = (unsigned)f32_to_bf16_bits(v[0]) | ((unsigned)f32_to_bf16_bits(v[1]) << 16);
+  t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
+  t.z = (unsigned)f32_to_bf16_bits(v[4]) | ((unsigned)f32_to_bf16_bits(v[5]) << 16);
+  t.w = (unsigned)f32_to_bf16_bits(v[6]) | ((unsigned)f32_to_bf16_bits(v[7]) << 16);
+  *reinterpret_cast<uint4*>(p) = t;
+}
+
+// One thread per 8 columns of one patch row.
+template <typename T>
+__global__ __launch_bounds__(256) void im2col_kernel(Im2colArgs a) {
+  const int g8 = a.Kc >> 3;
+  const int rps = a.Hs * a.Hs, Hb = 2 * a.Hs;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)a.n * rps * g8) return;
+  const long long row = idx / g8;
+  const int m0 = (int)(idx - row * g8) * 8;
+  const int j = (int)(row / rps), pix = (int)(row - (long long)j * rps);
+  if (j >= a.offs[a.L]) return;
+  const int y = pix / a.Hs, x = pix - y * a.Hs;
+  const int ntap = 16 * a.CB;
+  const T* img = nullptr;
+  const float* real = nullptr;
+  if (a.img) img = static_cast<const T*>(a.img) + ((long long)a.seg * a.seg_samples + j) * Hb * Hb * a.CB;
+  else real = a.real + (long long)a.perm[j] * a.CB * Hb * Hb;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int m = m0 + e;
+    float val = 0.f;
+    if (m < ntap) {
+      const int tap = m / a.CB, cb = m - tap * a.CB;
+      const int iy = 2 * y - 1 + (tap >> 2), ix = 2 * x - 1 + (tap & 3);
+      if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb)
+        val = img ? ldf(img + ((long long)iy * Hb + ix) * a.CB + cb) : real[((long long)cb * Hb + iy) * Hb + ix];
+    } else if (a.nslot > 0) {
+      const int q = m - ntap;
+      if (q < 9 * a.nslot) val = (q / 9 == a.sample_slot[j] && q % 9 == pos_class(y, x, a.Hs)) ? 1.f : 0.f;
+      else if (q == 9 * a.nslot) val = 1.f;
+    }
+    v[e] = val;
+  }
+  store8(static_cast<T*>(a.out) + (((long long)a.seg * a.seg_samples + j) * rps + pix) * a.Kc + m0, v);
+}
+template <typename T> void launch_im2col(const Im2colArgs& a, hipStream_t st) {
+  const long long tot = (long long)a.n * a.Hs * a.Hs * (a.Kc / 8);
+  if (tot == 0) return;
+  hipLaunchKernelGGL((im2col_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+}
+template void launch_im2col<float>(const Im2colArgs&, hipStream_t);
+template void launch_im2col<bf16_t>(const Im2colArgs&, hipStream_t);
+
+// Wp[l][cs][m]: the taps, then the summed label-map taps per (slot, class), then the bias.
+template <typename T>
+__global__ void pack_w_kernel(PackArgs a) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)a.L * a.Cs * a.Kc) return;
+  const int m = (int)(idx % a.Kc);
+  const int cs = (int)((idx / a.Kc) % a.Cs);
+  const int l = (int)(idx / ((long long)a.Kc * a.Cs));
+  const float* w = a.w + (long long)l * a.pstride;
+  const int ntap = 16 * a.CB;
+  float val = 0.f;
+  if (m < ntap) {
+    const int tap = m / a.CB, cb = m - tap * a.CB;
+    val = w[((long long)tap * a.CBT + cb) * a.Cs + cs];
+  } else if (a.nslot > 0) {
+    const int q = m - ntap;
+    if (q < 9 * a.nslot) {
+      const int slot = q / 9, cls = q - slot * 9;
+      if (a.CBT > a.CB) {
+        const int label = (a.L == 1) ? slot : l;
+        for (int tap = 0; tap < 16; ++tap)
+          if (tap_valid(cls / 3, tap >> 2) && tap_valid(cls % 3, tap & 3))
+            val += w[((long long)tap * a.CBT + a.CB + label) * a.Cs + cs];
+      }
+    } else if (q == 9 * a.nslot && a.bias) {
+      val = a.bias[(long long)l * a.pstride + cs];
+    }
+  }
+  static_cast<T*>(a.wp)[idx] = from_float<T>(val);
+}
+template <typename T> void launch_pack_w(const PackArgs& a, hipStream_t st) {
+  const long long tot = (long long)a.L * a.Cs * a.Kc;
+  hipLaunchKernelGGL((pack_w_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+}
+template void launch_pack_w<float>(const PackArgs&, hipStream_t);
+template void launch_pack_w<bf16_t>(const PackArgs&, hipStream_t);
+
+// dWp[l][m][cs] (fp32) -> the gradient block: taps, label-map channels (class sums over the positions where the
+// tap is inside), bias.
+__global__ void unpack_dw_kernel(PackArgs a) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int Cs = a.Cs;
+  const long long n_tap = (long long)a.L * 16 * a.CB * Cs;
+  const long long n_lab = (a.nslot > 0 && a.CBT > a.CB) ? (long long)a.L * a.nslot * 16 * Cs : 0;
+  const long long n_bias = (a.nslot > 0 && a.dbias) ? (long long)a.L * Cs : 0;
+  const int ntap = 16 * a.CB;
+  if (idx < n_tap) {
+    const int cs = (int)(idx % Cs);
+    const int m = (int)((idx / Cs) % ntap);
+    const int l = (int)(idx / ((long long)Cs * ntap));
+    const int tap = m / a.CB, cb = m - tap * a.CB;
+    a.dw[(long long)l * a.pstride + ((long long)tap * a.CBT + cb) * Cs + cs] = a.dwp[((long long)l * a.Kc + m) * Cs + cs];
+    return;
+  }
+  long long j = idx - n_tap;
+  if (j < n_lab) {
+    const int cs = (int)(j % Cs);
+    const int tap = (int)((j / Cs) % 16);
+    const int slot = (int)((j / ((long long)Cs * 16)) % a.nslot);
+    const int l = (int)(j / ((long long)Cs * 16 * a.nslot));
+    const int label = (a.L == 1) ? slot : l;
+    float s = 0.f;
+    for (int cls = 0; cls < 9; ++cls)
+      if (tap_valid(cls / 3, tap >> 2) && tap_valid(cls % 3, tap & 3))
+        s += a.dwp[((long long)l * a.Kc + ntap + slot * 9 + cls) * Cs + cs];
+    a.dw[(long long)l * a.pstride + ((long long)tap * a.CBT + a.CB + label) * Cs + cs] = s;
+    return;
+  }
+  j -= n_lab;
+  if (j < n_bias) {
+    const int l = (int)(j / Cs), cs = (int)(j - (long long)l * Cs);
+    a.dbias[(long long)l * a.pstride + cs] = a.dwp[((long long)l * a.Kc + ntap + 9 * a.nslot) * Cs + cs];
+  }
+}
+void launch_unpack_dw(const PackArgs& a, hipStream_t st) {
+  const long long tot = (long long)a.L * a.Cs * (16 * a.CB + (a.nslot > 0 ? a.nslot * 16 + 1 : 0));
+  hipLaunchKernelGGL(unpack_dw_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+}
+
+// dbias[cb] = sum over the model's image-side pixels (G's last layer): block (chunk of pixels, model) partial
+// sums, then one small pass adds the chunks in order.
+template <typename T>
+__global__ __launch_bounds__(256) void img_bias_partial_kernel(ImgBiasArgs a) {
+  __shared__ float red[256];
+  const int l = blockIdx.y;
+  const int cnt = a.offs[l + 1] - a.offs[l];
+  const long long pix = (long long)cnt * a.HW;
+  const long long per = (pix + gridDim.x - 1) / gridDim.x;
+  const long long p0 = per * blockIdx.x, p1 = min(pix, p0 + per);
+  const T* img = static_cast<const T*>(a.img) + (long long)a.offs[l] * a.HW * a.CB;
+  for (int cb = 0; cb < a.CB; ++cb) {
+    float s = 0.f;
+    for (long long i = p0 + threadIdx.x; i < p1; i += 256) s += ldf(img + i * a.CB + cb);
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+      if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) a.partial[((long long)l * gridDim.x + blockIdx.x) * 4 + cb] = red[0];
+    __syncthreads();
+  }
+}
+__global__ void img_bias_final_kernel(ImgBiasArgs a, int chunks) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= a.L * a.CB) return;
+  const int l = idx / a.CB, cb = idx - l * a.CB;
+  if (a.offs[l + 1] == a.offs[l]) return;
+  float s = 0.f;
+  for (int k = 0; k < chunks; ++k) s += a.partial[((long long)l * chunks + k) * 4 + cb];
+  a.dbias[(long long)l * a.pstride + cb] = s;
+}
+template <typename T> void launch_img_bias_grad(const ImgBiasArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((img_bias_partial_kernel<T>), dim3(IMG_BIAS_CHUNKS, a.L), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(img_bias_final_kernel, dim3((a.L * a.CB + 255) / 256), dim3(256), 0, st, a, IMG_BIAS_CHUNKS);
+}
+template void launch_img_bias_grad<float>(const ImgBiasArgs&, hipStream_t);
+template void launch_img_bias_grad<bf16_t>(const ImgBiasArgs&, hipStream_t);
+
+}  // namespace gan

@@ -71,53 +71,43 @@ template <typename T> void launch_bn_bwd_reduce(const NormArgs& a, hipStream_t s
 void launch_bn_param_grad(const NormArgs& a, hipStream_t st);
 template <typename T> void launch_bn_bwd_apply(const NormArgs& a, hipStream_t st);
 
-// The layers touching the image (1..4 channels): D's first conv and G's last transposed conv.
-struct SkinnyArgs {
-  const void* img;          // image-side tensor [rows_big][CB] (storage type), side 2*Hs
-  const void* feat;         // feature-side tensor [rows_small][Cs], side Hs
-  void* out;
-  const float* w;           // model 0 master weights [16][CBT][Cs]; per-model stride pstride
-  const float* bias;        // may be NULL
-  long long pstride;
-  const float* table;       // label-map table [L][nslot][9][Cs] (may be NULL)
-  const int* sample_slot;
-  int nslot;
-  const void* aux;          // up+tanh_bwd: the tanh output at the same position
+// The layers touching the image (1..4 channels) run as row-by-row GEMMs over an explicit patch matrix.
+struct Im2colArgs {
+  const void* img;          // NHWC image-side tensor (storage type), side 2*Hs, indexed by absolute sample; or NULL
+  const float* real;        // caller's NCHW fp32 batch, gathered through perm (used when img == NULL)
+  const int* perm;
+  void* out;                // [rows][Kc] (storage type), rows indexed by absolute sample
   const int* offs;
-  const int* tpre;
-  int L, CB, CBT, Cs, Hs;
-  int seg_first, nseg, seg_samples, ub_tiles;
-  int lrelu;                // down: apply LeakyReLU(slope)
-  int tanh_out;             // up: 1 = add bias and apply tanh ; 2 = multiply by (1 - aux^2)
-  float slope;
-  float* partial;           // wgrad: [nseg][ub_tiles][256/Cs][16*CB][Cs]
-  float* dw;                // wgrad: model 0 gradient [16][CBT][Cs], stride pstride
-  float* dbias;             // G last layer: [CB] per model (may be NULL)
+  const int* sample_slot;
+  int L, n, CB, Hs, Kc;
+  int nslot;                // 0: tap columns only ; > 0: + 9*nslot class indicators + one constant column
+  int seg, seg_samples;     // absolute segment of both the source tensor and the output rows
 };
-constexpr int SKINNY_DOWN_ROWS = 32;
-constexpr int SKINNY_UP_ROWS = 32;
-constexpr int SKINNY_WGRAD_ROWS = 2048;
-template <typename T> void launch_skinny_down(const SkinnyArgs& a, hipStream_t st);
-template <typename T> void launch_skinny_up(const SkinnyArgs& a, hipStream_t st);
-template <typename T> void launch_skinny_wgrad(const SkinnyArgs& a, hipStream_t st);
-template <typename T> void launch_img_bias_grad(const SkinnyArgs& a, hipStream_t st);
+template <typename T> void launch_im2col(const Im2colArgs& a, hipStream_t st);
 
-// Label maps of D's first conv: a constant one-hot plane contributes a per-position bias (border classes 3 x 3).
-struct LabelMapArgs {
-  const float* w;           // model 0 [16][CBT][Cs]
-  float* dw;
-  float* dbias;             // [Cs] per model
+struct PackArgs {
+  const float* w;           // model 0 master weights [16][CBT][Cs]; per-model stride pstride
+  const float* bias;        // [Cs] (may be NULL)
+  float* dw;                // unpack: gradient block of model 0, same layout as w
+  float* dbias;             // unpack: may be NULL
   long long pstride;
-  float* table;             // [L][nslot][9][Cs]
-  float* rsum;              // [L][nslot][9][Cs]
-  const void* dfeat;        // dx of the first conv's output [rows][Cs]
-  const int* offs;
-  const int* sample_slot;
-  int L, nslot, CB, CBT, Cs, Hs, nseg, seg_samples;
+  void* wp;                 // pack: [L][Cs][Kc] storage type
+  const float* dwp;         // unpack: [L][Kc][Cs] fp32
+  int L, CB, CBT, Cs, Kc, nslot;
 };
-void launch_labelmap_table(const LabelMapArgs& a, hipStream_t st);
-template <typename T> void launch_labelmap_reduce(const LabelMapArgs& a, hipStream_t st);
-void launch_labelmap_grads(const LabelMapArgs& a, hipStream_t st);
+template <typename T> void launch_pack_w(const PackArgs& a, hipStream_t st);
+void launch_unpack_dw(const PackArgs& a, hipStream_t st);
+
+constexpr int IMG_BIAS_CHUNKS = 32;
+struct ImgBiasArgs {
+  const void* img;          // [pixels][CB] of segment 0
+  float* partial;           // [L][IMG_BIAS_CHUNKS][4]
+  float* dbias;             // model 0, stride pstride
+  long long pstride;
+  const int* offs;
+  int L, CB, HW;
+};
+template <typename T> void launch_img_bias_grad(const ImgBiasArgs& a, hipStream_t st);
 
 // D's final linear layer (one logit), the two costs, and their gradients.
 struct HeadArgs {
