@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--precision", choices=["fp32", "bf16"], default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not time individual kernels (no roofline object)")
+    ap.add_argument("--detail", action="store_true", help="time every layer shape separately (analysis runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the label models shard with no per-step traffic; "
@@ -84,7 +85,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
     if not args.no_profile:
-        gan.profile_enable(True)
+        gan.profile_enable(True, detail=args.detail)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -112,6 +113,9 @@ def main():
                           "avg_launch_ms": per,
                           "tflops": r["flops"] / (r["ms"] * 1e9) if r["ms"] > 0 else 0.0,
                           "gbps": r["bytes"] / (r["ms"] * 1e6) if r["ms"] > 0 else 0.0}
+        if args.detail:
+            for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_per_step"]):
+                print("%-44s %5.1f launches %8.3f ms/step %8.1f TFLOP/s %8.1f GB/s" % (k, v["launches_per_step"], v["ms_per_step"], v["tflops"], v["gbps"]), file=sys.stderr)
         gemm = [k for k in kern if k.startswith("gemm_")]
         dom = max(gemm, key=lambda k: kern[k]["ms_per_step"])
         peak = PEAK["mfma_bf16"] if prec_name == "bf16" else PEAK["mfma_fp32"]

@@ -189,8 +189,8 @@ class Gan:
         self._check(self.lib.gan_get_routing(self.h, perm.ctypes.data_as(_IP), offs.ctypes.data_as(_IP)))
         return perm[:n], offs
 
-    def profile_enable(self, on=True):
-        self._check(self.lib.gan_profile_enable(self.h, 1 if on else 0))
+    def profile_enable(self, on=True, detail=False):
+        self._check(self.lib.gan_profile_enable(self.h, (2 if detail else 1) if on else 0))
 
     def profile_read(self, cap=64):
         names = (C.c_char_p * cap)()

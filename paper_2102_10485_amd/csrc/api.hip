@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <set>
 #include <string>
 #include <vector>
 
@@ -17,6 +18,10 @@ using namespace gan;
 namespace {
 
 inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
+
+// the weight gradient of a patch-matrix layer has a tiny output and a long reduction: its rows are split over this
+// many blocks per model, and the partial blocks are added in a fixed order when they are unpacked
+constexpr int IMG_KSPLIT = 8;
 
 // A (transposed) convolution between a "big" tensor (Cb channels, side 2*Hs) and a "small" one (Cs, side Hs).
 // Internal weight layout [tap][Cb (or CBT)][Cs].
@@ -71,7 +76,8 @@ struct gan_ctx {
   std::string err;
   std::vector<void*> allocs;
   // profiling
-  bool prof = false;
+  bool prof = false, prof_detail = false;
+  std::set<std::string> prof_names;
   std::vector<ProfEntry> prof_entries;
   std::vector<hipEvent_t> event_pool;
 };
@@ -104,6 +110,11 @@ const int* tpre_of(gan_ctx* c, int rps, int tile_rows) {
   const int g = geom_id(c, rps, tile_rows);
   return c->rb.tpre + (long long)g * (c->L + 1);
 }
+// tile height for a layer: from the average rows per model at the sizing batch (fixed at create, so the prefix
+// arrays built at every routing match)
+int layer_tile_rows(const gan_ctx* c, int n_out, int rps) {
+  return conv_tile_rows(n_out, (long long)c->NB * rps / c->L);
+}
 int ub_tiles(const gan_ctx* c, int n, int rps, int tile_rows) {
   return (int)(((long long)n * rps) / tile_rows) + (n < c->L ? n : c->L);
 }
@@ -111,8 +122,9 @@ int ub_tiles(const gan_ctx* c, int n, int rps, int tile_rows) {
 // ---- profiling: two events around a launch ------------------------------------------------------------
 struct Scope {
   gan_ctx* c; int idx = -1;
-  Scope(gan_ctx* c_, const char* name, double flops, double bytes) : c(c_) {
+  Scope(gan_ctx* c_, const char* name, double flops, double bytes, const char* detail = nullptr) : c(c_) {
     if (!c->prof) return;
+    if (c->prof_detail && detail) name = c->prof_names.insert(std::string(name) + detail).first->c_str();
     ProfEntry e; e.name = name; e.flops = flops; e.bytes = bytes;
     hipEventCreate(&e.e0); hipEventCreate(&e.e1);
     hipEventRecord(e.e0, c->st);
@@ -313,9 +325,10 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
                const float* bias = nullptr, long long bias_stride = 0, double flops_alg = -1.0) {
   ConvArgs a = {};
   a.A = A; a.W = W; a.Out = Out; a.Aux = Aux; a.bias = bias; a.bias_stride = bias_stride; a.w_nstride = w_nstride ? w_nstride : N;
-  a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, conv_tile_m());
+  const int tr = layer_tile_rows(c, N, Hr * Hr);
+  a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, tr); a.tile_rows = tr;
   a.w_stride = wstride; a.L = c->L; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n;
-  a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr; a.ub_tiles = ub_tiles(c, n, Hr * Hr, conv_tile_m());
+  a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr; a.ub_tiles = ub_tiles(c, n, Hr * Hr, tr);
   a.slope = c->cfg.leaky_slope;
   const int ntaps = mode == MODE_DOWN ? 16 : (mode == MODE_UP ? 4 : 1);
   const int phases = mode == MODE_UP ? 4 : 1;
@@ -324,21 +337,26 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
   const double flops = flops_alg >= 0 ? flops_alg : 2.0 * rows * N * C * ntaps * frac;
   const double in_elems = mode == MODE_DENSE ? rows * C : (double)n * nseg * Hin * Hin * C;
   const double bytes = sizeof(T) * (in_elems + rows * N + (double)c->L * (mode == MODE_DENSE ? 1 : 16) * C * N);
-  Scope s(c, name, flops, bytes);
+  char detail[64];
+  snprintf(detail, sizeof(detail), "[C%d N%d H%d seg%d]", C, N, Hr, nseg);
+  Scope s(c, name, flops, bytes, detail);
   launch_conv<T>(mode, epi, a, c->st);
 }
 
 template <typename T>
 void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small, float* dW, long long stride, int Cb, int Cs,
-                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0) {
+                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0, int ksplit = 1) {
   WgradArgs a = {};
   a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.dw_stride = stride;
-  a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps;
+  a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps; a.ksplit = ksplit;
+  a.split_stride = (long long)c->L * stride;
   const double rows = (double)n * nseg * Hs * Hs;
   const double frac = ntaps == 1 ? 1.0 : valid_tap_fraction(Hs);
   const double big_elems = ntaps == 1 ? rows * Cb : (double)n * nseg * 4 * Hs * Hs * Cb;
   const double bytes = sizeof(T) * (big_elems + rows * Cs) + 4.0 * c->L * ntaps * Cb * Cs;
-  Scope s(c, name, flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes);
+  char detail[64];
+  snprintf(detail, sizeof(detail), "[Cb%d Cs%d H%d seg%d]", Cb, Cs, Hs, nseg);
+  Scope s(c, name, flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes, detail);
   launch_wgrad<T>(a, c->st);
 }
 
@@ -405,7 +423,7 @@ PackArgs pack_args(gan_ctx* c, Net& net, const ConvLayer& cl, int Kc, int nslot,
   a.w = net.theta + cl.w; a.bias = (nslot > 0 && cl.bias >= 0) ? net.theta + cl.bias : nullptr;
   a.dw = net.g + cl.w; a.dbias = (nslot > 0 && cl.bias >= 0) ? net.g + cl.bias : nullptr;
   a.pstride = net.P; a.wp = wp; a.dwp = c->dwp;
-  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Kc = Kc; a.nslot = nslot;
+  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Kc = Kc; a.nslot = nslot; a.nsplit = IMG_KSPLIT;
   return a;
 }
 
@@ -501,7 +519,7 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
   if (param_grads) {
     // taps, label-map class sums and the bias gradient in one GEMM over the patch matrix
     wgrad_call<T>(c, "gemm_wgrad_img", c->colD, c->bufA, c->dwp, (long long)c->KcD * c1.Cs, c->KcD, c1.Cs, c1.Hs, 1, nseg, n,
-                  img_flops(c1, n, nseg));
+                  img_flops(c1, n, nseg), IMG_KSPLIT);
     launch_unpack_dw(pack_args(c, D, c1, c->KcD, c->nslot, c->wpD), c->st);
   }
   if (to_image)   // d cost / d fake, times the tanh derivative
@@ -519,7 +537,7 @@ void g_backward(gan_ctx* c, int n) {
   {
     im2col_call<T>(c, last, dlast, nullptr, c->colG, c->KcG, 0, 0, n);
     wgrad_call<T>(c, "gemm_wgrad_img", c->colG, c->gact[nl - 1], c->dwp, (long long)c->KcG * last.Cs, c->KcG, last.Cs, last.Hs, 1, 1, n,
-                  img_flops(last, n, 1));
+                  img_flops(last, n, 1), IMG_KSPLIT);
     launch_unpack_dw(pack_args(c, G, last, c->KcG, 0, c->wpG), c->st);
     ImgBiasArgs b;
     b.img = dlast; b.partial = c->bias_partial; b.dbias = G.g + last.bias; b.pstride = G.P; b.offs = c->rb.offs;
@@ -618,12 +636,25 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   const int L = c->L, NB = c->NB;
   const size_t es = esize(c);
   bool ok = alloc_net(c, c->G) && alloc_net(c, c->D);
-  // geometries used by any launch
+  // geometries used by any launch: (rows per sample, tile height) of every GEMM's row space
   {
-    const int bm = conv_tile_m();
-    geom_id(c, 1, bm);
-    for (auto& cl : c->G.conv) geom_id(c, cl.Hs * cl.Hs, bm);
-    for (auto& cl : c->D.conv) geom_id(c, cl.Hs * cl.Hs, bm);
+    const ConvLayer& gl = c->G.conv.back();
+    const ConvLayer& d1 = c->D.conv.front();
+    geom_id(c, 1, layer_tile_rows(c, c->G.J, 1));                                      // G's linear layer
+    for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) {
+      const ConvLayer& cl = c->G.conv[i];
+      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // forward (up)
+      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // data gradient (down)
+    }
+    geom_id(c, gl.Hs * gl.Hs, layer_tile_rows(c, gl.Cb, gl.Hs * gl.Hs));               // last layer forward (narrow)
+    geom_id(c, gl.Hs * gl.Hs, layer_tile_rows(c, gl.Cs, gl.Hs * gl.Hs));               // its data gradient (patch GEMM)
+    for (size_t j = 1; j < c->D.conv.size(); ++j) {
+      const ConvLayer& cl = c->D.conv[j];
+      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // forward (down)
+      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // data gradient (up)
+    }
+    geom_id(c, d1.Hs * d1.Hs, layer_tile_rows(c, d1.Cs, d1.Hs * d1.Hs));               // first conv (patch GEMM)
+    geom_id(c, d1.Hs * d1.Hs, layer_tile_rows(c, d1.Cb, d1.Hs * d1.Hs));               // its data gradient (narrow)
   }
   RouteBuffers& rb = c->rb;
   ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&
@@ -674,7 +705,7 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     const size_t d1 = (size_t)c->KcD * c1.Cs, g1 = (size_t)c->KcG * gl.Cs;
     ok = ok && dev_alloc(c, &c->colD, (size_t)2 * NB * c1.Hs * c1.Hs * c->KcD * es) &&
          dev_alloc(c, &c->colG, (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
-         dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)L * (d1 > g1 ? d1 : g1) * 4) &&
+         dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)IMG_KSPLIT * L * (d1 > g1 ? d1 : g1) * 4) &&
          dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
   }
   if (!ok) {
@@ -869,6 +900,7 @@ gan_status gan_profile_enable(gan_ctx* c, int32_t enable) {
   for (auto& e : c->prof_entries) { hipEventDestroy(e.e0); hipEventDestroy(e.e1); }
   c->prof_entries.clear();
   c->prof = enable != 0;
+  c->prof_detail = enable > 1;      // 2: one family per layer shape
   return GAN_OK;
 }
 
@@ -895,10 +927,10 @@ gan_status gan_profile_read(gan_ctx* c, int32_t cap, const char** names, int64_t
 }
 
 // ---- single operations ------------------------------------------------------------------------------------
-static gan_status op_common(gan_ctx* c, const int32_t* offs, int n_groups, int rps, int** tpre_out) {
+static gan_status op_common(gan_ctx* c, const int32_t* offs, int n_groups, int rps, int tile_rows, int** tpre_out) {
   int* tp = nullptr;
   if (hipMalloc((void**)&tp, (size_t)(n_groups + 1) * 4) != hipSuccess) return fail(c, GAN_E_OOM, "tile prefix alloc");
-  launch_tile_prefix(offs, n_groups, rps, conv_tile_m(), tp, c->st);
+  launch_tile_prefix(offs, n_groups, rps, tile_rows, tp, c->st);
   *tpre_out = tp;
   return GAN_OK;
 }
@@ -908,12 +940,13 @@ static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, vo
   if (!c || !A || !W || !Out || !offs || n_groups < 1 || n_samples < 0) return GAN_E_ARG;
   if (C % 64 || N < 1) return fail(c, GAN_E_SHAPE, "channels must be multiples of 64");
   int* tp = nullptr;
-  gan_status s = op_common(c, offs, n_groups, Hr * Hr, &tp);
+  const int tr = conv_tile_rows(N, (long long)n_samples * Hr * Hr / n_groups);
+  gan_status s = op_common(c, offs, n_groups, Hr * Hr, tr, &tp);
   if (s != GAN_OK) return s;
   ConvArgs a = {};
   a.A = A; a.W = W; a.Out = Out; a.Aux = nullptr; a.w_nstride = N; a.offs = offs; a.tpre = tp; a.w_stride = wstride; a.L = n_groups;
   a.seg_first = 0; a.nseg = 1; a.seg_samples = n_samples; a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr;
-  a.ub_tiles = (int)(((long long)n_samples * Hr * Hr) / conv_tile_m()) + n_groups; a.slope = 0.f;
+  a.ub_tiles = (int)(((long long)n_samples * Hr * Hr) / tr) + n_groups; a.slope = 0.f; a.tile_rows = tr;
   if (c->bf16) launch_conv<bf16_t>(mode, EPI_NONE, a, c->st); else launch_conv<float>(mode, EPI_NONE, a, c->st);
   s = sync(c);
   (void)hipFree(tp);
@@ -936,7 +969,7 @@ gan_status gan_op_conv_wgrad(gan_ctx* c, const void* big, const void* small_in, 
   if ((16 * cb) % 128 || cb % 8 || cs % 8) return fail(c, GAN_E_SHAPE, "unsupported channel counts");
   WgradArgs a = {};
   a.Big = big; a.Small = small_in; a.dW = dw; a.offs = offs; a.dw_stride = (long long)16 * cb * cs;
-  a.L = n_groups; a.nseg = 1; a.seg_samples = n_samples; a.Cb = cb; a.Cs = cs; a.Hs = hs; a.ntaps = 16;
+  a.L = n_groups; a.nseg = 1; a.seg_samples = n_samples; a.Cb = cb; a.Cs = cs; a.Hs = hs; a.ntaps = 16; a.ksplit = 1;
   if (c->bf16) launch_wgrad<bf16_t>(a, c->st); else launch_wgrad<float>(a, c->st);
   gan_status s = sync(c);
   const hipError_t e = hipGetLastError();

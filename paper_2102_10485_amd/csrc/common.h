@@ -56,6 +56,8 @@ struct ConvArgs {
   int Hin;               // side of the gathered tensor
   int Hr;                // side of the row space (rows per sample = Hr*Hr)
   int ub_tiles;          // launched upper bound of M-tiles per (segment, phase)
+  int tile_rows;         // rows per M-tile the prefix array was built for (conv_tile_rows)
+  int hr_shift;          // log2(Hr) or -1 (filled by the launcher)
   float slope;           // EPI_ACT_BWD: derivative on the non-positive side
 };
 
@@ -69,11 +71,15 @@ struct WgradArgs {
   int L, nseg, seg_samples;
   int Cb, Cs, Hs;
   int ntaps;             // 16 (conv) or 1 (dense)
+  int ksplit;            // >= 1: the rows of each segment are shared by this many blocks, each writing its own
+  long long split_stride;//        partial block dW + split * split_stride (the caller adds them in order)
+  int hs_shift;          // log2(Hs) or -1 (filled by the launcher)
 };
 
 template <typename T> void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st);
 template <typename T> void launch_wgrad(const WgradArgs& a, hipStream_t st);
 
-int conv_tile_m();   // rows per M-tile of the forward-type kernel (for tile prefix arrays)
+// rows per M-tile the forward-type kernel will use for n_out output channels and about rows_per_model rows
+int conv_tile_rows(int n_out, long long rows_per_model_hint);
 
 }  // namespace gan

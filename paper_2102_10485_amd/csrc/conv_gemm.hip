@@ -6,13 +6,15 @@
 // Forward-type kernel (conv_gemm_kernel): C[row][n] = sum_{tap, c} A(row, tap)[c] * W[tap][n][c]
 //   down : rows are output pixels of the small tensor, 16 taps gathered from the big tensor at (2y-1+ky, 2x-1+kx)
 //   up   : rows are the pixels of one output phase (Y%2, X%2) of the big tensor, 4 taps gathered from the small one
-//   dense: one tap, rows are samples (linear layer)
+//   dense: one tap, rows are read directly (linear layer, patch-matrix layers)
 // Weight-gradient kernel (wgrad_kernel): dW[tap][cb][cs] = sum_rows Big(row, tap)[cb] * Small(row)[cs]; the
 //   reduction index is the slow memory index of both operands, so tiles are transposed in registers on their
 //   way into LDS.
 //
-// Both stage 128-byte K-rows in LDS (row stride 144 bytes) and feed v_mfma_f32_32x32x16_bf16 (bf16 storage) or
-// v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
+// Both stage 128-byte K-rows in LDS (row stride 144 bytes, two buffers) and feed v_mfma_f32_32x32x16_bf16 (bf16
+// storage) or v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
+// The next K-chunk travels global -> registers while the MFMAs of the current one run, then registers -> the
+// other LDS buffer: one barrier per chunk.
 #include <stdlib.h>
 
 #include "common.h"
@@ -22,13 +24,28 @@ namespace gan {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128;          // tile rows
-constexpr int BN = 128;          // tile columns
 constexpr int BKB = 128;         // bytes of K per LDS row
 constexpr int LDS_STRIDE = BKB + 16;
-constexpr int NTHREADS = 256;    // 4 waves as 2 x 2, each 64 x 64 of the tile
 
-int conv_tile_m() { return BM; }
+// Block tile BM x BN computed by WM x WN waves, each (TM*32) x (TN*32).
+template <int BM_, int BN_, int WM_, int WN_>
+struct Tile {
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int NT = 64 * WM_ * WN_;
+  static constexpr int TM = BM_ / (32 * WM_), TN = BN_ / (32 * WN_);
+  static constexpr int RPP = NT / 8;                 // tile rows filled per pass (8 chunks of 16 bytes per row)
+  static constexpr int PA = BM_ / RPP, PB = BN_ / RPP;
+};
+typedef Tile<256, 256, 2, 4> TileBig;     // 512 threads, wave tile 128 x 64
+typedef Tile<256, 128, 4, 2> TileMid;     // 512 threads, wave tile 64 x 64
+typedef Tile<128, 128, 2, 2> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model)
+typedef Tile<128, 32, 4, 1> TileNarrow;   // image-side outputs (N <= 32)
+
+int conv_tile_rows(int n_out, long long rows_per_model_hint) {
+  if (n_out <= 32) return TileNarrow::BM;
+  if (rows_per_model_hint > 0 && rows_per_model_hint <= 128) return TileSmall::BM;
+  return TileBig::BM;
+}
 
 __device__ inline void mma16B(floatx16& acc, const uint4& a, const uint4& b, bf16_t) {
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
@@ -65,18 +82,35 @@ __device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As
 __device__ inline void store_out(float* p, float v) { *p = v; }
 __device__ inline void store_out(bf16_t* p, float v) { *p = from_float<bf16_t>(v); }
 
-// BN_ = 128: waves 2 x 2, each 64 x 64.  BN_ = 32 (image-side outputs, N <= 32): waves 4 x 1, each 32 x 32.
-template <typename T, int MODE, int EPI, int BN_>
-__global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
-  constexpr int WN = BN_ == 128 ? 2 : 1, WM = 4 / WN;
-  constexpr int TM = BM / (WM * 32), TN = BN_ / (WN * 32);
-  __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN_ * LDS_STRIDE];
+// row of a model -> (sample, y, x); shift form when the side is a power of two
+__device__ inline void decode_row(int r, int H, int rps, int sh, int& n, int& y, int& x) {
+  if (sh >= 0) {
+    n = r >> (2 * sh);
+    const int rem = r & (rps - 1);
+    y = rem >> sh;
+    x = rem & (H - 1);
+  } else {
+    n = r / rps;
+    const int rem = r - n * rps;
+    y = rem / H;
+    x = rem - y * H;
+  }
+}
+static int log2_or_neg(int v) {
+  for (int s = 0; s < 30; ++s)
+    if ((1 << s) == v) return s;
+  return -1;
+}
+
+template <typename T, int MODE, int EPI, typename TL>
+__global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
+  constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, PA = TL::PA, PB = TL::PB, RPP = TL::RPP;
+  __shared__ __attribute__((aligned(16))) unsigned char As[2][BM * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[2][BN * LDS_STRIDE];
   constexpr int BK = BKB / (int)sizeof(T);
   constexpr int EPV = 16 / (int)sizeof(T);
-  constexpr int BN = BN_;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
+  const int wm = wave / TL::WN, wn = wave % TL::WN;
 
   // ---- which tile: consecutive virtual ids stay on one XCD (block ids are dealt round-robin to the 8 XCDs)
   const int NT = (p.N + BN - 1) / BN;
@@ -107,22 +141,22 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
   const T* __restrict__ A = static_cast<const T*>(p.A);
   const T* __restrict__ W = static_cast<const T*>(p.W) + (long long)l * p.w_stride;
 
-  // ---- per-thread load assignment: 16-byte chunk (tid % 8) of rows tid/8 + 32 i
+  // ---- per-thread load assignment: 16-byte chunk (tid % 8) of rows tid/8 + RPP i
   const int chunk = tid & 7;
   const int row0 = tid >> 3;
-  long long abase[4];
-  int aby[4], abx[4];
+  long long abase[PA];
+  int aby[PA], abx[PA];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = m0 + row0 + 32 * i;
+  for (int i = 0; i < PA; ++i) {
+    const int r = m0 + row0 + RPP * i;
     if (r < Mrows) {
       if (MODE == MODE_DENSE) {               // rows are read directly: one "tap" at (0, 0) of a 1 x 1 map
         abase[i] = (sample_base * rps + r) * (long long)C;
         aby[i] = 0;
         abx[i] = 0;
       } else {
-        const int n = r / rps, rem = r - n * rps;
-        const int y = rem / Hr, x = rem - y * Hr;
+        int n, y, x;
+        decode_row(r, Hr, rps, p.hr_shift, n, y, x);
         abase[i] = (sample_base + n) * (long long)(Hin * Hin) * C;
         aby[i] = (MODE == MODE_DOWN) ? 2 * y - 1 : y;
         abx[i] = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
@@ -136,9 +170,8 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
 
   const int ntaps = (MODE == MODE_DOWN) ? 16 : (MODE == MODE_UP ? 4 : 1);
   const int nk = ntaps * C / BK;
-
   const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
-  uint4 ra[4], rb[BN / 32];
+  uint4 ra[PA], rb[PB];
   auto load_chunk = [&](int kc) {
     const int kk = kc * BK;
     const int tap = kk / C;
@@ -157,26 +190,26 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
       dy = 0; dx = 0; wtap = 0;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < PA; ++i) {
       const int iy = aby[i] + dy, ix = abx[i] + dx;
       const bool ok = (unsigned)iy < (unsigned)Hin && (unsigned)ix < (unsigned)Hin;
       ra[i] = ok ? *reinterpret_cast<const uint4*>(A + abase[i] + (long long)(iy * Hin + ix) * C + c0)
                  : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i) {
-      const int col = nt * BN + row0 + 32 * i;
+    for (int i = 0; i < PB; ++i) {
+      const int col = nt * BN + row0 + RPP * i;
       rb[i] = (col < N) ? *reinterpret_cast<const uint4*>(W + ((long long)wtap * wns + col) * C + c0)
                         : make_uint4(0, 0, 0, 0);
     }
   };
-  auto store_chunk = [&]() {
+  auto store_chunk = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4*>(As + (row0 + 32 * i) * LDS_STRIDE + chunk * 16) = ra[i];
+    for (int i = 0; i < PA; ++i)
+      *reinterpret_cast<uint4*>(As[buf] + (row0 + RPP * i) * LDS_STRIDE + chunk * 16) = ra[i];
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i)
-      *reinterpret_cast<uint4*>(Bs + (row0 + 32 * i) * LDS_STRIDE + chunk * 16) = rb[i];
+    for (int i = 0; i < PB; ++i)
+      *reinterpret_cast<uint4*>(Bs[buf] + (row0 + RPP * i) * LDS_STRIDE + chunk * 16) = rb[i];
   };
 
   floatx16 acc[TM][TN];
@@ -188,38 +221,80 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   load_chunk(0);
-  store_chunk();
+  store_chunk(0);
   __syncthreads();
   for (int kc = 0; kc < nk; ++kc) {
-    if (kc + 1 < nk) load_chunk(kc + 1);          // global loads in flight while the MFMAs run
-    tile_mma<T, TM, TN>(acc, As, Bs, wm, wn, lane);
+    const bool more = kc + 1 < nk;
+    if (more) load_chunk(kc + 1);                  // global loads in flight while the MFMAs run
+    tile_mma<T, TM, TN>(acc, As[kc & 1], Bs[kc & 1], wm, wn, lane);
+    if (more) store_chunk((kc + 1) & 1);           // the other buffer was last read before the previous barrier
     __syncthreads();
-    if (kc + 1 < nk) {
-      store_chunk();
-      __syncthreads();
-    }
   }
 
-  // ---- epilogue: output row index of every tile row, through LDS (As is free now)
-  long long* orow = reinterpret_cast<long long*>(As);
-  if (tid < BM) {
-    const int r = m0 + tid;
+  // ---- epilogue: output row index of every tile row, through LDS (the buffers are free now)
+  long long* orow = reinterpret_cast<long long*>(As[0]);
+  for (int t = tid; t < BM; t += TL::NT) {
+    const int r = m0 + t;
     long long o = -1;
     if (r < Mrows) {
       if (MODE == MODE_UP) {
-        const int n = r / rps, rem = r - n * rps;
-        const int y = rem / Hr, x = rem - y * Hr;
+        int n, y, x;
+        decode_row(r, Hr, rps, p.hr_shift, n, y, x);
         const int Hb = 2 * Hr;
         o = ((sample_base + n) * Hb + (2 * y + py)) * Hb + (2 * x + px);
       } else {
         o = sample_base * rps + r;
       }
     }
-    orow[tid] = o;
+    orow[t] = o;
   }
   __syncthreads();
   T* __restrict__ Out = static_cast<T*>(p.Out);
   const T* __restrict__ Aux = static_cast<const T*>(p.Aux);
+  if (BN >= 64) {
+    // Wide tiles: each wave passes its 32 x (TN*32) blocks through a private LDS patch so that every lane stores
+    // 16 contiguous bytes of an output row (full N is a multiple of 64 for these tiles).
+    constexpr int WCOLS = TN * 32;
+    constexpr int PSTRIDE = WCOLS * (int)sizeof(T) + 16;               // bytes per patch row
+    constexpr int CPR = WCOLS * (int)sizeof(T) / 16;                   // 16-byte chunks per patch row
+    unsigned char* patch = As[0] + BM * 8 + wave * (32 * PSTRIDE);      // after the row table
+    static_assert(2 * BM * LDS_STRIDE >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE, "patch area");
+    const int colw = nt * BN + wn * WCOLS;                              // first column of this wave
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int pr = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          float val = acc[tm][tn][e];
+          if (EPI == EPI_LRELU) val = val > 0.f ? val : val * p.slope;
+          *reinterpret_cast<T*>(patch + pr * PSTRIDE + (tn * 32 + (lane & 31)) * (int)sizeof(T)) = from_float<T>(val);
+        }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 32 * CPR / 64; ++i) {
+        const int cid = lane + 64 * i;
+        const int pr = cid / CPR, pc = cid - pr * CPR;
+        const long long o = orow[wm * TM * 32 + tm * 32 + pr];
+        const int col = colw + pc * EPV;
+        if (o >= 0 && col < N) {
+          uint4 vraw = *reinterpret_cast<const uint4*>(patch + pr * PSTRIDE + pc * 16);
+          if (EPI == EPI_ACT_BWD) {               // times the activation's derivative, from the saved output
+            const uint4 araw = *reinterpret_cast<const uint4*>(Aux + o * N + col);
+            T* vv = reinterpret_cast<T*>(&vraw);
+            const T* aa = reinterpret_cast<const T*>(&araw);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k)
+              if (!(to_float(aa[k]) > 0.f)) vv[k] = from_float<T>(to_float(vv[k]) * p.slope);
+          }
+          *reinterpret_cast<uint4*>(Out + o * N + col) = vraw;
+        }
+      }
+      __syncthreads();
+    }
+    return;
+  }
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -234,7 +309,7 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
         const long long o = orow[rr];
         if (o < 0) continue;
         float val = acc[tm][tn][e];
-        if (EPI == EPI_ACT_BWD) {                 // times the activation's derivative, from the saved output
+        if (EPI == EPI_ACT_BWD) {
           const float f = to_float(Aux[o * N + col]);
           val = f > 0.f ? val : val * p.slope;
         } else if (EPI == EPI_LRELU) {
@@ -250,13 +325,22 @@ __global__ __launch_bounds__(NTHREADS) void conv_gemm_kernel(ConvArgs p) {
     }
 }
 
-template <typename T, int MODE, int EPI, int BN_>
-static void launch_one(const ConvArgs& a, hipStream_t st) {
-  const int NT = (a.N + BN_ - 1) / BN_;
+template <typename T, int MODE, int EPI, typename TL>
+static void launch_one(ConvArgs a, hipStream_t st) {
+  if (a.tile_rows != TL::BM) abort();            // the tile prefix array must have been built for this tile height
+  a.hr_shift = log2_or_neg(a.Hr);
+  const int NT = (a.N + TL::BN - 1) / TL::BN;
   const long long blocks = ((long long)a.ub_tiles * NT + 7) / 8 * 8;
   if (blocks == 0 || a.nseg == 0) return;
   dim3 grid((unsigned)blocks, (unsigned)a.nseg, MODE == MODE_UP ? 4 : 1);
-  hipLaunchKernelGGL((conv_gemm_kernel<T, MODE, EPI, BN_>), grid, dim3(NTHREADS), 0, st, a);
+  hipLaunchKernelGGL((conv_gemm_kernel<T, MODE, EPI, TL>), grid, dim3(TL::NT), 0, st, a);
+}
+
+template <typename T, int MODE, int EPI>
+static void launch_wide(const ConvArgs& a, hipStream_t st) {
+  if (a.tile_rows == TileSmall::BM) return launch_one<T, MODE, EPI, TileSmall>(a, st);
+  if (a.N % 256 == 0) return launch_one<T, MODE, EPI, TileBig>(a, st);
+  return launch_one<T, MODE, EPI, TileMid>(a, st);
 }
 
 // The (mode, epilogue, tile) combinations the networks use.
@@ -267,14 +351,14 @@ void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
       ((epi == EPI_ACT_BWD || epi == EPI_TANH_BWD) && !a.Aux) || (epi == EPI_BIAS_TANH && !a.bias))
     abort();
   const bool narrow = a.N <= 32;
-  if (mode == MODE_DOWN && epi == EPI_NONE && !narrow) return launch_one<T, MODE_DOWN, EPI_NONE, 128>(a, st);
-  if (mode == MODE_UP && epi == EPI_NONE && !narrow) return launch_one<T, MODE_UP, EPI_NONE, 128>(a, st);
-  if (mode == MODE_UP && epi == EPI_ACT_BWD && !narrow) return launch_one<T, MODE_UP, EPI_ACT_BWD, 128>(a, st);
-  if (mode == MODE_UP && epi == EPI_NONE && narrow) return launch_one<T, MODE_UP, EPI_NONE, 32>(a, st);
-  if (mode == MODE_UP && epi == EPI_BIAS_TANH && narrow) return launch_one<T, MODE_UP, EPI_BIAS_TANH, 32>(a, st);
-  if (mode == MODE_UP && epi == EPI_TANH_BWD && narrow) return launch_one<T, MODE_UP, EPI_TANH_BWD, 32>(a, st);
-  if (mode == MODE_DENSE && epi == EPI_NONE && !narrow) return launch_one<T, MODE_DENSE, EPI_NONE, 128>(a, st);
-  if (mode == MODE_DENSE && epi == EPI_LRELU && !narrow) return launch_one<T, MODE_DENSE, EPI_LRELU, 128>(a, st);
+  if (mode == MODE_DOWN && epi == EPI_NONE && !narrow) return launch_wide<T, MODE_DOWN, EPI_NONE>(a, st);
+  if (mode == MODE_UP && epi == EPI_NONE && !narrow) return launch_wide<T, MODE_UP, EPI_NONE>(a, st);
+  if (mode == MODE_UP && epi == EPI_ACT_BWD && !narrow) return launch_wide<T, MODE_UP, EPI_ACT_BWD>(a, st);
+  if (mode == MODE_UP && epi == EPI_NONE && narrow) return launch_one<T, MODE_UP, EPI_NONE, TileNarrow>(a, st);
+  if (mode == MODE_UP && epi == EPI_BIAS_TANH && narrow) return launch_one<T, MODE_UP, EPI_BIAS_TANH, TileNarrow>(a, st);
+  if (mode == MODE_UP && epi == EPI_TANH_BWD && narrow) return launch_one<T, MODE_UP, EPI_TANH_BWD, TileNarrow>(a, st);
+  if (mode == MODE_DENSE && epi == EPI_NONE && !narrow) return launch_wide<T, MODE_DENSE, EPI_NONE>(a, st);
+  if (mode == MODE_DENSE && epi == EPI_LRELU && !narrow) return launch_wide<T, MODE_DENSE, EPI_LRELU>(a, st);
   abort();   // a combination no caller uses
 }
 template void launch_conv<float>(int, int, const ConvArgs&, hipStream_t);
@@ -301,128 +385,179 @@ __device__ inline void transpose8x8_b16(uint4 (&r)[8]) {
   for (int i = 0; i < 8; ++i) r[i] = make_uint4(out[i][0], out[i][1], out[i][2], out[i][3]);
 }
 
-template <typename T>
-__global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradArgs p) {
-  __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDS_STRIDE];
+// A loader task = 8 rows of the reduction index x one 16-byte channel group of one operand.
+//   bf16: 8 consecutive rows x 8 channels, transposed in registers, written as 8 x 16 bytes
+//   fp32: 8 rows strided by 4 x 4 channels, written as 32 scalars
+template <typename T, typename TL>
+__global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
+  constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN;
+  __shared__ __attribute__((aligned(16))) unsigned char As[2][BM * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[2][BN * LDS_STRIDE];
   constexpr int BKR = BKB / (int)sizeof(T);     // rows (reduction index) per chunk: 64 (bf16) or 32 (fp32)
   constexpr bool IS16 = sizeof(T) == 2;
+  constexpr int EPV = 16 / (int)sizeof(T);
+  constexpr int NTASK = (BM + BN + TL::NT - 1) / TL::NT;   // loader tasks per thread
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / TL::WN, wn = wave % TL::WN;
 
   // ---- tile: all tiles of a model run on one XCD, models are dealt round-robin to XCDs
   const int Cb = p.Cb, Cs = p.Cs, Hs = p.Hs;
   const int Mtot = p.ntaps * Cb;
   const int MT = (Mtot + BM - 1) / BM, NT = (Cs + BN - 1) / BN;
-  const int ntiles = MT * NT;
+  const int per_model = MT * NT * p.ksplit;
   const int bid = blockIdx.x;
-  const int l = (bid / (8 * ntiles)) * 8 + (bid & 7);
+  const int l = (bid / (8 * per_model)) * 8 + (bid & 7);
   if (l >= p.L) return;
-  const int tile = (bid >> 3) % ntiles;
+  const int q = (bid >> 3) % per_model;
+  const int tile = q % (MT * NT), split = q / (MT * NT);
   const int mt = tile / NT, nt = tile - mt * NT;
   const int s0 = p.offs[l], s1 = p.offs[l + 1];
   const int rps = Hs * Hs;
   const int R = (s1 - s0) * rps;
-  const int Hb = (p.ntaps == 1) ? 1 : 2 * Hs;
+  const int Hb = 2 * Hs;
   const T* __restrict__ Big = static_cast<const T*>(p.Big);
   const T* __restrict__ Small = static_cast<const T*>(p.Small);
+  // this block's share of each segment's rows
+  const int rows_split = ((R + p.ksplit - 1) / p.ksplit + BKR - 1) / BKR * BKR;
+  const int r_lo = split * rows_split, r_hi = min(R, r_lo + rows_split);
 
-  // ---- loader roles: waves 0-1 fill A^T (gathered big tensor), waves 2-3 fill B^T (small tensor)
-  const bool roleA = wave < 2;
-  const int t = tid & 127;
-  // bf16: 16 channel groups of 8 x 8 row groups of 8 ; fp32: 32 channel groups of 4 x 4 row lanes, 8 rows each strided by 4
-  const int cg = IS16 ? (t & 15) : (t & 31);
-  const int rg = IS16 ? (t >> 4) : (t >> 5);
-  constexpr int EPV = 16 / (int)sizeof(T);
-  int ch, ky = 1, kx = 1;
-  bool chan_ok = true;
-  if (roleA) {
-    const int m = mt * BM + cg * EPV;
-    chan_ok = m < Mtot;
-    const int tap = m / Cb;
-    ch = m - tap * Cb;
-    if (p.ntaps != 1) { ky = tap >> 2; kx = tap & 3; }
-  } else {
-    ch = nt * BN + cg * EPV;
-    chan_ok = ch < Cs;
-  }
-
-  floatx16 acc[2][2];
+  // ---- loader tasks
+  int t_ch[NTASK], t_ky[NTASK], t_kx[NTASK], t_cg[NTASK], t_rg[NTASK];
+  bool t_isA[NTASK], t_ok[NTASK];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  uint4 reg[8];
-  for (int seg = 0; seg < p.nseg; ++seg) {
-    const long long sample_base = (long long)seg * p.seg_samples + s0;
-    for (int k0 = 0; k0 < R; k0 += BKR) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int r = k0 + (IS16 ? rg * 8 + j : rg + 4 * j);
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (r < R && chan_ok) {
-          if (roleA && p.ntaps == 1) {           // rows of the big tensor are read directly
-            val = *reinterpret_cast<const uint4*>(Big + (sample_base * rps + r) * (long long)Cb + ch);
-          } else if (roleA) {
-            const int n = r / rps, rem = r - n * rps;
-            const int y = rem / Hs, x = rem - y * Hs;
-            const int iy = 2 * y - 1 + ky, ix = 2 * x - 1 + kx;
-            if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb)
-              val = *reinterpret_cast<const uint4*>(Big + (((sample_base + n) * Hb + iy) * Hb + ix) * (long long)Cb + ch);
-          } else {
-            val = *reinterpret_cast<const uint4*>(Small + (sample_base * rps + r) * (long long)Cs + ch);
-          }
-        }
-        reg[j] = val;
-      }
-      __syncthreads();                      // previous chunk's MFMAs are done with the LDS tiles
-      unsigned char* dst = roleA ? As : Bs;
-      if (IS16) {
-        transpose8x8_b16(reg);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<uint4*>(dst + (cg * 8 + j) * LDS_STRIDE + rg * 16) = reg[j];
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int kr = rg + 4 * j;
-          unsigned* d0 = reinterpret_cast<unsigned*>(dst + (cg * 4) * LDS_STRIDE + kr * 4);
-          d0[0] = reg[j].x;
-          d0[LDS_STRIDE / 4] = reg[j].y;
-          d0[2 * LDS_STRIDE / 4] = reg[j].z;
-          d0[3 * LDS_STRIDE / 4] = reg[j].w;
-        }
-      }
-      __syncthreads();
-      tile_mma<T, 2, 2>(acc, As, Bs, wm, wn, lane);
+  for (int k = 0; k < NTASK; ++k) {
+    const int t = tid + k * TL::NT;
+    t_isA[k] = t < BM;
+    const int u = t_isA[k] ? t : t - BM;                  // task index inside its operand
+    const int groups = (t_isA[k] ? BM : BN) / EPV;        // channel groups
+    t_cg[k] = u % groups;
+    t_rg[k] = u / groups;
+    t_ky[k] = 1; t_kx[k] = 1;
+    if (t_isA[k]) {
+      const int m = mt * BM + t_cg[k] * EPV;
+      t_ok[k] = m < Mtot;
+      const int tap = m / Cb;
+      t_ch[k] = m - tap * Cb;
+      if (p.ntaps != 1) { t_ky[k] = tap >> 2; t_kx[k] = tap & 3; }
+    } else {
+      t_ch[k] = nt * BN + t_cg[k] * EPV;
+      t_ok[k] = t < BM + BN && t_ch[k] < Cs;
     }
   }
 
-  float* __restrict__ dW = p.dW + (long long)l * p.dw_stride;
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int tm = 0; tm < 2; ++tm)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-      const int col = nt * BN + wn * 64 + tn * 32 + (lane & 31);
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  uint4 reg[NTASK][8];
+  auto load_chunk = [&](long long sample_base, int k0) {
+#pragma unroll
+    for (int k = 0; k < NTASK; ++k)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = k0 + (IS16 ? t_rg[k] * 8 + j : t_rg[k] + 4 * j);
+        uint4 val = make_uint4(0, 0, 0, 0);
+        if (r < r_hi && t_ok[k]) {
+          if (!t_isA[k]) {
+            val = *reinterpret_cast<const uint4*>(Small + (sample_base * rps + r) * (long long)Cs + t_ch[k]);
+          } else if (p.ntaps == 1) {             // rows of the big tensor are read directly
+            val = *reinterpret_cast<const uint4*>(Big + (sample_base * rps + r) * (long long)Cb + t_ch[k]);
+          } else {
+            int n, y, x;
+            decode_row(r, Hs, rps, p.hs_shift, n, y, x);
+            const int iy = 2 * y - 1 + t_ky[k], ix = 2 * x - 1 + t_kx[k];
+            if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb)
+              val = *reinterpret_cast<const uint4*>(Big + (((sample_base + n) * Hb + iy) * Hb + ix) * (long long)Cb + t_ch[k]);
+          }
+        }
+        reg[k][j] = val;
+      }
+  };
+  auto store_chunk = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < NTASK; ++k) {
+      if (tid + k * TL::NT >= BM + BN) continue;
+      unsigned char* dst = t_isA[k] ? As[buf] : Bs[buf];
+      if (IS16) {
+        transpose8x8_b16(reg[k]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          *reinterpret_cast<uint4*>(dst + (t_cg[k] * 8 + j) * LDS_STRIDE + t_rg[k] * 16) = reg[k][j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int kr = t_rg[k] + 4 * j;
+          unsigned* d0 = reinterpret_cast<unsigned*>(dst + (t_cg[k] * 4) * LDS_STRIDE + kr * 4);
+          d0[0] = reg[k][j].x;
+          d0[LDS_STRIDE / 4] = reg[k][j].y;
+          d0[2 * LDS_STRIDE / 4] = reg[k][j].z;
+          d0[3 * LDS_STRIDE / 4] = reg[k][j].w;
+        }
+      }
+    }
+  };
+
+  // chunks of all segments as one sequence
+  const int per_seg = r_hi > r_lo ? (r_hi - r_lo + BKR - 1) / BKR : 0;
+  const int nchunks = per_seg * p.nseg;
+  auto chunk_pos = [&](int c, long long& sample_base, int& k0) {
+    const int seg = c / per_seg;
+    sample_base = (long long)seg * p.seg_samples + s0;
+    k0 = r_lo + (c - seg * per_seg) * BKR;
+  };
+  if (nchunks > 0) {
+    long long sb; int k0;
+    chunk_pos(0, sb, k0);
+    load_chunk(sb, k0);
+    store_chunk(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+      const bool more = c + 1 < nchunks;
+      if (more) { chunk_pos(c + 1, sb, k0); load_chunk(sb, k0); }
+      tile_mma<T, TM, TN>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
+      if (more) store_chunk((c + 1) & 1);
+      __syncthreads();
+    }
+  }
+
+  float* __restrict__ dW = p.dW + (long long)split * p.split_stride + (long long)l * p.dw_stride;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int col = nt * BN + wn * TN * 32 + tn * 32 + (lane & 31);
       if (col >= Cs) continue;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int m = mt * BM + wm * 64 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int m = mt * BM + wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
         if (m < Mtot) dW[(long long)m * Cs + col] = acc[tm][tn][e];
       }
     }
 }
 
+typedef Tile<64, 128, 1, 4> TileWgImg;    // patch-matrix layers: 64 packed columns x 128 feature channels
+
+template <typename T, typename TL>
+static void launch_wgrad_one(WgradArgs a, hipStream_t st) {
+  a.hs_shift = log2_or_neg(a.Hs);
+  const int MT = (a.ntaps * a.Cb + TL::BM - 1) / TL::BM, NT = (a.Cs + TL::BN - 1) / TL::BN;
+  const long long blocks = (long long)((a.L + 7) / 8) * 8 * MT * NT * a.ksplit;
+  if (blocks == 0) return;
+  hipLaunchKernelGGL((wgrad_kernel<T, TL>), dim3((unsigned)blocks), dim3(TL::NT), 0, st, a);
+}
+
 template <typename T>
 void launch_wgrad(const WgradArgs& a, hipStream_t st) {
-  if (!a.Big || !a.Small || !a.dW || !a.offs || a.Cb % 8 || a.Cs % 8 || (a.ntaps != 1 && a.ntaps != 16)) abort();
-  const int MT = (a.ntaps * a.Cb + BM - 1) / BM, NT = (a.Cs + BN - 1) / BN;
-  const long long blocks = (long long)((a.L + 7) / 8) * 8 * MT * NT;
-  if (blocks == 0) return;
-  hipLaunchKernelGGL((wgrad_kernel<T>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, a);
+  if (!a.Big || !a.Small || !a.dW || !a.offs || a.Cb % 8 || a.Cs % 8 || (a.ntaps != 1 && a.ntaps != 16) || a.ksplit < 1 ||
+      (a.ksplit > 1 && a.split_stride <= 0))
+    abort();
+  if (a.ntaps * a.Cb <= 64) return launch_wgrad_one<T, TileWgImg>(a, st);
+  if (a.Cs % 256 == 0) return launch_wgrad_one<T, TileBig>(a, st);
+  return launch_wgrad_one<T, TileMid>(a, st);
 }
 template void launch_wgrad<float>(const WgradArgs&, hipStream_t);
 template void launch_wgrad<bf16_t>(const WgradArgs&, hipStream_t);

@@ -120,6 +120,13 @@ template void launch_pack_w<bf16_t>(const PackArgs&, hipStream_t);
 
 // dWp[l][m][cs] (fp32) -> the gradient block: taps, label-map channels (class sums over the positions where the
 // tap is inside), bias.
+// element (l, m, cs) of the packed gradient: the split partial blocks added in order
+__device__ inline float dwp_at(const PackArgs& a, int l, int m, int cs) {
+  float s = 0.f;
+  for (int k = 0; k < a.nsplit; ++k) s += a.dwp[(((long long)k * a.L + l) * a.Kc + m) * a.Cs + cs];
+  return s;
+}
+
 __global__ void unpack_dw_kernel(PackArgs a) {
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const int Cs = a.Cs;
@@ -132,7 +139,7 @@ __global__ void unpack_dw_kernel(PackArgs a) {
     const int m = (int)((idx / Cs) % ntap);
     const int l = (int)(idx / ((long long)Cs * ntap));
     const int tap = m / a.CB, cb = m - tap * a.CB;
-    a.dw[(long long)l * a.pstride + ((long long)tap * a.CBT + cb) * Cs + cs] = a.dwp[((long long)l * a.Kc + m) * Cs + cs];
+    a.dw[(long long)l * a.pstride + ((long long)tap * a.CBT + cb) * Cs + cs] = dwp_at(a, l, m, cs);
     return;
   }
   long long j = idx - n_tap;
@@ -145,14 +152,14 @@ __global__ void unpack_dw_kernel(PackArgs a) {
     float s = 0.f;
     for (int cls = 0; cls < 9; ++cls)
       if (tap_valid(cls / 3, tap >> 2) && tap_valid(cls % 3, tap & 3))
-        s += a.dwp[((long long)l * a.Kc + ntap + slot * 9 + cls) * Cs + cs];
+        s += dwp_at(a, l, ntap + slot * 9 + cls, cs);
     a.dw[(long long)l * a.pstride + ((long long)tap * a.CBT + a.CB + label) * Cs + cs] = s;
     return;
   }
   j -= n_lab;
   if (j < n_bias) {
     const int l = (int)(j / Cs), cs = (int)(j - (long long)l * Cs);
-    a.dbias[(long long)l * a.pstride + cs] = a.dwp[((long long)l * a.Kc + ntap + 9 * a.nslot) * Cs + cs];
+    a.dbias[(long long)l * a.pstride + cs] = dwp_at(a, l, ntap + 9 * a.nslot, cs);
   }
 }
 void launch_unpack_dw(const PackArgs& a, hipStream_t st) {

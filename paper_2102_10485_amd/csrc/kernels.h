@@ -92,8 +92,8 @@ struct PackArgs {
   float* dbias;             // unpack: may be NULL
   long long pstride;
   void* wp;                 // pack: [L][Cs][Kc] storage type
-  const float* dwp;         // unpack: [L][Kc][Cs] fp32
-  int L, CB, CBT, Cs, Kc, nslot;
+  const float* dwp;         // unpack: [nsplit][L][Kc][Cs] fp32 partial blocks
+  int L, CB, CBT, Cs, Kc, nslot, nsplit;
 };
 template <typename T> void launch_pack_w(const PackArgs& a, hipStream_t st);
 void launch_unpack_dw(const PackArgs& a, hipStream_t st);

@@ -31,6 +31,8 @@ CASES = [
     (128, 64, 8, [3, 7]),
     (64, 64, 7, [9, 2, 4]),
     (256, 128, 2, [70, 1]),
+    (128, 256, 4, [20, 5]),
+    (64, 512, 2, [130]),
 ]
 
 
