@@ -68,7 +68,7 @@ struct gan_ctx {
   float *logits = nullptr, *dlogits = nullptr, *loss_d = nullptr, *loss_g = nullptr;
   // image-side layers: patch matrices, packed weights, packed weight gradients
   void *colD = nullptr, *colG = nullptr, *wpD = nullptr, *wpG = nullptr;
-  float *dwp = nullptr, *bias_partial = nullptr;
+  float *dwp = nullptr, *bias_partial = nullptr, *stat_partial = nullptr;
   int KcD = 0, KcG = 0;
   int nslot = 1;
   int last_n = -1;
@@ -322,7 +322,7 @@ void refresh_shadows(gan_ctx* c) {
 template <typename T>
 void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, const void* W, long long wstride, void* Out,
                const void* Aux, int C, int N, int Hin, int Hr, int seg_first, int nseg, int n, int w_nstride = 0,
-               const float* bias = nullptr, long long bias_stride = 0, double flops_alg = -1.0) {
+               const float* bias = nullptr, long long bias_stride = 0, double flops_alg = -1.0, bool stats = false) {
   ConvArgs a = {};
   a.A = A; a.W = W; a.Out = Out; a.Aux = Aux; a.bias = bias; a.bias_stride = bias_stride; a.w_nstride = w_nstride ? w_nstride : N;
   const int tr = layer_tile_rows(c, N, Hr * Hr);
@@ -330,6 +330,7 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
   a.w_stride = wstride; a.L = c->L; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n;
   a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr; a.ub_tiles = ub_tiles(c, n, Hr * Hr, tr);
   a.slope = c->cfg.leaky_slope;
+  a.stat_partial = stats ? c->stat_partial : nullptr;
   const int ntaps = mode == MODE_DOWN ? 16 : (mode == MODE_UP ? 4 : 1);
   const int phases = mode == MODE_UP ? 4 : 1;
   const double rows = (double)n * nseg * Hr * Hr * phases;
@@ -376,14 +377,18 @@ NormArgs norm_args(gan_ctx* c, Net& net, int C, int rps, long long gamma, long l
 }
 
 // BatchNorm (batch statistics, or the running ones) + activation: x -> y
+// gemm_rps / gemm_phases describe the GEMM that produced x and left per-tile column sums in c->stat_partial
 template <typename T>
-void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running, bool update_running) {
+void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running, bool update_running, int gemm_rps,
+                int gemm_phases, int col_groups = 1) {
   a.x = x; a.y = y;
   const double elems = (double)a.n * a.nseg * a.rps * a.C;
   if (use_running) {
     launch_bn_from_running(a, c->st);
   } else {
-    { Scope s(c, "bn_stats", 0, elems * sizeof(T)); launch_bn_stats<T>(a, c->st); }
+    const int tr = layer_tile_rows(c, a.C, gemm_rps);
+    launch_bn_stats_from_partial(a, c->stat_partial, tpre_of(c, gemm_rps, tr), ub_tiles(c, a.n, gemm_rps, tr), gemm_phases, col_groups, tr,
+                                 gemm_rps, c->st);
     if (update_running) launch_bn_running(a, c->st);
   }
   Scope s(c, "bn_apply", 0, 2 * elems * sizeof(T));
@@ -433,18 +438,18 @@ void g_forward(gan_ctx* c, int n, bool use_running, bool update_running) {
   Net& G = c->G;
   const float relu = 0.f;
   conv_call<T>(c, "gemm_dense", MODE_DENSE, EPI_NONE, c->zin, (const T*)G.shadow_u + G.fc_w, G.P, c->gpre[0], nullptr, G.Kp, G.J,
-               1, 1, 0, 1, n);
+               1, 1, 0, 1, n, 0, nullptr, 0, -1.0, !use_running);
   bn_forward<T>(c, norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
                                 c->g_sums[0], 0, 1, n, relu),
-                c->gpre[0], c->gact[0], use_running, update_running);
+                c->gpre[0], c->gact[0], use_running, update_running, 1, 1, G.h0 * G.h0);
   const int nl = (int)G.conv.size();
   for (int i = 0; i + 1 < nl; ++i) {
     const ConvLayer& cl = G.conv[i];
     conv_call<T>(c, "gemm_up", MODE_UP, EPI_NONE, c->gact[i], (const T*)G.shadow_u + cl.w, G.P, c->gpre[i + 1], nullptr, cl.Cs, cl.Cb,
-                 cl.Hs, cl.Hs, 0, 1, n);
+                 cl.Hs, cl.Hs, 0, 1, n, 0, nullptr, 0, -1.0, !use_running);
     bn_forward<T>(c, norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
                                   c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, relu),
-                  c->gpre[i + 1], c->gact[i + 1], use_running, update_running);
+                  c->gpre[i + 1], c->gact[i + 1], use_running, update_running, cl.Hs * cl.Hs, 4);
   }
   // last transposed conv (+bias, tanh) straight into the fake half of D's image buffer
   const ConvLayer& cl = G.conv[nl - 1];
@@ -465,10 +470,10 @@ void d_forward(gan_ctx* c, int n, int seg_first, int nseg, bool update_running) 
   for (int j = 1; j < nl; ++j) {
     const ConvLayer& cl = D.conv[j];
     conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->dact[j - 1], (const T*)D.shadow_d + cl.w, D.P, c->dpre[j], nullptr, cl.Cb,
-                 cl.Cs, 2 * cl.Hs, cl.Hs, seg_first, nseg, n);
+                 cl.Cs, 2 * cl.Hs, cl.Hs, seg_first, nseg, n, 0, nullptr, 0, -1.0, true);
     bn_forward<T>(c, norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
                                   c->d_sums[j], seg_first, nseg, n, slope),
-                  c->dpre[j], c->dact[j], false, update_running);
+                  c->dpre[j], c->dact[j], false, update_running, cl.Hs * cl.Hs, 1);
   }
   HeadArgs h;
   memset(&h, 0, sizeof(h));
@@ -693,6 +698,21 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
              dev_alloc(c, (void**)&c->d_var[j], (size_t)2 * L * cl.Cs * 4) && dev_alloc(c, (void**)&c->d_rstd[j], (size_t)2 * L * cl.Cs * 4) &&
              dev_alloc(c, (void**)&c->d_sums[j], (size_t)4 * L * cl.Cs * 4);
     }
+  }
+  {
+    // per-tile column sums left by the GEMM in front of every BatchNorm: phases x segments x tiles x columns x 2
+    size_t mx = (size_t)ub_tiles(c, NB, 1, layer_tile_rows(c, c->G.J, 1)) * c->G.J;
+    for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) {
+      const ConvLayer& cl = c->G.conv[i];
+      const size_t v = (size_t)4 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs)) * cl.Cb;
+      mx = v > mx ? v : mx;
+    }
+    for (size_t j = 1; j < c->D.conv.size(); ++j) {
+      const ConvLayer& cl = c->D.conv[j];
+      const size_t v = (size_t)2 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs)) * cl.Cs;
+      mx = v > mx ? v : mx;
+    }
+    ok = ok && dev_alloc(c, (void**)&c->stat_partial, mx * 2 * 4);
   }
   ok = ok && dev_alloc(c, &c->bufA, (size_t)2 * NB * max_act * es) && dev_alloc(c, &c->bufB, (size_t)2 * NB * max_act * es) &&
        dev_alloc(c, (void**)&c->logits, (size_t)2 * NB * 4) && dev_alloc(c, (void**)&c->dlogits, (size_t)2 * NB * 4) &&

@@ -43,6 +43,8 @@ struct ConvArgs {
   const void* W;         // weights of model 0, K-contiguous: [tap][N][C] (storage type)
   void* Out;             // output activations (storage type)
   const void* Aux;       // EPI_ACT_BWD / EPI_TANH_BWD: saved forward output at the output position (storage type)
+  float* stat_partial;   // if set (wide tiles): per-tile column sums of the output and of its squared deviations from the tile's column mean,
+                         // [((phase * nseg + segment) * ub_tiles + tile) * N + col][2], for the BatchNorm that follows
   const float* bias;     // EPI_BIAS_TANH: per output channel, model 0; bias_stride elements between models
   long long bias_stride;
   int w_nstride;         // rows per tap in the weight block (>= N)

@@ -59,19 +59,24 @@ __device__ inline void mma16B(floatx16& acc, const uint4& a, const uint4& b, flo
 }
 
 // One K-chunk held in LDS: every wave multiplies its (TM*32) x (TN*32) sub-tile.
-template <typename T, int TM, int TN>
+// SWZ: the 16-byte chunk c of tile row R sits at position (c + R/16) mod 8 (the weight-gradient kernel writes its
+// tiles transposed, eight rows apart per lane, and rotates the chunks so that those writes spread over the banks).
+template <typename T, int TM, int TN, bool SWZ = false>
 __device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
                                 int lane) {
   const int r = lane & 31, h = lane >> 5;
+  const int rot = SWZ ? (r >> 4) : 0;        // tile rows start at multiples of 32, so R/16 = const + r/16
 #pragma unroll
   for (int vs = 0; vs < BKB / 32; ++vs) {
     uint4 a[TM], b[TN];
 #pragma unroll
     for (int t = 0; t < TM; ++t)
-      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * LDS_STRIDE + (vs * 2 + h) * 16);
+      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * LDS_STRIDE +
+                                             ((vs * 2 + h + (SWZ ? 2 * (wm * TM + t) + rot : 0)) & 7) * 16);
 #pragma unroll
     for (int t = 0; t < TN; ++t)
-      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * LDS_STRIDE + (vs * 2 + h) * 16);
+      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * LDS_STRIDE +
+                                             ((vs * 2 + h + (SWZ ? 2 * (wn * TN + t) + rot : 0)) & 7) * 16);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -251,6 +256,55 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   __syncthreads();
   T* __restrict__ Out = static_cast<T*>(p.Out);
   const T* __restrict__ Aux = static_cast<const T*>(p.Aux);
+  if (BN >= 64 && p.stat_partial) {
+    // For the BatchNorm that follows: per column of this tile, the sum of the fp32 results and the sum of squared
+    // deviations from the tile's own column mean (merged across tiles by the pairwise-update formula, which keeps
+    // the variance free of the E[x^2] - mean^2 cancellation).  Fixed order everywhere.
+    float* red = reinterpret_cast<float*>(Bs[0]);                       // [WM][BN][2]
+    const int valid_rows = min(BM, Mrows - m0);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      float s1 = 0.f;
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s1 += acc[tm][tn][e];             // rows past the model's end are exact zeros
+      s1 += __shfl_xor(s1, 32, 64);
+      if (lane < 32) red[(wm * BN + wn * TN * 32 + tn * 32 + lane) * 2] = s1;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int c = wn * TN * 32 + tn * 32 + (lane & 31);
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < TL::WM; ++w) tot += red[(w * BN + c) * 2];
+      const float mean = tot / (float)valid_rows;
+      float s2 = 0.f;
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int rr = wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          const float d = acc[tm][tn][e] - mean;
+          if (rr < valid_rows) s2 += d * d;
+        }
+      s2 += __shfl_xor(s2, 32, 64);
+      if (lane < 32) red[(wm * BN + c) * 2 + 1] = s2;
+    }
+    __syncthreads();
+    for (int c = tid; c < BN; c += TL::NT) {
+      const int col = nt * BN + c;
+      if (col >= N) continue;
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < TL::WM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
+      const long long t = ((long long)blockIdx.z * gridDim.y + blockIdx.y) * p.ub_tiles + mt;
+      p.stat_partial[(t * N + col) * 2] = s1;
+      p.stat_partial[(t * N + col) * 2 + 1] = s2;
+    }
+    // (the patches below live in As, the sums in Bs: no barrier needed between them)
+  }
   if (BN >= 64) {
     // Wide tiles: each wave passes its 32 x (TN*32) blocks through a private LDS patch so that every lane stores
     // 16 contiguous bytes of an output row (full N is a multiple of 64 for these tiles).
@@ -485,13 +539,14 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
       if (IS16) {
         transpose8x8_b16(reg[k]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<uint4*>(dst + (t_cg[k] * 8 + j) * LDS_STRIDE + t_rg[k] * 16) = reg[k][j];
+        for (int j = 0; j < 8; ++j)   // row t_cg*8 + j, chunk t_rg rotated by row/16 = t_cg/2
+          *reinterpret_cast<uint4*>(dst + (t_cg[k] * 8 + j) * LDS_STRIDE + ((t_rg[k] + (t_cg[k] >> 1)) & 7) * 16) = reg[k][j];
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const int kr = t_rg[k] + 4 * j;
-          unsigned* d0 = reinterpret_cast<unsigned*>(dst + (t_cg[k] * 4) * LDS_STRIDE + kr * 4);
+          const int kr = t_rg[k] + 4 * j;                       // rows t_cg*4 .. +3 share row/16 = t_cg/4
+          unsigned* d0 = reinterpret_cast<unsigned*>(dst + (t_cg[k] * 4) * LDS_STRIDE +
+                                                     (((kr >> 2) + (t_cg[k] >> 2)) & 7) * 16 + (kr & 3) * 4);
           d0[0] = reg[k][j].x;
           d0[LDS_STRIDE / 4] = reg[k][j].y;
           d0[2 * LDS_STRIDE / 4] = reg[k][j].z;
@@ -518,7 +573,7 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
     for (int c = 0; c < nchunks; ++c) {
       const bool more = c + 1 < nchunks;
       if (more) { chunk_pos(c + 1, sb, k0); load_chunk(sb, k0); }
-      tile_mma<T, TM, TN>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
+      tile_mma<T, TM, TN, true>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
       if (more) store_chunk((c + 1) & 1);
       __syncthreads();
     }

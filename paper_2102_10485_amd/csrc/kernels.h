@@ -63,7 +63,9 @@ struct NormArgs {
   int act;                  // ACT_RELU / ACT_LRELU
   float slope, eps, momentum;
 };
-template <typename T> void launch_bn_stats(const NormArgs& a, hipStream_t st);
+// statistics from the per-tile column sums a GEMM left behind (stat_partial of ConvArgs)
+void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
+                                  int groups, int tile_rows, int gemm_rps, hipStream_t st);
 void launch_bn_running(const NormArgs& a, hipStream_t st);
 void launch_bn_from_running(const NormArgs& a, hipStream_t st);   // mean/rstd <- running statistics
 template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st);

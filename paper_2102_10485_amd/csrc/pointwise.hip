@@ -192,66 +192,47 @@ __device__ inline void store4(bf16_t* p, const float (&v)[4]) {
   *reinterpret_cast<uint2*>(p) = t;
 }
 
-// Block (channel chunk of 64, group): 16 row lanes x 16 channel lanes of 4 channels.  Two passes over the
-// group's slab (mean, then centred second moment), the second served from cache.
-template <typename T>
-__global__ __launch_bounds__(256) void bn_stats_kernel(NormArgs a) {
-  __shared__ float red[16][64];
-  __shared__ float smean[64];
-  const int l = blockIdx.y % a.L, sidx = blockIdx.y / a.L;
-  const int seg = a.seg_first + sidx;
+// mean / var / rstd from what the producing GEMM left per tile and column: (sum, sum of squared deviations from the
+// tile's mean).  Tiles (and output phases, and column runs) of one (segment, model) are merged in a fixed order
+// with the pairwise update  mean += d n_t/(n+n_t),  M2 += M2_t + d^2 n n_t/(n+n_t),  d = mean_t - mean.
+// The GEMM's N columns are `groups` runs of the C channels (the linear layer feeding G's first BatchNorm has one
+// run per pixel of the first feature map; the convolutions have one).
+__global__ void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict__ partial, const int* __restrict__ tpre,
+                                             int ub_tiles, int nphase, int groups, int tile_rows, int gemm_rps) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)a.nseg * a.L * a.C) return;
+  const int c = (int)(idx % a.C);
+  const int l = (int)((idx / a.C) % a.L);
+  const int sidx = (int)(idx / ((long long)a.C * a.L));
   const int cnt = a.offs[l + 1] - a.offs[l];
-  const int g = seg * a.L + l;
-  const int c0 = blockIdx.x * 64;
-  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
-  const long long rows = (long long)cnt * a.rps;
-  if (rows == 0) return;
-  const T* x = static_cast<const T*>(a.x) + ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * 4;
-  float s[4] = {0.f, 0.f, 0.f, 0.f};
-  for (long long r = rl; r < rows; r += 16) {
-    float v[4];
-    load4(x + r * a.C, v);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) s[e] += v[e];
-  }
-#pragma unroll
-  for (int e = 0; e < 4; ++e) red[rl][cl * 4 + e] = s[e];
-  __syncthreads();
-  if (threadIdx.x < 64) {
-    float t = 0.f;
-    for (int i = 0; i < 16; ++i) t += red[i][threadIdx.x];
-    smean[threadIdx.x] = t / (float)rows;
-  }
-  __syncthreads();
-  float mu[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) { mu[e] = smean[cl * 4 + e]; s[e] = 0.f; }
-  for (long long r = rl; r < rows; r += 16) {
-    float v[4];
-    load4(x + r * a.C, v);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { const float d = v[e] - mu[e]; s[e] += d * d; }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < 4; ++e) red[rl][cl * 4 + e] = s[e];
-  __syncthreads();
-  if (threadIdx.x < 64) {
-    float t = 0.f;
-    for (int i = 0; i < 16; ++i) t += red[i][threadIdx.x];
-    const float var = t / (float)rows;
-    const long long o = (long long)g * a.C + c0 + threadIdx.x;
-    a.mean[o] = smean[threadIdx.x];
-    a.var[o] = var;
-    a.rstd[o] = 1.0f / sqrtf(var + a.eps);
-  }
+  if (cnt == 0) return;
+  const int rows = cnt * gemm_rps;                     // rows of this model in the GEMM's row space (per phase)
+  float n = 0.f, mean = 0.f, m2 = 0.f;
+  for (int ph = 0; ph < nphase; ++ph)
+    for (int t = tpre[l]; t < tpre[l + 1]; ++t) {
+      const float nt = (float)min(tile_rows, rows - (t - tpre[l]) * tile_rows);
+      for (int g = 0; g < groups; ++g) {
+        const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
+        const float d = partial[o] / nt - mean;
+        const float nn = n + nt;
+        mean += d * (nt / nn);
+        m2 += partial[o + 1] + d * d * (n * nt / nn);
+        n = nn;
+      }
+    }
+  const float var = m2 / n;
+  const long long o = (long long)((a.seg_first + sidx) * a.L + l) * a.C + c;
+  a.mean[o] = mean;
+  a.var[o] = var;
+  a.rstd[o] = 1.0f / sqrtf(var + a.eps);
 }
-template <typename T> void launch_bn_stats(const NormArgs& a, hipStream_t st) {
-  if (a.nseg == 0) return;
-  hipLaunchKernelGGL((bn_stats_kernel<T>), dim3(a.C / 64, a.L * a.nseg), dim3(256), 0, st, a);
+void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
+                                  int groups, int tile_rows, int gemm_rps, hipStream_t st) {
+  const long long tot = (long long)a.nseg * a.L * a.C;
+  if (tot == 0) return;
+  hipLaunchKernelGGL(bn_stats_from_partial_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a, partial, tpre,
+                     ub_tiles, nphase, groups, tile_rows, gemm_rps);
 }
-template void launch_bn_stats<float>(const NormArgs&, hipStream_t);
-template void launch_bn_stats<bf16_t>(const NormArgs&, hipStream_t);
 
 // running <- (1 - momentum) running + momentum * batch, once per segment in order; unbiased variance stored.
 __global__ void bn_running_kernel(NormArgs a) {

@@ -1,0 +1,109 @@
+"""Full-size workloads in the launch configuration bench.py times, checked on sampled outputs against stored
+oracle results (tests/golden/config*.npz, written by tests/golden/make_golden.py from the CPU oracle alone).
+
+The label models are independent (Eq. 5), so the oracle is run for a few of them (first / last, or largest /
+median / smallest batch) while the GPU steps all of them; routing is checked bit for bit for every sample.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2102_10485_amd import binding, synth
+from tests import gpu_util as U
+from tests.golden import make_golden as MG
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def run_config(config, precision):
+    torch = U.torch_mod()
+    path = os.path.join(GOLD, "config%d.npz" % config)
+    if not os.path.exists(path):
+        pytest.skip("no stored oracle results for config %d" % config)
+    gold = np.load(path)
+    plan = MG.PLAN[config]
+    work = synth.Workload(config)
+    models = [int(m) for m in gold["models"]]
+    assert np.array_equal(gold["batch_sizes"], work.batch_sizes)
+    prec = binding.BF16 if precision == "bf16" else binding.FP32
+    tol = 2e-2 if precision == "bf16" else 1e-4
+    gan = binding.Gan(binding.make_config(work.spec, work.n_models, work.n_labels, work.n, prec),
+                      torch.cuda.current_stream().cuda_stream)
+    for l in range(work.n_models):
+        for which in (0, 1):
+            gan.set_params(which, l, work.params(which, l))
+    pos = {which: MG.sample_positions(work.spec, which) for which in (0, 1)}
+    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
+    d_lab = torch.from_numpy(lab).cuda()
+    worst = {}
+    for step in range(1, plan["steps"] + 1):
+        z, x = work.noise(), work.images(lab)
+        dz, dx = torch.from_numpy(z).cuda(), torch.from_numpy(x).cuda()
+        gan.train_step(d_lab.data_ptr(), dz.data_ptr(), dx.data_ptr(), work.n)
+        jd, jg, cnt = gan.get_losses()
+        assert np.array_equal(cnt, work.batch_sizes if work.n_models > 1 else [work.n])
+        if step == 1:
+            # routing, every sample: the stable partition written out on the host
+            perm, offs = gan.get_routing(work.n)
+            mdl = lab if work.n_models > 1 else np.zeros_like(lab)
+            assert np.array_equal(perm, np.argsort(mdl, kind="stable"))
+            assert np.array_equal(offs, np.concatenate([[0], np.cumsum(np.bincount(mdl, minlength=work.n_models))]))
+
+        def bound(tag_quantity_drift):
+            # fp32 from the second iteration on: widened by the measured drift of the single-precision oracle
+            if precision == "fp32" and step >= 2 and plan["single"]:
+                return max(tol, 4.0 * tag_quantity_drift)
+            return tol
+
+        for i, l in enumerate(models):
+            for name, got in (("jd", jd[l]), ("jg", jg[l])):
+                ref = gold["f64_%s_%d" % (name, step)][i]
+                drift = abs(gold["f32_%s_%d" % (name, step)][i] - ref) / abs(ref) if plan["single"] else 0.0
+                err = abs(got - ref) / abs(ref)
+                worst[name] = max(worst.get(name, 0), err)
+                assert err <= bound(drift), (config, step, l, name, got, ref, drift)
+        if step in plan["snaps"]:
+            for l in models:
+                for which in (0, 1):
+                    th = gan.get_params(which, l)
+                    all_got, all_ref, all_f32 = [], [], []
+                    for name, idx in pos[which].items():
+                        ref = gold["f64_p_%d_%d_%d_%s" % (step, l, which, name)]
+                        f32 = gold["f32_p_%d_%d_%d_%s" % (step, l, which, name)] if plan["single"] else ref
+                        got = th[idx]
+                        floor = 0.02 * np.sqrt(idx.size)
+                        err = U.rel_l2(got, ref, floor=floor)
+                        assert err <= bound(U.rel_l2(f32, ref, floor=floor)), (config, step, l, which, name, err)
+                        all_got.append(got); all_ref.append(ref); all_f32.append(f32)
+                    g, r, s = (np.concatenate(a) for a in (all_got, all_ref, all_f32))
+                    err = U.rel_l2(g, r)
+                    worst["params"] = max(worst.get("params", 0), err)
+                    assert err <= bound(U.rel_l2(s, r)), (config, step, l, which, err)
+    gan.close()
+    print("config %d %s worst relative errors: %s" % (config, precision, worst))
+
+
+def test_config0_fp32():
+    run_config(0, "fp32")
+
+
+def test_config1_fp32():
+    run_config(1, "fp32")
+
+
+def test_config1_bf16():
+    run_config(1, "bf16")
+
+
+def test_config2_bf16():
+    run_config(2, "bf16")
+
+
+def test_config3_bf16():
+    run_config(3, "bf16")
+
+
+def test_config4_bf16_ragged():
+    run_config(4, "bf16")
