@@ -57,3 +57,10 @@ def tensor_errors(spec, which, got, ref, scale_floor):
         n = int(np.prod(shape))
         out[name] = rel_l2(got[sl], ref[sl], floor=scale_floor * np.sqrt(n))
     return out
+
+
+def one_flip(numel, lr=2e-4, scale=0.02):
+    """Relative L2 (against the floored norm scale*sqrt(numel)) of ONE element landing on the other side of an
+    Adam step: on the first steps every parameter moves by about lr*sign(g), and an element whose gradient is below
+    rounding noise legitimately takes either sign.  Per-tensor checks allow one such element (x1.1 for slack)."""
+    return 1.1 * 2.0 * lr / (scale * np.sqrt(numel))

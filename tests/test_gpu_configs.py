@@ -37,7 +37,7 @@ def run_config(config, precision):
     pos = {which: MG.sample_positions(work.spec, which) for which in (0, 1)}
     lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
     d_lab = torch.from_numpy(lab).cuda()
-    worst = {}
+    worst, failures, table = {}, [], []
     for step in range(1, plan["steps"] + 1):
         z, x = work.noise(), work.images(lab)
         dz, dx = torch.from_numpy(z).cuda(), torch.from_numpy(x).cuda()
@@ -51,10 +51,12 @@ def run_config(config, precision):
             assert np.array_equal(perm, np.argsort(mdl, kind="stable"))
             assert np.array_equal(offs, np.concatenate([[0], np.cumsum(np.bincount(mdl, minlength=work.n_models))]))
 
-        def bound(tag_quantity_drift):
-            # fp32 from the second iteration on: widened by the measured drift of the single-precision oracle
-            if precision == "fp32" and step >= 2 and plan["single"]:
-                return max(tol, 4.0 * tag_quantity_drift)
+        def bound(drift):
+            # From the second iteration on the bound is widened where the iteration itself amplifies rounding: the
+            # distance of the single-precision oracle from the fp64 oracle on the same inputs measures that
+            # amplification.  fp32 storage: 10 x that drift (another fp32 summation order); bf16 storage: 20 x.
+            if step >= 2 and plan["single"]:
+                return max(tol, (10.0 if precision == "fp32" else 20.0) * drift)
             return tol
 
         for i, l in enumerate(models):
@@ -63,7 +65,9 @@ def run_config(config, precision):
                 drift = abs(gold["f32_%s_%d" % (name, step)][i] - ref) / abs(ref) if plan["single"] else 0.0
                 err = abs(got - ref) / abs(ref)
                 worst[name] = max(worst.get(name, 0), err)
-                assert err <= bound(drift), (config, step, l, name, got, ref, drift)
+                table.append((step, l, name, float(got), float(ref), err, drift))
+                if err > bound(drift):
+                    failures.append((config, step, l, name, float(got), float(ref), err, drift))
         if step in plan["snaps"]:
             for l in models:
                 for which in (0, 1):
@@ -75,14 +79,20 @@ def run_config(config, precision):
                         got = th[idx]
                         floor = 0.02 * np.sqrt(idx.size)
                         err = U.rel_l2(got, ref, floor=floor)
-                        assert err <= bound(U.rel_l2(f32, ref, floor=floor)), (config, step, l, which, name, err)
+                        if err > max(bound(U.rel_l2(f32, ref, floor=floor)), U.one_flip(idx.size)):
+                            failures.append((config, step, l, which, name, err, U.rel_l2(f32, ref, floor=floor)))
                         all_got.append(got); all_ref.append(ref); all_f32.append(f32)
                     g, r, s = (np.concatenate(a) for a in (all_got, all_ref, all_f32))
                     err = U.rel_l2(g, r)
                     worst["params"] = max(worst.get("params", 0), err)
-                    assert err <= bound(U.rel_l2(s, r)), (config, step, l, which, err)
+                    table.append((step, l, "params%d" % which, 0.0, 0.0, err, U.rel_l2(s, r)))
+                    if err > bound(U.rel_l2(s, r)):
+                        failures.append((config, step, l, which, "params", err, U.rel_l2(s, r)))
     gan.close()
+    for row in table:
+        print("config %d %s step %d model %d %-8s got %.6g ref %.6g err %.2e (fp32-oracle drift %.2e)" % ((config, precision) + row))
     print("config %d %s worst relative errors: %s" % (config, precision, worst))
+    assert not failures, failures
 
 
 def test_config0_fp32():
@@ -99,6 +109,10 @@ def test_config1_bf16():
 
 def test_config2_bf16():
     run_config(2, "bf16")
+
+
+def test_config2_fp32():
+    run_config(2, "fp32")
 
 
 def test_config3_bf16():

@@ -8,7 +8,7 @@ network (strict) and per tensor with the denominator floored at the initialisati
 The two-player iteration amplifies rounding from step to step (Adam divides by the root of the second moment, so
 a parameter whose gradient is near zero moves by about lr in a direction decided by the last bits).  The oracle's
 own loops compiled in single precision drift from the double-precision result by more than 1e-4 after two or
-three iterations.  From the second iteration on the fp32 bound is therefore max(1e-4, 4 x that drift), the drift
+three iterations.  From the second iteration on the fp32 bound is therefore max(1e-4, 10 x that drift), the drift
 being measured in the same test on the same inputs; the first iteration is always held to 1e-4.
 """
 import numpy as np
@@ -67,7 +67,7 @@ class Pair:
         tol = TOL[self.prec]
         if self.o32 is None or self.nsteps < 2:
             return tol
-        return max(tol, 4.0 * drift)
+        return max(tol, 10.0 * drift)
 
     def compare(self, what=""):
         tol = TOL[self.prec]
@@ -93,7 +93,9 @@ class Pair:
                 assert e <= b, (what, "params", which, l, e, b)
                 per = U.tensor_errors(self.spec, which, got, ref, 0.02)
                 dr = U.tensor_errors(self.spec, which, sng, ref, 0.02)
-                bad = {k: (v, self.bound(dr[k])) for k, v in per.items() if v > self.bound(dr[k])}
+                numel = {k: int(np.prod(sh)) for k, (_, sh) in synth.param_slices(self.spec, which).items()}
+                bad = {k: (v, self.bound(dr[k])) for k, v in per.items()
+                       if v > max(self.bound(dr[k]), U.one_flip(numel[k]))}
                 assert not bad, (what, which, l, bad)
         return worst
 
