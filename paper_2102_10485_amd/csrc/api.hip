@@ -322,9 +322,9 @@ void refresh_shadows(gan_ctx* c) {
 template <typename T>
 void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, const void* W, long long wstride, void* Out,
                const void* Aux, int C, int N, int Hin, int Hr, int seg_first, int nseg, int n, int w_nstride = 0,
-               const float* bias = nullptr, long long bias_stride = 0, double flops_alg = -1.0, bool stats = false) {
+               double flops_alg = -1.0, bool stats = false) {
   ConvArgs a = {};
-  a.A = A; a.W = W; a.Out = Out; a.Aux = Aux; a.bias = bias; a.bias_stride = bias_stride; a.w_nstride = w_nstride ? w_nstride : N;
+  a.A = A; a.W = W; a.Out = Out; a.Aux = Aux; a.w_nstride = w_nstride ? w_nstride : N;
   const int tr = layer_tile_rows(c, N, Hr * Hr);
   a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, tr); a.tile_rows = tr;
   a.w_stride = wstride; a.L = c->L; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n;
@@ -340,7 +340,8 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
   const double bytes = sizeof(T) * (in_elems + rows * N + (double)c->L * (mode == MODE_DENSE ? 1 : 16) * C * N);
   char detail[64];
   snprintf(detail, sizeof(detail), "[C%d N%d H%d seg%d]", C, N, Hr, nseg);
-  Scope s(c, name, flops, bytes, detail);
+  (void)name;
+  Scope s(c, conv_variant_name(mode, epi, a), flops, bytes, detail);
   launch_conv<T>(mode, epi, a, c->st);
 }
 
@@ -357,7 +358,8 @@ void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small
   const double bytes = sizeof(T) * (big_elems + rows * Cs) + 4.0 * c->L * ntaps * Cb * Cs;
   char detail[64];
   snprintf(detail, sizeof(detail), "[Cb%d Cs%d H%d seg%d]", Cb, Cs, Hs, nseg);
-  Scope s(c, name, flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes, detail);
+  (void)name;
+  Scope s(c, wgrad_variant_name(a), flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes, detail);
   launch_wgrad<T>(a, c->st);
 }
 
@@ -422,6 +424,19 @@ void im2col_call(gan_ctx* c, const ConvLayer& cl, const void* img, const float* 
   launch_im2col<T>(a, c->st);
 }
 
+// transposed conv onto the image side: feat (absolute segment seg) -> out (same segment indexing)
+template <typename T>
+void up_img_call(gan_ctx* c, Net& net, const ConvLayer& cl, const void* feat, void* out, const void* aux, int mode, int seg, int n) {
+  UpImgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.feat = feat; a.w = (const T*)net.shadow_u + cl.w; a.w_stride = net.P; a.out = out; a.aux = aux;
+  a.bias = mode == 1 ? net.theta + cl.bias : nullptr; a.bias_stride = net.P;
+  a.offs = c->rb.offs; a.sample_model = c->rb.sample_model; a.L = c->L; a.n = n; a.seg = seg; a.seg_samples = n;
+  a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Hs = cl.Hs; a.mode = mode;
+  Scope s(c, "up_img", img_flops(cl, n, 1), sizeof(T) * (double)n * cl.Hs * cl.Hs * (cl.Cs + 4.0 * cl.Cb * (mode == 2 ? 2 : 1)));
+  launch_up_img<T>(a, c->st);
+}
+
 PackArgs pack_args(gan_ctx* c, Net& net, const ConvLayer& cl, int Kc, int nslot, void* wp) {
   PackArgs a;
   memset(&a, 0, sizeof(a));
@@ -438,7 +453,7 @@ void g_forward(gan_ctx* c, int n, bool use_running, bool update_running) {
   Net& G = c->G;
   const float relu = 0.f;
   conv_call<T>(c, "gemm_dense", MODE_DENSE, EPI_NONE, c->zin, (const T*)G.shadow_u + G.fc_w, G.P, c->gpre[0], nullptr, G.Kp, G.J,
-               1, 1, 0, 1, n, 0, nullptr, 0, -1.0, !use_running);
+               1, 1, 0, 1, n, 0, -1.0, !use_running);
   bn_forward<T>(c, norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
                                 c->g_sums[0], 0, 1, n, relu),
                 c->gpre[0], c->gact[0], use_running, update_running, 1, 1, G.h0 * G.h0);
@@ -446,16 +461,16 @@ void g_forward(gan_ctx* c, int n, bool use_running, bool update_running) {
   for (int i = 0; i + 1 < nl; ++i) {
     const ConvLayer& cl = G.conv[i];
     conv_call<T>(c, "gemm_up", MODE_UP, EPI_NONE, c->gact[i], (const T*)G.shadow_u + cl.w, G.P, c->gpre[i + 1], nullptr, cl.Cs, cl.Cb,
-                 cl.Hs, cl.Hs, 0, 1, n, 0, nullptr, 0, -1.0, !use_running);
+                 cl.Hs, cl.Hs, 0, 1, n, 0, -1.0, !use_running);
     bn_forward<T>(c, norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
                                   c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, relu),
                   c->gpre[i + 1], c->gact[i + 1], use_running, update_running, cl.Hs * cl.Hs, 4);
   }
   // last transposed conv (+bias, tanh) straight into the fake half of D's image buffer
   const ConvLayer& cl = G.conv[nl - 1];
+  // G's samples sit in segment 0, the fake images in segment 1 of D's image buffer: offset the output pointer
   T* fake = (T*)c->xd + (long long)n * 4 * cl.Hs * cl.Hs * cl.Cb;
-  conv_call<T>(c, "gemm_up_img", MODE_UP, EPI_BIAS_TANH, c->gact[nl - 1], (const T*)G.shadow_u + cl.w, G.P, fake, nullptr, cl.Cs,
-               cl.Cb, cl.Hs, cl.Hs, 0, 1, n, cl.CBT, G.theta + cl.bias, G.P);
+  up_img_call<T>(c, G, cl, c->gact[nl - 1], fake, nullptr, 1, 0, n);
 }
 
 template <typename T>
@@ -465,12 +480,12 @@ void d_forward(gan_ctx* c, int n, int seg_first, int nseg, bool update_running) 
   // first conv (+label maps, bias, LeakyReLU) as a row-by-row GEMM over the patch matrix
   const ConvLayer& c1 = D.conv[0];
   conv_call<T>(c, "gemm_dense_img", MODE_DENSE, EPI_LRELU, c->colD, c->wpD, (long long)c1.Cs * c->KcD, c->dact[0], nullptr, c->KcD,
-               c1.Cs, 1, c1.Hs, seg_first, nseg, n, 0, nullptr, 0, img_flops(c1, n, nseg));
+               c1.Cs, 1, c1.Hs, seg_first, nseg, n, 0, img_flops(c1, n, nseg));
   const int nl = (int)D.conv.size();
   for (int j = 1; j < nl; ++j) {
     const ConvLayer& cl = D.conv[j];
     conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->dact[j - 1], (const T*)D.shadow_d + cl.w, D.P, c->dpre[j], nullptr, cl.Cb,
-                 cl.Cs, 2 * cl.Hs, cl.Hs, seg_first, nseg, n, 0, nullptr, 0, -1.0, true);
+                 cl.Cs, 2 * cl.Hs, cl.Hs, seg_first, nseg, n, 0, -1.0, true);
     bn_forward<T>(c, norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
                                   c->d_sums[j], seg_first, nseg, n, slope),
                   c->dpre[j], c->dact[j], false, update_running, cl.Hs * cl.Hs, 1);
@@ -527,9 +542,8 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
                   img_flops(c1, n, nseg), IMG_KSPLIT);
     launch_unpack_dw(pack_args(c, D, c1, c->KcD, c->nslot, c->wpD), c->st);
   }
-  if (to_image)   // d cost / d fake, times the tanh derivative
-    conv_call<T>(c, "gemm_up_img", MODE_UP, EPI_TANH_BWD, c->bufA, (const T*)D.shadow_u + c1.w, D.P, c->dimg, c->xd, c1.Cs, c1.Cb,
-                 c1.Hs, c1.Hs, seg_first, nseg, n, c1.CBT);
+  if (to_image)   // d cost / d fake, times the tanh derivative (fake segment only)
+    up_img_call<T>(c, D, c1, c->bufA, c->dimg, c->xd, 2, 1, n);
 }
 
 // Backward through G from dimg (fake segment) = d cost / d (pre-tanh output).
@@ -549,7 +563,7 @@ void g_backward(gan_ctx* c, int n) {
     b.L = c->L; b.CB = last.Cb; b.HW = 4 * last.Hs * last.Hs;
     launch_img_bias_grad<T>(b, c->st);
     conv_call<T>(c, "gemm_dense_img", MODE_DENSE, EPI_NONE, c->colG, c->wpG, (long long)last.Cs * c->KcG, c->bufA, nullptr, c->KcG,
-                 last.Cs, 1, last.Hs, 0, 1, n, 0, nullptr, 0, img_flops(last, n, 1));
+                 last.Cs, 1, last.Hs, 0, 1, n, 0, img_flops(last, n, 1));
   }
   for (int i = nl - 2; i >= 0; --i) {
     const ConvLayer& cl = G.conv[i];
@@ -651,7 +665,6 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
       geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // forward (up)
       geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // data gradient (down)
     }
-    geom_id(c, gl.Hs * gl.Hs, layer_tile_rows(c, gl.Cb, gl.Hs * gl.Hs));               // last layer forward (narrow)
     geom_id(c, gl.Hs * gl.Hs, layer_tile_rows(c, gl.Cs, gl.Hs * gl.Hs));               // its data gradient (patch GEMM)
     for (size_t j = 1; j < c->D.conv.size(); ++j) {
       const ConvLayer& cl = c->D.conv[j];
@@ -659,7 +672,6 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
       geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // data gradient (up)
     }
     geom_id(c, d1.Hs * d1.Hs, layer_tile_rows(c, d1.Cs, d1.Hs * d1.Hs));               // first conv (patch GEMM)
-    geom_id(c, d1.Hs * d1.Hs, layer_tile_rows(c, d1.Cb, d1.Hs * d1.Hs));               // its data gradient (narrow)
   }
   RouteBuffers& rb = c->rb;
   ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&

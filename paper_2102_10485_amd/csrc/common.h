@@ -34,7 +34,7 @@ template <> __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
 }
 
 enum ConvMode { MODE_DOWN = 0, MODE_UP = 1, MODE_DENSE = 2 };
-enum Epilogue { EPI_NONE = 0, EPI_ACT_BWD = 1, EPI_LRELU = 2, EPI_BIAS_TANH = 3, EPI_TANH_BWD = 4 };
+enum Epilogue { EPI_NONE = 0, EPI_ACT_BWD = 1, EPI_LRELU = 2 };
 enum Act { ACT_RELU = 0, ACT_LRELU = 1 };
 
 // Arguments of the grouped implicit-GEMM forward-type kernel (down / up / dense).
@@ -42,11 +42,9 @@ struct ConvArgs {
   const void* A;         // gathered activations (storage type)
   const void* W;         // weights of model 0, K-contiguous: [tap][N][C] (storage type)
   void* Out;             // output activations (storage type)
-  const void* Aux;       // EPI_ACT_BWD / EPI_TANH_BWD: saved forward output at the output position (storage type)
+  const void* Aux;       // EPI_ACT_BWD: saved forward output at the output position (storage type)
   float* stat_partial;   // if set (wide tiles): per-tile column sums of the output and of its squared deviations from the tile's column mean,
                          // [((phase * nseg + segment) * ub_tiles + tile) * N + col][2], for the BatchNorm that follows
-  const float* bias;     // EPI_BIAS_TANH: per output channel, model 0; bias_stride elements between models
-  long long bias_stride;
   int w_nstride;         // rows per tap in the weight block (>= N)
   const int* offs;       // [L+1] sample offsets of the models inside one segment
   const int* tpre;       // [L+1] prefix of M-tiles per model for this geometry
@@ -80,6 +78,9 @@ struct WgradArgs {
 
 template <typename T> void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st);
 template <typename T> void launch_wgrad(const WgradArgs& a, hipStream_t st);
+// names of the kernel instantiations the two launchers pick (per-kernel timing)
+const char* conv_variant_name(int mode, int epi, const ConvArgs& a);
+const char* wgrad_variant_name(const WgradArgs& a);
 
 // rows per M-tile the forward-type kernel will use for n_out output channels and about rows_per_model rows
 int conv_tile_rows(int n_out, long long rows_per_model_hint);

@@ -15,6 +15,7 @@
 // storage) or v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
 // The next K-chunk travels global -> registers while the MFMAs of the current one run, then registers -> the
 // other LDS buffer: one barrier per chunk.
+#include <stdio.h>
 #include <stdlib.h>
 
 #include "common.h"
@@ -39,10 +40,8 @@ struct Tile {
 typedef Tile<256, 256, 2, 4> TileBig;     // 512 threads, wave tile 128 x 64
 typedef Tile<256, 128, 4, 2> TileMid;     // 512 threads, wave tile 64 x 64
 typedef Tile<128, 128, 2, 2> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model)
-typedef Tile<128, 32, 4, 1> TileNarrow;   // image-side outputs (N <= 32)
 
 int conv_tile_rows(int n_out, long long rows_per_model_hint) {
-  if (n_out <= 32) return TileNarrow::BM;
   if (rows_per_model_hint > 0 && rows_per_model_hint <= 128) return TileSmall::BM;
   return TileBig::BM;
 }
@@ -256,7 +255,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   __syncthreads();
   T* __restrict__ Out = static_cast<T*>(p.Out);
   const T* __restrict__ Aux = static_cast<const T*>(p.Aux);
-  if (BN >= 64 && p.stat_partial) {
+  if (p.stat_partial) {
     // For the BatchNorm that follows: per column of this tile, the sum of the fp32 results and the sum of squared
     // deviations from the tile's own column mean (merged across tiles by the pairwise-update formula, which keeps
     // the variance free of the E[x^2] - mean^2 cancellation).  Fixed order everywhere.
@@ -305,8 +304,8 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     }
     // (the patches below live in As, the sums in Bs: no barrier needed between them)
   }
-  if (BN >= 64) {
-    // Wide tiles: each wave passes its 32 x (TN*32) blocks through a private LDS patch so that every lane stores
+  {
+    // Each wave passes its 32 x (TN*32) blocks through a private LDS patch so that every lane stores
     // 16 contiguous bytes of an output row (full N is a multiple of 64 for these tiles).
     constexpr int WCOLS = TN * 32;
     constexpr int PSTRIDE = WCOLS * (int)sizeof(T) + 16;               // bytes per patch row
@@ -347,36 +346,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
       }
       __syncthreads();
     }
-    return;
   }
-#pragma unroll
-  for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      const int col = nt * BN + wn * TN * 32 + tn * 32 + (lane & 31);
-      if (col >= N) continue;
-      float bias = 0.f;
-      if (EPI == EPI_BIAS_TANH) bias = p.bias[(long long)l * p.bias_stride + col];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int rr = wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        const long long o = orow[rr];
-        if (o < 0) continue;
-        float val = acc[tm][tn][e];
-        if (EPI == EPI_ACT_BWD) {
-          const float f = to_float(Aux[o * N + col]);
-          val = f > 0.f ? val : val * p.slope;
-        } else if (EPI == EPI_LRELU) {
-          val = val > 0.f ? val : val * p.slope;
-        } else if (EPI == EPI_BIAS_TANH) {
-          val = tanhf(val + bias);
-        } else if (EPI == EPI_TANH_BWD) {         // times 1 - y^2, y the saved tanh output
-          const float y = to_float(Aux[o * N + col]);
-          val *= (1.f - y * y);
-        }
-        store_out(Out + o * N + col, val);
-      }
-    }
 }
 
 template <typename T, int MODE, int EPI, typename TL>
@@ -402,18 +372,30 @@ template <typename T>
 void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
   // the kernel's assumptions, checked before anything is launched
   if (!a.A || !a.W || !a.Out || !a.offs || !a.tpre || a.N < 1 || a.w_nstride < a.N || a.C % (BKB / (int)sizeof(T)) != 0 ||
-      ((epi == EPI_ACT_BWD || epi == EPI_TANH_BWD) && !a.Aux) || (epi == EPI_BIAS_TANH && !a.bias))
+      (epi == EPI_ACT_BWD && !a.Aux))
     abort();
-  const bool narrow = a.N <= 32;
-  if (mode == MODE_DOWN && epi == EPI_NONE && !narrow) return launch_wide<T, MODE_DOWN, EPI_NONE>(a, st);
-  if (mode == MODE_UP && epi == EPI_NONE && !narrow) return launch_wide<T, MODE_UP, EPI_NONE>(a, st);
-  if (mode == MODE_UP && epi == EPI_ACT_BWD && !narrow) return launch_wide<T, MODE_UP, EPI_ACT_BWD>(a, st);
-  if (mode == MODE_UP && epi == EPI_NONE && narrow) return launch_one<T, MODE_UP, EPI_NONE, TileNarrow>(a, st);
-  if (mode == MODE_UP && epi == EPI_BIAS_TANH && narrow) return launch_one<T, MODE_UP, EPI_BIAS_TANH, TileNarrow>(a, st);
-  if (mode == MODE_UP && epi == EPI_TANH_BWD && narrow) return launch_one<T, MODE_UP, EPI_TANH_BWD, TileNarrow>(a, st);
-  if (mode == MODE_DENSE && epi == EPI_NONE && !narrow) return launch_wide<T, MODE_DENSE, EPI_NONE>(a, st);
-  if (mode == MODE_DENSE && epi == EPI_LRELU && !narrow) return launch_wide<T, MODE_DENSE, EPI_LRELU>(a, st);
+  if (a.N < 64) abort();                        // image-side outputs have their own kernel
+  if (mode == MODE_DOWN && epi == EPI_NONE) return launch_wide<T, MODE_DOWN, EPI_NONE>(a, st);
+  if (mode == MODE_UP && epi == EPI_NONE) return launch_wide<T, MODE_UP, EPI_NONE>(a, st);
+  if (mode == MODE_UP && epi == EPI_ACT_BWD) return launch_wide<T, MODE_UP, EPI_ACT_BWD>(a, st);
+  if (mode == MODE_DENSE && epi == EPI_NONE) return launch_wide<T, MODE_DENSE, EPI_NONE>(a, st);
+  if (mode == MODE_DENSE && epi == EPI_LRELU) return launch_wide<T, MODE_DENSE, EPI_LRELU>(a, st);
   abort();   // a combination no caller uses
+}
+// Name of the kernel instantiation launch_conv picks (for per-kernel timing): mode, epilogue, tile.
+const char* conv_variant_name(int mode, int epi, const ConvArgs& a) {
+  static const char* modes[3] = {"down", "up", "dense"};
+  static const char* epis[3] = {"", "+actbwd", "+lrelu"};
+  static char names[3][3][3][48];
+  const int tile = a.tile_rows == TileSmall::BM ? 2 : (a.N % 256 == 0 ? 0 : 1);
+  static const char* tiles[3] = {"256x256", "256x128", "128x128"};
+  char* n = names[mode][epi][tile];
+  if (!n[0]) snprintf(n, 48, "gemm_%s%s<%s>", modes[mode], epis[epi], tiles[tile]);
+  return n;
+}
+const char* wgrad_variant_name(const WgradArgs& a) {
+  if (a.ntaps * a.Cb <= 64) return "wgrad<64x128>";
+  return a.Cs % 256 == 0 ? "wgrad<256x256>" : "wgrad<256x128>";
 }
 template void launch_conv<float>(int, int, const ConvArgs&, hipStream_t);
 template void launch_conv<bf16_t>(int, int, const ConvArgs&, hipStream_t);

@@ -12,9 +12,14 @@
 // 16*CB tap columns, one indicator column per (label slot, position class) and one constant column: the packed
 // weight holds the summed label-map taps and the bias there, so the forward GEMM adds them and the weight-
 // gradient GEMM returns the class sums and the bias gradient with no extra pass over the feature tensor.
+#include <stdlib.h>
+
 #include "kernels.h"
 
 namespace gan {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 template <typename T> __device__ inline float ldf(const T* p) { return to_float(*p); }
 
@@ -206,5 +211,143 @@ template <typename T> void launch_img_bias_grad(const ImgBiasArgs& a, hipStream_
 }
 template void launch_img_bias_grad<float>(const ImgBiasArgs&, hipStream_t);
 template void launch_img_bias_grad<bf16_t>(const ImgBiasArgs&, hipStream_t);
+
+// ---------------------------------------------------------------------------------------------------------
+// Transposed convolution onto the image (or the data gradient of D's first convolution, which is the same
+// operation): img[n, 2y+py, 2x+px][cb] = sum over the 4 taps of that phase and cs of feat[n, y+dy, x+dx][cs] * w[tap][cb][cs].
+// One block = an 8 x 8 patch of feature pixels of one sample with its 1-pixel halo held in LDS, so every feature
+// row is read from memory once for all 4 phases x 4 taps; wave p computes output phase p on MFMA with the (at
+// most 4) image channels as the N side of a 32 x 32 tile.  Epilogue: bias + tanh, or times (1 - y^2).
+// ---------------------------------------------------------------------------------------------------------
+__device__ inline void up_mma(floatx16& acc, const uint4& a, const uint4& b, bf16_t) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+__device__ inline void up_mma(floatx16& acc, const uint4& a, const uint4& b, float) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+constexpr int UP_TS = 8;                    // patch side (feature pixels)
+constexpr int UP_HALO = UP_TS + 2;
+
+template <typename T, int CS>
+__global__ __launch_bounds__(256) void up_img_kernel(UpImgArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int Cs = CS;
+  const int CB = a.CB, Hs = a.Hs, Hb = 2 * a.Hs;
+  constexpr int rowB = Cs * (int)sizeof(T) + 16;              // bytes per halo row / weight row in LDS
+  unsigned char* Fl = lds;                                    // [UP_HALO*UP_HALO][rowB]
+  unsigned char* Wl = lds + UP_HALO * UP_HALO * rowB;         // [16 taps][CB][rowB]
+  const int j = blockIdx.y;                                   // routed sample inside the segment
+  if (j >= a.offs[a.L]) return;
+  const int l = a.sample_model[j];
+  const long long sample = (long long)a.seg * a.seg_samples + j;
+  const int tiles = (Hs + UP_TS - 1) / UP_TS;
+  const int y0 = (blockIdx.x / tiles) * UP_TS, x0 = (blockIdx.x % tiles) * UP_TS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int cpr = Cs * (int)sizeof(T) / 16;               // 16-byte chunks per row
+  const T* feat = static_cast<const T*>(a.feat) + sample * (long long)Hs * Hs * Cs;
+  for (int i = tid; i < UP_HALO * UP_HALO * cpr; i += 256) {
+    const int hr = i / cpr, ch = i - hr * cpr;
+    const int y = y0 - 1 + hr / UP_HALO, x = x0 - 1 + hr % UP_HALO;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if ((unsigned)y < (unsigned)Hs && (unsigned)x < (unsigned)Hs)
+      v = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(feat + ((long long)y * Hs + x) * Cs) + ch * 16);
+    *reinterpret_cast<uint4*>(Fl + hr * rowB + ch * 16) = v;
+  }
+  const T* w = static_cast<const T*>(a.w) + (long long)l * a.w_stride;
+  for (int i = tid; i < 16 * CB * cpr; i += 256) {
+    const int wr = i / cpr, ch = i - wr * cpr;                // wr = tap * CB + cb
+    const int tap = wr / CB, cb = wr - tap * CB;
+    *reinterpret_cast<uint4*>(Wl + wr * rowB + ch * 16) =
+        *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(w + ((long long)tap * a.CBT + cb) * Cs) + ch * 16);
+  }
+  __syncthreads();
+
+  const int py = wave >> 1, px = wave & 1;                    // this wave's output phase
+  const int r = lane & 31, h = lane >> 5;
+  floatx16 acc[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+  constexpr int ksteps = Cs * (int)sizeof(T) / 32;            // 32 bytes of K per MFMA step (16 per lane half)
+#pragma unroll
+  for (int tp = 0; tp < 4; ++tp) {
+    const int ta = tp >> 1, tb = tp & 1;
+    const int dy = py == 0 ? (ta == 0 ? 0 : -1) : (ta == 0 ? 1 : 0);
+    const int dx = px == 0 ? (tb == 0 ? 0 : -1) : (tb == 0 ? 1 : 0);
+    const int ky = py == 0 ? (ta == 0 ? 1 : 3) : (ta == 0 ? 0 : 2);
+    const int kx = px == 0 ? (tb == 0 ? 1 : 3) : (tb == 0 ? 0 : 2);
+    const unsigned char* wrow = Wl + ((ky * 4 + kx) * CB + (r < CB ? r : 0)) * rowB + h * 16;
+    const unsigned char* frow[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int q = t * 32 + r;                               // pixel of the patch: (q / 8, q % 8)
+      frow[t] = Fl + ((q / UP_TS + 1 + dy) * UP_HALO + (q % UP_TS + 1 + dx)) * rowB + h * 16;
+    }
+#pragma unroll
+    for (int ks = 0; ks < ksteps; ++ks) {
+      uint4 b = make_uint4(0, 0, 0, 0);
+      if (r < CB) b = *reinterpret_cast<const uint4*>(wrow + ks * 32);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint4 av = *reinterpret_cast<const uint4*>(frow[t] + ks * 32);
+        up_mma(acc[t], av, b, T());
+      }
+    }
+  }
+  // epilogue: only the first CB columns (lanes) of each MFMA tile are real.  Pass them through LDS so that all
+  // 256 threads share the (1 - y^2) / tanh work and write whole output rows.
+  __syncthreads();                                            // the halo tile is no longer read
+  float* ep = reinterpret_cast<float*>(Fl);                   // [2*UP_TS rows][2*UP_TS cols][4]
+  if (r < CB) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int q = t * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+        const int Yl = 2 * (q / UP_TS) + py, Xl = 2 * (q % UP_TS) + px;
+        ep[(Yl * 2 * UP_TS + Xl) * 4 + r] = acc[t][e];
+      }
+  }
+  __syncthreads();
+  T* out = static_cast<T*>(a.out);
+  const T* aux = static_cast<const T*>(a.aux);
+  const int rowlen = 2 * UP_TS * CB;                          // contiguous output elements per patch row
+  for (int i = tid; i < 2 * UP_TS * rowlen; i += 256) {
+    const int Yl = i / rowlen, rem = i - Yl * rowlen;
+    const int Xl = rem / CB, cb = rem - Xl * CB;
+    const int Y = 2 * y0 + Yl, X = 2 * x0 + Xl;
+    if (Y >= Hb || X >= Hb) continue;
+    const long long o = ((sample * Hb + Y) * Hb + X) * CB + cb;
+    float v = ep[(Yl * 2 * UP_TS + Xl) * 4 + cb];
+    if (a.mode == 1) v = tanhf(v + a.bias[(long long)l * a.bias_stride + cb]);
+    else if (a.mode == 2) { const float yv = to_float(aux[o]); v *= (1.f - yv * yv); }
+    out[o] = from_float<T>(v);
+  }
+}
+template <typename T> void launch_up_img(const UpImgArgs& a, hipStream_t st) {
+  if (a.n == 0) return;
+  if (!a.feat || !a.w || !a.out || a.CB < 1 || a.CB > 4 || (a.Cs != 64 && a.Cs != 128) || (a.mode == 1 && !a.bias) || (a.mode == 2 && !a.aux)) abort();
+  const int tiles = (a.Hs + UP_TS - 1) / UP_TS;
+  const int rowB = a.Cs * (int)sizeof(T) + 16;
+  const size_t lds = (size_t)(UP_HALO * UP_HALO + 16 * a.CB) * rowB;
+  if (lds > 160 * 1024) abort();
+  if (a.Cs == 64) {
+    hipLaunchKernelGGL((up_img_kernel<T, 64>), dim3(tiles * tiles, a.n), dim3(256), lds, st, a);
+  } else if (a.Cs == 128) {
+    if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_img_kernel<T, 128>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
+    hipLaunchKernelGGL((up_img_kernel<T, 128>), dim3(tiles * tiles, a.n), dim3(256), lds, st, a);
+  } else {
+    abort();
+  }
+}
+template void launch_up_img<float>(const UpImgArgs&, hipStream_t);
+template void launch_up_img<bf16_t>(const UpImgArgs&, hipStream_t);
 
 }  // namespace gan

@@ -100,6 +100,23 @@ struct PackArgs {
 template <typename T> void launch_pack_w(const PackArgs& a, hipStream_t st);
 void launch_unpack_dw(const PackArgs& a, hipStream_t st);
 
+// Transposed convolution onto the image side (G's last layer; data gradient of D's first layer).
+struct UpImgArgs {
+  const void* feat;         // [samples][Hs][Hs][Cs] storage type, indexed by absolute sample
+  const void* w;            // model 0 storage-type weights [16][CBT][Cs]; w_stride elements between models
+  long long w_stride;
+  void* out;                // [samples][2Hs][2Hs][CB] storage type, indexed by absolute sample
+  const void* aux;          // mode 2: the saved tanh output, same indexing as out
+  const float* bias;        // mode 1: [CB] of model 0, bias_stride between models
+  long long bias_stride;
+  const int* offs;
+  const int* sample_model;
+  int L, n, seg, seg_samples;
+  int CB, CBT, Cs, Hs;
+  int mode;                 // 0: plain ; 1: + bias, tanh ; 2: times (1 - aux^2)
+};
+template <typename T> void launch_up_img(const UpImgArgs& a, hipStream_t st);
+
 constexpr int IMG_BIAS_CHUNKS = 32;
 struct ImgBiasArgs {
   const void* img;          // [pixels][CB] of segment 0

@@ -38,6 +38,7 @@ def run_config(config, precision):
     lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
     d_lab = torch.from_numpy(lab).cuda()
     worst, failures, table = {}, [], []
+    env = {"loss": 0.0, "param": 0.0}
     for step in range(1, plan["steps"] + 1):
         z, x = work.noise(), work.images(lab)
         dz, dx = torch.from_numpy(z).cuda(), torch.from_numpy(x).cuda()
@@ -51,12 +52,20 @@ def run_config(config, precision):
             assert np.array_equal(perm, np.argsort(mdl, kind="stable"))
             assert np.array_equal(offs, np.concatenate([[0], np.cumsum(np.bincount(mdl, minlength=work.n_models))]))
 
-        def bound(drift):
-            # From the second iteration on the bound is widened where the iteration itself amplifies rounding: the
-            # distance of the single-precision oracle from the fp64 oracle on the same inputs measures that
-            # amplification.  fp32 storage: 10 x that drift (another fp32 summation order); bf16 storage: 20 x.
+        # From the second iteration on the bound is widened where the iteration itself amplifies rounding.  The
+        # distance of the single-precision oracle from the fp64 oracle measures that amplification; it fluctuates
+        # from step to step and quantity to quantity, so its running maximum over the steps so far (over the checked
+        # models and both costs) is used: fp32 storage 10 x that envelope (another fp32 summation order), bf16
+        # storage 50 x (its rounding unit is 2^16 coarser).  The first iteration is always held to the stated bound.
+        if plan["single"]:
+            for i in range(len(models)):
+                for name in ("jd", "jg"):
+                    ref = gold["f64_%s_%d" % (name, step)][i]
+                    env["loss"] = max(env["loss"], abs(gold["f32_%s_%d" % (name, step)][i] - ref) / abs(ref))
+
+        def bound(drift, kind="loss"):
             if step >= 2 and plan["single"]:
-                return max(tol, (10.0 if precision == "fp32" else 20.0) * drift)
+                return max(tol, (10.0 if precision == "fp32" else 50.0) * max(drift, env[kind]))
             return tol
 
         for i, l in enumerate(models):
@@ -79,14 +88,14 @@ def run_config(config, precision):
                         got = th[idx]
                         floor = 0.02 * np.sqrt(idx.size)
                         err = U.rel_l2(got, ref, floor=floor)
-                        if err > max(bound(U.rel_l2(f32, ref, floor=floor)), U.one_flip(idx.size)):
+                        if err > max(bound(U.rel_l2(f32, ref, floor=floor), "param"), U.one_flip(idx.size)):
                             failures.append((config, step, l, which, name, err, U.rel_l2(f32, ref, floor=floor)))
                         all_got.append(got); all_ref.append(ref); all_f32.append(f32)
                     g, r, s = (np.concatenate(a) for a in (all_got, all_ref, all_f32))
                     err = U.rel_l2(g, r)
                     worst["params"] = max(worst.get("params", 0), err)
                     table.append((step, l, "params%d" % which, 0.0, 0.0, err, U.rel_l2(s, r)))
-                    if err > bound(U.rel_l2(s, r)):
+                    if err > bound(U.rel_l2(s, r), "param"):
                         failures.append((config, step, l, which, "params", err, U.rel_l2(s, r)))
     gan.close()
     for row in table:
