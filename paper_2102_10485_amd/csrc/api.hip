@@ -107,7 +107,13 @@ int geom_id(gan_ctx* c, int rps, int tile_rows) {
   return c->geoms.n++;
 }
 const int* tpre_of(gan_ctx* c, int rps, int tile_rows) {
-  const int g = geom_id(c, rps, tile_rows);
+  int g = -1;
+  for (int i = 0; i < c->geoms.n; ++i)
+    if (c->geoms.rps[i] == rps && c->geoms.tile_rows[i] == tile_rows) g = i;
+  if (g < 0) {   // every geometry a launch uses is registered at create; anything else would read an unbuilt prefix
+    fprintf(stderr, "gan: tile geometry (%d, %d) was not registered\n", rps, tile_rows);
+    abort();
+  }
   return c->rb.tpre + (long long)g * (c->L + 1);
 }
 // tile height for a layer: from the average rows per model at the sizing batch (fixed at create, so the prefix
@@ -402,7 +408,10 @@ template <typename T>
 void bn_backward(gan_ctx* c, NormArgs a, const void* x, const void* dy, void* dx, bool param_grads) {
   a.x = x; a.dy = dy; a.y = dx;
   const double elems = (double)a.n * a.nseg * a.rps * a.C;
-  { Scope s(c, "bn_bwd_reduce", 0, 2 * elems * sizeof(T)); launch_bn_bwd_reduce<T>(a, c->st); }
+  {
+    Scope s(c, "bn_bwd_reduce", 0, 2 * elems * sizeof(T));
+    launch_bn_bwd_reduce<T>(a, tpre_of(c, a.rps, BN_RED_ROWS), ub_tiles(c, a.n, a.rps, BN_RED_ROWS), c->stat_partial, c->st);
+  }
   if (param_grads) launch_bn_param_grad(a, c->st);
   Scope s(c, "bn_bwd_apply", 0, 3 * elems * sizeof(T));
   launch_bn_bwd_apply<T>(a, c->st);
@@ -657,21 +666,26 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   bool ok = alloc_net(c, c->G) && alloc_net(c, c->D);
   // geometries used by any launch: (rows per sample, tile height) of every GEMM's row space
   {
+    auto reg = [&](int rps, int tile_rows) { if (geom_id(c, rps, tile_rows) < 0) ok = false; };
     const ConvLayer& gl = c->G.conv.back();
     const ConvLayer& d1 = c->D.conv.front();
-    geom_id(c, 1, layer_tile_rows(c, c->G.J, 1));                                      // G's linear layer
+    reg(1, layer_tile_rows(c, c->G.J, 1));                                      // G's linear layer
     for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) {
       const ConvLayer& cl = c->G.conv[i];
-      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // forward (up)
-      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // data gradient (down)
+      reg(cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // forward (up)
+      reg(cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // data gradient (down)
     }
-    geom_id(c, gl.Hs * gl.Hs, layer_tile_rows(c, gl.Cs, gl.Hs * gl.Hs));               // its data gradient (patch GEMM)
+    reg(gl.Hs * gl.Hs, layer_tile_rows(c, gl.Cs, gl.Hs * gl.Hs));               // its data gradient (patch GEMM)
     for (size_t j = 1; j < c->D.conv.size(); ++j) {
       const ConvLayer& cl = c->D.conv[j];
-      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // forward (down)
-      geom_id(c, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // data gradient (up)
+      reg(cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs));             // forward (down)
+      reg(cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs));             // data gradient (up)
     }
-    geom_id(c, d1.Hs * d1.Hs, layer_tile_rows(c, d1.Cs, d1.Hs * d1.Hs));               // first conv (patch GEMM)
+    reg(d1.Hs * d1.Hs, layer_tile_rows(c, d1.Cs, d1.Hs * d1.Hs));               // first conv (patch GEMM)
+    // row space of every BatchNorm, in blocks of BN_RED_ROWS rows (backward reduction)
+    reg(c->G.h0 * c->G.h0, BN_RED_ROWS);
+    for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) reg(4 * c->G.conv[i].Hs * c->G.conv[i].Hs, BN_RED_ROWS);
+    for (size_t j = 1; j < c->D.conv.size(); ++j) reg(c->D.conv[j].Hs * c->D.conv[j].Hs, BN_RED_ROWS);
   }
   RouteBuffers& rb = c->rb;
   ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&
@@ -723,6 +737,21 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
       const ConvLayer& cl = c->D.conv[j];
       const size_t v = (size_t)2 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs)) * cl.Cs;
       mx = v > mx ? v : mx;
+    }
+    // and the BatchNorm backward reduction: segments x row blocks x channels x 2
+    {
+      size_t v = (size_t)ub_tiles(c, NB, c->G.h0 * c->G.h0, BN_RED_ROWS) * c->G.C0;
+      mx = v > mx ? v : mx;
+      for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) {
+        const ConvLayer& cl = c->G.conv[i];
+        v = (size_t)ub_tiles(c, NB, 4 * cl.Hs * cl.Hs, BN_RED_ROWS) * cl.Cb;
+        mx = v > mx ? v : mx;
+      }
+      for (size_t j = 1; j < c->D.conv.size(); ++j) {
+        const ConvLayer& cl = c->D.conv[j];
+        v = (size_t)2 * ub_tiles(c, NB, cl.Hs * cl.Hs, BN_RED_ROWS) * cl.Cs;
+        mx = v > mx ? v : mx;
+      }
     }
     ok = ok && dev_alloc(c, (void**)&c->stat_partial, mx * 2 * 4);
   }

@@ -7,7 +7,7 @@
 namespace gan {
 
 constexpr int ROUTE_CHUNKS = 256;   // sequential chunks of the flat batch, one thread each
-constexpr int MAX_GEOMS = 16;
+constexpr int MAX_GEOMS = 32;
 
 // One "geometry" = how rows of a layer split into tiles: rows per sample and rows per tile.
 struct GeomTable {
@@ -69,7 +69,9 @@ void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const
 void launch_bn_running(const NormArgs& a, hipStream_t st);
 void launch_bn_from_running(const NormArgs& a, hipStream_t st);   // mean/rstd <- running statistics
 template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st);
-template <typename T> void launch_bn_bwd_reduce(const NormArgs& a, hipStream_t st);
+constexpr int BN_RED_ROWS = 1024;   // rows per block of the backward reduction (tile prefix geometry (rps, BN_RED_ROWS))
+template <typename T>
+void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, int ub_tiles, float* partial, hipStream_t st);
 void launch_bn_param_grad(const NormArgs& a, hipStream_t st);
 template <typename T> void launch_bn_bwd_apply(const NormArgs& a, hipStream_t st);
 

@@ -305,17 +305,28 @@ template void launch_bn_apply<float>(const NormArgs&, hipStream_t);
 template void launch_bn_apply<bf16_t>(const NormArgs&, hipStream_t);
 
 // sums[g][c] = (sum g, sum g * xhat) with g = dy * act'(u), u = gamma * xhat + beta.
+// Stage 1: block (64 channels, tile of BN_RED_ROWS rows of one model, segment) -> partial[segment][tile][C][2].
+// Stage 2: the tiles of a (segment, model) added in order.
 template <typename T>
-__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a) {
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
+                                                            float* __restrict__ partial) {
   __shared__ float red[2][16][64];
-  const int l = blockIdx.y % a.L, sidx = blockIdx.y / a.L;
+  const int tile = blockIdx.y;
+  if (tile >= tpre[a.L]) return;
+  int lo = 0, hi = a.L;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (tpre[mid] <= tile) lo = mid; else hi = mid;
+  }
+  const int l = lo, sidx = blockIdx.z;
   const int seg = a.seg_first + sidx;
   const int cnt = a.offs[l + 1] - a.offs[l];
   const int g = seg * a.L + l;
   const int c0 = blockIdx.x * 64;
   const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
   const long long rows = (long long)cnt * a.rps;
-  if (rows == 0) return;
+  const long long r0 = (long long)(tile - tpre[l]) * BN_RED_ROWS;
+  const long long r1 = min(rows, r0 + BN_RED_ROWS);
   const long long base = ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * 4;
   const T* x = static_cast<const T*>(a.x) + base;
   const T* dy = static_cast<const T*>(a.dy) + base;
@@ -328,7 +339,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a) {
     ga[e] = a.gamma[(long long)l * a.pstride + c];
     be[e] = a.beta[(long long)l * a.pstride + c];
   }
-  for (long long r = rl; r < rows; r += 16) {
+  for (long long r = r0 + rl; r < r1; r += 16) {
     float v[4], d[4];
     load4(x + r * a.C, v);
     load4(dy + r * a.C, d);
@@ -348,15 +359,37 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a) {
     const int w = threadIdx.x >> 6, c = threadIdx.x & 63;
     float t = 0.f;
     for (int i = 0; i < 16; ++i) t += red[w][i][c];
-    a.sums[((long long)g * a.C + c0 + c) * 2 + w] = t;
+    partial[(((long long)sidx * ub_tiles + tile) * a.C + c0 + c) * 2 + w] = t;
   }
 }
-template <typename T> void launch_bn_bwd_reduce(const NormArgs& a, hipStream_t st) {
-  if (a.nseg == 0) return;
-  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(a.C / 64, a.L * a.nseg), dim3(256), 0, st, a);
+__global__ void bn_bwd_reduce_final_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
+                                           const float* __restrict__ partial) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)a.nseg * a.L * a.C) return;
+  const int c = (int)(idx % a.C);
+  const int l = (int)((idx / a.C) % a.L);
+  const int sidx = (int)(idx / ((long long)a.C * a.L));
+  if (a.offs[l + 1] == a.offs[l]) return;
+  float s0 = 0.f, s1 = 0.f;
+  for (int t = tpre[l]; t < tpre[l + 1]; ++t) {
+    const long long o = (((long long)sidx * ub_tiles + t) * a.C + c) * 2;
+    s0 += partial[o];
+    s1 += partial[o + 1];
+  }
+  const long long o = ((long long)((a.seg_first + sidx) * a.L + l) * a.C + c) * 2;
+  a.sums[o] = s0;
+  a.sums[o + 1] = s1;
 }
-template void launch_bn_bwd_reduce<float>(const NormArgs&, hipStream_t);
-template void launch_bn_bwd_reduce<bf16_t>(const NormArgs&, hipStream_t);
+template <typename T>
+void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, int ub_tiles, float* partial, hipStream_t st) {
+  if (a.nseg == 0 || ub_tiles == 0) return;
+  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(a.C / 64, ub_tiles, a.nseg), dim3(256), 0, st, a, tpre, ub_tiles, partial);
+  const long long tot = (long long)a.nseg * a.L * a.C;
+  hipLaunchKernelGGL(bn_bwd_reduce_final_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a, tpre, ub_tiles,
+                     partial);
+}
+template void launch_bn_bwd_reduce<float>(const NormArgs&, const int*, int, float*, hipStream_t);
+template void launch_bn_bwd_reduce<bf16_t>(const NormArgs&, const int*, int, float*, hipStream_t);
 
 // dgamma, dbeta: the segments' sums added in order.
 __global__ void bn_param_grad_kernel(NormArgs a) {
