@@ -116,31 +116,39 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / TL::WN, wn = wave % TL::WN;
 
-  // ---- which tile: consecutive virtual ids stay on one XCD (block ids are dealt round-robin to the 8 XCDs)
+  // ---- which tile: consecutive virtual ids stay on one XCD (block ids are dealt round-robin to the 8 XCDs).
+  // Virtual id = ((M-tile * segments + segment) * phases + phase) * N-tiles + N-tile: blocks that run together on
+  // an XCD read the same activations (other phase / N-tile) or the same model's weights (other M-tile, segment)
+  // out of that XCD's L2.
+  constexpr int NPH = (MODE == MODE_UP) ? 4 : 1;
   const int NT = (p.N + BN - 1) / BN;
   const int Ttot = p.tpre[p.L];
-  const int total = Ttot * NT;
+  const int total = Ttot * NT * p.nseg * NPH;
   const int per_xcd = (total + 7) >> 3;
   const int slot = blockIdx.x >> 3;
   if (slot >= per_xcd) return;
   const int v = (blockIdx.x & 7) * per_xcd + slot;
   if (v >= total) return;
-  const int mt = v / NT, nt = v - mt * NT;
+  const int nt = v % NT;
+  const int v1 = v / NT;
+  const int phase = v1 % NPH;
+  const int v2 = v1 / NPH;
+  const int sidx = v2 % p.nseg;
+  const int mt = v2 / p.nseg;
   int lo = 0, hi = p.L;
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
     if (p.tpre[mid] <= mt) lo = mid; else hi = mid;
   }
   const int l = lo;
-  const int seg = p.seg_first + blockIdx.y;
+  const int seg = p.seg_first + sidx;
   const int s0 = p.offs[l], s1 = p.offs[l + 1];
   const int Hr = p.Hr, Hin = p.Hin, C = p.C, N = p.N;
   const int rps = Hr * Hr;
   const int Mrows = (s1 - s0) * rps;
   const int m0 = (mt - p.tpre[l]) * BM;
   const long long sample_base = (long long)seg * p.seg_samples + s0;
-  const int py = (MODE == MODE_UP) ? (int)(blockIdx.z >> 1) : 0;
-  const int px = (MODE == MODE_UP) ? (int)(blockIdx.z & 1) : 0;
+  const int py = phase >> 1, px = phase & 1;
 
   const T* __restrict__ A = static_cast<const T*>(p.A);
   const T* __restrict__ W = static_cast<const T*>(p.W) + (long long)l * p.w_stride;
@@ -174,12 +182,27 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
 
   const int ntaps = (MODE == MODE_DOWN) ? 16 : (MODE == MODE_UP ? 4 : 1);
   const int nk = ntaps * C / BK;
+  const int cpt = C / BK;        // channel chunks per tap
   const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
   uint4 ra[PA], rb[PB];
   auto load_chunk = [&](int kc) {
-    const int kk = kc * BK;
-    const int tap = kk / C;
-    const int c0 = kk - tap * C + chunk * EPV;
+    // K order: taps whose gathers land on the same input pixels (shifted by one) run back to back on one channel
+    // chunk, so that all but the first find their rows in L2: down - the 4 taps of a (ky%2, kx%2) class; up - the
+    // phase's 4 taps.
+    const int j4 = kc & 3;
+    const int rest = kc >> 2;
+    int tap, c0;
+    if (MODE == MODE_DOWN) {
+      const int cls = rest / cpt;
+      c0 = (rest - cls * cpt) * BK + chunk * EPV;
+      tap = (((cls >> 1) + 2 * (j4 >> 1)) << 2) + (cls & 1) + 2 * (j4 & 1);
+    } else if (MODE == MODE_UP) {
+      c0 = rest * BK + chunk * EPV;
+      tap = j4;
+    } else {
+      c0 = kc * BK + chunk * EPV;
+      tap = 0;
+    }
     int dy, dx, wtap;
     if (MODE == MODE_DOWN) {
       dy = tap >> 2; dx = tap & 3; wtap = tap;
@@ -298,7 +321,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int w = 0; w < TL::WM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
-      const long long t = ((long long)blockIdx.z * gridDim.y + blockIdx.y) * p.ub_tiles + mt;
+      const long long t = ((long long)phase * p.nseg + sidx) * p.ub_tiles + mt;
       p.stat_partial[(t * N + col) * 2] = s1;
       p.stat_partial[(t * N + col) * 2 + 1] = s2;
     }
@@ -354,9 +377,9 @@ static void launch_one(ConvArgs a, hipStream_t st) {
   if (a.tile_rows != TL::BM) abort();            // the tile prefix array must have been built for this tile height
   a.hr_shift = log2_or_neg(a.Hr);
   const int NT = (a.N + TL::BN - 1) / TL::BN;
-  const long long blocks = ((long long)a.ub_tiles * NT + 7) / 8 * 8;
+  const long long blocks = ((long long)a.ub_tiles * NT * a.nseg * (MODE == MODE_UP ? 4 : 1) + 7) / 8 * 8;
   if (blocks == 0 || a.nseg == 0) return;
-  dim3 grid((unsigned)blocks, (unsigned)a.nseg, MODE == MODE_UP ? 4 : 1);
+  dim3 grid((unsigned)blocks, 1, 1);
   hipLaunchKernelGGL((conv_gemm_kernel<T, MODE, EPI, TL>), grid, dim3(TL::NT), 0, st, a);
 }
 
