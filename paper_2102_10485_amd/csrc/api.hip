@@ -595,8 +595,23 @@ void adam_call(gan_ctx* c, Net& net, bool isG) {
   a.theta = net.theta; a.m = net.m; a.v = net.v; a.g = net.g; a.shadow = c->bf16 ? net.shadow_u : nullptr;
   a.P = net.P; a.L = c->L; a.counts = c->rb.counts; a.t = net.t; a.bc = net.bc;
   a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps;
-  { Scope s(c, "adam", 0, (double)c->L * net.P * (28.0 + (c->bf16 ? 2.0 : 0.0))); launch_adam(a, c->st); }
-  refresh_transposes<T>(c, net, isG);
+  // convolution weights the GEMM engine also reads in "down" form: the update writes that transposed copy too
+  a.shadow_t = net.shadow_d;
+  for (size_t i = 0; i < net.conv.size(); ++i) {
+    const bool gemm = isG ? (i + 1 < net.conv.size()) : (i > 0);
+    if (!gemm) continue;
+    a.reg_w[a.nregions] = net.conv[i].w; a.reg_cb[a.nregions] = net.conv[i].Cb; a.reg_cs[a.nregions] = net.conv[i].Cs;
+    ++a.nregions;
+  }
+  {
+    double tbytes = 0;
+    for (int r = 0; r < a.nregions; ++r) tbytes += 16.0 * a.reg_cb[r] * a.reg_cs[r] * sizeof(T);
+    Scope s(c, "adam", 0, (double)c->L * (net.P * (28.0 + (c->bf16 ? 2.0 : 0.0)) + tbytes));
+    launch_adam<T>(a, c->st);
+  }
+  // the image-side layer multiplies a patch matrix: its packed weights are rebuilt from the new master weights
+  if (isG) launch_pack_w<T>(pack_args(c, net, net.conv.back(), c->KcG, 0, c->wpG), c->st);
+  else launch_pack_w<T>(pack_args(c, net, net.conv.front(), c->KcD, c->nslot, c->wpD), c->st);
 }
 
 template <typename T>

@@ -153,17 +153,29 @@ void launch_loss(const HeadArgs& a, hipStream_t st);
 template <typename T> void launch_head_bwd_data(const HeadArgs& a, hipStream_t st);
 template <typename T> void launch_head_bwd_w(const HeadArgs& a, hipStream_t st);
 
+constexpr int ADAM_MAX_REGIONS = 8;
 struct AdamArgs {
   float* theta; float* m; float* v; const float* g;
   void* shadow;             // storage-type copy of theta (NULL when the storage type is fp32)
+  void* shadow_t;           // storage-type copy with every region below transposed: [tap][cs][cb]
   long long P;              // elements per model
   int L;
   const int* counts;
   int* t;                   // [L] step counts
   float* bc;                // [L][2] scratch: 1-beta1^t, 1-beta2^t
   float lr, beta1, beta2, eps;
+  // Convolution weights [16][Cb][Cs] (Cb, Cs multiples of 64) that need the transposed copy: updated tile by tile.
+  // Everything else is the list of gaps between them, updated as flat ranges.
+  int nregions;
+  long long reg_w[ADAM_MAX_REGIONS];
+  int reg_cb[ADAM_MAX_REGIONS], reg_cs[ADAM_MAX_REGIONS];
+  int reg_tile0[ADAM_MAX_REGIONS + 1];    // prefix of 64 x 64 tiles (filled by the launcher)
+  int ngaps;
+  long long gap_lo[ADAM_MAX_REGIONS + 1], gap_hi[ADAM_MAX_REGIONS + 1];
+  int gap_blk0[ADAM_MAX_REGIONS + 2];     // prefix of 1024-element blocks (filled by the launcher)
 };
-void launch_adam(const AdamArgs& a, hipStream_t st);
+// T: storage type of the shadows
+template <typename T> void launch_adam(AdamArgs a, hipStream_t st);
 template <typename T> void launch_cast_shadow(const float* theta, T* shadow, long long total, hipStream_t st);
 // dst[tap][cs][cb] <- src[tap][cb][cs] for every model (src: T or float master)
 template <typename T, typename S>

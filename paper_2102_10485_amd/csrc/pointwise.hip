@@ -597,19 +597,11 @@ __global__ void adam_prepare_kernel(AdamArgs a) {
   a.bc[2 * l + 1] = (float)(1.0 - pow((double)a.beta2, (double)t));
 }
 
-__global__ __launch_bounds__(256) void adam_kernel(AdamArgs a) {
-  const int l = blockIdx.y;
-  if (a.counts[l] == 0) return;
-  const long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i >= a.P) return;
-  const long long o = (long long)l * a.P + i;
-  const float bc1 = a.bc[2 * l], bc2 = a.bc[2 * l + 1];
-  const float4 g = *reinterpret_cast<const float4*>(a.g + o);
-  float4 th = *reinterpret_cast<const float4*>(a.theta + o);
-  float4 m = *reinterpret_cast<const float4*>(a.m + o);
-  float4 v = *reinterpret_cast<const float4*>(a.v + o);
+__device__ inline void adam_update4(const AdamArgs& a, float bc1, float bc2, const float4& g, float4& th, float4& m, float4& v,
+                                    float (&tt)[4]) {
   const float gg[4] = {g.x, g.y, g.z, g.w};
-  float tt[4] = {th.x, th.y, th.z, th.w}, mm[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
+  float mm[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
+  tt[0] = th.x; tt[1] = th.y; tt[2] = th.z; tt[3] = th.w;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     mm[e] = a.beta1 * mm[e] + (1.f - a.beta1) * gg[e];
@@ -617,15 +609,110 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamArgs a) {
     const float mh = mm[e] / bc1, vh = vv[e] / bc2;
     tt[e] -= a.lr * mh / (sqrtf(vh) + a.eps);
   }
-  *reinterpret_cast<float4*>(a.theta + o) = make_float4(tt[0], tt[1], tt[2], tt[3]);
-  *reinterpret_cast<float4*>(a.m + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
-  *reinterpret_cast<float4*>(a.v + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+  th = make_float4(tt[0], tt[1], tt[2], tt[3]);
+  m = make_float4(mm[0], mm[1], mm[2], mm[3]);
+  v = make_float4(vv[0], vv[1], vv[2], vv[3]);
+}
+
+// the ranges between the tiled regions
+__global__ __launch_bounds__(256) void adam_kernel(AdamArgs a) {
+  const int l = blockIdx.y;
+  if (a.counts[l] == 0) return;
+  int r = 0;
+  while (r + 1 < a.ngaps && (int)blockIdx.x >= a.gap_blk0[r + 1]) ++r;
+  const long long i = a.gap_lo[r] + ((long long)(blockIdx.x - a.gap_blk0[r]) * 256 + threadIdx.x) * 4;
+  if (i >= a.gap_hi[r]) return;
+  const long long o = (long long)l * a.P + i;
+  const float4 g = *reinterpret_cast<const float4*>(a.g + o);
+  float4 th = *reinterpret_cast<const float4*>(a.theta + o);
+  float4 m = *reinterpret_cast<const float4*>(a.m + o);
+  float4 v = *reinterpret_cast<const float4*>(a.v + o);
+  float tt[4];
+  adam_update4(a, a.bc[2 * l], a.bc[2 * l + 1], g, th, m, v, tt);
+  *reinterpret_cast<float4*>(a.theta + o) = th;
+  *reinterpret_cast<float4*>(a.m + o) = m;
+  *reinterpret_cast<float4*>(a.v + o) = v;
   if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
 }
-void launch_adam(const AdamArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(adam_prepare_kernel, dim3((a.L + 255) / 256), dim3(256), 0, st, a);
-  hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((a.P / 4 + 255) / 256), a.L), dim3(256), 0, st, a);
+
+// One 64 (cb) x 64 (cs) tile of one tap of a convolution weight: the update, the storage-type copy, and - through
+// LDS - the transposed storage-type copy, so that the new weights are read from HBM once.
+template <typename T>
+__global__ __launch_bounds__(256) void adam_tile_kernel(AdamArgs a) {
+  constexpr int EPV = 16 / (int)sizeof(T);
+  constexpr int TSTRIDE = 64 * (int)sizeof(T) + 16;            // bytes per transposed row (64 cb)
+  __shared__ __attribute__((aligned(16))) unsigned char tile[64 * TSTRIDE];
+  const int l = blockIdx.y;
+  if (a.counts[l] == 0) return;
+  int r = 0;
+  while (r + 1 < a.nregions && (int)blockIdx.x >= a.reg_tile0[r + 1]) ++r;
+  const int Cb = a.reg_cb[r], Cs = a.reg_cs[r];
+  const int tcs_n = Cs >> 6, tcb_n = Cb >> 6;
+  int q = blockIdx.x - a.reg_tile0[r];
+  const int tcs = q % tcs_n; q /= tcs_n;
+  const int tcb = q % tcb_n;
+  const int tap = q / tcb_n;
+  const long long base = (long long)l * a.P + a.reg_w[r];
+  const float bc1 = a.bc[2 * l], bc2 = a.bc[2 * l + 1];
+  const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = r0 + 16 * i;                                // cb inside the tile
+    const long long o = base + ((long long)tap * Cb + tcb * 64 + row) * Cs + tcs * 64 + c4;
+    const float4 g = *reinterpret_cast<const float4*>(a.g + o);
+    float4 th = *reinterpret_cast<const float4*>(a.theta + o);
+    float4 m = *reinterpret_cast<const float4*>(a.m + o);
+    float4 v = *reinterpret_cast<const float4*>(a.v + o);
+    float tt[4];
+    adam_update4(a, bc1, bc2, g, th, m, v, tt);
+    *reinterpret_cast<float4*>(a.theta + o) = th;
+    *reinterpret_cast<float4*>(a.m + o) = m;
+    *reinterpret_cast<float4*>(a.v + o) = v;
+    if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) *reinterpret_cast<T*>(tile + (c4 + e) * TSTRIDE + row * (int)sizeof(T)) = from_float<T>(tt[e]);
+  }
+  __syncthreads();
+  T* dst = static_cast<T*>(a.shadow_t) + base;
+  constexpr int CPR = 64 / EPV;                                 // 16-byte chunks per transposed row
+#pragma unroll
+  for (int i = 0; i < 64 * CPR / 256; ++i) {
+    const int cid = threadIdx.x + 256 * i;
+    const int cs = cid / CPR, ch = cid - cs * CPR;
+    const uint4 val = *reinterpret_cast<const uint4*>(tile + cs * TSTRIDE + ch * 16);
+    *reinterpret_cast<uint4*>(dst + ((long long)tap * Cs + tcs * 64 + cs) * Cb + tcb * 64 + ch * EPV) = val;
+  }
 }
+
+template <typename T>
+void launch_adam(AdamArgs a, hipStream_t st) {
+  // regions sorted by offset are the caller's job; the gaps between them cover the rest of [0, P)
+  if (a.nregions < 0 || a.nregions > ADAM_MAX_REGIONS || a.P % 8) abort();
+  long long pos = 0;
+  a.ngaps = 0;
+  a.reg_tile0[0] = 0;
+  a.gap_blk0[0] = 0;
+  for (int r = 0; r <= a.nregions; ++r) {
+    const long long lo = r < a.nregions ? a.reg_w[r] : a.P;
+    if (lo < pos || lo % 4) abort();
+    if (lo > pos) {
+      a.gap_lo[a.ngaps] = pos; a.gap_hi[a.ngaps] = lo;
+      a.gap_blk0[a.ngaps + 1] = a.gap_blk0[a.ngaps] + (int)((lo - pos + 1023) / 1024);
+      ++a.ngaps;
+    }
+    if (r < a.nregions) {
+      if (a.reg_cb[r] % 64 || a.reg_cs[r] % 64 || !a.shadow_t) abort();
+      a.reg_tile0[r + 1] = a.reg_tile0[r] + 16 * (a.reg_cb[r] / 64) * (a.reg_cs[r] / 64);
+      pos = lo + 16LL * a.reg_cb[r] * a.reg_cs[r];
+    }
+  }
+  hipLaunchKernelGGL(adam_prepare_kernel, dim3((a.L + 255) / 256), dim3(256), 0, st, a);
+  if (a.ngaps > 0) hipLaunchKernelGGL(adam_kernel, dim3((unsigned)a.gap_blk0[a.ngaps], a.L), dim3(256), 0, st, a);
+  if (a.nregions > 0)
+    hipLaunchKernelGGL((adam_tile_kernel<T>), dim3((unsigned)a.reg_tile0[a.nregions], a.L), dim3(256), 0, st, a);
+}
+template void launch_adam<float>(AdamArgs, hipStream_t);
+template void launch_adam<bf16_t>(AdamArgs, hipStream_t);
 
 template <typename T>
 __global__ void cast_shadow_kernel(const float* __restrict__ theta, T* __restrict__ shadow, long long total) {
