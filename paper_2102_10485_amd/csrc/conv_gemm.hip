@@ -11,10 +11,13 @@
 //   reduction index is the slow memory index of both operands, so tiles are transposed in registers on their
 //   way into LDS.
 //
-// Both stage 128-byte K-rows in LDS (row stride 144 bytes, two buffers) and feed v_mfma_f32_32x32x16_bf16 (bf16
-// storage) or v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
-// The next K-chunk travels global -> registers while the MFMAs of the current one run, then registers -> the
-// other LDS buffer: one barrier per chunk.
+// Both stage 128-byte K-rows in LDS (two buffers) and feed v_mfma_f32_32x32x16_bf16 (bf16 storage) or
+// v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
+// Forward-type kernel: the next K-chunk travels global -> LDS directly (global_load_lds_dwordx4, no registers in
+// between) while the MFMAs of the current one run; rows are 128 bytes apart and the 16-byte chunk c of row R sits
+// at position c ^ ((R / 2) % 8), which keeps both the 1 KiB-per-wave writes and the MFMA operand reads off each
+// other's banks.  Weight-gradient kernel: global -> registers (8 x 8 transposes) -> LDS, row stride 144 bytes.
+// One barrier per chunk in both.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -58,30 +61,45 @@ __device__ inline void mma16B(floatx16& acc, const uint4& a, const uint4& b, flo
 }
 
 // One K-chunk held in LDS: every wave multiplies its (TM*32) x (TN*32) sub-tile.
-// SWZ: the 16-byte chunk c of tile row R sits at position (c + R/16) mod 8 (the weight-gradient kernel writes its
-// tiles transposed, eight rows apart per lane, and rotates the chunks so that those writes spread over the banks).
-template <typename T, int TM, int TN, bool SWZ = false>
+// LAYOUT_XOR: rows 128 bytes apart, chunk c of tile row R at position c ^ ((R/2) % 8).
+// LAYOUT_ROT: rows 144 bytes apart, chunk c of tile row R at position (c + R/16) mod 8 (the weight-gradient kernel
+//             writes its tiles transposed, eight rows apart per lane; the rotation spreads those writes over the banks).
+enum { LAYOUT_XOR = 0, LAYOUT_ROT = 1 };
+template <typename T, int TM, int TN, int LAYOUT>
 __device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
                                 int lane) {
   const int r = lane & 31, h = lane >> 5;
-  const int rot = SWZ ? (r >> 4) : 0;        // tile rows start at multiples of 32, so R/16 = const + r/16
+  constexpr int STRIDE = LAYOUT == LAYOUT_XOR ? BKB : LDS_STRIDE;
+  const int rot = r >> 4;        // tile rows start at multiples of 32, so R/16 = const + r/16
+  const int sw = (r >> 1) & 7;   // and (R/2) % 8 = (r/2) % 8
 #pragma unroll
   for (int vs = 0; vs < BKB / 32; ++vs) {
     uint4 a[TM], b[TN];
 #pragma unroll
-    for (int t = 0; t < TM; ++t)
-      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * LDS_STRIDE +
-                                             ((vs * 2 + h + (SWZ ? 2 * (wm * TM + t) + rot : 0)) & 7) * 16);
+    for (int t = 0; t < TM; ++t) {
+      const int pos = LAYOUT == LAYOUT_XOR ? ((vs * 2 + h) ^ sw) : ((vs * 2 + h + 2 * (wm * TM + t) + rot) & 7);
+      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * STRIDE + pos * 16);
+    }
 #pragma unroll
-    for (int t = 0; t < TN; ++t)
-      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * LDS_STRIDE +
-                                             ((vs * 2 + h + (SWZ ? 2 * (wn * TN + t) + rot : 0)) & 7) * 16);
+    for (int t = 0; t < TN; ++t) {
+      const int pos = LAYOUT == LAYOUT_XOR ? ((vs * 2 + h) ^ sw) : ((vs * 2 + h + 2 * (wn * TN + t) + rot) & 7);
+      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * STRIDE + pos * 16);
+    }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn) mma16B(acc[tm][tn], a[tm], b[tn], T());
   }
 }
+
+// 16 bytes per lane from global memory straight into LDS: the wave's 64 lanes fill the 1 KiB starting at lds_base
+// (wave-uniform) in lane order.  Completion is counted by vmcnt like any vector load.
+__device__ inline void load16_to_lds(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+__device__ inline void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+// source of the 16 zero bytes a lane fetches for a padding tap, a row past the model's end, or a column past N
+__device__ __attribute__((aligned(16))) unsigned char zero_chunk[16];
 
 __device__ inline void store_out(float* p, float v) { *p = v; }
 __device__ inline void store_out(bf16_t* p, float v) { *p = from_float<bf16_t>(v); }
@@ -109,11 +127,13 @@ static int log2_or_neg(int v) {
 template <typename T, int MODE, int EPI, typename TL>
 __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, PA = TL::PA, PB = TL::PB, RPP = TL::RPP;
-  __shared__ __attribute__((aligned(16))) unsigned char As[2][BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) unsigned char Bs[2][BN * LDS_STRIDE];
+  constexpr int SMEM = 2 * (BM + BN) * BKB;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
+  unsigned char* const As = smem;                    // stage s at As + s * BM * BKB
+  unsigned char* const Bs = smem + 2 * BM * BKB;     // stage s at Bs + s * BN * BKB
   constexpr int BK = BKB / (int)sizeof(T);
   constexpr int EPV = 16 / (int)sizeof(T);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / TL::WN, wn = wave % TL::WN;
 
   // ---- which tile: consecutive virtual ids stay on one XCD (block ids are dealt round-robin to the 8 XCDs).
@@ -153,9 +173,10 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const T* __restrict__ A = static_cast<const T*>(p.A);
   const T* __restrict__ W = static_cast<const T*>(p.W) + (long long)l * p.w_stride;
 
-  // ---- per-thread load assignment: 16-byte chunk (tid % 8) of rows tid/8 + RPP i
-  const int chunk = tid & 7;
+  // ---- per-thread load assignment: rows tid/8 + RPP i, LDS position tid % 8 of the row, which holds the row's
+  // 16-byte chunk (tid % 8) ^ ((row / 2) % 8) (RPP is a multiple of 16, so the same chunk in every pass)
   const int row0 = tid >> 3;
+  const int chunk = (tid & 7) ^ ((row0 >> 1) & 7);
   long long abase[PA];
   int aby[PA], abx[PA];
 #pragma unroll
@@ -184,8 +205,8 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const int nk = ntaps * C / BK;
   const int cpt = C / BK;        // channel chunks per tap
   const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
-  uint4 ra[PA], rb[PB];
-  auto load_chunk = [&](int kc) {
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;     // LDS byte address of the buffers
+  auto load_chunk = [&](int kc, int stage) {
     // K order: taps whose gathers land on the same input pixels (shifted by one) run back to back on one channel
     // chunk, so that all but the first find their rows in L2: down - the 4 taps of a (ky%2, kx%2) class; up - the
     // phase's 4 taps.
@@ -216,27 +237,21 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     } else {
       dy = 0; dx = 0; wtap = 0;
     }
+    const unsigned a_dst = lds0 + (stage * BM + wave * 8) * BKB;                 // + pass * RPP rows
+    const unsigned b_dst = lds0 + (2 * BM + stage * BN + wave * 8) * BKB;
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
       const int iy = aby[i] + dy, ix = abx[i] + dx;
       const bool ok = (unsigned)iy < (unsigned)Hin && (unsigned)ix < (unsigned)Hin;
-      ra[i] = ok ? *reinterpret_cast<const uint4*>(A + abase[i] + (long long)(iy * Hin + ix) * C + c0)
-                 : make_uint4(0, 0, 0, 0);
+      const void* src = ok ? (const void*)(A + abase[i] + (long long)(iy * Hin + ix) * C + c0) : (const void*)zero_chunk;
+      load16_to_lds(src, a_dst + i * RPP * BKB);
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       const int col = nt * BN + row0 + RPP * i;
-      rb[i] = (col < N) ? *reinterpret_cast<const uint4*>(W + ((long long)wtap * wns + col) * C + c0)
-                        : make_uint4(0, 0, 0, 0);
+      const void* src = (col < N) ? (const void*)(W + ((long long)wtap * wns + col) * C + c0) : (const void*)zero_chunk;
+      load16_to_lds(src, b_dst + i * RPP * BKB);
     }
-  };
-  auto store_chunk = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < PA; ++i)
-      *reinterpret_cast<uint4*>(As[buf] + (row0 + RPP * i) * LDS_STRIDE + chunk * 16) = ra[i];
-#pragma unroll
-    for (int i = 0; i < PB; ++i)
-      *reinterpret_cast<uint4*>(Bs[buf] + (row0 + RPP * i) * LDS_STRIDE + chunk * 16) = rb[i];
   };
 
   floatx16 acc[TM][TN];
@@ -247,19 +262,19 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  load_chunk(0);
-  store_chunk(0);
+  load_chunk(0, 0);
+  wait_vm0();
   __syncthreads();
   for (int kc = 0; kc < nk; ++kc) {
-    const bool more = kc + 1 < nk;
-    if (more) load_chunk(kc + 1);                  // global loads in flight while the MFMAs run
-    tile_mma<T, TM, TN>(acc, As[kc & 1], Bs[kc & 1], wm, wn, lane);
-    if (more) store_chunk((kc + 1) & 1);           // the other buffer was last read before the previous barrier
+    // the other buffer was last read before the previous barrier: its refill runs under this chunk's MFMAs
+    if (kc + 1 < nk) load_chunk(kc + 1, (kc + 1) & 1);
+    tile_mma<T, TM, TN, LAYOUT_XOR>(acc, As + (kc & 1) * BM * BKB, Bs + (kc & 1) * BN * BKB, wm, wn, lane);
+    wait_vm0();
     __syncthreads();
   }
 
   // ---- epilogue: output row index of every tile row, through LDS (the buffers are free now)
-  long long* orow = reinterpret_cast<long long*>(As[0]);
+  long long* orow = reinterpret_cast<long long*>(smem);
   for (int t = tid; t < BM; t += TL::NT) {
     const int r = m0 + t;
     long long o = -1;
@@ -282,7 +297,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     // For the BatchNorm that follows: per column of this tile, the sum of the fp32 results and the sum of squared
     // deviations from the tile's own column mean (merged across tiles by the pairwise-update formula, which keeps
     // the variance free of the E[x^2] - mean^2 cancellation).  Fixed order everywhere.
-    float* red = reinterpret_cast<float*>(Bs[0]);                       // [WM][BN][2]
+    float* red = reinterpret_cast<float*>(smem + SMEM - TL::WM * BN * 8);   // [WM][BN][2], at the end of the buffers
     const int valid_rows = min(BM, Mrows - m0);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
@@ -325,7 +340,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
       p.stat_partial[(t * N + col) * 2] = s1;
       p.stat_partial[(t * N + col) * 2 + 1] = s2;
     }
-    // (the patches below live in As, the sums in Bs: no barrier needed between them)
+    // (the patches below sit after the row table, the sums at the end of the buffers: no barrier needed between them)
   }
   {
     // Each wave passes its 32 x (TN*32) blocks through a private LDS patch so that every lane stores
@@ -333,8 +348,8 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     constexpr int WCOLS = TN * 32;
     constexpr int PSTRIDE = WCOLS * (int)sizeof(T) + 16;               // bytes per patch row
     constexpr int CPR = WCOLS * (int)sizeof(T) / 16;                   // 16-byte chunks per patch row
-    unsigned char* patch = As[0] + BM * 8 + wave * (32 * PSTRIDE);      // after the row table
-    static_assert(2 * BM * LDS_STRIDE >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE, "patch area");
+    unsigned char* patch = smem + BM * 8 + wave * (32 * PSTRIDE);       // after the row table
+    static_assert(SMEM >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8, "patch area");
     const int colw = nt * BN + wn * WCOLS;                              // first column of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -578,7 +593,7 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
     for (int c = 0; c < nchunks; ++c) {
       const bool more = c + 1 < nchunks;
       if (more) { chunk_pos(c + 1, sb, k0); load_chunk(sb, k0); }
-      tile_mma<T, TM, TN, true>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
+      tile_mma<T, TM, TN, LAYOUT_ROT>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
       if (more) store_chunk((c + 1) & 1);
       __syncthreads();
     }
