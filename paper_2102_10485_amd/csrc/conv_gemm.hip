@@ -13,7 +13,7 @@
 //
 // Both stage 128-byte K-rows in LDS (two buffers) and feed v_mfma_f32_32x32x16_bf16 (bf16 storage) or
 // v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
-// Forward-type kernel: the next K-chunk travels global -> LDS directly (global_load_lds_dwordx4, no registers in
+// Forward-type kernel: the next K-chunk travels global -> LDS directly (buffer_load_dwordx4 ... lds, no registers in
 // between) while the MFMAs of the current one run; rows are 128 bytes apart and the 16-byte chunk c of row R sits
 // at position c ^ ((R / 2) % 8), which keeps both the 1 KiB-per-wave writes and the MFMA operand reads off each
 // other's banks.  Weight-gradient kernel: global -> registers (8 x 8 transposes) -> LDS, row stride 144 bytes.
@@ -92,14 +92,26 @@ __device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As
   }
 }
 
-// 16 bytes per lane from global memory straight into LDS: the wave's 64 lanes fill the 1 KiB starting at lds_base
-// (wave-uniform) in lane order.  Completion is counted by vmcnt like any vector load.
-__device__ inline void load16_to_lds(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+// 16 bytes per lane from a buffer straight into LDS: the wave's 64 lanes fill the 1 KiB starting at lds_base
+// (wave-uniform) in lane order; a lane whose byte offset lies outside the buffer (NO_ROW below) delivers zeros,
+// which is how padding taps, rows past a model's end and columns past N are filled.  Completion is counted by
+// vmcnt like any vector load.
+typedef int int4v __attribute__((ext_vector_type(4)));
+constexpr unsigned NO_ROW = 0xffffffffu;
+__device__ inline int4v make_rsrc(const void* base, unsigned long long bytes) {
+  const unsigned long long p = (unsigned long long)base;
+  int4v r;
+  r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)p);
+  r.y = __builtin_amdgcn_readfirstlane((int)((unsigned)(p >> 32) & 0xffffu));                 // stride 0: raw buffer
+  r.z = __builtin_amdgcn_readfirstlane((int)(unsigned)(bytes > 0xfffffff0ull ? 0xfffffff0ull : bytes));
+  r.w = 0x00020000;
+  return r;
+}
+__device__ inline void load16_to_lds(const int4v& rsrc, unsigned byte_off, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               : : "v"(byte_off), "s"(rsrc), "s"(lds_base) : "memory", "m0");
 }
 __device__ inline void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
-// source of the 16 zero bytes a lane fetches for a padding tap, a row past the model's end, or a column past N
-__device__ __attribute__((aligned(16))) unsigned char zero_chunk[16];
 
 __device__ inline void store_out(float* p, float v) { *p = v; }
 __device__ inline void store_out(bf16_t* p, float v) { *p = from_float<bf16_t>(v); }
@@ -170,41 +182,55 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const long long sample_base = (long long)seg * p.seg_samples + s0;
   const int py = phase >> 1, px = phase & 1;
 
-  const T* __restrict__ A = static_cast<const T*>(p.A);
-  const T* __restrict__ W = static_cast<const T*>(p.W) + (long long)l * p.w_stride;
-
-  // ---- per-thread load assignment: rows tid/8 + RPP i, LDS position tid % 8 of the row, which holds the row's
-  // 16-byte chunk (tid % 8) ^ ((row / 2) % 8) (RPP is a multiple of 16, so the same chunk in every pass)
-  const int row0 = tid >> 3;
-  const int chunk = (tid & 7) ^ ((row0 >> 1) & 7);
-  long long abase[PA];
-  int aby[PA], abx[PA];
-#pragma unroll
-  for (int i = 0; i < PA; ++i) {
-    const int r = m0 + row0 + RPP * i;
-    if (r < Mrows) {
-      if (MODE == MODE_DENSE) {               // rows are read directly: one "tap" at (0, 0) of a 1 x 1 map
-        abase[i] = (sample_base * rps + r) * (long long)C;
-        aby[i] = 0;
-        abx[i] = 0;
-      } else {
-        int n, y, x;
-        decode_row(r, Hr, rps, p.hr_shift, n, y, x);
-        abase[i] = (sample_base + n) * (long long)(Hin * Hin) * C;
-        aby[i] = (MODE == MODE_DOWN) ? 2 * y - 1 : y;
-        abx[i] = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
-      }
-    } else {
-      abase[i] = 0;
-      aby[i] = -100000;   // never in range
-      abx[i] = -100000;
-    }
-  }
-
+  constexpr int SZ = (int)sizeof(T);
   const int ntaps = (MODE == MODE_DOWN) ? 16 : (MODE == MODE_UP ? 4 : 1);
   const int nk = ntaps * C / BK;
   const int cpt = C / BK;        // channel chunks per tap
   const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
+  // this model's slice of the gathered tensor (one segment) and its weight block, as bounds-checked buffers
+  const int nsamp = s1 - s0;
+  const long long a_elems = (MODE == MODE_DENSE) ? (long long)nsamp * rps * C : (long long)nsamp * Hin * Hin * C;
+  const T* a_base = static_cast<const T*>(p.A) + ((MODE == MODE_DENSE) ? sample_base * rps * C : sample_base * (long long)(Hin * Hin) * C);
+  const int4v a_rsrc = make_rsrc(a_base, (unsigned long long)a_elems * SZ);
+  const int4v w_rsrc = make_rsrc(static_cast<const T*>(p.W) + (long long)l * p.w_stride,
+                                 (unsigned long long)(MODE == MODE_DENSE ? 1 : 16) * wns * C * SZ);
+
+  // ---- per-thread load assignment: rows tid/8 + RPP i, LDS position tid % 8 of the row, which holds the row's
+  // 16-byte chunk (tid % 8) ^ ((row / 2) % 8) (RPP is a multiple of 16, so the same chunk in every pass).
+  // Per row: byte offset of its pixel at tap offset (0, 0) and the set of taps that stay inside the map.
+  const int row0 = tid >> 3;
+  const int chunk = (tid & 7) ^ ((row0 >> 1) & 7);
+  unsigned apix[PA], amask[PA], bcol[PB];
+#pragma unroll
+  for (int i = 0; i < PA; ++i) {
+    const int r = m0 + row0 + RPP * i;
+    apix[i] = 0;
+    amask[i] = 0;
+    if (r < Mrows) {
+      if (MODE == MODE_DENSE) {
+        apix[i] = (unsigned)((r * C + chunk * EPV) * SZ);
+        amask[i] = 1;
+      } else {
+        int n, y, x;
+        decode_row(r, Hr, rps, p.hr_shift, n, y, x);
+        const int by = (MODE == MODE_DOWN) ? 2 * y - 1 : y, bx = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
+        apix[i] = (unsigned)((((n * Hin + by) * Hin + bx) * C + chunk * EPV) * SZ);     // may wrap below zero: masked
+        for (int t = 0; t < ntaps; ++t) {
+          int dy, dx;
+          if (MODE == MODE_DOWN) { dy = t >> 2; dx = t & 3; }
+          else { dy = py == 0 ? ((t >> 1) == 0 ? 0 : -1) : ((t >> 1) == 0 ? 1 : 0); dx = px == 0 ? ((t & 1) == 0 ? 0 : -1) : ((t & 1) == 0 ? 1 : 0); }
+          const int iy = by + dy, ix = bx + dx;
+          if ((unsigned)iy < (unsigned)Hin && (unsigned)ix < (unsigned)Hin) amask[i] |= 1u << t;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < PB; ++i) {
+    const int col = nt * BN + row0 + RPP * i;
+    bcol[i] = col < N ? (unsigned)((col * C + chunk * EPV) * SZ) : NO_ROW;
+  }
+
   const unsigned lds0 = (unsigned)(uintptr_t)smem;     // LDS byte address of the buffers
   auto load_chunk = [&](int kc, int stage) {
     // K order: taps whose gathers land on the same input pixels (shifted by one) run back to back on one channel
@@ -212,16 +238,16 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     // phase's 4 taps.
     const int j4 = kc & 3;
     const int rest = kc >> 2;
-    int tap, c0;
+    int tap, cc;
     if (MODE == MODE_DOWN) {
       const int cls = rest / cpt;
-      c0 = (rest - cls * cpt) * BK + chunk * EPV;
+      cc = rest - cls * cpt;
       tap = (((cls >> 1) + 2 * (j4 >> 1)) << 2) + (cls & 1) + 2 * (j4 & 1);
     } else if (MODE == MODE_UP) {
-      c0 = rest * BK + chunk * EPV;
+      cc = rest;
       tap = j4;
     } else {
-      c0 = kc * BK + chunk * EPV;
+      cc = kc;
       tap = 0;
     }
     int dy, dx, wtap;
@@ -237,21 +263,16 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     } else {
       dy = 0; dx = 0; wtap = 0;
     }
+    const unsigned a_delta = (unsigned)(((dy * Hin + dx) * C + cc * BK) * SZ);    // wave-uniform
+    const unsigned w_delta = (unsigned)((wtap * wns * C + cc * BK) * SZ);
     const unsigned a_dst = lds0 + (stage * BM + wave * 8) * BKB;                 // + pass * RPP rows
     const unsigned b_dst = lds0 + (2 * BM + stage * BN + wave * 8) * BKB;
 #pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      const int iy = aby[i] + dy, ix = abx[i] + dx;
-      const bool ok = (unsigned)iy < (unsigned)Hin && (unsigned)ix < (unsigned)Hin;
-      const void* src = ok ? (const void*)(A + abase[i] + (long long)(iy * Hin + ix) * C + c0) : (const void*)zero_chunk;
-      load16_to_lds(src, a_dst + i * RPP * BKB);
-    }
+    for (int i = 0; i < PA; ++i)
+      load16_to_lds(a_rsrc, ((amask[i] >> tap) & 1u) ? apix[i] + a_delta : NO_ROW, a_dst + i * RPP * BKB);
 #pragma unroll
-    for (int i = 0; i < PB; ++i) {
-      const int col = nt * BN + row0 + RPP * i;
-      const void* src = (col < N) ? (const void*)(W + ((long long)wtap * wns + col) * C + c0) : (const void*)zero_chunk;
-      load16_to_lds(src, b_dst + i * RPP * BKB);
-    }
+    for (int i = 0; i < PB; ++i)
+      load16_to_lds(w_rsrc, bcol[i] != NO_ROW ? bcol[i] + w_delta : NO_ROW, b_dst + i * RPP * BKB);
   };
 
   floatx16 acc[TM][TN];
@@ -413,6 +434,13 @@ void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
       (epi == EPI_ACT_BWD && !a.Aux))
     abort();
   if (a.N < 64) abort();                        // image-side outputs have their own kernel
+  {
+    // the loaders address one model's slice of A and one weight block with 32-bit byte offsets
+    const long long side = mode == MODE_DENSE ? a.Hr : a.Hin;
+    if ((long long)a.seg_samples * side * side * a.C * (long long)sizeof(T) >= (1LL << 31) ||
+        16LL * a.w_nstride * a.C * (long long)sizeof(T) >= (1LL << 31))
+      abort();
+  }
   if (mode == MODE_DOWN && epi == EPI_NONE) return launch_wide<T, MODE_DOWN, EPI_NONE>(a, st);
   if (mode == MODE_UP && epi == EPI_NONE) return launch_wide<T, MODE_UP, EPI_NONE>(a, st);
   if (mode == MODE_UP && epi == EPI_ACT_BWD) return launch_wide<T, MODE_UP, EPI_ACT_BWD>(a, st);
