@@ -642,6 +642,176 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
     }
 }
 
+// ---- bf16 weight gradient: tiles stay in their memory layout ---------------------------------------------
+// Both operands are stored [row][channel] in HBM while the MFMA wants, per lane, eight consecutive rows (the
+// reduction index) of one channel.  The bf16 kernel copies K-chunks of 64 rows x BM (BN) channels global -> LDS
+// as they are and lets ds_read_b64_tr_b16 do the transposition on the way to the registers: within each block of
+// 16 lanes, lane i receives element i%4 of the 8-byte groups addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.
+// Pointing lane s of a block at row (s/4), channel group (s%4) therefore hands lane i rows 0..3 of channel i.
+// LDS rows are BM*2 (BN*2) bytes; the 16-byte chunk c of row R sits at position c ^ swz(R) so that the four rows
+// a 32-lane half reads fall into different 64-byte bank groups.
+constexpr int WG_KR = 64;      // rows (reduction index) per chunk
+template <int ROWB>
+__device__ inline int wg_swz(int row) {   // in 16-byte chunks
+  return ROWB >= 256 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
+}
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ inline uint2 lds_read_tr16(const unsigned char* p) {
+  const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(p));
+  return __builtin_bit_cast(uint2, v);
+}
+
+template <typename TL>
+__global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
+  typedef bf16_t T;
+  constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, NT_ = TL::NT;
+  constexpr int RBA = BM * 2, RBB = BN * 2;                 // bytes per LDS row
+  constexpr int CPA = BM / 8, CPB = BN / 8;                 // 16-byte chunks per row
+  constexpr int PA = WG_KR * CPA / NT_, PB = WG_KR * CPB / NT_;
+  constexpr int RPA = NT_ / CPA, RPB = NT_ / CPB;           // rows per loader pass (multiples of 4)
+  static_assert(WG_KR * CPA % NT_ == 0 && WG_KR * CPB % NT_ == 0 && RPA % 4 == 0 && RPB % 4 == 0, "loader shape");
+  constexpr int STAGE_A = WG_KR * RBA, STAGE_B = WG_KR * RBB;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * (STAGE_A + STAGE_B)];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / TL::WN, wn = wave % TL::WN;
+
+  // ---- tile: all tiles of a model run on one XCD, models are dealt round-robin to XCDs
+  const int Cb = p.Cb, Cs = p.Cs, Hs = p.Hs;
+  const int Mtot = p.ntaps * Cb;
+  const int MT = (Mtot + BM - 1) / BM, NTL = (Cs + BN - 1) / BN;
+  const int per_model = MT * NTL * p.ksplit;
+  const int bid = blockIdx.x;
+  const int l = (bid / (8 * per_model)) * 8 + (bid & 7);
+  if (l >= p.L) return;
+  const int q = (bid >> 3) % per_model;
+  const int tile = q % (MT * NTL), split = q / (MT * NTL);
+  const int mt = tile / NTL, nt = tile - mt * NTL;
+  const int s0 = p.offs[l], s1 = p.offs[l + 1];
+  const int rps = Hs * Hs;
+  const int R = (s1 - s0) * rps;
+  const int Hb = 2 * Hs;
+  const int rows_split = ((R + p.ksplit - 1) / p.ksplit + WG_KR - 1) / WG_KR * WG_KR;
+  const int r_lo = split * rows_split, r_hi = min(R, r_lo + rows_split);
+
+  // ---- loader: slot = pass * NT + tid is the 16-byte LDS slot; it holds chunk (slot % CP) ^ swz(row) of row slot / CP
+  const int rowA0 = tid / CPA, rowB0 = tid / CPB;
+  const int chA = (tid % CPA) ^ wg_swz<RBA>(rowA0), chB = (tid % CPB) ^ wg_swz<RBB>(rowB0);
+  const int mA = mt * BM + chA * 8;                          // first of this thread's 8 channels along M
+  const bool okA = mA < Mtot;
+  const int tapA = okA ? mA / Cb : 0;
+  const int cA = mA - tapA * Cb;
+  const int kyA = p.ntaps == 1 ? 1 : (tapA >> 2), kxA = p.ntaps == 1 ? 1 : (tapA & 3);
+  const int cB = nt * BN + chB * 8;
+  const bool okB = cB < Cs;
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  const long long big_per_sample = p.ntaps == 1 ? (long long)rps * Cb : (long long)Hb * Hb * Cb;
+
+  auto load_chunk = [&](int seg, int k0, int stage) {
+    const long long sb = (long long)seg * p.seg_samples + s0;
+    const int4v a_rsrc = make_rsrc(static_cast<const T*>(p.Big) + sb * big_per_sample, (unsigned long long)(s1 - s0) * big_per_sample * 2);
+    const int4v b_rsrc = make_rsrc(static_cast<const T*>(p.Small) + sb * rps * Cs, (unsigned long long)R * Cs * 2);
+    const unsigned a_dst = lds0 + stage * STAGE_A + wave * 1024;
+    const unsigned b_dst = lds0 + 2 * STAGE_A + stage * STAGE_B + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+      const int r = k0 + rowA0 + i * RPA;
+      unsigned off = NO_ROW;
+      if (r < r_hi && okA) {
+        if (p.ntaps == 1) {
+          off = (unsigned)((r * Cb + cA) * 2);
+        } else {
+          int n, y, x;
+          decode_row(r, Hs, rps, p.hs_shift, n, y, x);
+          const int iy = 2 * y - 1 + kyA, ix = 2 * x - 1 + kxA;
+          if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb) off = (unsigned)((((n * Hb + iy) * Hb + ix) * Cb + cA) * 2);
+        }
+      }
+      load16_to_lds(a_rsrc, off, a_dst + i * NT_ * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int r = k0 + rowB0 + i * RPB;
+      const unsigned off = (r < r_hi && okB) ? (unsigned)((r * Cs + cB) * 2) : NO_ROW;
+      load16_to_lds(b_rsrc, off, b_dst + i * NT_ * 16);
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // ---- fragment addressing: lane = 32 * kgrp + 16 * hb + s ; it points at row 8*kgrp + 4*half + s/4 of the k-step,
+  // channels 16*hb + 4*(s%4) .. +3 of the 32-channel fragment
+  const int s16 = lane & 15, hb = (lane >> 4) & 1, kgrp = lane >> 5;
+  const int frow = 8 * kgrp + (s16 >> 2);                    // + 16 * kstep + 4 * half
+  const int fch = 2 * hb + ((s16 & 3) >> 1);                 // 16-byte chunk inside the 32-channel fragment (0..3)
+  const int fbyte = 8 * (s16 & 1);
+  const int swzA = wg_swz<RBA>(frow), swzB = wg_swz<RBB>(frow);   // frow % 4 (and (frow/2) % 2) do not change with kstep or half
+  auto mma_chunk = [&](int stage) {
+    const unsigned char* As = smem + stage * STAGE_A;
+    const unsigned char* Bs = smem + 2 * STAGE_A + stage * STAGE_B;
+#pragma unroll
+    for (int ks = 0; ks < WG_KR / 16; ++ks) {
+      uint4 a[TM], b[TN];
+#pragma unroll
+      for (int t = 0; t < TM; ++t) {
+        const int ch = ((wm * TM + t) * 4 + fch) ^ swzA;
+        const unsigned char* q0 = As + (ks * 16 + frow) * RBA + ch * 16 + fbyte;
+        const uint2 lo = lds_read_tr16(q0), hi = lds_read_tr16(q0 + 4 * RBA);
+        a[t] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+#pragma unroll
+      for (int t = 0; t < TN; ++t) {
+        const int ch = ((wn * TN + t) * 4 + fch) ^ swzB;
+        const unsigned char* q0 = Bs + (ks * 16 + frow) * RBB + ch * 16 + fbyte;
+        const uint2 lo = lds_read_tr16(q0), hi = lds_read_tr16(q0 + 4 * RBB);
+        b[t] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) mma16B(acc[tm][tn], a[tm], b[tn], T());
+    }
+  };
+
+  // chunks of all segments as one sequence
+  const int per_seg = r_hi > r_lo ? (r_hi - r_lo + WG_KR - 1) / WG_KR : 0;
+  const int nchunks = per_seg * p.nseg;
+  if (nchunks > 0) {
+    load_chunk(0, r_lo, 0);
+    wait_vm0();
+    __syncthreads();
+    int seg = 0, cin = 0;
+    for (int c = 0; c < nchunks; ++c) {
+      if (c + 1 < nchunks) {
+        if (++cin == per_seg) { cin = 0; ++seg; }
+        load_chunk(seg, r_lo + cin * WG_KR, (c + 1) & 1);
+      }
+      mma_chunk(c & 1);
+      wait_vm0();
+      __syncthreads();
+    }
+  }
+
+  float* __restrict__ dW = p.dW + (long long)split * p.split_stride + (long long)l * p.dw_stride;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int col = nt * BN + wn * TN * 32 + tn * 32 + (lane & 31);
+      if (col >= Cs) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = mt * BM + wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (m < Mtot) dW[(long long)m * Cs + col] = acc[tm][tn][e];
+      }
+    }
+}
+
 typedef Tile<64, 128, 1, 4> TileWgImg;    // patch-matrix layers: 64 packed columns x 128 feature channels
 
 template <typename T, typename TL>
@@ -650,7 +820,15 @@ static void launch_wgrad_one(WgradArgs a, hipStream_t st) {
   const int MT = (a.ntaps * a.Cb + TL::BM - 1) / TL::BM, NT = (a.Cs + TL::BN - 1) / TL::BN;
   const long long blocks = (long long)((a.L + 7) / 8) * 8 * MT * NT * a.ksplit;
   if (blocks == 0) return;
-  hipLaunchKernelGGL((wgrad_kernel<T, TL>), dim3((unsigned)blocks), dim3(TL::NT), 0, st, a);
+  if (sizeof(T) == 2) {
+    // 32-bit byte offsets inside one model's slice of either operand
+    const long long side = a.ntaps == 1 ? a.Hs : 2 * a.Hs;
+    if ((long long)a.seg_samples * side * side * a.Cb * 2 >= (1LL << 31) || (long long)a.seg_samples * a.Hs * a.Hs * a.Cs * 2 >= (1LL << 31))
+      abort();
+    hipLaunchKernelGGL((wgrad_tr_kernel<TL>), dim3((unsigned)blocks), dim3(TL::NT), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((wgrad_kernel<T, TL>), dim3((unsigned)blocks), dim3(TL::NT), 0, st, a);
+  }
 }
 
 template <typename T>
