@@ -192,6 +192,26 @@ __device__ inline void store4(bf16_t* p, const float (&v)[4]) {
   *reinterpret_cast<uint2*>(p) = t;
 }
 
+// 16 bytes of consecutive channels as floats: 4 (fp32) or 8 (bf16).
+template <typename T> struct Vec16 { static constexpr int N = 16 / (int)sizeof(T); };
+__device__ inline void loadv(const float* p, float (&v)[4]) { load4(p, v); }
+__device__ inline void loadv(const bf16_t* p, float (&v)[8]) {
+  const uint4 t = *reinterpret_cast<const uint4*>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+  v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u);
+  v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xffff0000u);
+}
+__device__ inline void storev(float* p, const float (&v)[4]) { store4(p, v); }
+__device__ inline void storev(bf16_t* p, const float (&v)[8]) {
+  uint4 t;
+  t.x = (unsigned)f32_to_bf16_bits(v[0]) | ((unsigned)f32_to_bf16_bits(v[1]) << 16);
+  t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
+  t.z = (unsigned)f32_to_bf16_bits(v[4]) | ((unsigned)f32_to_bf16_bits(v[5]) << 16);
+  t.w = (unsigned)f32_to_bf16_bits(v[6]) | ((unsigned)f32_to_bf16_bits(v[7]) << 16);
+  *reinterpret_cast<uint4*>(p) = t;
+}
+
 // mean / var / rstd from what the producing GEMM left per tile and column: (sum, sum of squared deviations from the
 // tile's mean).  Tiles (and output phases, and column runs) of one (segment, model) are merged in a fixed order
 // with the pairwise update  mean += d n_t/(n+n_t),  M2 += M2_t + d^2 n n_t/(n+n_t),  d = mean_t - mean.
@@ -269,37 +289,50 @@ void launch_bn_from_running(const NormArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(bn_from_running_kernel, dim3((a.L * a.C + 255) / 256), dim3(256), 0, st, a);
 }
 
-// y = act(gamma * (x - mean) * rstd + beta); one thread per 4 channels of one row.
+// y = act(gamma * (x - mean) * rstd + beta).  One block per (sample, segment): a thread keeps the parameters of its
+// 16 bytes of channels in registers and walks down the sample's rows.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_kernel(NormArgs a) {
-  const int c4 = a.C / 4;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  const long long rows_seg = (long long)a.n * a.rps;
-  if (idx >= rows_seg * c4 * a.nseg) return;
-  const long long row_all = idx / c4;
-  const int c = (int)(idx - row_all * c4) * 4;
-  const int sidx = (int)(row_all / rows_seg);
-  const long long row = row_all - (long long)sidx * rows_seg;
-  const int j = (int)(row / a.rps);
+  constexpr int EPV = Vec16<T>::N;
+  const int j = blockIdx.x, sidx = blockIdx.y;
   if (j >= a.offs[a.L]) return;
   const int l = a.sample_model[j];
   const int seg = a.seg_first + sidx;
-  const long long e = (((long long)seg * a.seg_samples) * a.rps + row) * a.C + c;
-  const long long so = (long long)(seg * a.L + l) * a.C + c;
-  float v[4];
-  load4(static_cast<const T*>(a.x) + e, v);
+  const int cg = a.C / EPV;                           // channel groups per row
+  const long long base = ((long long)seg * a.seg_samples + j) * a.rps * a.C;
+  const T* x = static_cast<const T*>(a.x) + base;
+  T* y = static_cast<T*>(a.y) + base;
+  const long long so = (long long)(seg * a.L + l) * a.C;
+  // a thread's channel group is fixed when the block's thread count is a multiple of cg (the usual case); otherwise
+  // it changes from pass to pass and the parameters are reloaded
+  const int total = a.rps * cg;
+  int cur = -1;
+  float sc[EPV], mu[EPV], be[EPV];
+  for (int t = threadIdx.x; t < total; t += 256) {
+    const int r = t / cg, g = t - r * cg;
+    if (g != cur) {
+      cur = g;
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const float sc = a.gamma[(long long)l * a.pstride + c + k] * a.rstd[so + k];
-    const float u = (v[k] - a.mean[so + k]) * sc + a.beta[(long long)l * a.pstride + c + k];
-    v[k] = u > 0.f ? u : u * a.slope;
+      for (int k = 0; k < EPV; ++k) {
+        const int c = g * EPV + k;
+        sc[k] = a.gamma[(long long)l * a.pstride + c] * a.rstd[so + c];
+        mu[k] = a.mean[so + c];
+        be[k] = a.beta[(long long)l * a.pstride + c];
+      }
+    }
+    float v[EPV];
+    loadv(x + (long long)r * a.C + g * EPV, v);
+#pragma unroll
+    for (int k = 0; k < EPV; ++k) {
+      const float u = (v[k] - mu[k]) * sc[k] + be[k];
+      v[k] = u > 0.f ? u : u * a.slope;
+    }
+    storev(y + (long long)r * a.C + g * EPV, v);
   }
-  store4(static_cast<T*>(a.y) + e, v);
 }
 template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st) {
-  const long long tot = (long long)a.n * a.rps * (a.C / 4) * a.nseg;
-  if (tot == 0) return;
-  hipLaunchKernelGGL((bn_apply_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+  if (a.n == 0 || a.nseg == 0) return;
+  hipLaunchKernelGGL((bn_apply_kernel<T>), dim3((unsigned)a.n, (unsigned)a.nseg), dim3(256), 0, st, a);
 }
 template void launch_bn_apply<float>(const NormArgs&, hipStream_t);
 template void launch_bn_apply<bf16_t>(const NormArgs&, hipStream_t);
@@ -310,7 +343,9 @@ template void launch_bn_apply<bf16_t>(const NormArgs&, hipStream_t);
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
                                                             float* __restrict__ partial) {
-  __shared__ float red[2][16][64];
+  constexpr int EPV = Vec16<T>::N;
+  constexpr int CL = 64 / EPV, RL = 256 / CL;       // channel lanes x row lanes
+  __shared__ float red[2][RL][64];
   const int tile = blockIdx.y;
   if (tile >= tpre[a.L]) return;
   int lo = 0, hi = a.L;
@@ -323,28 +358,30 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const in
   const int cnt = a.offs[l + 1] - a.offs[l];
   const int g = seg * a.L + l;
   const int c0 = blockIdx.x * 64;
-  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
   const long long rows = (long long)cnt * a.rps;
   const long long r0 = (long long)(tile - tpre[l]) * BN_RED_ROWS;
   const long long r1 = min(rows, r0 + BN_RED_ROWS);
-  const long long base = ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * 4;
+  const long long base = ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * EPV;
   const T* x = static_cast<const T*>(a.x) + base;
   const T* dy = static_cast<const T*>(a.dy) + base;
-  float mu[4], rs[4], ga[4], be[4], sg[4] = {0, 0, 0, 0}, sgx[4] = {0, 0, 0, 0};
+  float mu[EPV], rs[EPV], ga[EPV], be[EPV], sg[EPV], sgx[EPV];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int c = c0 + cl * 4 + e;
+  for (int e = 0; e < EPV; ++e) {
+    const int c = c0 + cl * EPV + e;
     mu[e] = a.mean[(long long)g * a.C + c];
     rs[e] = a.rstd[(long long)g * a.C + c];
     ga[e] = a.gamma[(long long)l * a.pstride + c];
     be[e] = a.beta[(long long)l * a.pstride + c];
+    sg[e] = 0.f;
+    sgx[e] = 0.f;
   }
-  for (long long r = r0 + rl; r < r1; r += 16) {
-    float v[4], d[4];
-    load4(x + r * a.C, v);
-    load4(dy + r * a.C, d);
+  for (long long r = r0 + rl; r < r1; r += RL) {
+    float v[EPV], d[EPV];
+    loadv(x + r * a.C, v);
+    loadv(dy + r * a.C, d);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < EPV; ++e) {
       const float xh = (v[e] - mu[e]) * rs[e];
       const float u = ga[e] * xh + be[e];
       const float gg = u > 0.f ? d[e] : d[e] * a.slope;
@@ -353,12 +390,12 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const in
     }
   }
 #pragma unroll
-  for (int e = 0; e < 4; ++e) { red[0][rl][cl * 4 + e] = sg[e]; red[1][rl][cl * 4 + e] = sgx[e]; }
+  for (int e = 0; e < EPV; ++e) { red[0][rl][cl * EPV + e] = sg[e]; red[1][rl][cl * EPV + e] = sgx[e]; }
   __syncthreads();
   if (threadIdx.x < 128) {
     const int w = threadIdx.x >> 6, c = threadIdx.x & 63;
     float t = 0.f;
-    for (int i = 0; i < 16; ++i) t += red[w][i][c];
+    for (int i = 0; i < RL; ++i) t += red[w][i][c];
     partial[(((long long)sidx * ub_tiles + tile) * a.C + c0 + c) * 2 + w] = t;
   }
 }
@@ -410,42 +447,55 @@ void launch_bn_param_grad(const NormArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(bn_param_grad_kernel, dim3((a.L * a.C + 255) / 256), dim3(256), 0, st, a);
 }
 
-// dx = gamma * rstd * (g - sum_g / S - xhat * sum_gx / S)
+// dx = gamma * rstd * (g - sum_g / S - xhat * sum_gx / S).  Same block shape as the forward pass.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(NormArgs a) {
-  const int c4 = a.C / 4;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  const long long rows_seg = (long long)a.n * a.rps;
-  if (idx >= rows_seg * c4 * a.nseg) return;
-  const long long row_all = idx / c4;
-  const int c = (int)(idx - row_all * c4) * 4;
-  const int sidx = (int)(row_all / rows_seg);
-  const long long row = row_all - (long long)sidx * rows_seg;
-  const int j = (int)(row / a.rps);
+  constexpr int EPV = Vec16<T>::N;
+  const int j = blockIdx.x, sidx = blockIdx.y;
   if (j >= a.offs[a.L]) return;
   const int l = a.sample_model[j];
   const int seg = a.seg_first + sidx;
+  const int cg = a.C / EPV;
   const float invS = 1.0f / ((float)(a.offs[l + 1] - a.offs[l]) * (float)a.rps);
-  const long long e = (((long long)seg * a.seg_samples) * a.rps + row) * a.C + c;
-  const long long so = (long long)(seg * a.L + l) * a.C + c;
-  float v[4], d[4];
-  load4(static_cast<const T*>(a.x) + e, v);
-  load4(static_cast<const T*>(a.dy) + e, d);
+  const long long base = ((long long)seg * a.seg_samples + j) * a.rps * a.C;
+  const T* x = static_cast<const T*>(a.x) + base;
+  const T* dy = static_cast<const T*>(a.dy) + base;
+  T* dx = static_cast<T*>(a.y) + base;
+  const long long so = (long long)(seg * a.L + l) * a.C;
+  const int total = a.rps * cg;
+  int cur = -1;
+  float rs[EPV], ga[EPV], mu[EPV], be[EPV], s1[EPV], s2[EPV];
+  for (int t = threadIdx.x; t < total; t += 256) {
+    const int r = t / cg, g = t - r * cg;
+    if (g != cur) {
+      cur = g;
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const float rs = a.rstd[so + k];
-    const float ga = a.gamma[(long long)l * a.pstride + c + k];
-    const float xh = (v[k] - a.mean[so + k]) * rs;
-    const float u = ga * xh + a.beta[(long long)l * a.pstride + c + k];
-    const float gg = u > 0.f ? d[k] : d[k] * a.slope;
-    v[k] = ga * rs * (gg - a.sums[(so + k) * 2] * invS - xh * a.sums[(so + k) * 2 + 1] * invS);
+      for (int k = 0; k < EPV; ++k) {
+        const int c = g * EPV + k;
+        rs[k] = a.rstd[so + c];
+        ga[k] = a.gamma[(long long)l * a.pstride + c];
+        mu[k] = a.mean[so + c];
+        be[k] = a.beta[(long long)l * a.pstride + c];
+        s1[k] = a.sums[(so + c) * 2] * invS;
+        s2[k] = a.sums[(so + c) * 2 + 1] * invS;
+      }
+    }
+    float v[EPV], d[EPV];
+    loadv(x + (long long)r * a.C + g * EPV, v);
+    loadv(dy + (long long)r * a.C + g * EPV, d);
+#pragma unroll
+    for (int k = 0; k < EPV; ++k) {
+      const float xh = (v[k] - mu[k]) * rs[k];
+      const float u = ga[k] * xh + be[k];
+      const float gg = u > 0.f ? d[k] : d[k] * a.slope;
+      v[k] = ga[k] * rs[k] * (gg - s1[k] - xh * s2[k]);
+    }
+    storev(dx + (long long)r * a.C + g * EPV, v);
   }
-  store4(static_cast<T*>(a.y) + e, v);
 }
 template <typename T> void launch_bn_bwd_apply(const NormArgs& a, hipStream_t st) {
-  const long long tot = (long long)a.n * a.rps * (a.C / 4) * a.nseg;
-  if (tot == 0) return;
-  hipLaunchKernelGGL((bn_bwd_apply_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+  if (a.n == 0 || a.nseg == 0) return;
+  hipLaunchKernelGGL((bn_bwd_apply_kernel<T>), dim3((unsigned)a.n, (unsigned)a.nseg), dim3(256), 0, st, a);
 }
 template void launch_bn_bwd_apply<float>(const NormArgs&, hipStream_t);
 template void launch_bn_bwd_apply<bf16_t>(const NormArgs&, hipStream_t);
