@@ -651,6 +651,8 @@ bool check_config(const gan_config* f, std::string& why) {
   if (((f->img_hw >> f->n_d) << f->n_d) != f->img_hw || (f->img_hw >> f->n_d) < 1) { why = "img_hw must be divisible by 2^n_d"; return false; }
   for (int i = 0; i < f->n_g; ++i) if (f->g_ch[i] <= 0 || f->g_ch[i] % 64) { why = "g_ch must be multiples of 64"; return false; }
   for (int i = 0; i < f->n_d; ++i) if (f->d_ch[i] <= 0 || f->d_ch[i] % 64) { why = "d_ch must be multiples of 64"; return false; }
+  for (int i = 0; i < f->n_g; ++i) if (f->g_ch[i] > 1024) { why = "at most 1024 channels per layer"; return false; }
+  for (int i = 0; i < f->n_d; ++i) if (f->d_ch[i] > 1024) { why = "at most 1024 channels per layer"; return false; }
   if (f->g_ch[f->n_g - 1] > 128 || f->d_ch[0] > 128) { why = "the layers next to the image support 64 or 128 feature channels"; return false; }
   if ((f->g_ch[0] * f->g_h0 * f->g_h0) % 128) { why = "g_ch[0]*g_h0^2 must be a multiple of 128"; return false; }
   if (f->z_dim < 1 || f->cond_g < 0 || f->cond_d < 0 || f->max_total_batch < 1) { why = "bad z_dim / cond / max_total_batch"; return false; }

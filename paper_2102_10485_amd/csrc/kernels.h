@@ -69,7 +69,7 @@ void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const
 void launch_bn_running(const NormArgs& a, hipStream_t st);
 void launch_bn_from_running(const NormArgs& a, hipStream_t st);   // mean/rstd <- running statistics
 template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st);
-constexpr int BN_RED_ROWS = 1024;   // rows per block of the backward reduction (tile prefix geometry (rps, BN_RED_ROWS))
+constexpr int BN_RED_ROWS = 256;    // rows per block of the backward reduction (tile prefix geometry (rps, BN_RED_ROWS))
 template <typename T>
 void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, int ub_tiles, float* partial, hipStream_t st);
 void launch_bn_param_grad(const NormArgs& a, hipStream_t st);

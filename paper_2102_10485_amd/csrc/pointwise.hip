@@ -338,37 +338,37 @@ template void launch_bn_apply<float>(const NormArgs&, hipStream_t);
 template void launch_bn_apply<bf16_t>(const NormArgs&, hipStream_t);
 
 // sums[g][c] = (sum g, sum g * xhat) with g = dy * act'(u), u = gamma * xhat + beta.
-// Stage 1: block (64 channels, tile of BN_RED_ROWS rows of one model, segment) -> partial[segment][tile][C][2].
+// Stage 1: block (tile of BN_RED_ROWS rows of one model, segment), all channels -> partial[segment][tile][C][2].
 // Stage 2: the tiles of a (segment, model) added in order.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
                                                             float* __restrict__ partial) {
   constexpr int EPV = Vec16<T>::N;
-  constexpr int CL = 64 / EPV, RL = 256 / CL;       // channel lanes x row lanes
-  __shared__ float red[2][RL][64];
-  const int tile = blockIdx.y;
+  extern __shared__ float red[];                    // [2][RL][C]
+  const int tile = blockIdx.x;
   if (tile >= tpre[a.L]) return;
   int lo = 0, hi = a.L;
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
     if (tpre[mid] <= tile) lo = mid; else hi = mid;
   }
-  const int l = lo, sidx = blockIdx.z;
+  const int l = lo, sidx = blockIdx.y;
   const int seg = a.seg_first + sidx;
   const int cnt = a.offs[l + 1] - a.offs[l];
   const int g = seg * a.L + l;
-  const int c0 = blockIdx.x * 64;
-  const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
+  const int cg = a.C / EPV;                         // channel lanes (<= 256, a divisor of 256 or not)
+  const int RL = 256 / cg;                          // row lanes
+  const int cl = threadIdx.x % cg, rl = threadIdx.x / cg;
   const long long rows = (long long)cnt * a.rps;
   const long long r0 = (long long)(tile - tpre[l]) * BN_RED_ROWS;
   const long long r1 = min(rows, r0 + BN_RED_ROWS);
-  const long long base = ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + c0 + cl * EPV;
+  const long long base = ((long long)seg * a.seg_samples + a.offs[l]) * a.rps * a.C + cl * EPV;
   const T* x = static_cast<const T*>(a.x) + base;
   const T* dy = static_cast<const T*>(a.dy) + base;
   float mu[EPV], rs[EPV], ga[EPV], be[EPV], sg[EPV], sgx[EPV];
 #pragma unroll
   for (int e = 0; e < EPV; ++e) {
-    const int c = c0 + cl * EPV + e;
+    const int c = cl * EPV + e;
     mu[e] = a.mean[(long long)g * a.C + c];
     rs[e] = a.rstd[(long long)g * a.C + c];
     ga[e] = a.gamma[(long long)l * a.pstride + c];
@@ -376,27 +376,32 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const in
     sg[e] = 0.f;
     sgx[e] = 0.f;
   }
-  for (long long r = r0 + rl; r < r1; r += RL) {
-    float v[EPV], d[EPV];
-    loadv(x + r * a.C, v);
-    loadv(dy + r * a.C, d);
+  if (rl < RL) {
+    for (long long r = r0 + rl; r < r1; r += RL) {
+      float v[EPV], d[EPV];
+      loadv(x + r * a.C, v);
+      loadv(dy + r * a.C, d);
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) {
+        const float xh = (v[e] - mu[e]) * rs[e];
+        const float u = ga[e] * xh + be[e];
+        const float gg = u > 0.f ? d[e] : d[e] * a.slope;
+        sg[e] += gg;
+        sgx[e] += gg * xh;
+      }
+    }
 #pragma unroll
     for (int e = 0; e < EPV; ++e) {
-      const float xh = (v[e] - mu[e]) * rs[e];
-      const float u = ga[e] * xh + be[e];
-      const float gg = u > 0.f ? d[e] : d[e] * a.slope;
-      sg[e] += gg;
-      sgx[e] += gg * xh;
+      red[(0 * RL + rl) * a.C + cl * EPV + e] = sg[e];
+      red[(1 * RL + rl) * a.C + cl * EPV + e] = sgx[e];
     }
   }
-#pragma unroll
-  for (int e = 0; e < EPV; ++e) { red[0][rl][cl * EPV + e] = sg[e]; red[1][rl][cl * EPV + e] = sgx[e]; }
   __syncthreads();
-  if (threadIdx.x < 128) {
-    const int w = threadIdx.x >> 6, c = threadIdx.x & 63;
-    float t = 0.f;
-    for (int i = 0; i < RL; ++i) t += red[w][i][c];
-    partial[(((long long)sidx * ub_tiles + tile) * a.C + c0 + c) * 2 + w] = t;
+  for (int t = threadIdx.x; t < 2 * a.C; t += 256) {
+    const int w = t / a.C, c = t - w * a.C;
+    float acc = 0.f;
+    for (int i = 0; i < RL; ++i) acc += red[(w * RL + i) * a.C + c];
+    partial[(((long long)sidx * ub_tiles + tile) * a.C + c) * 2 + w] = acc;
   }
 }
 __global__ void bn_bwd_reduce_final_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
@@ -420,7 +425,10 @@ __global__ void bn_bwd_reduce_final_kernel(NormArgs a, const int* __restrict__ t
 template <typename T>
 void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, int ub_tiles, float* partial, hipStream_t st) {
   if (a.nseg == 0 || ub_tiles == 0) return;
-  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(a.C / 64, ub_tiles, a.nseg), dim3(256), 0, st, a, tpre, ub_tiles, partial);
+  const int cg = a.C / Vec16<T>::N;
+  if (cg < 1 || cg > 256) abort();                  // one thread per 16 bytes of a row
+  const size_t lds = (size_t)2 * (256 / cg) * a.C * sizeof(float);
+  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(ub_tiles, a.nseg), dim3(256), lds, st, a, tpre, ub_tiles, partial);
   const long long tot = (long long)a.nseg * a.L * a.C;
   hipLaunchKernelGGL(bn_bwd_reduce_final_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a, tpre, ub_tiles,
                      partial);
