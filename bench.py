@@ -14,6 +14,38 @@ import numpy as np
 
 PEAK = {"mfma_bf16": 2500.0, "mfma_fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s (published MI355X figures)
 
+# HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, averaged over the
+# launches of a kernel instantiation in `bench.py --steps 3 --warmup 1 --no-profile --copy-probe`, config 2 bf16), scaled by what
+# the same counters read for the 1 GiB elementwise probe (fetch x 2.0, write x 1.0).  Valid only for the kernel sources they
+# were taken with: `sources` is the digest of csrc/ at that time, and the roofline reports null traffic when it differs.
+MEASURED_TRAFFIC = {
+    "sources": None,
+    "workload": "config 2 bf16",
+    "fetch_scale": 2.0, "write_scale": 1.0,
+    "kib_per_launch": {},     # kernel family -> (FETCH_SIZE, WRITE_SIZE)
+}
+
+
+def sources_digest():
+    import glob
+    import hashlib
+    import os
+    h = hashlib.sha256()
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2102_10485_amd", "csrc")
+    for f in sorted(glob.glob(os.path.join(root, "*.hip")) + glob.glob(os.path.join(root, "*.h"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(kernel, workload):
+    m = MEASURED_TRAFFIC
+    if m["sources"] != sources_digest() or m["workload"] != workload or kernel not in m["kib_per_launch"]:
+        return None
+    fetch, write = m["kib_per_launch"][kernel]
+    return 1024.0 * (fetch * m["fetch_scale"] + write * m["write_scale"])
+
+
 DESCR = {
     0: "config 0: one conditional pair, 28x28x1, batch 64, fp32",
     1: "config 1: 10 label models, 28x28x1, batch 128 per label",
@@ -57,6 +89,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not time individual kernels (no roofline object)")
     ap.add_argument("--detail", action="store_true", help="time every layer shape separately (analysis runs)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="before the timed region, run one elementwise kernel over 1 GiB (reads 1 GiB, writes 1 GiB: known traffic for scaling "
+                         "hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the label models shard with no per-step traffic; "
@@ -87,6 +122,12 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)      # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_profile:
         gan.profile_enable(True, detail=args.detail)
     torch.cuda.synchronize()
@@ -123,7 +164,10 @@ def main():
         dom = max(gemm, key=lambda k: kern[k]["ms_per_step"])
         peak = PEAK["mfma_bf16"] if prec_name == "bf16" else PEAK["mfma_fp32"]
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": kern[dom]["tflops"], "peak": peak,
-                           "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / peak, "traffic": None,
+                           "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / peak,
+                           "traffic": measured_traffic(dom, "config %d %s" % (args.config, prec_name)),
+                           "traffic_unit": "HBM bytes per launch (counters)",
+                           "algorithmic_bytes": prof[dom]["bytes"] / max(prof[dom]["launches"], 1),
                            "avg_launch_ms": kern[dom]["avg_launch_ms"]}
         gemm_ms = sum(kern[k]["ms_per_step"] for k in gemm)
         gemm_fl = sum(prof[k]["flops"] for k in gemm) / args.steps
