@@ -13,10 +13,13 @@
 //
 // Both stage 128-byte K-rows in LDS (two buffers) and feed v_mfma_f32_32x32x16_bf16 (bf16 storage) or
 // v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
-// Forward-type kernel: the next K-chunk travels global -> LDS directly (buffer_load_dwordx4 ... lds, no registers in
-// between) while the MFMAs of the current one run; rows are 128 bytes apart and the 16-byte chunk c of row R sits
-// at position c ^ ((R / 2) % 8), which keeps both the 1 KiB-per-wave writes and the MFMA operand reads off each
-// other's banks.  Weight-gradient kernel: global -> registers (8 x 8 transposes) -> LDS, row stride 144 bytes.
+// Forward-type kernel: K-chunks of KB bytes per row travel global -> LDS directly (buffer_load_dwordx4 ... lds, no
+// registers in between) into a ring of NST buffers while the MFMAs of the current chunk run.  The 256 x 256 tile uses
+// KB = 128 with two buffers (one block per CU); the narrower tiles use KB = 64 with three, which leaves room for two
+// blocks per CU so that one block's epilogue and barriers hide behind the other's MFMAs.  The 16-byte chunk c of row
+// R sits at position c ^ ((R / (256/KB)) % (KB/16)), which keeps both the 1 KiB-per-wave copies and the MFMA operand
+// reads conflict-free.  Weight-gradient kernels: bf16 copies tiles in memory layout and transposes while reading LDS;
+// fp32 goes global -> registers (transposes) -> LDS, row stride 144 bytes.
 // One barrier per chunk in both.
 #include <stdio.h>
 #include <stdlib.h>
@@ -31,18 +34,20 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKB = 128;         // bytes of K per LDS row
 constexpr int LDS_STRIDE = BKB + 16;
 
-// Block tile BM x BN computed by WM x WN waves, each (TM*32) x (TN*32).
-template <int BM_, int BN_, int WM_, int WN_>
+// Block tile BM x BN computed by WM x WN waves, each (TM*32) x (TN*32); forward kernel: KB bytes of K per LDS row,
+// NST buffers.
+template <int BM_, int BN_, int WM_, int WN_, int KB_ = 128, int NST_ = 2>
 struct Tile {
-  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, KB = KB_, NST = NST_;
   static constexpr int NT = 64 * WM_ * WN_;
   static constexpr int TM = BM_ / (32 * WM_), TN = BN_ / (32 * WN_);
-  static constexpr int RPP = NT / 8;                 // tile rows filled per pass (8 chunks of 16 bytes per row)
+  static constexpr int CPR = KB_ / 16;               // 16-byte chunks per LDS row
+  static constexpr int RPP = NT / CPR;               // tile rows filled per loader pass
   static constexpr int PA = BM_ / RPP, PB = BN_ / RPP;
 };
-typedef Tile<256, 256, 2, 4> TileBig;     // 512 threads, wave tile 128 x 64
-typedef Tile<256, 128, 4, 2> TileMid;     // 512 threads, wave tile 64 x 64
-typedef Tile<128, 128, 2, 2> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model)
+typedef Tile<256, 256, 2, 4, 128, 2> TileBig;    // 512 threads, wave tile 128 x 64, 128 KiB of LDS
+typedef Tile<256, 128, 4, 2, 64, 3> TileMid;     // 512 threads, wave tile 64 x 64, 72 KiB of LDS
+typedef Tile<128, 128, 2, 2, 64, 3> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model), 48 KiB of LDS
 
 int conv_tile_rows(int n_out, long long rows_per_model_hint) {
   if (rows_per_model_hint > 0 && rows_per_model_hint <= 128) return TileSmall::BM;
@@ -60,31 +65,50 @@ __device__ inline void mma16B(floatx16& acc, const uint4& a, const uint4& b, flo
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 
-// One K-chunk held in LDS: every wave multiplies its (TM*32) x (TN*32) sub-tile.
-// LAYOUT_XOR: rows 128 bytes apart, chunk c of tile row R at position c ^ ((R/2) % 8).
-// LAYOUT_ROT: rows 144 bytes apart, chunk c of tile row R at position (c + R/16) mod 8 (the weight-gradient kernel
-//             writes its tiles transposed, eight rows apart per lane; the rotation spreads those writes over the banks).
-enum { LAYOUT_XOR = 0, LAYOUT_ROT = 1 };
-template <typename T, int TM, int TN, int LAYOUT>
+// One K-chunk of the fp32 weight-gradient kernel held in LDS: every wave multiplies its (TM*32) x (TN*32) sub-tile.
+// Rows 144 bytes apart, chunk c of tile row R at position (c + R/16) mod 8 (that kernel writes its tiles transposed,
+// eight rows apart per lane; the rotation spreads those writes over the banks).
+template <typename T, int TM, int TN>
 __device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
                                 int lane) {
   const int r = lane & 31, h = lane >> 5;
-  constexpr int STRIDE = LAYOUT == LAYOUT_XOR ? BKB : LDS_STRIDE;
   const int rot = r >> 4;        // tile rows start at multiples of 32, so R/16 = const + r/16
-  const int sw = (r >> 1) & 7;   // and (R/2) % 8 = (r/2) % 8
 #pragma unroll
   for (int vs = 0; vs < BKB / 32; ++vs) {
     uint4 a[TM], b[TN];
 #pragma unroll
-    for (int t = 0; t < TM; ++t) {
-      const int pos = LAYOUT == LAYOUT_XOR ? ((vs * 2 + h) ^ sw) : ((vs * 2 + h + 2 * (wm * TM + t) + rot) & 7);
-      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * STRIDE + pos * 16);
-    }
+    for (int t = 0; t < TM; ++t)
+      a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * LDS_STRIDE +
+                                             ((vs * 2 + h + 2 * (wm * TM + t) + rot) & 7) * 16);
 #pragma unroll
-    for (int t = 0; t < TN; ++t) {
-      const int pos = LAYOUT == LAYOUT_XOR ? ((vs * 2 + h) ^ sw) : ((vs * 2 + h + 2 * (wn * TN + t) + rot) & 7);
-      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * STRIDE + pos * 16);
-    }
+    for (int t = 0; t < TN; ++t)
+      b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * LDS_STRIDE +
+                                             ((vs * 2 + h + 2 * (wn * TN + t) + rot) & 7) * 16);
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) mma16B(acc[tm][tn], a[tm], b[tn], T());
+  }
+}
+
+// One K-chunk of the forward-type kernel: rows KB bytes apart, the 16-byte chunk c of tile row R at position
+// c ^ ((R / (256/KB)) % (KB/16)).  Sixteen lanes reading one chunk index of sixteen consecutive rows then touch
+// sixteen different 16-byte slots of the 256-byte bank period, and so do the rows one wave-wide copy fills.
+template <int KB>
+__device__ inline int fwd_swz(int row) { return (row / (256 / KB)) % (KB / 16); }
+template <typename T, int TM, int TN, int KB>
+__device__ inline void tile_mma_fwd(floatx16 (&acc)[TM][TN], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
+                                    int lane) {
+  const int r = lane & 31, h = lane >> 5;
+  const int sw = fwd_swz<KB>(r);   // tile rows start at multiples of 32, a multiple of the swizzle period
+#pragma unroll
+  for (int vs = 0; vs < KB / 32; ++vs) {
+    uint4 a[TM], b[TN];
+    const int pos = ((vs * 2 + h) ^ sw) * 16;
+#pragma unroll
+    for (int t = 0; t < TM; ++t) a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * KB + pos);
+#pragma unroll
+    for (int t = 0; t < TN; ++t) b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * KB + pos);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -112,6 +136,14 @@ __device__ inline void load16_to_lds(const int4v& rsrc, unsigned byte_off, unsig
                : : "v"(byte_off), "s"(rsrc), "s"(lds_base) : "memory", "m0");
 }
 __device__ inline void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+// wait until at most `chunks` (wave-uniform; 2 or more counts as 2) groups of LPT loads are still in flight
+template <int LPT>
+__device__ inline void wait_vm_chunks(int chunks) {
+  static_assert(2 * LPT <= 63, "vmcnt range");
+  if (chunks >= 2) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 * LPT) : "memory");
+  else if (chunks == 1) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LPT) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+}
 
 __device__ inline void store_out(float* p, float v) { *p = v; }
 __device__ inline void store_out(bf16_t* p, float v) { *p = from_float<bf16_t>(v); }
@@ -139,12 +171,17 @@ static int log2_or_neg(int v) {
 template <typename T, int MODE, int EPI, typename TL>
 __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, PA = TL::PA, PB = TL::PB, RPP = TL::RPP;
-  constexpr int SMEM = 2 * (BM + BN) * BKB;
+  constexpr int KB = TL::KB, NST = TL::NST;
+  constexpr int SMEM_RING = NST * (BM + BN) * KB;
+  constexpr int SMEM_EPI = BM * 8 + (TL::NT / 64) * 32 * (TN * 32 * (int)sizeof(T) + 16) + TL::WM * BN * 8;   // see the epilogue
+  constexpr int SMEM = SMEM_RING > SMEM_EPI ? SMEM_RING : SMEM_EPI;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
-  unsigned char* const As = smem;                    // stage s at As + s * BM * BKB
-  unsigned char* const Bs = smem + 2 * BM * BKB;     // stage s at Bs + s * BN * BKB
-  constexpr int BK = BKB / (int)sizeof(T);
+  unsigned char* const As = smem;                      // buffer s at As + s * BM * KB
+  unsigned char* const Bs = smem + NST * BM * KB;      // buffer s at Bs + s * BN * KB
+  constexpr int BK = KB / (int)sizeof(T);              // elements of K per chunk
+  constexpr int LINES = 128 / KB;                      // chunks per 128-byte line
   constexpr int EPV = 16 / (int)sizeof(T);
+  constexpr int LPT = PA + PB;                         // loads per thread per chunk
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / TL::WN, wn = wave % TL::WN;
 
@@ -185,7 +222,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   constexpr int SZ = (int)sizeof(T);
   const int ntaps = (MODE == MODE_DOWN) ? 16 : (MODE == MODE_UP ? 4 : 1);
   const int nk = ntaps * C / BK;
-  const int cpt = C / BK;        // channel chunks per tap
+  const int cpl = C * SZ / 128;   // 128-byte channel lines per tap
   const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
   // this model's slice of the gathered tensor (one segment) and its weight block, as bounds-checked buffers
   const int nsamp = s1 - s0;
@@ -195,11 +232,12 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const int4v w_rsrc = make_rsrc(static_cast<const T*>(p.W) + (long long)l * p.w_stride,
                                  (unsigned long long)(MODE == MODE_DENSE ? 1 : 16) * wns * C * SZ);
 
-  // ---- per-thread load assignment: rows tid/8 + RPP i, LDS position tid % 8 of the row, which holds the row's
-  // 16-byte chunk (tid % 8) ^ ((row / 2) % 8) (RPP is a multiple of 16, so the same chunk in every pass).
-  // Per row: byte offset of its pixel at tap offset (0, 0) and the set of taps that stay inside the map.
-  const int row0 = tid >> 3;
-  const int chunk = (tid & 7) ^ ((row0 >> 1) & 7);
+  // ---- per-thread load assignment: rows tid/CPR + RPP i, LDS position tid % CPR of the row, which holds the row's
+  // 16-byte chunk (tid % CPR) ^ swizzle(row) (RPP is a multiple of the swizzle period, so the same chunk in every
+  // pass).  Per row: byte offset of its pixel at tap offset (0, 0) and the set of taps that stay inside the map.
+  constexpr int CPR = TL::CPR;
+  const int row0 = tid / CPR;
+  const int chunk = (tid % CPR) ^ fwd_swz<KB>(row0);
   unsigned apix[PA], amask[PA], bcol[PB];
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
@@ -233,19 +271,18 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
 
   const unsigned lds0 = (unsigned)(uintptr_t)smem;     // LDS byte address of the buffers
   auto load_chunk = [&](int kc, int stage) {
-    // K order: taps whose gathers land on the same input pixels (shifted by one) run back to back on one channel
-    // chunk, so that all but the first find their rows in L2: down - the 4 taps of a (ky%2, kx%2) class; up - the
-    // phase's 4 taps.
-    const int j4 = kc & 3;
-    const int rest = kc >> 2;
+    // K order, fastest first: the chunks of one 128-byte line; the taps whose gathers land on the same input pixels
+    // shifted by one (down: the 4 taps of a (ky%2, kx%2) class, up: the phase's 4 taps), which find their rows in
+    // L2; the channel line; (down) the class.
     int tap, cc;
     if (MODE == MODE_DOWN) {
-      const int cls = rest / cpt;
-      cc = rest - cls * cpt;
+      const int part = kc % LINES, j4 = (kc / LINES) & 3, rest = kc / (4 * LINES);
+      const int cls = rest / cpl;
+      cc = (rest - cls * cpl) * LINES + part;
       tap = (((cls >> 1) + 2 * (j4 >> 1)) << 2) + (cls & 1) + 2 * (j4 & 1);
     } else if (MODE == MODE_UP) {
-      cc = rest;
-      tap = j4;
+      cc = (kc / (4 * LINES)) * LINES + kc % LINES;
+      tap = (kc / LINES) & 3;
     } else {
       cc = kc;
       tap = 0;
@@ -265,14 +302,14 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     }
     const unsigned a_delta = (unsigned)(((dy * Hin + dx) * C + cc * BK) * SZ);    // wave-uniform
     const unsigned w_delta = (unsigned)((wtap * wns * C + cc * BK) * SZ);
-    const unsigned a_dst = lds0 + (stage * BM + wave * 8) * BKB;                 // + pass * RPP rows
-    const unsigned b_dst = lds0 + (2 * BM + stage * BN + wave * 8) * BKB;
+    const unsigned a_dst = lds0 + (stage * BM + wave * (1024 / KB)) * KB;        // + pass * RPP rows
+    const unsigned b_dst = lds0 + (NST * BM + stage * BN + wave * (1024 / KB)) * KB;
 #pragma unroll
     for (int i = 0; i < PA; ++i)
-      load16_to_lds(a_rsrc, ((amask[i] >> tap) & 1u) ? apix[i] + a_delta : NO_ROW, a_dst + i * RPP * BKB);
+      load16_to_lds(a_rsrc, ((amask[i] >> tap) & 1u) ? apix[i] + a_delta : NO_ROW, a_dst + i * RPP * KB);
 #pragma unroll
     for (int i = 0; i < PB; ++i)
-      load16_to_lds(w_rsrc, bcol[i] != NO_ROW ? bcol[i] + w_delta : NO_ROW, b_dst + i * RPP * BKB);
+      load16_to_lds(w_rsrc, bcol[i] != NO_ROW ? bcol[i] + w_delta : NO_ROW, b_dst + i * RPP * KB);
   };
 
   floatx16 acc[TM][TN];
@@ -283,14 +320,16 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  load_chunk(0, 0);
-  wait_vm0();
+  // Ring of NST buffers: chunk c lives in buffer c % NST.  While chunk c is multiplied, chunks c+1 .. c+NST-1 are on
+  // their way; the barrier that ends iteration c tells every wave that chunk c+1 has landed everywhere and that
+  // buffer c % NST may be refilled (with chunk c+NST, by the next iteration).
+  for (int c = 0; c < NST - 1 && c < nk; ++c) load_chunk(c, c);
+  wait_vm_chunks<LPT>(min(nk, NST - 1) - 1);
   __syncthreads();
   for (int kc = 0; kc < nk; ++kc) {
-    // the other buffer was last read before the previous barrier: its refill runs under this chunk's MFMAs
-    if (kc + 1 < nk) load_chunk(kc + 1, (kc + 1) & 1);
-    tile_mma<T, TM, TN, LAYOUT_XOR>(acc, As + (kc & 1) * BM * BKB, Bs + (kc & 1) * BN * BKB, wm, wn, lane);
-    wait_vm0();
+    if (kc + NST - 1 < nk) load_chunk(kc + NST - 1, (kc + NST - 1) % NST);
+    tile_mma_fwd<T, TM, TN, KB>(acc, As + (kc % NST) * BM * KB, Bs + (kc % NST) * BN * KB, wm, wn, lane);
+    wait_vm_chunks<LPT>(min(nk - 1, kc + NST - 1) - (kc + 1));     // chunks after kc+1 may stay in flight
     __syncthreads();
   }
 
@@ -370,7 +409,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     constexpr int PSTRIDE = WCOLS * (int)sizeof(T) + 16;               // bytes per patch row
     constexpr int CPR = WCOLS * (int)sizeof(T) / 16;                   // 16-byte chunks per patch row
     unsigned char* patch = smem + BM * 8 + wave * (32 * PSTRIDE);       // after the row table
-    static_assert(SMEM >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8, "patch area");
+    static_assert(SMEM >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8 && SMEM_EPI == BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8, "patch area");
     const int colw = nt * BN + wn * WCOLS;                              // first column of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -430,7 +469,7 @@ static void launch_wide(const ConvArgs& a, hipStream_t st) {
 template <typename T>
 void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
   // the kernel's assumptions, checked before anything is launched
-  if (!a.A || !a.W || !a.Out || !a.offs || !a.tpre || a.N < 1 || a.w_nstride < a.N || a.C % (BKB / (int)sizeof(T)) != 0 ||
+  if (!a.A || !a.W || !a.Out || !a.offs || !a.tpre || a.N < 1 || a.w_nstride < a.N || a.C % (128 / (int)sizeof(T)) != 0 ||
       (epi == EPI_ACT_BWD && !a.Aux))
     abort();
   if (a.N < 64) abort();                        // image-side outputs have their own kernel
@@ -621,7 +660,7 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
     for (int c = 0; c < nchunks; ++c) {
       const bool more = c + 1 < nchunks;
       if (more) { chunk_pos(c + 1, sb, k0); load_chunk(sb, k0); }
-      tile_mma<T, TM, TN, LAYOUT_ROT>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
+      tile_mma<T, TM, TN>(acc, As[c & 1], Bs[c & 1], wm, wn, lane);
       if (more) store_chunk((c + 1) & 1);
       __syncthreads();
     }
