@@ -196,7 +196,8 @@ __device__ inline void store4(bf16_t* p, const float (&v)[4]) {
 template <typename T> struct Vec16 { static constexpr int N = 16 / (int)sizeof(T); };
 __device__ inline void loadv(const float* p, float (&v)[4]) { load4(p, v); }
 __device__ inline void loadv(const bf16_t* p, float (&v)[8]) {
-  const uint4 t = *reinterpret_cast<const uint4*>(p);
+  typedef unsigned u4 __attribute__((ext_vector_type(4)));
+  const u4 t = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
   v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
   v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
   v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u);
@@ -209,7 +210,9 @@ __device__ inline void storev(bf16_t* p, const float (&v)[8]) {
   t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
   t.z = (unsigned)f32_to_bf16_bits(v[4]) | ((unsigned)f32_to_bf16_bits(v[5]) << 16);
   t.w = (unsigned)f32_to_bf16_bits(v[6]) | ((unsigned)f32_to_bf16_bits(v[7]) << 16);
-  *reinterpret_cast<uint4*>(p) = t;
+  typedef unsigned u4 __attribute__((ext_vector_type(4)));
+  u4 q; q.x = t.x; q.y = t.y; q.z = t.z; q.w = t.w;
+  __builtin_nontemporal_store(q, reinterpret_cast<u4*>(p));
 }
 
 // mean / var / rstd from what the producing GEMM left per tile and column: (sum, sum of squared deviations from the
@@ -655,6 +658,17 @@ __global__ void adam_prepare_kernel(AdamArgs a) {
   a.bc[2 * l + 1] = (float)(1.0 - pow((double)a.beta2, (double)t));
 }
 
+// streaming accesses of the optimiser state: every element is touched once per step
+__device__ inline float4 ld_stream(const float* p) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ inline void st_stream(float* p, const float4& v) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  f4 t; t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
+}
 __device__ inline void adam_update4(const AdamArgs& a, float bc1, float bc2, const float4& g, float4& th, float4& m, float4& v,
                                     float (&tt)[4]) {
   const float gg[4] = {g.x, g.y, g.z, g.w};
@@ -681,15 +695,15 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamArgs a) {
   const long long i = a.gap_lo[r] + ((long long)(blockIdx.x - a.gap_blk0[r]) * 256 + threadIdx.x) * 4;
   if (i >= a.gap_hi[r]) return;
   const long long o = (long long)l * a.P + i;
-  const float4 g = *reinterpret_cast<const float4*>(a.g + o);
-  float4 th = *reinterpret_cast<const float4*>(a.theta + o);
-  float4 m = *reinterpret_cast<const float4*>(a.m + o);
-  float4 v = *reinterpret_cast<const float4*>(a.v + o);
+  const float4 g = ld_stream(a.g + o);
+  float4 th = ld_stream(a.theta + o);
+  float4 m = ld_stream(a.m + o);
+  float4 v = ld_stream(a.v + o);
   float tt[4];
   adam_update4(a, a.bc[2 * l], a.bc[2 * l + 1], g, th, m, v, tt);
-  *reinterpret_cast<float4*>(a.theta + o) = th;
-  *reinterpret_cast<float4*>(a.m + o) = m;
-  *reinterpret_cast<float4*>(a.v + o) = v;
+  st_stream(a.theta + o, th);
+  st_stream(a.m + o, m);
+  st_stream(a.v + o, v);
   if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
 }
 
@@ -717,15 +731,15 @@ __global__ __launch_bounds__(256) void adam_tile_kernel(AdamArgs a) {
   for (int i = 0; i < 4; ++i) {
     const int row = r0 + 16 * i;                                // cb inside the tile
     const long long o = base + ((long long)tap * Cb + tcb * 64 + row) * Cs + tcs * 64 + c4;
-    const float4 g = *reinterpret_cast<const float4*>(a.g + o);
-    float4 th = *reinterpret_cast<const float4*>(a.theta + o);
-    float4 m = *reinterpret_cast<const float4*>(a.m + o);
-    float4 v = *reinterpret_cast<const float4*>(a.v + o);
+    const float4 g = ld_stream(a.g + o);
+    float4 th = ld_stream(a.theta + o);
+    float4 m = ld_stream(a.m + o);
+    float4 v = ld_stream(a.v + o);
     float tt[4];
     adam_update4(a, bc1, bc2, g, th, m, v, tt);
-    *reinterpret_cast<float4*>(a.theta + o) = th;
-    *reinterpret_cast<float4*>(a.m + o) = m;
-    *reinterpret_cast<float4*>(a.v + o) = v;
+    st_stream(a.theta + o, th);
+    st_stream(a.m + o, m);
+    st_stream(a.v + o, v);
     if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
 #pragma unroll
     for (int e = 0; e < 4; ++e) *reinterpret_cast<T*>(tile + (c4 + e) * TSTRIDE + row * (int)sizeof(T)) = from_float<T>(tt[e]);
