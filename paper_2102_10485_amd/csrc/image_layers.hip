@@ -78,9 +78,76 @@ __global__ __launch_bounds__(256) void im2col_kernel(Im2colArgs a) {
   }
   store8(static_cast<T*>(a.out) + (((long long)a.seg * a.seg_samples + j) * rps + pix) * a.Kc + m0, v);
 }
+// Same result, one block per sample: the sample's image goes through LDS once (NHWC, storage type), and every thread
+// keeps the (tap, channel) decoding of its 8 columns while it walks down the sample's patch rows.
+template <typename T>
+__global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  T* tile = reinterpret_cast<T*>(lds_raw);                       // [Hb][Hb][CB]
+  const int j = blockIdx.x;
+  if (j >= a.offs[a.L]) return;
+  const int g8 = a.Kc >> 3;
+  const int rps = a.Hs * a.Hs, Hb = 2 * a.Hs, CB = a.CB;
+  const int npix = Hb * Hb;
+  if (a.img) {
+    const T* img = static_cast<const T*>(a.img) + ((long long)a.seg * a.seg_samples + j) * npix * CB;
+    for (int t = threadIdx.x; t < npix * CB; t += 256) tile[t] = img[t];
+  } else {
+    const float* real = a.real + (long long)a.perm[j] * CB * npix;     // NCHW fp32
+    for (int t = threadIdx.x; t < npix * CB; t += 256) {
+      const int cb = t / npix, p = t - cb * npix;
+      tile[p * CB + cb] = from_float<T>(real[t]);
+    }
+  }
+  __syncthreads();
+  const int ntap = 16 * CB;
+  const int slot = a.nslot > 0 ? a.sample_slot[j] : 0;
+  T* out = static_cast<T*>(a.out) + ((long long)a.seg * a.seg_samples + j) * rps * a.Kc;
+  int cur = -1;
+  int dyv[8], dxv[8], cbv[8], kind[8];            // kind: 0 tap, 1 zero, 2 one, 3 + class: label-map indicator of this class
+  for (int t = threadIdx.x; t < rps * g8; t += 256) {
+    const int pix = t / g8, g = t - pix * g8;
+    if (g != cur) {                                // fixed per thread whenever 256 is a multiple of g8
+      cur = g;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int m = g * 8 + e;
+        dyv[e] = 0; dxv[e] = 0; cbv[e] = 0; kind[e] = 1;
+        if (m < ntap) {
+          const int tap = m / CB;
+          cbv[e] = m - tap * CB; dyv[e] = (tap >> 2) - 1; dxv[e] = (tap & 3) - 1; kind[e] = 0;
+        } else if (a.nslot > 0) {
+          const int q = m - ntap;
+          if (q < 9 * a.nslot) { if (q / 9 == slot) kind[e] = 3 + q % 9; }
+          else if (q == 9 * a.nslot) kind[e] = 2;
+        }
+      }
+    }
+    const int y = pix / a.Hs, x = pix - y * a.Hs;
+    const int cls = pos_class(y, x, a.Hs);
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float val = 0.f;
+      if (kind[e] == 0) {
+        const int iy = 2 * y + dyv[e], ix = 2 * x + dxv[e];
+        if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb) val = to_float(tile[(iy * Hb + ix) * CB + cbv[e]]);
+      } else if (kind[e] == 2 || kind[e] == 3 + cls) {
+        val = 1.f;
+      }
+      v[e] = val;
+    }
+    store8(out + (long long)pix * a.Kc + g * 8, v);
+  }
+}
 template <typename T> void launch_im2col(const Im2colArgs& a, hipStream_t st) {
   const long long tot = (long long)a.n * a.Hs * a.Hs * (a.Kc / 8);
   if (tot == 0) return;
+  const size_t lds = (size_t)4 * a.Hs * a.Hs * a.CB * sizeof(T);
+  if (lds <= 64 * 1024) {
+    hipLaunchKernelGGL((im2col_sample_kernel<T>), dim3((unsigned)a.n), dim3(256), lds, st, a);
+    return;
+  }
   hipLaunchKernelGGL((im2col_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
 }
 template void launch_im2col<float>(const Im2colArgs&, hipStream_t);
