@@ -173,7 +173,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, PA = TL::PA, PB = TL::PB, RPP = TL::RPP;
   constexpr int KB = TL::KB, NST = TL::NST;
   constexpr int SMEM_RING = NST * (BM + BN) * KB;
-  constexpr int SMEM_EPI = BM * 8 + (TL::NT / 64) * 32 * (TN * 32 * (int)sizeof(T) + 16) + TL::WM * BN * 8;   // see the epilogue
+  constexpr int SMEM_EPI = BM * 8 + (TL::NT / 64) * 32 * (TN * 32 * 4 + 16) + TL::WM * BN * 8;   // see the epilogue
   constexpr int SMEM = SMEM_RING > SMEM_EPI ? SMEM_RING : SMEM_EPI;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
   unsigned char* const As = smem;                      // buffer s at As + s * BM * KB
@@ -403,11 +403,12 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     // (the patches below sit after the row table, the sums at the end of the buffers: no barrier needed between them)
   }
   {
-    // Each wave passes its 32 x (TN*32) blocks through a private LDS patch so that every lane stores
-    // 16 contiguous bytes of an output row (full N is a multiple of 64 for these tiles).
+    // Each wave passes its 32 x (TN*32) blocks (fp32) through a private LDS patch so that every lane stores 16
+    // contiguous bytes of an output row (full N is a multiple of 64 for these tiles).  The patch belongs to one
+    // wave, whose LDS operations execute in order: no block-wide barrier is needed around it.
     constexpr int WCOLS = TN * 32;
-    constexpr int PSTRIDE = WCOLS * (int)sizeof(T) + 16;               // bytes per patch row
-    constexpr int CPR = WCOLS * (int)sizeof(T) / 16;                   // 16-byte chunks per patch row
+    constexpr int PSTRIDE = WCOLS * 4 + 16;                             // bytes per patch row
+    constexpr int CPR = WCOLS / EPV;                                    // 16-byte output chunks per patch row
     unsigned char* patch = smem + BM * 8 + wave * (32 * PSTRIDE);       // after the row table
     static_assert(SMEM >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8 && SMEM_EPI == BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8, "patch area");
     const int colw = nt * BN + wn * WCOLS;                              // first column of this wave
@@ -420,9 +421,10 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
           const int pr = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
           float val = acc[tm][tn][e];
           if (EPI == EPI_LRELU) val = val > 0.f ? val : val * p.slope;
-          *reinterpret_cast<T*>(patch + pr * PSTRIDE + (tn * 32 + (lane & 31)) * (int)sizeof(T)) = from_float<T>(val);
+          *reinterpret_cast<float*>(patch + pr * PSTRIDE + (tn * 32 + (lane & 31)) * 4) = val;
         }
-      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i = 0; i < 32 * CPR / 64; ++i) {
         const int cid = lane + 64 * i;
@@ -430,19 +432,28 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
         const long long o = orow[wm * TM * 32 + tm * 32 + pr];
         const int col = colw + pc * EPV;
         if (o >= 0 && col < N) {
-          uint4 vraw = *reinterpret_cast<const uint4*>(patch + pr * PSTRIDE + pc * 16);
+          float vf[EPV];
+#pragma unroll
+          for (int k = 0; k < EPV; k += 4) {
+            const float4 t4 = *reinterpret_cast<const float4*>(patch + pr * PSTRIDE + (pc * EPV + k) * 4);
+            vf[k] = t4.x; vf[k + 1] = t4.y; vf[k + 2] = t4.z; vf[k + 3] = t4.w;
+          }
           if (EPI == EPI_ACT_BWD) {               // times the activation's derivative, from the saved output
             const uint4 araw = *reinterpret_cast<const uint4*>(Aux + o * N + col);
-            T* vv = reinterpret_cast<T*>(&vraw);
             const T* aa = reinterpret_cast<const T*>(&araw);
 #pragma unroll
             for (int k = 0; k < EPV; ++k)
-              if (!(to_float(aa[k]) > 0.f)) vv[k] = from_float<T>(to_float(vv[k]) * p.slope);
+              if (!(to_float(aa[k]) > 0.f)) vf[k] *= p.slope;
           }
+          uint4 vraw;
+          T* vv = reinterpret_cast<T*>(&vraw);
+#pragma unroll
+          for (int k = 0; k < EPV; ++k) vv[k] = from_float<T>(vf[k]);
           *reinterpret_cast<uint4*>(Out + o * N + col) = vraw;
         }
       }
-      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
