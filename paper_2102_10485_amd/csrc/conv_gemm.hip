@@ -847,19 +847,38 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
     }
   }
 
+  // Epilogue: each wave passes its 32 x (TN*32) blocks through a private LDS patch (the K buffers are free after the
+  // loop's last barrier) so that every lane stores 16 contiguous bytes of a row of dW.
   float* __restrict__ dW = p.dW + (long long)split * p.split_stride + (long long)l * p.dw_stride;
+  constexpr int WCOLS = TN * 32;
+  constexpr int PSTRIDE = WCOLS * 4 + 16;
+  constexpr int CPRW = WCOLS / 4;                                       // 16-byte chunks per patch row
+  static_assert((TL::NT / 64) * 32 * PSTRIDE <= 2 * (STAGE_A + STAGE_B), "patch area");
+  unsigned char* patch = smem + wave * (32 * PSTRIDE);
+  const int colw = nt * BN + wn * WCOLS;
 #pragma unroll
-  for (int tm = 0; tm < TM; ++tm)
+  for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      const int col = nt * BN + wn * TN * 32 + tn * 32 + (lane & 31);
-      if (col >= Cs) continue;
+    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int m = mt * BM + wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        if (m < Mtot) dW[(long long)m * Cs + col] = acc[tm][tn][e];
+        const int pr = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        *reinterpret_cast<float*>(patch + pr * PSTRIDE + (tn * 32 + (lane & 31)) * 4) = acc[tm][tn][e];
       }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 32 * CPRW / 64; ++i) {
+      const int cid = lane + 64 * i;
+      const int pr = cid / CPRW, pc = cid - pr * CPRW;
+      const int m = mt * BM + wm * TM * 32 + tm * 32 + pr;
+      const int col = colw + pc * 4;
+      if (m < Mtot && col < Cs)         // Cs is a multiple of 8: a 16-byte chunk is inside or outside
+        *reinterpret_cast<float4*>(dW + (long long)m * Cs + col) = *reinterpret_cast<const float4*>(patch + pr * PSTRIDE + pc * 16);
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 typedef Tile<64, 128, 1, 4> TileWgImg;    // patch-matrix layers: 64 packed columns x 128 feature channels
