@@ -88,7 +88,9 @@ def main():
     ap.add_argument("--precision", choices=["fp32", "bf16"], default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not time individual kernels (no roofline object)")
-    ap.add_argument("--detail", action="store_true", help="time every layer shape separately (analysis runs)")
+    ap.add_argument("--detail", action="store_true", help="time every kernel, one line per layer shape (analysis runs)")
+    ap.add_argument("--all-kernels", action="store_true",
+                    help="time every kernel, not only the MFMA ones (two stream-draining events per launch: slower steps)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="before the timed region, run one elementwise kernel over 1 GiB (reads 1 GiB, writes 1 GiB: known traffic for scaling "
                          "hardware byte counters)")
@@ -129,7 +131,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_profile:
-        gan.profile_enable(True, detail=args.detail)
+        gan.profile_enable(True, detail=args.detail, gemm_only=not (args.detail or args.all_kernels))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):

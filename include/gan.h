@@ -132,9 +132,10 @@ gan_status gan_get_routing(gan_ctx* ctx, int32_t* perm, int32_t* offs);
 const char* gan_last_error(const gan_ctx* ctx);
 
 /* ---- profiling ------------------------------------------------------------------------------------ */
-/* Time every kernel launch of the next steps with HIP events on the context's stream (enable = 1; 2 = one
-   family per layer shape), or stop
-   (enable = 0).  Costs two events per launch; off by default. */
+/* Time kernel launches of the next steps with HIP events on the context's stream: enable = 1 every launch, one
+   family per kernel instantiation; 2 every launch, one family per layer shape; 3 only the MFMA kernels (GEMM and
+   weight-gradient instantiations); 0 stop.  Costs two events per timed launch, each of which drains the stream;
+   off by default. */
 gan_status gan_profile_enable(gan_ctx* ctx, int32_t enable);
 /* Accumulated since enabling: for each of up to `cap` kernel families, its name (pointer to a static string),
    launch count, total milliseconds, and the algorithmic flops and bytes those launches stood for.

@@ -189,8 +189,9 @@ class Gan:
         self._check(self.lib.gan_get_routing(self.h, perm.ctypes.data_as(_IP), offs.ctypes.data_as(_IP)))
         return perm[:n], offs
 
-    def profile_enable(self, on=True, detail=False):
-        self._check(self.lib.gan_profile_enable(self.h, (2 if detail else 1) if on else 0))
+    def profile_enable(self, on=True, detail=False, gemm_only=False):
+        level = 0 if not on else (2 if detail else (3 if gemm_only else 1))
+        self._check(self.lib.gan_profile_enable(self.h, level))
 
     def profile_read(self, cap=64):
         names = (C.c_char_p * cap)()

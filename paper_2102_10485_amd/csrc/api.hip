@@ -76,7 +76,7 @@ struct gan_ctx {
   std::string err;
   std::vector<void*> allocs;
   // profiling
-  bool prof = false, prof_detail = false;
+  bool prof = false, prof_detail = false, prof_gemm_only = false;
   std::set<std::string> prof_names;
   std::vector<ProfEntry> prof_entries;
   std::vector<hipEvent_t> event_pool;
@@ -130,9 +130,13 @@ struct Scope {
   gan_ctx* c; int idx = -1;
   Scope(gan_ctx* c_, const char* name, double flops, double bytes, const char* detail = nullptr) : c(c_) {
     if (!c->prof) return;
+    if (c->prof_gemm_only && strncmp(name, "gemm_", 5) != 0 && strncmp(name, "wgrad", 5) != 0) return;
     if (c->prof_detail && detail) name = c->prof_names.insert(std::string(name) + detail).first->c_str();
     ProfEntry e; e.name = name; e.flops = flops; e.bytes = bytes;
-    hipEventCreate(&e.e0); hipEventCreate(&e.e1);
+    for (hipEvent_t* ev : {&e.e0, &e.e1}) {          // events are reused across profiling sessions
+      if (c->event_pool.empty()) hipEventCreate(ev);
+      else { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
+    }
     hipEventRecord(e.e0, c->st);
     c->prof_entries.push_back(e);
     idx = (int)c->prof_entries.size() - 1;
@@ -811,6 +815,7 @@ gan_status gan_destroy(gan_ctx* c) {
   if (!c) return GAN_E_ARG;
   (void)hipStreamSynchronize(c->st);
   for (auto& e : c->prof_entries) { hipEventDestroy(e.e0); hipEventDestroy(e.e1); }
+  for (auto& e : c->event_pool) hipEventDestroy(e);
   for (void* p : c->allocs) (void)hipFree(p);
   delete c;
   return GAN_OK;
@@ -975,10 +980,11 @@ gan_status gan_profile_enable(gan_ctx* c, int32_t enable) {
   if (!c) return GAN_E_ARG;
   gan_status s = sync(c);
   if (s != GAN_OK) return s;
-  for (auto& e : c->prof_entries) { hipEventDestroy(e.e0); hipEventDestroy(e.e1); }
+  for (auto& e : c->prof_entries) { c->event_pool.push_back(e.e0); c->event_pool.push_back(e.e1); }
   c->prof_entries.clear();
   c->prof = enable != 0;
-  c->prof_detail = enable > 1;      // 2: one family per layer shape
+  c->prof_detail = enable == 2;     // 2: one family per layer shape
+  c->prof_gemm_only = enable == 3;  // 3: only the MFMA kernels (fewest events in the stream)
   return GAN_OK;
 }
 
