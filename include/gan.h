@@ -91,7 +91,9 @@ typedef struct {
 
 /* Allocate a context on the current device.  hip_stream is a hipStream_t (0 = the null stream).
    Fails with GAN_E_SHAPE when a channel count is not a multiple of 64, img_c > 4, the sides do not
-   match (img_hw = g_h0 * 2^n_g, img_hw divisible by 2^n_d), or n_models is neither 1 nor n_labels. */
+   match (img_hw = g_h0 * 2^n_g, img_hw divisible by 2^n_d), n_models is neither 1 nor n_labels, a layer has more
+   than 1024 channels, or max_total_batch makes one segment of an activation tensor 2 GiB or larger (the
+   kernels address a segment with 32-bit byte offsets). */
 gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out);
 gan_status gan_destroy(gan_ctx* ctx);
 

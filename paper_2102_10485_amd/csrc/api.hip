@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
+#include <algorithm>
 
 #include <set>
 #include <string>
@@ -789,6 +790,19 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
          dev_alloc(c, &c->colG, (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
          dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)IMG_KSPLIT * L * (d1 > g1 ? d1 : g1) * 4) &&
          dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
+  }
+  {
+    // the GEMM loaders address one segment of any activation tensor or patch matrix with 32-bit byte offsets
+    const ConvLayer& c1 = c->D.conv[0];
+    const ConvLayer& gl = c->G.conv.back();
+    const long long lim = 1LL << 31;
+    const long long big = std::max({(long long)NB * max_act * (long long)es, (long long)NB * c1.Hs * c1.Hs * c->KcD * (long long)es,
+                                    (long long)NB * gl.Hs * gl.Hs * c->KcG * (long long)es});
+    if (big >= lim) {
+      for (void* p : c->allocs) (void)hipFree(p);
+      delete c;
+      return GAN_E_SHAPE;
+    }
   }
   if (!ok) {
     for (void* p : c->allocs) (void)hipFree(p);
