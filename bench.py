@@ -175,6 +175,12 @@ def main():
         gemm_fl = sum(prof[k]["flops"] for k in gemm) / args.steps
         out["conv_mfma"] = {"tflops": gemm_fl / (gemm_ms * 1e9), "frac_of_peak": gemm_fl / (gemm_ms * 1e9) / peak,
                             "ms_per_step": gemm_ms}
+        # the same figures against what the simplest kernels reach on this chip (register-only MFMA loop, plain copy)
+        mfma_meas = binding.probe_mfma(prec, torch.cuda.current_stream().cuda_stream)
+        copy_meas = binding.probe_copy(1 << 30, torch.cuda.current_stream().cuda_stream)
+        out["measured_ceilings"] = {"mfma_loop_tflops": mfma_meas, "device_copy_gbps": copy_meas,
+                                    "roofline_frac_of_mfma_loop": kern[dom]["tflops"] / mfma_meas,
+                                    "conv_mfma_frac_of_mfma_loop": gemm_fl / (gemm_ms * 1e9) / mfma_meas}
         out["kernels"] = {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(kern.items(),
                                                                                         key=lambda kv: -kv[1]["ms_per_step"])}
         out["kernel_ms_sum"] = sum(v["ms_per_step"] for v in kern.values())

@@ -145,6 +145,15 @@ gan_status gan_profile_enable(gan_ctx* ctx, int32_t enable);
 gan_status gan_profile_read(gan_ctx* ctx, int32_t cap, const char** names, int64_t* launches, double* ms,
                             double* flops, double* bytes, int32_t* n_out);
 
+/* ---- what the chip delivers to the simplest kernels (Section 5 of the paper reports GPU usage only; these give the
+   achievable ceilings the step's kernels are reported against, next to the published peaks) -------------- */
+/* TFLOP/s of a register-only MFMA loop in the arithmetic of `precision` (bf16 inputs, or fp32), every CU busy.
+   Allocates and frees a small buffer; synchronises the stream.  *tflops is a HOST double. */
+gan_status gan_probe_mfma(int32_t precision, void* hip_stream, double* tflops);
+/* GB/s (bytes read + bytes written per second) of a plain device-to-device copy of `bytes` (a multiple of 16, at
+   least 1 MiB); allocates and frees two buffers of that size; synchronises the stream.  *gbps is a HOST double. */
+gan_status gan_probe_copy(int64_t bytes, void* hip_stream, double* gbps);
+
 /* ---- single operations, for per-kernel parity tests ---------------------------------------------- */
 /* All pointers DEVICE.  Activations are NHWC in the context's storage type (fp32, or bf16 as uint16),
    rows model-major; offs is DEVICE int32 [n_groups + 1] of sample offsets.  Weights are in the library's

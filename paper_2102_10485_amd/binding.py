@@ -76,8 +76,28 @@ def load_library():
     L.gan_op_conv_down.argtypes = op
     L.gan_op_conv_up.argtypes = op
     L.gan_op_conv_wgrad.argtypes = op
+    L.gan_probe_mfma.argtypes = [C.c_int32, _VP, C.POINTER(C.c_double)]
+    L.gan_probe_copy.argtypes = [C.c_int64, _VP, C.POINTER(C.c_double)]
     _lib = L
     return L
+
+
+def probe_mfma(precision, stream=0):
+    """TFLOP/s of a register-only MFMA loop in this precision's arithmetic."""
+    v = C.c_double()
+    st = load_library().gan_probe_mfma(precision, stream, C.byref(v))
+    if st != GAN_OK:
+        raise GanError(st, "gan_probe_mfma")
+    return v.value
+
+
+def probe_copy(nbytes=1 << 30, stream=0):
+    """GB/s (read + written) of a plain device-to-device copy."""
+    v = C.c_double()
+    st = load_library().gan_probe_copy(nbytes, stream, C.byref(v))
+    if st != GAN_OK:
+        raise GanError(st, "gan_probe_copy")
+    return v.value
 
 
 def make_config(spec, n_models, n_labels, max_total_batch, precision=FP32, hyper=None, seed=1):

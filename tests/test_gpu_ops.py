@@ -86,3 +86,15 @@ def test_conv_down_up_wgrad(ctxs, prec, cb, cs, hs, groups):
         _, dW, _ = O.conv2d_bwd(big[offs[i]:offs[i + 1]], W[i], small[offs[i]:offs[i + 1]], need_dx=False)
         ref = dW.transpose(2, 3, 1, 0)                                   # [cs][cb][ky][kx] -> [ky][kx][cb][cs]
         assert np.max(np.abs(got[i] - ref)) <= 2e-5 * np.max(np.abs(ref)) * (50 if bf else 1), "wgrad group %d" % i
+
+
+@pytest.mark.gpu
+def test_probes_report_plausible_ceilings():
+    """The register-only MFMA loop and the plain copy return rates of the right order for this chip."""
+    U.torch_mod().cuda.set_device(0)
+    bf = binding.probe_mfma(binding.BF16)
+    fp = binding.probe_mfma(binding.FP32)
+    cp = binding.probe_copy(1 << 28)
+    assert 500.0 < bf < 2600.0          # published dense bf16 peak: 2.5 PFLOP/s
+    assert 30.0 < fp < 170.0            # published fp32 matrix peak: 157.3 TFLOP/s
+    assert 1000.0 < cp < 8200.0         # published HBM peak: 8 TB/s
