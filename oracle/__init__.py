@@ -89,6 +89,11 @@ def lib(real=np.float64):
         _lib.oracle_train_step.argtypes = [C.c_void_p, _I, _D, _D, C.c_int32, C.c_int32]
         _lib.oracle_generate.argtypes = [C.c_void_p, _I, _D, C.c_int32, _D, C.c_int32, C.c_int32]
         _lib.oracle_get_losses.argtypes = [C.c_void_p, _D, _D, _I]
+        _F32 = C.POINTER(C.c_float)
+        _F64 = C.POINTER(C.c_double)
+        _lib.oracle_draw_labels.argtypes = [_F64, C.c_int, _F32, C.c_int, _I]
+        _lib.oracle_sample.argtypes = [C.c_void_p, _F64, _F32, _D, C.c_int32, _D, _I, C.c_int32]
+        _lib.oracle_anova_f.argtypes = [_I, _F32, C.c_int, C.c_int, C.c_int, C.c_int, _F64]
         _lib.oracle_get_routing.argtypes = [C.c_void_p, _I, _I]
         _lib.oracle_eval_losses.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
         _lib.oracle_eval_grads.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
@@ -201,6 +206,18 @@ class Oracle:
         out = np.zeros((n,) + self.img_shape, self.real)
         rc = self.L.oracle_generate(self.h, _i(label_ids), _d(noise), n, _d(out), use_running_stats, only_model)
         return rc, out
+
+    def sample(self, prior, u, noise, use_running_stats=1):
+        """Mixture samples (Eq. 5): labels drawn from `prior` with the caller's uniforms, then the per-label generators."""
+        prior = np.ascontiguousarray(prior, np.float64)
+        u = np.ascontiguousarray(u, np.float32)
+        noise = np.ascontiguousarray(noise, self.real)
+        n = u.size
+        out = np.zeros((n,) + self.img_shape, self.real)
+        labels = np.empty(n, np.int32)
+        rc = self.L.oracle_sample(self.h, prior.ctypes.data_as(C.POINTER(C.c_double)), u.ctypes.data_as(C.POINTER(C.c_float)),
+                                  _d(noise), n, _d(out), _i(labels), use_running_stats)
+        return rc, out, labels
 
     def get_losses(self):
         K = self.n_models
@@ -364,6 +381,26 @@ def route(label_ids, n_models, n_labels):
     perm, offs, bad = np.empty(max(n, 1), np.int32), np.empty(n_models + 1, np.int32), C.c_int32()
     lib().oracle_route(_i(label_ids), n, n_models, n_labels, _i(perm), _i(offs), C.byref(bad))
     return perm[:n], offs, bad.value
+
+
+def draw_labels(prior, u):
+    prior = np.ascontiguousarray(prior, np.float64)
+    u = np.ascontiguousarray(u, np.float32)
+    labels = np.empty(u.size, np.int32)
+    rc = lib().oracle_draw_labels(prior.ctypes.data_as(C.POINTER(C.c_double)), prior.size,
+                                  u.ctypes.data_as(C.POINTER(C.c_float)), u.size, _i(labels))
+    return rc, labels
+
+
+def anova_f(label_ids, images, n_labels):
+    """F-statistic per channel of the per-image mean intensities grouped by label; images [n, C, H, W] float32."""
+    label_ids = np.ascontiguousarray(label_ids, np.int32)
+    images = np.ascontiguousarray(images, np.float32)
+    n, Cc, H, W = images.shape
+    F = np.zeros(Cc, np.float64)
+    rc = lib().oracle_anova_f(_i(label_ids), images.ctypes.data_as(C.POINTER(C.c_float)), n, n_labels, Cc, H * W,
+                              F.ctypes.data_as(C.POINTER(C.c_double)))
+    return rc, F
 
 
 def threads():

@@ -900,6 +900,79 @@ int oracle_generate(oracle_ctx* c, const int32_t* label_ids, const oreal* noise,
   return bad ? -5 : 0;
 }
 
+/* Eq. 5: the model distribution is the prior-weighted mixture of the per-label generators. */
+int oracle_draw_labels(const double* prior, int n_labels, const float* u, int n, int32_t* labels) {
+  double total = 0.0;
+  for (int k = 0; k < n_labels; ++k) {
+    if (!(prior[k] >= 0.0)) return -1;
+    total += prior[k];
+  }
+  if (!(total > 0.0)) return -1;
+  for (int i = 0; i < n; ++i) {
+    const double ui = (double)u[i];
+    double cum = 0.0;
+    int pick = -1;
+    for (int k = 0; k < n_labels; ++k) {
+      cum += prior[k] / total;
+      if (pick < 0 && prior[k] > 0.0 && ui < cum) pick = k;
+    }
+    if (pick < 0)                       /* rounding left the last cumulative value below u: the last possible class */
+      for (int k = n_labels - 1; k >= 0; --k)
+        if (prior[k] > 0.0) { pick = k; break; }
+    labels[i] = pick;
+  }
+  return 0;
+}
+
+int oracle_sample(oracle_ctx* c, const double* prior, const float* u, const oreal* noise, int32_t n,
+                  oreal* out_images, int32_t* out_labels, int32_t use_running_stats) {
+  if (!c || n < 0) return -1;
+  if (oracle_draw_labels(prior, c->cfg.n_labels, u, n, out_labels) != 0) return -1;
+  return oracle_generate(c, out_labels, noise, n, out_images, use_running_stats, -1);
+}
+
+int oracle_anova_f(const int32_t* label_ids, const float* images, int n, int n_labels, int C, int HW, double* F) {
+  int rc = 0;
+  double* x = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+  double* gsum = (double*)malloc(sizeof(double) * (size_t)n_labels);
+  int* gcnt = (int*)malloc(sizeof(int) * (size_t)n_labels);
+  for (int c = 0; c < C; ++c) {
+    for (int i = 0; i < n; ++i) {                  /* observation: mean intensity of channel c of image i */
+      const float* p = images + ((int64_t)i * C + c) * HW;
+      double s = 0.0;
+      for (int q = 0; q < HW; ++q) s += (double)p[q];
+      x[i] = s / (double)HW;
+    }
+    for (int k = 0; k < n_labels; ++k) { gsum[k] = 0.0; gcnt[k] = 0; }
+    double all = 0.0;
+    int nn = 0;
+    for (int i = 0; i < n; ++i) {
+      const int y = label_ids[i];
+      if (y < 0 || y >= n_labels) continue;
+      gsum[y] += x[i]; gcnt[y] += 1; all += x[i]; nn += 1;
+    }
+    int kk = 0;
+    for (int k = 0; k < n_labels; ++k) kk += gcnt[k] > 0;
+    if (kk < 2 || nn <= kk) { rc = -1; F[c] = 0.0; continue; }
+    const double grand = all / (double)nn;
+    double ssb = 0.0, ssw = 0.0;
+    for (int k = 0; k < n_labels; ++k)
+      if (gcnt[k] > 0) {
+        const double mk = gsum[k] / (double)gcnt[k];
+        ssb += (double)gcnt[k] * (mk - grand) * (mk - grand);
+      }
+    for (int i = 0; i < n; ++i) {
+      const int y = label_ids[i];
+      if (y < 0 || y >= n_labels) continue;
+      const double mk = gsum[y] / (double)gcnt[y];
+      ssw += (x[i] - mk) * (x[i] - mk);
+    }
+    F[c] = (ssb / (double)(kk - 1)) / (ssw / (double)(nn - kk));
+  }
+  free(x); free(gsum); free(gcnt);
+  return rc;
+}
+
 int oracle_get_losses(const oracle_ctx* c, oreal* d_loss, oreal* g_loss, int32_t* counts) {
   for (int l = 0; l < c->cfg.n_models; ++l) {
     if (d_loss) d_loss[l] = c->jd[l];

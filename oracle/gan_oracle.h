@@ -130,6 +130,25 @@ void oracle_adam(oreal* theta, oreal* m, oreal* v, const oreal* g, int64_t n, in
 void oracle_route(const int32_t* label_ids, int n, int n_models, int n_labels,
                   int32_t* perm, int32_t* offs, int32_t* n_bad);
 
+/* ---- the mixture over the per-label generators (Eq. 5) ------------------------------------------------- */
+/* Class draws from the prior p_y: label_i = the first k whose cumulative probability exceeds u_i, where the
+   cumulative probabilities are the running sums (in double, in index order) of prior[k] / sum(prior) and u_i in
+   [0, 1) is supplied by the caller.  Always in double, whatever oreal is: the decision is an integer.
+   Returns -1 if the prior has a negative entry or sums to zero. */
+int oracle_draw_labels(const double* prior, int n_labels, const float* u, int n, int32_t* labels);
+/* Samples of the mixture: labels drawn as above, then image i = G_{label_i}(noise_i) (running statistics when
+   use_running_stats != 0, statistics of the generated batch per model otherwise).  Same return codes as
+   oracle_generate. */
+int oracle_sample(oracle_ctx* ctx, const double* prior, const float* u, const oreal* noise, int32_t n,
+                  oreal* out_images, int32_t* out_labels, int32_t use_running_stats);
+
+/* ---- one-way analysis of variance of the image intensities by class (Section 4: the F-statistic quoted per
+   channel for every dataset).  Observation (i, c) = the mean of channel c over the pixels of image i; groups =
+   labels; F_c = [sum_k n_k (m_kc - m_c)^2 / (K' - 1)] / [sum_k sum_{i in k} (x_ic - m_kc)^2 / (n' - K')] over the
+   K' labels that occur and the n' images with a valid label.  images: [n, C, H, W] floats.  Always in double.
+   Returns -1 when fewer than two labels occur or n' <= K'. ------------------------------------------------- */
+int oracle_anova_f(const int32_t* label_ids, const float* images, int n, int n_labels, int C, int HW, double* F);
+
 #ifdef __cplusplus
 }
 #endif
