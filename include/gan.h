@@ -145,6 +145,25 @@ gan_status gan_profile_enable(gan_ctx* ctx, int32_t enable);
 gan_status gan_profile_read(gan_ctx* ctx, int32_t cap, const char** names, int64_t* launches, double* ms,
                             double* flops, double* bytes, int32_t* n_out);
 
+/* ---- next to the training step ----------------------------------------------------------------------- */
+/* n samples of the mixture of Eq. 5: label_i is drawn from the class prior p_y, then x_i = G_{label_i}(noise_i).
+   prior: HOST double [n_labels], non-negative, not all zero (it is normalised by its sum).  u: DEVICE fp32 [n],
+   the caller's uniforms in [0, 1): label_i is the first k whose cumulative probability (running sums of
+   prior[k] / sum in double, in index order) exceeds u_i.  noise, out_images, use_running_stats: as gan_generate
+   (the paper combines the trained generators, so the running statistics, 1, are the usual choice).
+   out_labels: DEVICE int32 [n].  Returns GAN_E_ARG for a bad prior.  Copies the cumulative prior to the device
+   synchronously, then enqueues on the context's stream. */
+gan_status gan_sample(gan_ctx* ctx, const double* prior, const float* u, const float* noise, int32_t n,
+                      float* out_images, int32_t* out_labels, int32_t use_running_stats);
+
+/* One-way analysis of variance of the image intensities by class: the F-statistic per channel that Section 4 quotes
+   for each dataset as the justification for partitioning by label.  Observation (i, c) = mean of channel c over the
+   pixels of image i; groups = label ids in [0, n_labels) (others are ignored).
+   label_ids: DEVICE int32 [n]; images: DEVICE fp32 [n, img_c, img_hw, img_hw]; n <= max_total_batch;
+   F: HOST double [img_c].  All arithmetic in double, in a fixed order.  Synchronises the stream.
+   Returns GAN_E_STATE (and F = 0) when fewer than two labels occur or there are not more images than labels. */
+gan_status gan_anova_f(gan_ctx* ctx, const int32_t* label_ids, const float* images, int32_t n, double* F);
+
 /* ---- what the chip delivers to the simplest kernels (Section 5 of the paper reports GPU usage only; these give the
    achievable ceilings the step's kernels are reported against, next to the published peaks) -------------- */
 /* TFLOP/s of a register-only MFMA loop in the arithmetic of `precision` (bf16 inputs, or fp32), every CU busy.

@@ -76,6 +76,8 @@ def load_library():
     L.gan_op_conv_down.argtypes = op
     L.gan_op_conv_up.argtypes = op
     L.gan_op_conv_wgrad.argtypes = op
+    L.gan_sample.argtypes = [_VP, C.POINTER(C.c_double), _VP, _VP, C.c_int32, _VP, _VP, C.c_int32]
+    L.gan_anova_f.argtypes = [_VP, _VP, _VP, C.c_int32, C.POINTER(C.c_double)]
     L.gan_probe_mfma.argtypes = [C.c_int32, _VP, C.POINTER(C.c_double)]
     L.gan_probe_copy.argtypes = [C.c_int64, _VP, C.POINTER(C.c_double)]
     _lib = L
@@ -159,6 +161,16 @@ class Gan:
 
     def generate(self, label_ids_ptr, noise_ptr, n, out_ptr, use_running_stats=0):
         self._check(self.lib.gan_generate(self.h, label_ids_ptr, noise_ptr, n, out_ptr, use_running_stats))
+
+    def sample(self, prior, u_ptr, noise_ptr, n, out_ptr, labels_ptr, use_running_stats=1):
+        prior = np.ascontiguousarray(prior, np.float64)
+        self._check(self.lib.gan_sample(self.h, prior.ctypes.data_as(C.POINTER(C.c_double)), u_ptr, noise_ptr, n, out_ptr,
+                                        labels_ptr, use_running_stats))
+
+    def anova_f(self, label_ids_ptr, images_ptr, n, img_c):
+        F = np.zeros(img_c, np.float64)
+        st = self.lib.gan_anova_f(self.h, label_ids_ptr, images_ptr, n, F.ctypes.data_as(C.POINTER(C.c_double)))
+        return st, F
 
     def get_losses(self, check=True):
         K = self.n_models

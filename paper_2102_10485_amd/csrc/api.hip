@@ -76,6 +76,10 @@ struct gan_ctx {
   bool shadows_dirty = true;
   std::string err;
   std::vector<void*> allocs;
+  // mixture sampling and ANOVA: buffers allocated at first use
+  double* cdf = nullptr;            // [n_labels]
+  double *an_x = nullptr, *an_gsum = nullptr, *an_ssw = nullptr;   // [NB*img_c], [n_labels*img_c] x 2
+  int* an_gcnt = nullptr;           // [n_labels]
   // profiling
   bool prof = false, prof_detail = false, prof_gemm_only = false;
   std::set<std::string> prof_names;
@@ -878,6 +882,75 @@ gan_status gan_generate(gan_ctx* c, const int32_t* label_ids, const float* noise
   }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("launch failed: ") + hipGetErrorString(e));
+  return GAN_OK;
+}
+
+gan_status gan_sample(gan_ctx* c, const double* prior, const float* u, const float* noise, int32_t n, float* out_images,
+                      int32_t* out_labels, int32_t use_running_stats) {
+  if (!c) return GAN_E_ARG;
+  if (n < 0 || n > c->NB) return fail(c, GAN_E_ARG, "n out of range [0, max_total_batch]");
+  if (!prior) return fail(c, GAN_E_ARG, "null prior");
+  const int K = c->cfg.n_labels;
+  double total = 0.0;
+  int last = -1;
+  for (int k = 0; k < K; ++k) {
+    if (!(prior[k] >= 0.0)) return fail(c, GAN_E_ARG, "negative (or NaN) prior entry");
+    total += prior[k];
+    if (prior[k] > 0.0) last = k;
+  }
+  if (!(total > 0.0)) return fail(c, GAN_E_ARG, "the prior sums to zero");
+  if (n == 0) return GAN_OK;
+  if (!u || !noise || !out_images || !out_labels) return fail(c, GAN_E_ARG, "null pointer");
+  std::vector<double> cdf((size_t)K);
+  double cum = 0.0;
+  for (int k = 0; k < K; ++k) { cum += prior[k] / total; cdf[(size_t)k] = cum; }
+  if (!c->cdf && !dev_alloc(c, (void**)&c->cdf, (size_t)K * sizeof(double))) return fail(c, GAN_E_OOM, "cumulative prior");
+  if (hipStreamSynchronize(c->st) != hipSuccess ||      // an earlier call may still read the buffer
+      hipMemcpy(c->cdf, cdf.data(), (size_t)K * sizeof(double), hipMemcpyHostToDevice) != hipSuccess)
+    return fail(c, GAN_E_HIP, "copy of the cumulative prior failed");
+  launch_draw_labels(u, c->cdf, K, last, n, out_labels, c->st);
+  return gan_generate(c, out_labels, noise, n, out_images, use_running_stats);
+}
+
+gan_status gan_anova_f(gan_ctx* c, const int32_t* label_ids, const float* images, int32_t n, double* F) {
+  if (!c || !F) return GAN_E_ARG;
+  if (n < 0 || n > c->NB) return fail(c, GAN_E_ARG, "n out of range [0, max_total_batch]");
+  const gan_config& f = c->cfg;
+  const int K = f.n_labels, C = f.img_c, HW = f.img_hw * f.img_hw;
+  for (int ch = 0; ch < C; ++ch) F[ch] = 0.0;
+  if (n == 0) return fail(c, GAN_E_STATE, "no images");
+  if (!label_ids || !images) return fail(c, GAN_E_ARG, "null pointer");
+  if (!c->an_x) {
+    if (!dev_alloc(c, (void**)&c->an_x, (size_t)c->NB * C * sizeof(double)) ||
+        !dev_alloc(c, (void**)&c->an_gsum, (size_t)K * C * sizeof(double)) ||
+        !dev_alloc(c, (void**)&c->an_ssw, (size_t)K * C * sizeof(double)) || !dev_alloc(c, (void**)&c->an_gcnt, (size_t)K * sizeof(int)))
+      return fail(c, GAN_E_OOM, "analysis-of-variance buffers");
+  }
+  launch_anova(label_ids, images, n, K, C, HW, c->an_x, c->an_gsum, c->an_gcnt, c->an_ssw, c->st);
+  std::vector<double> gsum((size_t)K * C), ssw((size_t)K * C);
+  std::vector<int> gcnt((size_t)K);
+  if (hipStreamSynchronize(c->st) != hipSuccess ||
+      hipMemcpy(gsum.data(), c->an_gsum, gsum.size() * sizeof(double), hipMemcpyDeviceToHost) != hipSuccess ||
+      hipMemcpy(ssw.data(), c->an_ssw, ssw.size() * sizeof(double), hipMemcpyDeviceToHost) != hipSuccess ||
+      hipMemcpy(gcnt.data(), c->an_gcnt, gcnt.size() * sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(c, GAN_E_HIP, "analysis of variance failed on the device");
+  int kk = 0;
+  long long nn = 0;
+  for (int k = 0; k < K; ++k) { kk += gcnt[(size_t)k] > 0; nn += gcnt[(size_t)k]; }
+  if (kk < 2 || nn <= kk) return fail(c, GAN_E_STATE, "fewer than two labels present, or not more images than labels");
+  for (int ch = 0; ch < C; ++ch) {
+    double all = 0.0;
+    for (int k = 0; k < K; ++k) all += gsum[(size_t)k * C + ch];
+    const double grand = all / (double)nn;
+    double ssb = 0.0, sw = 0.0;
+    for (int k = 0; k < K; ++k) {
+      if (gcnt[(size_t)k] == 0) continue;
+      const double mk = gsum[(size_t)k * C + ch] / (double)gcnt[(size_t)k];
+      ssb += (double)gcnt[(size_t)k] * (mk - grand) * (mk - grand);
+      sw += ssw[(size_t)k * C + ch];
+    }
+    F[ch] = (ssb / (double)(kk - 1)) / (sw / (double)(nn - kk));
+  }
   return GAN_OK;
 }
 

@@ -183,4 +183,14 @@ void launch_transpose_w(const S* src, T* dst, long long pstride, int L, int Cb, 
 
 void launch_tile_prefix(const int* offs, int L, int rps, int tile_rows, int* tpre, hipStream_t st);
 
+// Class draws: labels[i] = first k with cdf[k] > (double)u[i]; if none (rounding), `last` .
+void launch_draw_labels(const float* u, const double* cdf, int n_labels, int last, int n, int* labels, hipStream_t st);
+
+// One-way analysis of variance of the per-image channel means by label; all arithmetic in double, fixed order.
+//   x[i][c]    = mean over the pixels of channel c of image i (images: NCHW fp32)
+//   gsum[k][c] = sum of x over the images of label k, gcnt[k] = their number
+//   ssw[k][c]  = sum over the images of label k of (x - gsum/gcnt)^2
+void launch_anova(const int* label_ids, const float* images, int n, int n_labels, int C, int HW, double* x, double* gsum,
+                  int* gcnt, double* ssw, hipStream_t st);
+
 }  // namespace gan

@@ -824,4 +824,83 @@ void launch_transpose_w(const S* src, T* dst, long long pstride, int L, int Cb, 
 template void launch_transpose_w<float, float>(const float*, float*, long long, int, int, int, hipStream_t);
 template void launch_transpose_w<bf16_t, bf16_t>(const bf16_t*, bf16_t*, long long, int, int, int, hipStream_t);
 
+// ---------------------------------------------------------------------------------------------------------
+// Mixture sampling (Eq. 5): class draws from the prior.  The cumulative probabilities come from the host in
+// double; the comparison is done in double so that the integer result does not depend on who computes it.
+// ---------------------------------------------------------------------------------------------------------
+__global__ void draw_labels_kernel(const float* __restrict__ u, const double* __restrict__ cdf, int K, int last, int n,
+                                   int* __restrict__ labels) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const double ui = (double)u[i];
+  int lo = 0, hi = K;                 // first k in [0, K) with cdf[k] > ui (cdf is non-decreasing), K if none
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (cdf[mid] > ui) hi = mid; else lo = mid + 1;
+  }
+  labels[i] = lo < K ? lo : last;
+}
+void launch_draw_labels(const float* u, const double* cdf, int n_labels, int last, int n, int* labels, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(draw_labels_kernel, dim3((n + 255) / 256), dim3(256), 0, st, u, cdf, n_labels, last, n, labels);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// One-way ANOVA of the image intensities by class (Section 4).  Three small kernels, double arithmetic, every sum in
+// a fixed order: thread-strided partial sums, then a tree over the 256 threads.
+// ---------------------------------------------------------------------------------------------------------
+__device__ inline double block_sum_256(double v, double* sh) {
+  sh[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+    __syncthreads();
+  }
+  const double r = sh[0];
+  __syncthreads();
+  return r;
+}
+__global__ __launch_bounds__(256) void anova_image_mean_kernel(const float* __restrict__ images, int C, int HW, double* __restrict__ x) {
+  __shared__ double sh[256];
+  const long long ic = blockIdx.x;                                     // image * C + channel
+  const float* p = images + ic * HW;
+  double s = 0.0;
+  for (int q = threadIdx.x; q < HW; q += 256) s += (double)p[q];
+  s = block_sum_256(s, sh);
+  if (threadIdx.x == 0) x[ic] = s / (double)HW;
+}
+__global__ __launch_bounds__(256) void anova_group_kernel(const int* __restrict__ label_ids, const double* __restrict__ x, int n, int C,
+                                                          const double* __restrict__ gsum_in, const int* __restrict__ gcnt_in,
+                                                          double* __restrict__ out, int* __restrict__ gcnt_out) {
+  __shared__ double sh[256];
+  const int k = blockIdx.x, c = blockIdx.y;
+  // pass 1 (gsum_in == NULL): sum of x and count ; pass 2: sum of squared deviations from the group mean
+  double mean = 0.0;
+  if (gsum_in) {
+    const int cnt = gcnt_in[k];
+    mean = cnt > 0 ? gsum_in[(long long)k * C + c] / (double)cnt : 0.0;
+  }
+  double s = 0.0, cntd = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    if (label_ids[i] != k) continue;
+    const double v = x[(long long)i * C + c];
+    if (gsum_in) { s += (v - mean) * (v - mean); } else { s += v; cntd += 1.0; }
+  }
+  s = block_sum_256(s, sh);
+  if (!gsum_in) cntd = block_sum_256(cntd, sh);
+  if (threadIdx.x == 0) {
+    out[(long long)k * C + c] = s;
+    if (!gsum_in && c == 0) gcnt_out[k] = (int)cntd;
+  }
+}
+void launch_anova(const int* label_ids, const float* images, int n, int n_labels, int C, int HW, double* x, double* gsum,
+                  int* gcnt, double* ssw, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(anova_image_mean_kernel, dim3((unsigned)((long long)n * C)), dim3(256), 0, st, images, C, HW, x);
+  hipLaunchKernelGGL(anova_group_kernel, dim3(n_labels, C), dim3(256), 0, st, label_ids, x, n, C, (const double*)nullptr,
+                     (const int*)nullptr, gsum, gcnt);
+  hipLaunchKernelGGL(anova_group_kernel, dim3(n_labels, C), dim3(256), 0, st, label_ids, x, n, C, (const double*)gsum,
+                     (const int*)gcnt, ssw, (int*)nullptr);
+}
+
 }  // namespace gan
