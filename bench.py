@@ -79,6 +79,60 @@ def cpu_baseline(work, min_seconds=10.0, max_models=16):
                       % (len(models), work.n_models, images, dt)}
 
 
+def other_rows(args, torch, binding, work, gan, prec, prec_name, d_lab, d_real, d_noise, n):
+    """The two rows next to the training step, timed the same way (inputs resident, warm-up, K timed calls)."""
+    rng = np.random.default_rng(work.seed + 77)
+    descr = DESCR[args.config] + (", %s" % prec_name)
+    if args.row == "sample":
+        # a few training steps first so that the running statistics are those of a trained-ish model
+        for i in range(2):
+            gan.train_step(d_lab.data_ptr(), d_noise[i].data_ptr(), d_real.data_ptr(), n)
+        prior = np.bincount(work.labels(), minlength=work.n_labels).astype(np.float64)      # the class frequencies of the workload
+        d_u = torch.from_numpy(rng.random(n).astype(np.float32)).cuda()
+        out = torch.empty((n, work.spec["img_c"], work.spec["img_hw"], work.spec["img_hw"]), dtype=torch.float32, device="cuda")
+        labels = torch.empty(n, dtype=torch.int32, device="cuda")
+
+        def call(i):
+            gan.sample(prior, d_u.data_ptr(), d_noise[i % 4].data_ptr(), n, out.data_ptr(), labels.data_ptr(), 1)
+        metric, unit = "mixture samples/sec (class draw + per-label generators, running statistics)", "images/s"
+    else:
+        def call(i):
+            st, F = gan.anova_f(d_lab.data_ptr(), d_real.data_ptr(), n, work.spec["img_c"])
+            assert st == 0 and np.all(np.isfinite(F))
+        metric, unit = "images/sec through the per-channel ANOVA F-statistic (device reductions + host finish)", "images/s"
+    for i in range(args.warmup):
+        call(i)
+    torch.cuda.synchronize()
+    if args.row == "sample" and not args.no_profile:
+        gan.profile_enable(True, gemm_only=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        call(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out_j = {"metric": metric, "value": n * args.steps / dt, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+             "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+             "dtype": prec_name if args.row == "sample" else "f64", "data": "synthetic",
+             "config": {"workload": descr + ", row: " + args.row, "images_per_step": n}}
+    if args.row == "sample" and not args.no_profile:
+        prof = gan.profile_read()
+        gan.profile_enable(False)
+        dom = max(prof, key=lambda k: prof[k]["ms"])
+        r = prof[dom]
+        peak = PEAK["mfma_bf16"] if prec_name == "bf16" else PEAK["mfma_fp32"]
+        tf = r["flops"] / (r["ms"] * 1e9)
+        out_j["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
+                             "traffic": None, "avg_launch_ms": r["ms"] / max(r["launches"], 1)}
+    elif args.row == "anova":
+        nbytes = float(n) * work.spec["img_c"] * work.spec["img_hw"] ** 2 * 4
+        gbps = nbytes * args.steps / dt / 1e9
+        out_j["roofline"] = {"kernel": "anova (whole call, including the synchronising copy back)", "bound": "hbm", "achieved": gbps,
+                             "peak": PEAK["hbm"], "unit": "GB/s", "frac": gbps / PEAK["hbm"], "traffic": None}
+    gan.close()
+    print(json.dumps(out_j))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +145,9 @@ def main():
     ap.add_argument("--detail", action="store_true", help="time every kernel, one line per layer shape (analysis runs)")
     ap.add_argument("--all-kernels", action="store_true",
                     help="time every kernel, not only the MFMA ones (two stream-draining events per launch: slower steps)")
+    ap.add_argument("--row", choices=["train", "sample", "anova"], default="train",
+                    help="train (default): the training step; sample: mixture sampling (Eq. 5) of images_per_step images per "
+                         "call; anova: the per-channel F-statistic of one batch")
     ap.add_argument("--copy-probe", action="store_true",
                     help="before the timed region, run one elementwise kernel over 1 GiB (reads 1 GiB, writes 1 GiB: known traffic for scaling "
                          "hardware byte counters)")
@@ -117,6 +174,9 @@ def main():
     d_real = torch.from_numpy(work.images(lab)).cuda()
     d_noise = [torch.from_numpy(work.noise()).cuda() for _ in range(4)]
     torch.cuda.synchronize()
+
+    if args.row != "train":
+        return other_rows(args, torch, binding, work, gan, prec, prec_name, d_lab, d_real, d_noise, n)
 
     def step(i):
         gan.train_step(d_lab.data_ptr(), d_noise[i % 4].data_ptr(), d_real.data_ptr(), n)
