@@ -33,6 +33,9 @@ CASES = [
     (256, 128, 2, [70, 1]),
     (128, 256, 4, [20, 5]),
     (64, 512, 2, [130]),
+    (256, 512, 4, [33, 40]),       # 256-wide output tiles in both directions, several M-tiles per model
+    (128, 128, 16, [3]),           # one sample is a whole 256-row tile
+    (64, 128, 4, [1, 1, 2]),       # models with a single sample
 ]
 
 
