@@ -111,6 +111,11 @@ int geom_id(gan_ctx* c, int rps, int tile_rows) {
   c->geoms.tile_rows[c->geoms.n] = tile_rows;
   return c->geoms.n++;
 }
+const int* tmodel_of(gan_ctx* c, int rps, int tile_rows) {
+  for (int i = 0; i < c->geoms.n; ++i)
+    if (c->geoms.rps[i] == rps && c->geoms.tile_rows[i] == tile_rows) return c->rb.tmodel + (long long)i * c->rb.tmodel_stride;
+  return nullptr;
+}
 const int* tpre_of(gan_ctx* c, int rps, int tile_rows) {
   int g = -1;
   for (int i = 0; i < c->geoms.n; ++i)
@@ -341,7 +346,7 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
   ConvArgs a = {};
   a.A = A; a.W = W; a.Out = Out; a.Aux = Aux; a.w_nstride = w_nstride ? w_nstride : N;
   const int tr = layer_tile_rows(c, N, Hr * Hr);
-  a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, tr); a.tile_rows = tr;
+  a.offs = c->rb.offs; a.tpre = tpre_of(c, Hr * Hr, tr); a.tmodel = tmodel_of(c, Hr * Hr, tr); a.tile_rows = tr;
   a.w_stride = wstride; a.L = c->L; a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n;
   a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr; a.ub_tiles = ub_tiles(c, n, Hr * Hr, tr);
   a.slope = c->cfg.leaky_slope;
@@ -419,7 +424,8 @@ void bn_backward(gan_ctx* c, NormArgs a, const void* x, const void* dy, void* dx
   const double elems = (double)a.n * a.nseg * a.rps * a.C;
   {
     Scope s(c, "bn_bwd_reduce", 0, 2 * elems * sizeof(T));
-    launch_bn_bwd_reduce<T>(a, tpre_of(c, a.rps, BN_RED_ROWS), ub_tiles(c, a.n, a.rps, BN_RED_ROWS), c->stat_partial, c->st);
+    launch_bn_bwd_reduce<T>(a, tpre_of(c, a.rps, BN_RED_ROWS), tmodel_of(c, a.rps, BN_RED_ROWS), ub_tiles(c, a.n, a.rps, BN_RED_ROWS),
+                            c->stat_partial, c->st);
   }
   if (param_grads) launch_bn_param_grad(a, c->st);
   Scope s(c, "bn_bwd_apply", 0, 3 * elems * sizeof(T));
@@ -718,6 +724,12 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
        dev_alloc(c, (void**)&rb.offs, (size_t)(L + 1) * 4) && dev_alloc(c, (void**)&rb.perm, (size_t)NB * 4) &&
        dev_alloc(c, (void**)&rb.sample_model, (size_t)NB * 4) && dev_alloc(c, (void**)&rb.sample_slot, (size_t)NB * 4) &&
        dev_alloc(c, (void**)&rb.tpre, (size_t)MAX_GEOMS * (L + 1) * 4) && dev_alloc(c, (void**)&rb.flags, 16);
+  {
+    int mx = 1;
+    for (int g = 0; g < c->geoms.n; ++g) mx = std::max(mx, ub_tiles(c, NB, c->geoms.rps[g], c->geoms.tile_rows[g]));
+    rb.tmodel_stride = mx;
+    ok = ok && dev_alloc(c, (void**)&rb.tmodel, (size_t)c->geoms.n * mx * 4);
+  }
   const long long img_elems = (long long)cfg->img_hw * cfg->img_hw * cfg->img_c;
   long long max_act = img_elems;
   ok = ok && dev_alloc(c, &c->zin, (size_t)NB * c->G.Kp * es) && dev_alloc(c, &c->xd, (size_t)2 * NB * img_elems * es) &&

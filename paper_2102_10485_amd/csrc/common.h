@@ -48,6 +48,7 @@ struct ConvArgs {
   int w_nstride;         // rows per tap in the weight block (>= N)
   const int* offs;       // [L+1] sample offsets of the models inside one segment
   const int* tpre;       // [L+1] prefix of M-tiles per model for this geometry
+  const int* tmodel;     // model of every M-tile of this geometry (NULL: found by bisection in tpre)
   long long w_stride;    // elements between two models' weight blocks
   int L;                 // models
   int seg_first, nseg;   // segments to process: rows of segment s start at sample s*seg_samples

@@ -204,10 +204,15 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const int v2 = v1 / NPH;
   const int sidx = v2 % p.nseg;
   const int mt = v2 / p.nseg;
-  int lo = 0, hi = p.L;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (p.tpre[mid] <= mt) lo = mid; else hi = mid;
+  int lo = 0;
+  if (p.tmodel) {
+    lo = p.tmodel[mt];
+  } else {
+    int hi = p.L;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.tpre[mid] <= mt) lo = mid; else hi = mid;
+    }
   }
   const int l = lo;
   const int seg = p.seg_first + sidx;

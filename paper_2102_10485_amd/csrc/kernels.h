@@ -24,6 +24,8 @@ struct RouteBuffers {
   int* sample_model;  // [n] model of the j-th routed sample
   int* sample_slot;   // [n] label-map slot of the j-th routed sample
   int* tpre;          // [MAX_GEOMS][L+1]
+  int* tmodel;        // [MAX_GEOMS][tmodel_stride]: model of every tile of every geometry (built with tpre)
+  int tmodel_stride;
   int* flags;         // [0]: out-of-range label seen
 };
 
@@ -71,7 +73,7 @@ void launch_bn_from_running(const NormArgs& a, hipStream_t st);   // mean/rstd <
 template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st);
 constexpr int BN_RED_ROWS = 256;    // rows per block of the backward reduction (tile prefix geometry (rps, BN_RED_ROWS))
 template <typename T>
-void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, int ub_tiles, float* partial, hipStream_t st);
+void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, const int* tmodel, int ub_tiles, float* partial, hipStream_t st);
 void launch_bn_param_grad(const NormArgs& a, hipStream_t st);
 template <typename T> void launch_bn_bwd_apply(const NormArgs& a, hipStream_t st);
 
@@ -182,6 +184,8 @@ template <typename T, typename S>
 void launch_transpose_w(const S* src, T* dst, long long pstride, int L, int Cb, int Cs, hipStream_t st);
 
 void launch_tile_prefix(const int* offs, int L, int rps, int tile_rows, int* tpre, hipStream_t st);
+// tmodel[t] = model of tile t for t < tpre[L] (cap entries available)
+void launch_tile_models(const int* tpre, int L, int* tmodel, int cap, hipStream_t st);
 
 // Class draws: labels[i] = first k with cdf[k] > (double)u[i]; if none (rounding), `last` .
 void launch_draw_labels(const float* u, const double* cdf, int n_labels, int last, int n, int* labels, hipStream_t st);

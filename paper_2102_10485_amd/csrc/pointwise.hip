@@ -75,6 +75,23 @@ __global__ void route_scatter_kernel(const int* __restrict__ label_ids, int n, i
   }
 }
 
+// model of every tile of every geometry: grid (tile blocks, geometries)
+__global__ void tile_model_kernel(const int* __restrict__ tpre_all, int L, int* __restrict__ tmodel_all, int stride) {
+  const int* tpre = tpre_all + (long long)blockIdx.y * (L + 1);
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= tpre[L] || t >= stride) return;
+  int lo = 0, hi = L;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (tpre[mid] <= t) lo = mid; else hi = mid;
+  }
+  tmodel_all[(long long)blockIdx.y * stride + t] = lo;
+}
+void launch_tile_models(const int* tpre, int L, int* tmodel, int cap, hipStream_t st) {
+  if (cap <= 0) return;
+  hipLaunchKernelGGL(tile_model_kernel, dim3((cap + 255) / 256, 1), dim3(256), 0, st, tpre, L, tmodel, cap);
+}
+
 void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTable& geoms, const RouteBuffers& rb,
                   hipStream_t st) {
   hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.flags);
@@ -82,6 +99,9 @@ void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTa
   hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(64), 0, st, rb.counts, rb.offs, rb.tpre, L, geoms);
   hipLaunchKernelGGL(route_scatter_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.offs,
                      rb.perm, rb.sample_model, rb.sample_slot);
+  if (rb.tmodel && geoms.n > 0)
+    hipLaunchKernelGGL(tile_model_kernel, dim3((rb.tmodel_stride + 255) / 256, geoms.n), dim3(256), 0, st, rb.tpre, L, rb.tmodel,
+                       rb.tmodel_stride);
 }
 
 __global__ void tile_prefix_kernel(const int* offs, int L, int rps, int tile_rows, int* tpre) {
@@ -344,16 +364,21 @@ template void launch_bn_apply<bf16_t>(const NormArgs&, hipStream_t);
 // Stage 1: block (tile of BN_RED_ROWS rows of one model, segment), all channels -> partial[segment][tile][C][2].
 // Stage 2: the tiles of a (segment, model) added in order.
 template <typename T>
-__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
-                                                            float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const int* __restrict__ tpre, const int* __restrict__ tmodel,
+                                                            int ub_tiles, float* __restrict__ partial) {
   constexpr int EPV = Vec16<T>::N;
   extern __shared__ float red[];                    // [2][RL][C]
   const int tile = blockIdx.x;
   if (tile >= tpre[a.L]) return;
-  int lo = 0, hi = a.L;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (tpre[mid] <= tile) lo = mid; else hi = mid;
+  int lo = 0;
+  if (tmodel) {
+    lo = tmodel[tile];
+  } else {
+    int hi = a.L;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (tpre[mid] <= tile) lo = mid; else hi = mid;
+    }
   }
   const int l = lo, sidx = blockIdx.y;
   const int seg = a.seg_first + sidx;
@@ -426,18 +451,18 @@ __global__ void bn_bwd_reduce_final_kernel(NormArgs a, const int* __restrict__ t
   a.sums[o + 1] = s1;
 }
 template <typename T>
-void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, int ub_tiles, float* partial, hipStream_t st) {
+void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, const int* tmodel, int ub_tiles, float* partial, hipStream_t st) {
   if (a.nseg == 0 || ub_tiles == 0) return;
   const int cg = a.C / Vec16<T>::N;
   if (cg < 1 || cg > 256) abort();                  // one thread per 16 bytes of a row
   const size_t lds = (size_t)2 * (256 / cg) * a.C * sizeof(float);
-  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(ub_tiles, a.nseg), dim3(256), lds, st, a, tpre, ub_tiles, partial);
+  hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(ub_tiles, a.nseg), dim3(256), lds, st, a, tpre, tmodel, ub_tiles, partial);
   const long long tot = (long long)a.nseg * a.L * a.C;
   hipLaunchKernelGGL(bn_bwd_reduce_final_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a, tpre, ub_tiles,
                      partial);
 }
-template void launch_bn_bwd_reduce<float>(const NormArgs&, const int*, int, float*, hipStream_t);
-template void launch_bn_bwd_reduce<bf16_t>(const NormArgs&, const int*, int, float*, hipStream_t);
+template void launch_bn_bwd_reduce<float>(const NormArgs&, const int*, const int*, int, float*, hipStream_t);
+template void launch_bn_bwd_reduce<bf16_t>(const NormArgs&, const int*, const int*, int, float*, hipStream_t);
 
 // dgamma, dbeta: the segments' sums added in order.
 __global__ void bn_param_grad_kernel(NormArgs a) {
