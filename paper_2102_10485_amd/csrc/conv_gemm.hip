@@ -258,12 +258,20 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
         decode_row(r, Hr, rps, p.hr_shift, n, y, x);
         const int by = (MODE == MODE_DOWN) ? 2 * y - 1 : y, bx = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
         apix[i] = (unsigned)((((n * Hin + by) * Hin + bx) * C + chunk * EPV) * SZ);     // may wrap below zero: masked
-        for (int t = 0; t < ntaps; ++t) {
-          int dy, dx;
-          if (MODE == MODE_DOWN) { dy = t >> 2; dx = t & 3; }
-          else { dy = py == 0 ? ((t >> 1) == 0 ? 0 : -1) : ((t >> 1) == 0 ? 1 : 0); dx = px == 0 ? ((t & 1) == 0 ? 0 : -1) : ((t & 1) == 0 ? 1 : 0); }
-          const int iy = by + dy, ix = bx + dx;
-          if ((unsigned)iy < (unsigned)Hin && (unsigned)ix < (unsigned)Hin) amask[i] |= 1u << t;
+        if (MODE == MODE_DOWN) {             // tap (ky, kx) is inside iff row by + ky and column bx + kx are: separable
+          unsigned xm = 0;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) xm |= ((unsigned)(bx + k) < (unsigned)Hin ? 1u : 0u) << k;
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if ((unsigned)(by + k) < (unsigned)Hin) amask[i] |= xm << (4 * k);
+        } else {
+          for (int t = 0; t < ntaps; ++t) {
+            const int dy = py == 0 ? ((t >> 1) == 0 ? 0 : -1) : ((t >> 1) == 0 ? 1 : 0);
+            const int dx = px == 0 ? ((t & 1) == 0 ? 0 : -1) : ((t & 1) == 0 ? 1 : 0);
+            const int iy = by + dy, ix = bx + dx;
+            if ((unsigned)iy < (unsigned)Hin && (unsigned)ix < (unsigned)Hin) amask[i] |= 1u << t;
+          }
         }
       }
     }
