@@ -153,8 +153,8 @@ def main():
                          "hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the label models shard with no per-step traffic; "
-                 "see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: the library runs on one GPU (the label models shard across GPUs with no per-step traffic, "
+                 "each GPU running this same step on its labels); run with --gpus 1")
 
     import torch
     from paper_2102_10485_amd import binding, synth
