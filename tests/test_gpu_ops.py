@@ -36,6 +36,10 @@ CASES = [
     (256, 512, 4, [33, 40]),       # 256-wide output tiles in both directions, several M-tiles per model
     (128, 128, 16, [3]),           # one sample is a whole 256-row tile
     (64, 128, 4, [1, 1, 2]),       # models with a single sample
+    (64, 256, 8, [5, 0, 3]),       # down: 256-wide tiles of four samples each, ragged tails
+    (256, 64, 8, [2, 7]),          # up: the same, per output phase
+    (64, 256, 16, [2, 1]),         # down: one sample per 256-row tile
+    (256, 64, 16, [1, 2]),         # up: one sample per tile
 ]
 
 
