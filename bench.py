@@ -148,6 +148,10 @@ def main():
     ap.add_argument("--row", choices=["train", "sample", "anova"], default="train",
                     help="train (default): the training step; sample: mixture sampling (Eq. 5) of images_per_step images per "
                          "call; anova: the per-channel F-statistic of one batch")
+    ap.add_argument("--single-pair", choices=["cgan", "gan"], default=None,
+                    help="train row on the paper's comparison systems instead of the label models: ONE pair of the same widths over "
+                         "the same flat batch -- cgan: conditioned on the label of every sample (Tables 3 and 4); gan: unconditional "
+                         "(Tables 1 and 2)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="before the timed region, run one elementwise kernel over 1 GiB (reads 1 GiB, writes 1 GiB: known traffic for scaling "
                          "hardware byte counters)")
@@ -166,13 +170,34 @@ def main():
     prec_name = args.precision or work.precision
     prec = binding.BF16 if prec_name == "bf16" else binding.FP32
     n = work.n
-    cfg = binding.make_config(work.spec, work.n_models, work.n_labels, n, prec, seed=work.seed)
+    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
+    spec, n_models, n_labels, descr = work.spec, work.n_models, work.n_labels, DESCR[args.config]
+    img_lab = lab                              # the classes the real images are drawn from
+    if args.single_pair:
+        if args.row != "train":
+            sys.exit("bench.py: --single-pair goes with the train row")
+        spec, n_models = dict(work.spec), 1
+        if args.single_pair == "cgan":
+            n_labels = max(work.n_labels, 2)
+            spec["cond_g"] = spec["cond_d"] = n_labels
+            # one model owns the whole batch, and the library addresses one model's slice of any tensor with 32-bit
+            # byte offsets; the largest slice is the patch matrix of D's first layer
+            kc = -(-(16 * spec["img_c"] + 9 * n_labels + 1) // 64) * 64
+            row_bytes = kc * (2 if prec_name == "bf16" else 4) * (spec["img_hw"] // 2) ** 2
+            n = min(n, ((1 << 31) - 1) // row_bytes // 64 * 64)
+            descr = "one conditional pair (all %d labels) of config %d's widths, batch %d" % (n_labels, args.config, n)
+        else:
+            n_labels = 1
+            spec["cond_g"] = spec["cond_d"] = 0
+            descr = "one unconditional pair of config %d's widths, batch %d" % (args.config, n)
+            lab = np.zeros_like(lab)
+        lab, img_lab = lab[:n], img_lab[:n]
+    cfg = binding.make_config(spec, n_models, n_labels, n, prec, seed=work.seed)
     gan = binding.Gan(cfg, torch.cuda.current_stream().cuda_stream)
 
-    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
     d_lab = torch.from_numpy(lab).cuda()
-    d_real = torch.from_numpy(work.images(lab)).cuda()
-    d_noise = [torch.from_numpy(work.noise()).cuda() for _ in range(4)]
+    d_real = torch.from_numpy(work.images(img_lab)).cuda()
+    d_noise = [torch.from_numpy(work.noise()[:n].copy()).cuda() for _ in range(4)]
     torch.cuda.synchronize()
 
     if args.row != "train":
@@ -205,9 +230,9 @@ def main():
         "metric": "training images/sec (G+D step, all labels)", "value": n * args.steps / dt, "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": prec_name, "data": "synthetic",
-        "config": {"workload": DESCR[args.config] + (", %s" % prec_name), "n_models": work.n_models, "images_per_step": n,
+        "config": {"workload": descr + (", %s" % prec_name), "n_models": n_models, "images_per_step": n,
                    "batch_sizes": "min %d / median %d / max %d" % (work.batch_sizes.min(), np.median(work.batch_sizes),
-                                                                  work.batch_sizes.max())},
+                                                                  work.batch_sizes.max()) if not args.single_pair else str(n)},
     }
     if not args.no_profile:
         prof = gan.profile_read()
@@ -245,7 +270,7 @@ def main():
                                                                                         key=lambda kv: -kv[1]["ms_per_step"])}
         out["kernel_ms_sum"] = sum(v["ms_per_step"] for v in kern.values())
     gan.close()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.single_pair:
         out["cpu_baseline"] = cpu_baseline(synth.Workload(args.config))
     print(json.dumps(out))
 

@@ -23,6 +23,7 @@ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m
 // the weight gradient of a patch-matrix layer has a tiny output and a long reduction: its rows are split over this
 // many blocks per model, and the partial blocks are added in a fixed order when they are unpacked
 constexpr int IMG_KSPLIT = 8;
+constexpr int WG_MAX_KSPLIT = 16;
 
 // A (transposed) convolution between a "big" tensor (Cb channels, side 2*Hs) and a "small" one (Cs, side Hs).
 // Internal weight layout [tap][Cb (or CBT)][Cs].
@@ -70,6 +71,7 @@ struct gan_ctx {
   // image-side layers: patch matrices, packed weights, packed weight gradients
   void *colD = nullptr, *colG = nullptr, *wpD = nullptr, *wpG = nullptr;
   float *dwp = nullptr, *bias_partial = nullptr, *stat_partial = nullptr;
+  float* wg_part = nullptr;        // row-split partial weight gradients (few models only)
   int KcD = 0, KcG = 0;
   int nslot = 1;
   int last_n = -1;
@@ -365,13 +367,31 @@ void conv_call(gan_ctx* c, const char* name, int mode, int epi, const void* A, c
   launch_conv<T>(mode, epi, a, c->st);
 }
 
+// Row splits of a weight-gradient launch whose output tiles alone would not fill the chip (few models): every
+// model's rows are shared by this many blocks per tile, whose partial results are added in a fixed order.  A function
+// of the configuration only -- the number of models and the layer's shape -- never of the batch.
+int wgrad_ksplit(const gan_ctx* c, int Cb, int Cs, int ntaps) {
+  const long long blocks = (long long)c->L * wgrad_tiles_per_model(ntaps, Cb, Cs);
+  return (int)std::min<long long>(std::max<long long>(512 / blocks, 1), WG_MAX_KSPLIT);
+}
+
+// ksplit == 0: split as wgrad_ksplit says, through c->wg_part, and leave the sum in dW; ksplit >= 1: the caller's
+// own split (partials left at dW + split * L * stride).
 template <typename T>
 void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small, float* dW, long long stride, int Cb, int Cs,
-                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0, int ksplit = 1) {
+                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0, int ksplit = 0) {
   WgradArgs a = {};
   a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.dw_stride = stride;
   a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps; a.ksplit = ksplit;
   a.split_stride = (long long)c->L * stride;
+  const long long layer = (long long)ntaps * Cb * Cs;
+  const int auto_split = ksplit == 0 ? wgrad_ksplit(c, Cb, Cs, ntaps) : 0;
+  if (ksplit == 0) {
+    a.ksplit = auto_split;
+    if (auto_split > 1) {
+      a.dW = c->wg_part; a.dw_stride = layer; a.split_stride = (long long)c->L * layer;
+    }
+  }
   const double rows = (double)n * nseg * Hs * Hs;
   const double frac = ntaps == 1 ? 1.0 : valid_tap_fraction(Hs);
   const double big_elems = ntaps == 1 ? rows * Cb : (double)n * nseg * 4 * Hs * Hs * Cb;
@@ -379,8 +399,11 @@ void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small
   char detail[64];
   snprintf(detail, sizeof(detail), "[Cb%d Cs%d H%d seg%d]", Cb, Cs, Hs, nseg);
   (void)name;
-  Scope s(c, wgrad_variant_name(a), flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes, detail);
-  launch_wgrad<T>(a, c->st);
+  {
+    Scope s(c, wgrad_variant_name(a), flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes, detail);
+    launch_wgrad<T>(a, c->st);
+  }
+  if (auto_split > 1) launch_sum_splits(c->wg_part, dW, stride, layer, c->L, auto_split, c->st);
 }
 
 template <typename T>
@@ -806,6 +829,19 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
          dev_alloc(c, &c->colG, (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
          dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)IMG_KSPLIT * L * (d1 > g1 ? d1 : g1) * 4) &&
          dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
+  }
+  {
+    // partial blocks of the weight gradients that are split over rows (few models only)
+    size_t need = 0;
+    auto want = [&](int Cb, int Cs, int ntaps) {
+      const int ks = wgrad_ksplit(c, Cb, Cs, ntaps);
+      if (ks > 1) need = std::max(need, (size_t)ks * L * ntaps * Cb * Cs * 4);
+    };
+    for (size_t j = 1; j < c->D.conv.size(); ++j) want(c->D.conv[j].Cb, c->D.conv[j].Cs, 16);
+    for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) want(c->G.conv[i].Cb, c->G.conv[i].Cs, 16);
+    want(c->G.J, c->G.Kp, 1);
+    c->wg_part = nullptr;
+    if (need) ok = ok && dev_alloc(c, (void**)&c->wg_part, need);
   }
   {
     // the GEMM loaders address one segment of any activation tensor or patch matrix with 32-bit byte offsets

@@ -82,6 +82,8 @@ template <typename T> void launch_wgrad(const WgradArgs& a, hipStream_t st);
 // names of the kernel instantiations the two launchers pick (per-kernel timing)
 const char* conv_variant_name(int mode, int epi, const ConvArgs& a);
 const char* wgrad_variant_name(const WgradArgs& a);
+// output tiles per model of the weight-gradient launch for this layer shape
+int wgrad_tiles_per_model(int ntaps, int Cb, int Cs);
 
 // rows per M-tile the forward-type kernel will use for n_out output channels and about rows_per_model rows
 int conv_tile_rows(int n_out, long long rows_per_model_hint);

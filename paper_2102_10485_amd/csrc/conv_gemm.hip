@@ -922,6 +922,12 @@ void launch_wgrad(const WgradArgs& a, hipStream_t st) {
   if (a.Cs % 256 == 0) return launch_wgrad_one<T, TileBig>(a, st);
   return launch_wgrad_one<T, TileMid>(a, st);
 }
+int wgrad_tiles_per_model(int ntaps, int Cb, int Cs) {
+  const int M = ntaps * Cb;
+  if (M <= 64) return (M + TileWgImg::BM - 1) / TileWgImg::BM * ((Cs + TileWgImg::BN - 1) / TileWgImg::BN);
+  if (Cs % 256 == 0) return (M + TileBig::BM - 1) / TileBig::BM * (Cs / TileBig::BN);
+  return (M + TileMid::BM - 1) / TileMid::BM * ((Cs + TileMid::BN - 1) / TileMid::BN);
+}
 template void launch_wgrad<float>(const WgradArgs&, hipStream_t);
 template void launch_wgrad<bf16_t>(const WgradArgs&, hipStream_t);
 

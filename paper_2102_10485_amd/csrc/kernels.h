@@ -183,6 +183,10 @@ template <typename T> void launch_cast_shadow(const float* theta, T* shadow, lon
 template <typename T, typename S>
 void launch_transpose_w(const S* src, T* dst, long long pstride, int L, int Cb, int Cs, hipStream_t st);
 
+// dW[l * dw_stride + i] = part[(0 * L + l) * size + i] + part[(1 * L + l) * size + i] + ... (nsplit terms, in this
+// order), i < size (a multiple of 4), l < L
+void launch_sum_splits(const float* part, float* dW, long long dw_stride, long long size, int L, int nsplit, hipStream_t st);
+
 void launch_tile_prefix(const int* offs, int L, int rps, int tile_rows, int* tpre, hipStream_t st);
 // tmodel[t] = model of tile t for t < tpre[L] (cap entries available)
 void launch_tile_models(const int* tpre, int L, int* tmodel, int cap, hipStream_t st);

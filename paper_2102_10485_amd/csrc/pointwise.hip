@@ -87,6 +87,27 @@ __global__ void tile_model_kernel(const int* __restrict__ tpre_all, int L, int* 
   }
   tmodel_all[(long long)blockIdx.y * stride + t] = lo;
 }
+__global__ __launch_bounds__(256) void sum_splits_kernel(const float* __restrict__ part, float* __restrict__ dW, long long dw_stride,
+                                                          long long size4, int L, int nsplit) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= size4 * L) return;
+  const int l = (int)(idx / size4);
+  const long long i = idx - (long long)l * size4;
+  const float4* p = reinterpret_cast<const float4*>(part) + (long long)l * size4 + i;
+  float4 s = p[0];
+  for (int k = 1; k < nsplit; ++k) {
+    const float4 t = p[(long long)k * L * size4];
+    s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+  }
+  *reinterpret_cast<float4*>(dW + (long long)l * dw_stride + 4 * i) = s;
+}
+void launch_sum_splits(const float* part, float* dW, long long dw_stride, long long size, int L, int nsplit, hipStream_t st) {
+  if (size % 4 != 0 || dw_stride % 4 != 0 || ((uintptr_t)dW & 15) != 0 || ((uintptr_t)part & 15) != 0) abort();
+  const long long tot = size / 4 * L;
+  if (tot == 0) return;
+  hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, part, dW, dw_stride, size / 4, L, nsplit);
+}
+
 void launch_tile_models(const int* tpre, int L, int* tmodel, int cap, hipStream_t st) {
   if (cap <= 0) return;
   hipLaunchKernelGGL(tile_model_kernel, dim3((cap + 255) / 256, 1), dim3(256), 0, st, tpre, L, tmodel, cap);
