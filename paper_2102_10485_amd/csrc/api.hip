@@ -22,7 +22,9 @@ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m
 
 // the weight gradient of a patch-matrix layer has a tiny output and a long reduction: its rows are split over this
 // many blocks per model, and the partial blocks are added in a fixed order when they are unpacked
-constexpr int IMG_KSPLIT = 8;
+// Row splits of the image-side weight gradients (one or a few output tiles per model): 8 when there are many
+// models, more when the models alone would leave most of the chip idle.  A function of the model count only.
+static int img_ksplit_for(int L) { return std::min(std::max(800 / L, 8), 128); }
 constexpr int WG_MAX_KSPLIT = 16;
 
 // A (transposed) convolution between a "big" tensor (Cb channels, side 2*Hs) and a "small" one (Cs, side Hs).
@@ -71,6 +73,7 @@ struct gan_ctx {
   // image-side layers: patch matrices, packed weights, packed weight gradients
   void *colD = nullptr, *colG = nullptr, *wpD = nullptr, *wpG = nullptr;
   float *dwp = nullptr, *bias_partial = nullptr, *stat_partial = nullptr;
+  int img_ksplit = 8;
   float* wg_part = nullptr;        // row-split partial weight gradients (few models only)
   int KcD = 0, KcG = 0;
   int nslot = 1;
@@ -490,7 +493,7 @@ PackArgs pack_args(gan_ctx* c, Net& net, const ConvLayer& cl, int Kc, int nslot,
   a.w = net.theta + cl.w; a.bias = (nslot > 0 && cl.bias >= 0) ? net.theta + cl.bias : nullptr;
   a.dw = net.g + cl.w; a.dbias = (nslot > 0 && cl.bias >= 0) ? net.g + cl.bias : nullptr;
   a.pstride = net.P; a.wp = wp; a.dwp = c->dwp;
-  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Kc = Kc; a.nslot = nslot; a.nsplit = IMG_KSPLIT;
+  a.L = c->L; a.CB = cl.Cb; a.CBT = cl.CBT; a.Cs = cl.Cs; a.Kc = Kc; a.nslot = nslot; a.nsplit = c->img_ksplit;
   return a;
 }
 
@@ -586,7 +589,7 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
   if (param_grads) {
     // taps, label-map class sums and the bias gradient in one GEMM over the patch matrix
     wgrad_call<T>(c, "gemm_wgrad_img", c->colD, c->bufA, c->dwp, (long long)c->KcD * c1.Cs, c->KcD, c1.Cs, c1.Hs, 1, nseg, n,
-                  img_flops(c1, n, nseg), IMG_KSPLIT);
+                  img_flops(c1, n, nseg), c->img_ksplit);
     launch_unpack_dw(pack_args(c, D, c1, c->KcD, c->nslot, c->wpD), c->st);
   }
   if (to_image)   // d cost / d fake, times the tanh derivative (fake segment only)
@@ -603,7 +606,7 @@ void g_backward(gan_ctx* c, int n) {
   {
     im2col_call<T>(c, last, dlast, nullptr, c->colG, c->KcG, 0, 0, n);
     wgrad_call<T>(c, "gemm_wgrad_img", c->colG, c->gact[nl - 1], c->dwp, (long long)c->KcG * last.Cs, c->KcG, last.Cs, last.Hs, 1, 1, n,
-                  img_flops(last, n, 1), IMG_KSPLIT);
+                  img_flops(last, n, 1), c->img_ksplit);
     launch_unpack_dw(pack_args(c, G, last, c->KcG, 0, c->wpG), c->st);
     ImgBiasArgs b;
     b.img = dlast; b.partial = c->bias_partial; b.dbias = G.g + last.bias; b.pstride = G.P; b.offs = c->rb.offs;
@@ -822,12 +825,13 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   {
     const ConvLayer& c1 = c->D.conv[0];
     const ConvLayer& gl = c->G.conv.back();
+    c->img_ksplit = img_ksplit_for(L);
     c->KcD = (int)round_up(16 * c1.Cb + 9 * c->nslot + 1, 64);
     c->KcG = (int)round_up(16 * gl.Cb, 64);
     const size_t d1 = (size_t)c->KcD * c1.Cs, g1 = (size_t)c->KcG * gl.Cs;
     ok = ok && dev_alloc(c, &c->colD, (size_t)2 * NB * c1.Hs * c1.Hs * c->KcD * es) &&
          dev_alloc(c, &c->colG, (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
-         dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)IMG_KSPLIT * L * (d1 > g1 ? d1 : g1) * 4) &&
+         dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)c->img_ksplit * L * (d1 > g1 ? d1 : g1) * 4) &&
          dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
   }
   {

@@ -565,16 +565,16 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / TL::WN, wn = wave % TL::WN;
 
-  // ---- tile: all tiles of a model run on one XCD, models are dealt round-robin to XCDs
+  // ---- tile: all tiles of one (model, row split) run on one XCD -- they read the same rows -- and the
+  // (model, split) pairs are dealt round-robin to the XCDs
   const int Cb = p.Cb, Cs = p.Cs, Hs = p.Hs;
   const int Mtot = p.ntaps * Cb;
   const int MT = (Mtot + BM - 1) / BM, NT = (Cs + BN - 1) / BN;
-  const int per_model = MT * NT * p.ksplit;
   const int bid = blockIdx.x;
-  const int l = (bid / (8 * per_model)) * 8 + (bid & 7);
-  if (l >= p.L) return;
-  const int q = (bid >> 3) % per_model;
-  const int tile = q % (MT * NT), split = q / (MT * NT);
+  const int unit = (bid / (8 * MT * NT)) * 8 + (bid & 7);
+  if (unit >= p.L * p.ksplit) return;
+  const int l = unit / p.ksplit, split = unit - l * p.ksplit;
+  const int tile = (bid >> 3) % (MT * NT);
   const int mt = tile / NT, nt = tile - mt * NT;
   const int s0 = p.offs[l], s1 = p.offs[l + 1];
   const int rps = Hs * Hs;
@@ -738,16 +738,16 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / TL::WN, wn = wave % TL::WN;
 
-  // ---- tile: all tiles of a model run on one XCD, models are dealt round-robin to XCDs
+  // ---- tile: all tiles of one (model, row split) run on one XCD -- they read the same rows -- and the
+  // (model, split) pairs are dealt round-robin to the XCDs
   const int Cb = p.Cb, Cs = p.Cs, Hs = p.Hs;
   const int Mtot = p.ntaps * Cb;
   const int MT = (Mtot + BM - 1) / BM, NTL = (Cs + BN - 1) / BN;
-  const int per_model = MT * NTL * p.ksplit;
   const int bid = blockIdx.x;
-  const int l = (bid / (8 * per_model)) * 8 + (bid & 7);
-  if (l >= p.L) return;
-  const int q = (bid >> 3) % per_model;
-  const int tile = q % (MT * NTL), split = q / (MT * NTL);
+  const int unit = (bid / (8 * MT * NTL)) * 8 + (bid & 7);
+  if (unit >= p.L * p.ksplit) return;
+  const int l = unit / p.ksplit, split = unit - l * p.ksplit;
+  const int tile = (bid >> 3) % (MT * NTL);
   const int mt = tile / NTL, nt = tile - mt * NTL;
   const int s0 = p.offs[l], s1 = p.offs[l + 1];
   const int rps = Hs * Hs;
@@ -900,7 +900,7 @@ template <typename T, typename TL>
 static void launch_wgrad_one(WgradArgs a, hipStream_t st) {
   a.hs_shift = log2_or_neg(a.Hs);
   const int MT = (a.ntaps * a.Cb + TL::BM - 1) / TL::BM, NT = (a.Cs + TL::BN - 1) / TL::BN;
-  const long long blocks = (long long)((a.L + 7) / 8) * 8 * MT * NT * a.ksplit;
+  const long long blocks = ((long long)a.L * a.ksplit + 7) / 8 * 8 * MT * NT;
   if (blocks == 0) return;
   if (sizeof(T) == 2) {
     // 32-bit byte offsets inside one model's slice of either operand
