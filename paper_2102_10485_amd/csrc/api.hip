@@ -74,6 +74,8 @@ struct gan_ctx {
   void *colD = nullptr, *colG = nullptr, *wpD = nullptr, *wpG = nullptr;
   float *dwp = nullptr, *bias_partial = nullptr, *stat_partial = nullptr;
   int img_ksplit = 8;
+  float* head_part = nullptr;      // row-split partial sums of the linear head's weight gradient (few models only)
+  int head_rsplit = 1;
   float* wg_part = nullptr;        // row-split partial weight gradients (few models only)
   int KcD = 0, KcG = 0;
   int nslot = 1;
@@ -570,6 +572,7 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
   memset(&h, 0, sizeof(h));
   h.feat = c->dact[nl - 1]; h.dfeat = c->bufA; h.w = D.theta + D.fc_w; h.b = D.theta + D.fc_b;
   h.dw = D.g + D.fc_w; h.db = D.g + D.fc_b; h.pstride = D.P; h.dlogits = c->dlogits;
+  h.part = c->head_part; h.rsplit = c->head_rsplit;
   h.offs = c->rb.offs; h.sample_model = c->rb.sample_model; h.L = c->L; h.K = D.K;
   h.seg_first = seg_first; h.nseg = nseg; h.seg_samples = n; h.n = n;
   { Scope s(c, "head_bwd_data", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_data<T>(h, c->st); }
@@ -846,6 +849,9 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     want(c->G.J, c->G.Kp, 1);
     c->wg_part = nullptr;
     if (need) ok = ok && dev_alloc(c, (void**)&c->wg_part, need);
+    // the linear head's weight gradient: blocks of 1024 columns per model, rows split when that leaves the chip idle
+    c->head_rsplit = (int)std::min<long long>(std::max<long long>(512 / ((long long)L * ((c->D.K + 1023) / 1024)), 1), 64);
+    if (c->head_rsplit > 1) ok = ok && dev_alloc(c, (void**)&c->head_part, (size_t)c->head_rsplit * L * (c->D.K + 4) * 4);
   }
   {
     // the GEMM loaders address one segment of any activation tensor or patch matrix with 32-bit byte offsets

@@ -149,6 +149,10 @@ struct HeadArgs {
   int L, K, seg_first, nseg, seg_samples, n;
   int mode;                 // loss: 0 = discriminator cost on (real, fake) ; 1 = generator cost on fake
   float scale;
+  // head_bwd_w: rsplit > 1 shares every model's rows among rsplit blocks per K chunk; their partial sums go to
+  // part[rsplit][L][K + 4] (the bias term at index K) and are added in order by a second kernel
+  float* part;
+  int rsplit;
 };
 template <typename T> void launch_head_fwd(const HeadArgs& a, hipStream_t st);
 void launch_loss(const HeadArgs& a, hipStream_t st);

@@ -261,22 +261,31 @@ __device__ inline void storev(bf16_t* p, const float (&v)[8]) {
 // with the pairwise update  mean += d n_t/(n+n_t),  M2 += M2_t + d^2 n n_t/(n+n_t),  d = mean_t - mean.
 // The GEMM's N columns are `groups` runs of the C channels (the linear layer feeding G's first BatchNorm has one
 // run per pixel of the first feature map; the convolutions have one).
-__global__ void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict__ partial, const int* __restrict__ tpre,
-                                             int ub_tiles, int nphase, int groups, int tile_rows, int gemm_rps) {
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (long long)a.nseg * a.L * a.C) return;
-  const int c = (int)(idx % a.C);
-  const int l = (int)((idx / a.C) % a.L);
-  const int sidx = (int)(idx / ((long long)a.C * a.L));
+// A block = 16 channels x RED_SLICES slices of the (phase, tile) sequence of one (segment, model): every thread
+// merges its contiguous slice in order, then the slices are merged in order.  The slicing depends on the model's own
+// tile count only.
+constexpr int RED_SLICES = 16;
+__global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict__ partial,
+                                                                    const int* __restrict__ tpre, int ub_tiles, int nphase,
+                                                                    int groups, int tile_rows, int gemm_rps) {
+  __shared__ float sh[RED_SLICES][16][3];
+  const int cx = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int cblocks = (a.C + 15) / 16;
+  const int c = (blockIdx.x % cblocks) * 16 + cx;
+  const int l = (blockIdx.x / cblocks) % a.L;
+  const int sidx = blockIdx.x / (cblocks * a.L);
   const int cnt = a.offs[l + 1] - a.offs[l];
-  if (cnt == 0) return;
+  if (cnt == 0) return;                                // block-uniform
   const int rows = cnt * gemm_rps;                     // rows of this model in the GEMM's row space (per phase)
+  const int t0 = tpre[l], ntiles = tpre[l + 1] - t0;
+  const int seq = nphase * ntiles, per = (seq + RED_SLICES - 1) / RED_SLICES;
   float n = 0.f, mean = 0.f, m2 = 0.f;
-  for (int ph = 0; ph < nphase; ++ph)
-    for (int t = tpre[l]; t < tpre[l + 1]; ++t) {
-      const float nt = (float)min(tile_rows, rows - (t - tpre[l]) * tile_rows);
+  if (c < a.C)
+    for (int q = sl * per; q < min(seq, (sl + 1) * per); ++q) {
+      const int ph = q / ntiles, t = q - ph * ntiles;
+      const float nt = (float)min(tile_rows, rows - t * tile_rows);
       for (int g = 0; g < groups; ++g) {
-        const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
+        const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles + t0 + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
         const float d = partial[o] / nt - mean;
         const float nn = n + nt;
         mean += d * (nt / nn);
@@ -284,6 +293,18 @@ __global__ void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict
         n = nn;
       }
     }
+  sh[sl][cx][0] = n; sh[sl][cx][1] = mean; sh[sl][cx][2] = m2;
+  __syncthreads();
+  if (sl != 0 || c >= a.C) return;
+  for (int k = 1; k < RED_SLICES; ++k) {
+    const float nt = sh[k][cx][0];
+    if (nt == 0.f) continue;                           // an empty slice
+    const float d = sh[k][cx][1] - mean;
+    const float nn = n + nt;
+    mean += d * (nt / nn);
+    m2 += sh[k][cx][2] + d * d * (n * nt / nn);
+    n = nn;
+  }
   const float var = m2 / n;
   const long long o = (long long)((a.seg_first + sidx) * a.L + l) * a.C + c;
   a.mean[o] = mean;
@@ -292,10 +313,10 @@ __global__ void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict
 }
 void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
                                   int groups, int tile_rows, int gemm_rps, hipStream_t st) {
-  const long long tot = (long long)a.nseg * a.L * a.C;
+  const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
   if (tot == 0) return;
-  hipLaunchKernelGGL(bn_stats_from_partial_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a, partial, tpre,
-                     ub_tiles, nphase, groups, tile_rows, gemm_rps);
+  hipLaunchKernelGGL(bn_stats_from_partial_kernel, dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
+                     groups, tile_rows, gemm_rps);
 }
 
 // running <- (1 - momentum) running + momentum * batch, once per segment in order; unbiased variance stored.
@@ -453,20 +474,28 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const in
     partial[(((long long)sidx * ub_tiles + tile) * a.C + c) * 2 + w] = acc;
   }
 }
-__global__ void bn_bwd_reduce_final_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
-                                           const float* __restrict__ partial) {
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (long long)a.nseg * a.L * a.C) return;
-  const int c = (int)(idx % a.C);
-  const int l = (int)((idx / a.C) % a.L);
-  const int sidx = (int)(idx / ((long long)a.C * a.L));
-  if (a.offs[l + 1] == a.offs[l]) return;
+__global__ __launch_bounds__(256) void bn_bwd_reduce_final_kernel(NormArgs a, const int* __restrict__ tpre, int ub_tiles,
+                                                                  const float* __restrict__ partial) {
+  __shared__ float sh[RED_SLICES][16][2];
+  const int cx = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int cblocks = (a.C + 15) / 16;
+  const int c = (blockIdx.x % cblocks) * 16 + cx;
+  const int l = (blockIdx.x / cblocks) % a.L;
+  const int sidx = blockIdx.x / (cblocks * a.L);
+  if (a.offs[l + 1] == a.offs[l]) return;              // block-uniform
+  const int t0 = tpre[l], ntiles = tpre[l + 1] - t0;
+  const int per = (ntiles + RED_SLICES - 1) / RED_SLICES;
   float s0 = 0.f, s1 = 0.f;
-  for (int t = tpre[l]; t < tpre[l + 1]; ++t) {
-    const long long o = (((long long)sidx * ub_tiles + t) * a.C + c) * 2;
-    s0 += partial[o];
-    s1 += partial[o + 1];
-  }
+  if (c < a.C)
+    for (int t = t0 + sl * per; t < t0 + min(ntiles, (sl + 1) * per); ++t) {
+      const long long o = (((long long)sidx * ub_tiles + t) * a.C + c) * 2;
+      s0 += partial[o];
+      s1 += partial[o + 1];
+    }
+  sh[sl][cx][0] = s0; sh[sl][cx][1] = s1;
+  __syncthreads();
+  if (sl != 0 || c >= a.C) return;
+  for (int k = 1; k < RED_SLICES; ++k) { s0 += sh[k][cx][0]; s1 += sh[k][cx][1]; }
   const long long o = ((long long)((a.seg_first + sidx) * a.L + l) * a.C + c) * 2;
   a.sums[o] = s0;
   a.sums[o + 1] = s1;
@@ -478,9 +507,8 @@ void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, const int* tmodel,
   if (cg < 1 || cg > 256) abort();                  // one thread per 16 bytes of a row
   const size_t lds = (size_t)2 * (256 / cg) * a.C * sizeof(float);
   hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(ub_tiles, a.nseg), dim3(256), lds, st, a, tpre, tmodel, ub_tiles, partial);
-  const long long tot = (long long)a.nseg * a.L * a.C;
-  hipLaunchKernelGGL(bn_bwd_reduce_final_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a, tpre, ub_tiles,
-                     partial);
+  const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
+  hipLaunchKernelGGL(bn_bwd_reduce_final_kernel, dim3((unsigned)tot), dim3(256), 0, st, a, tpre, ub_tiles, partial);
 }
 template void launch_bn_bwd_reduce<float>(const NormArgs&, const int*, const int*, int, float*, hipStream_t);
 template void launch_bn_bwd_reduce<bf16_t>(const NormArgs&, const int*, const int*, int, float*, hipStream_t);
@@ -667,10 +695,13 @@ __global__ __launch_bounds__(256) void head_bwd_w_kernel(HeadArgs a) {
   const int s0 = a.offs[l], cnt = a.offs[l + 1] - s0;
   if (cnt == 0) return;
   const int k = blockIdx.x * 1024 + threadIdx.x * 4;
+  const int rsplit = a.rsplit > 1 ? a.rsplit : 1, sp = blockIdx.z;
+  const int per = (cnt + rsplit - 1) / rsplit;
+  const int i0 = sp * per, i1 = min(cnt, i0 + per);
   float acc[4] = {0, 0, 0, 0}, accb = 0.f;
   for (int s = 0; s < a.nseg; ++s) {
     const long long r0 = (long long)(a.seg_first + s) * a.seg_samples + s0;
-    for (int i = 0; i < cnt; ++i) {
+    for (int i = i0; i < i1; ++i) {
       const float d = a.dlogits[r0 + i];
       accb += d;
       if (k < a.K) {
@@ -681,11 +712,34 @@ __global__ __launch_bounds__(256) void head_bwd_w_kernel(HeadArgs a) {
       }
     }
   }
+  if (rsplit > 1) {
+    float* part = a.part + ((long long)sp * a.L + l) * (a.K + 4);
+    if (k < a.K) *reinterpret_cast<float4*>(part + k) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) part[a.K] = accb;
+    return;
+  }
   if (k < a.K) *reinterpret_cast<float4*>(a.dw + (long long)l * a.pstride + k) = make_float4(acc[0], acc[1], acc[2], acc[3]);
   if (blockIdx.x == 0 && threadIdx.x == 0) a.db[(long long)l * a.pstride] = accb;
 }
+// the row splits' partial sums, added in order (index K: the bias term)
+__global__ void head_bwd_w_final_kernel(HeadArgs a) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)a.L * (a.K + 1)) return;
+  const int l = (int)(idx / (a.K + 1)), k = (int)(idx - (long long)l * (a.K + 1));
+  if (a.offs[l + 1] == a.offs[l]) return;
+  float s = 0.f;
+  for (int sp = 0; sp < a.rsplit; ++sp) s += a.part[((long long)sp * a.L + l) * (a.K + 4) + k];
+  if (k < a.K) a.dw[(long long)l * a.pstride + k] = s;
+  else a.db[(long long)l * a.pstride] = s;
+}
 template <typename T> void launch_head_bwd_w(const HeadArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((head_bwd_w_kernel<T>), dim3((a.K + 1023) / 1024, a.L), dim3(256), 0, st, a);
+  if (a.K % 4 != 0 || (a.rsplit > 1 && !a.part)) abort();
+  const int rsplit = a.rsplit > 1 ? a.rsplit : 1;
+  hipLaunchKernelGGL((head_bwd_w_kernel<T>), dim3((a.K + 1023) / 1024, a.L, rsplit), dim3(256), 0, st, a);
+  if (rsplit > 1) {
+    const long long tot = (long long)a.L * (a.K + 1);
+    hipLaunchKernelGGL(head_bwd_w_final_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+  }
 }
 template void launch_head_bwd_w<float>(const HeadArgs&, hipStream_t);
 template void launch_head_bwd_w<bf16_t>(const HeadArgs&, hipStream_t);
