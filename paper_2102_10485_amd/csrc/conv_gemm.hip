@@ -25,6 +25,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include <type_traits>
 
 namespace gan {
 
@@ -96,24 +97,64 @@ __device__ inline void tile_mma(floatx16 (&acc)[TM][TN], const unsigned char* As
 // sixteen different 16-byte slots of the 256-byte bank period, and so do the rows one wave-wide copy fills.
 template <int KB>
 __device__ inline int fwd_swz(int row) { return (row / (256 / KB)) % (KB / 16); }
+// The operand reads of the forward-type kernel are issued by hand so that the reads of K-step vs+1 are in flight
+// while the MFMAs of K-step vs run (two register sets).  The compiler does not count these reads, so the waits are
+// explicit; each wait names the registers it makes valid, which orders the MFMAs behind it.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+template <int OFF>
+__device__ inline void lds_read16(u32x4& d, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int N, int TM, int TN>
+__device__ inline void lds_wait(u32x4 (&a)[TM], u32x4 (&b)[TN]) {
+  static_assert(TM <= 4 && TN <= 4, "operand list below");
+  // at most N reads still in flight; all of a[] and b[] were issued before those
+  if constexpr (TM == 4 && TN == 2)
+    asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]) : "n"(N) : "memory");
+  else if constexpr (TM == 2 && TN == 2)
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]) : "n"(N) : "memory");
+  else
+    static_assert(TM == 4 && TN == 2, "add the operand list for this wave tile");
+}
+template <int I, int N, typename F>
+__device__ inline void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 template <typename T, int TM, int TN, int KB>
 __device__ inline void tile_mma_fwd(floatx16 (&acc)[TM][TN], const unsigned char* As, const unsigned char* Bs, int wm, int wn,
                                     int lane) {
   const int r = lane & 31, h = lane >> 5;
   const int sw = fwd_swz<KB>(r);   // tile rows start at multiples of 32, a multiple of the swizzle period
-#pragma unroll
-  for (int vs = 0; vs < KB / 32; ++vs) {
-    uint4 a[TM], b[TN];
-    const int pos = ((vs * 2 + h) ^ sw) * 16;
-#pragma unroll
-    for (int t = 0; t < TM; ++t) a[t] = *reinterpret_cast<const uint4*>(As + (wm * TM * 32 + t * 32 + r) * KB + pos);
-#pragma unroll
-    for (int t = 0; t < TN; ++t) b[t] = *reinterpret_cast<const uint4*>(Bs + (wn * TN * 32 + t * 32 + r) * KB + pos);
+  constexpr int NV = KB / 32;
+  // LDS byte address of this lane's 16 bytes of K-step 0 in its first A / B row; K-step vs sits at the same
+  // address with bit 5 .. flipped by vs (chunk index (2 vs + h) ^ sw = (2 vs) ^ (h ^ sw): no carries)
+  const unsigned a0 = (unsigned)(uintptr_t)As + (wm * TM * 32 + r) * KB + ((h ^ sw) << 4);
+  const unsigned b0 = (unsigned)(uintptr_t)Bs + (wn * TN * 32 + r) * KB + ((h ^ sw) << 4);
+  u32x4 a[2][TM], b[2][TN];
+  auto fetch = [&](auto vs, auto set) {
+    const unsigned aa = a0 ^ (vs.value << 5), bb = b0 ^ (vs.value << 5);
+    static_for<0, TM>([&](auto t) { lds_read16<t.value * 32 * KB>(a[set.value][t.value], aa); });
+    static_for<0, TN>([&](auto t) { lds_read16<t.value * 32 * KB>(b[set.value][t.value], bb); });
+  };
+  fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+  static_for<0, NV>([&](auto vs) {
+    constexpr int cur = vs.value & 1;
+    if constexpr (vs.value + 1 < NV) {
+      fetch(std::integral_constant<int, vs.value + 1>{}, std::integral_constant<int, cur ^ 1>{});
+      lds_wait<TM + TN>(a[cur], b[cur]);
+    } else {
+      lds_wait<0>(a[cur], b[cur]);
+    }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) mma16B(acc[tm][tn], a[tm], b[tn], T());
-  }
+      for (int tn = 0; tn < TN; ++tn)
+        mma16B(acc[tm][tn], __builtin_bit_cast(uint4, a[cur][tm]), __builtin_bit_cast(uint4, b[cur][tn]), T());
+    __builtin_amdgcn_sched_barrier(0);       // keep these MFMAs in front of the next K-step's wait
+  });
 }
 
 // 16 bytes per lane from a buffer straight into LDS: the wave's 64 lanes fill the 1 KiB starting at lds_base
