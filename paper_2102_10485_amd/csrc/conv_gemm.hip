@@ -810,34 +810,77 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   const long long big_per_sample = p.ntaps == 1 ? (long long)rps * Cb : (long long)Hb * Hb * Cb;
 
+  // Chunks start at multiples of 64 rows.  With a power-of-two side of at most 64 a chunk is a whole number of
+  // samples or of pixel rows, so a thread's rows keep their x, their y offset inside the chunk and their sample
+  // offset: everything that depends on the row is computed once, and a chunk only adds a wave-uniform offset
+  // (sample n0, pixel row y0 of the chunk's first row) and re-tests the vertical border.
+  const bool fast = p.ntaps == 1 || (p.hs_shift >= 0 && Hs <= 64);
+  unsigned fa_off[PA], fb_off[PB];
+  int fa_iy[PA];                   // 2 * (y inside the chunk) - 1 + ky ; a large value marks a lane that never loads
+#pragma unroll
+  for (int i = 0; i < PA; ++i) {
+    const int c = rowA0 + i * RPA;
+    fa_off[i] = 0;
+    fa_iy[i] = 1 << 20;
+    if (okA) {
+      if (p.ntaps == 1) {
+        fa_off[i] = (unsigned)((c * Cb + cA) * 2);
+        fa_iy[i] = 0;
+      } else if (fast) {
+        const int sh = p.hs_shift;
+        const int ni = c >> (2 * sh), rem = c & (rps - 1);
+        const int yi = rem >> sh, xi = rem & (Hs - 1);
+        const int ix = 2 * xi - 1 + kxA;
+        if ((unsigned)ix < (unsigned)Hb) {
+          fa_iy[i] = 2 * yi - 1 + kyA;
+          fa_off[i] = (unsigned)((((ni * Hb + fa_iy[i]) * Hb + ix) * Cb + cA) * 2);    // may wrap below zero: masked
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < PB; ++i) fb_off[i] = (unsigned)(((rowB0 + i * RPB) * Cs + cB) * 2);
+
   auto load_chunk = [&](int seg, int k0, int stage) {
     const long long sb = (long long)seg * p.seg_samples + s0;
     const int4v a_rsrc = make_rsrc(static_cast<const T*>(p.Big) + sb * big_per_sample, (unsigned long long)(s1 - s0) * big_per_sample * 2);
     const int4v b_rsrc = make_rsrc(static_cast<const T*>(p.Small) + sb * rps * Cs, (unsigned long long)R * Cs * 2);
     const unsigned a_dst = lds0 + stage * STAGE_A + wave * 1024;
     const unsigned b_dst = lds0 + 2 * STAGE_A + stage * STAGE_B + wave * 1024;
+    const int left = r_hi - k0;                 // rows of this chunk that exist
+    if (fast) {
+      unsigned a_delta;
+      int y2 = 0;
+      if (p.ntaps == 1) {
+        a_delta = (unsigned)(k0 * Cb * 2);
+      } else {
+        const int n0 = k0 >> (2 * p.hs_shift), y0 = (k0 & (rps - 1)) >> p.hs_shift;
+        a_delta = (unsigned)(((n0 * Hb + 2 * y0) * Hb) * Cb * 2);
+        y2 = 2 * y0;
+      }
 #pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      const int r = k0 + rowA0 + i * RPA;
-      unsigned off = NO_ROW;
-      if (r < r_hi && okA) {
-        if (p.ntaps == 1) {
-          off = (unsigned)((r * Cb + cA) * 2);
-        } else {
+      for (int i = 0; i < PA; ++i) {
+        const bool ok = rowA0 + i * RPA < left && (unsigned)(fa_iy[i] + y2) < (unsigned)Hb;
+        load16_to_lds(a_rsrc, ok ? fa_off[i] + a_delta : NO_ROW, a_dst + i * NT_ * 16);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PA; ++i) {
+        const int r = k0 + rowA0 + i * RPA;
+        unsigned off = NO_ROW;
+        if (r < r_hi && okA) {
           int n, y, x;
           decode_row(r, Hs, rps, p.hs_shift, n, y, x);
           const int iy = 2 * y - 1 + kyA, ix = 2 * x - 1 + kxA;
           if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb) off = (unsigned)((((n * Hb + iy) * Hb + ix) * Cb + cA) * 2);
         }
+        load16_to_lds(a_rsrc, off, a_dst + i * NT_ * 16);
       }
-      load16_to_lds(a_rsrc, off, a_dst + i * NT_ * 16);
     }
+    const unsigned b_delta = (unsigned)(k0 * Cs * 2);
 #pragma unroll
-    for (int i = 0; i < PB; ++i) {
-      const int r = k0 + rowB0 + i * RPB;
-      const unsigned off = (r < r_hi && okB) ? (unsigned)((r * Cs + cB) * 2) : NO_ROW;
-      load16_to_lds(b_rsrc, off, b_dst + i * NT_ * 16);
-    }
+    for (int i = 0; i < PB; ++i)
+      load16_to_lds(b_rsrc, (rowB0 + i * RPB < left && okB) ? fb_off[i] + b_delta : NO_ROW, b_dst + i * NT_ * 16);
   };
 
   floatx16 acc[TM][TN];
