@@ -386,7 +386,7 @@ template <typename T>
 void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small, float* dW, long long stride, int Cb, int Cs,
                 int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0, int ksplit = 0) {
   WgradArgs a = {};
-  a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.dw_stride = stride;
+  a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.order = c->rb.order; a.dw_stride = stride;
   a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps; a.ksplit = ksplit;
   a.split_stride = (long long)c->L * stride;
   const long long layer = (long long)ntaps * Cb * Cs;
@@ -752,7 +752,8 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&
        dev_alloc(c, (void**)&rb.offs, (size_t)(L + 1) * 4) && dev_alloc(c, (void**)&rb.perm, (size_t)NB * 4) &&
        dev_alloc(c, (void**)&rb.sample_model, (size_t)NB * 4) && dev_alloc(c, (void**)&rb.sample_slot, (size_t)NB * 4) &&
-       dev_alloc(c, (void**)&rb.tpre, (size_t)MAX_GEOMS * (L + 1) * 4) && dev_alloc(c, (void**)&rb.flags, 16);
+       dev_alloc(c, (void**)&rb.tpre, (size_t)MAX_GEOMS * (L + 1) * 4) && dev_alloc(c, (void**)&rb.flags, 16) &&
+       dev_alloc(c, (void**)&rb.order, (size_t)L * 4);
   {
     int mx = 1;
     for (int g = 0; g < c->geoms.n; ++g) mx = std::max(mx, ub_tiles(c, NB, c->geoms.rps[g], c->geoms.tile_rows[g]));

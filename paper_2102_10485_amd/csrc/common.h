@@ -68,6 +68,8 @@ struct WgradArgs {
   const void* Small;     // tensor indexed directly by row, side Hs, channels Cs
   float* dW;             // fp32 output of model 0: [ntaps][Cb][Cs]
   const int* offs;       // [L+1]
+  const int* order;      // [L] models by decreasing row count, or NULL: which model a group of blocks takes (the
+                         //     big models start first and the XCDs get equal shares; no effect on the results)
   long long dw_stride;   // elements between two models' blocks
   int L, nseg, seg_samples;
   int Cb, Cs, Hs;

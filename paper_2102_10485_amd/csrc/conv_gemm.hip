@@ -591,6 +591,16 @@ __device__ inline void transpose8x8_b16(uint4 (&r)[8]) {
   for (int i = 0; i < 8; ++i) r[i] = make_uint4(out[i][0], out[i][1], out[i][2], out[i][3]);
 }
 
+// Which model the i-th group of blocks works on.  Groups are dealt round-robin to the 8 XCDs in rows of eight; with
+// the models sorted by decreasing size the rows alternate direction, so that every XCD gets the same share of the
+// rows and starts with its largest models.
+__device__ inline int wgrad_model(const WgradArgs& p, int i) {
+  if (!p.order) return i;
+  const int row = i >> 3;
+  if ((row & 1) && row * 8 + 8 <= p.L) i = row * 8 + 7 - (i & 7);
+  return p.order[i];
+}
+
 // A loader task = 8 rows of the reduction index x one 16-byte channel group of one operand.
 //   bf16: 8 consecutive rows x 8 channels, transposed in registers, written as 8 x 16 bytes
 //   fp32: 8 rows strided by 4 x 4 channels, written as 32 scalars
@@ -614,7 +624,7 @@ __global__ __launch_bounds__(TL::NT) void wgrad_kernel(WgradArgs p) {
   const int bid = blockIdx.x;
   const int unit = (bid / (8 * MT * NT)) * 8 + (bid & 7);
   if (unit >= p.L * p.ksplit) return;
-  const int l = unit / p.ksplit, split = unit - l * p.ksplit;
+  const int l = wgrad_model(p, unit / p.ksplit), split = unit % p.ksplit;
   const int tile = (bid >> 3) % (MT * NT);
   const int mt = tile / NT, nt = tile - mt * NT;
   const int s0 = p.offs[l], s1 = p.offs[l + 1];
@@ -787,7 +797,7 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
   const int bid = blockIdx.x;
   const int unit = (bid / (8 * MT * NTL)) * 8 + (bid & 7);
   if (unit >= p.L * p.ksplit) return;
-  const int l = unit / p.ksplit, split = unit - l * p.ksplit;
+  const int l = wgrad_model(p, unit / p.ksplit), split = unit % p.ksplit;
   const int tile = (bid >> 3) % (MT * NTL);
   const int mt = tile / NTL, nt = tile - mt * NTL;
   const int s0 = p.offs[l], s1 = p.offs[l + 1];

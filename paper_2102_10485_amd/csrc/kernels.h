@@ -27,6 +27,8 @@ struct RouteBuffers {
   int* tmodel;        // [MAX_GEOMS][tmodel_stride]: model of every tile of every geometry (built with tpre)
   int tmodel_stride;
   int* flags;         // [0]: out-of-range label seen
+  int* order;         // [L] models by decreasing sample count (ties by index), for kernels whose work per model
+                      //     follows the count (may be NULL)
 };
 
 void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTable& geoms, const RouteBuffers& rb,

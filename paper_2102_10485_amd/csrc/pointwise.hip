@@ -113,6 +113,19 @@ void launch_tile_models(const int* tpre, int L, int* tmodel, int cap, hipStream_
   hipLaunchKernelGGL(tile_model_kernel, dim3((cap + 255) / 256, 1), dim3(256), 0, st, tpre, L, tmodel, cap);
 }
 
+// order[rank of l] = l, rank = number of models with more samples, or as many and a smaller index
+__global__ void model_order_kernel(const int* __restrict__ counts, int L, int* __restrict__ order) {
+  const int l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= L) return;
+  const int c = counts[l];
+  int rank = 0;
+  for (int j = 0; j < L; ++j) {
+    const int cj = counts[j];
+    rank += (cj > c || (cj == c && j < l)) ? 1 : 0;
+  }
+  order[rank] = l;
+}
+
 void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTable& geoms, const RouteBuffers& rb,
                   hipStream_t st) {
   hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.flags);
@@ -120,6 +133,7 @@ void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTa
   hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(64), 0, st, rb.counts, rb.offs, rb.tpre, L, geoms);
   hipLaunchKernelGGL(route_scatter_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.offs,
                      rb.perm, rb.sample_model, rb.sample_slot);
+  if (rb.order) hipLaunchKernelGGL(model_order_kernel, dim3((L + 255) / 256), dim3(256), 0, st, rb.counts, L, rb.order);
   if (rb.tmodel && geoms.n > 0)
     hipLaunchKernelGGL(tile_model_kernel, dim3((rb.tmodel_stride + 255) / 256, geoms.n), dim3(256), 0, st, rb.tpre, L, rb.tmodel,
                        rb.tmodel_stride);
