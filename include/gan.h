@@ -99,7 +99,11 @@ gan_status gan_destroy(gan_ctx* ctx);
 
 /* One training iteration for every model that receives at least one sample (Section 2: Eq. 3, Eq. 4, Adam).
    label_ids: DEVICE int32 [n]; noise: DEVICE fp32 [n, z_dim]; real_batch: DEVICE fp32 [n, img_c, img_hw, img_hw].
-   A model with no sample in this call is left untouched (parameters, moments, step count, statistics). */
+   A model with no sample in this call is left untouched (parameters, moments, step count, statistics).
+   Reproducibility: every sum runs in an order fixed by the configuration (model count, layer shapes,
+   max_total_batch) and by the model's own samples, so a model's result is bit-identical from run to run, does not
+   depend on the other models' samples in the call, and does not depend on the order of the flat batch beyond the
+   relative order of that model's own samples. */
 gan_status gan_train_step(gan_ctx* ctx, const int32_t* label_ids, const float* noise,
                           const float* real_batch, int32_t n);
 
