@@ -316,20 +316,41 @@ __global__ __launch_bounds__(256) void up_img_kernel(UpImgArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int cpr = Cs * (int)sizeof(T) / 16;               // 16-byte chunks per row
   const T* feat = static_cast<const T*>(a.feat) + sample * (long long)Hs * Hs * Cs;
-  for (int i = tid; i < UP_HALO * UP_HALO * cpr; i += 256) {
+  // all of the block's global loads are issued before the first of them is stored to LDS
+  constexpr int NF = (UP_HALO * UP_HALO * cpr + 255) / 256;
+  uint4 fv[NF];
+#pragma unroll
+  for (int k = 0; k < NF; ++k) {
+    const int i = tid + 256 * k;
     const int hr = i / cpr, ch = i - hr * cpr;
     const int y = y0 - 1 + hr / UP_HALO, x = x0 - 1 + hr % UP_HALO;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if ((unsigned)y < (unsigned)Hs && (unsigned)x < (unsigned)Hs)
-      v = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(feat + ((long long)y * Hs + x) * Cs) + ch * 16);
-    *reinterpret_cast<uint4*>(Fl + hr * rowB + ch * 16) = v;
+    fv[k] = make_uint4(0, 0, 0, 0);
+    if (i < UP_HALO * UP_HALO * cpr && (unsigned)y < (unsigned)Hs && (unsigned)x < (unsigned)Hs)
+      fv[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(feat + ((long long)y * Hs + x) * Cs) + ch * 16);
   }
   const T* w = static_cast<const T*>(a.w) + (long long)l * a.w_stride;
-  for (int i = tid; i < 16 * CB * cpr; i += 256) {
-    const int wr = i / cpr, ch = i - wr * cpr;                // wr = tap * CB + cb
+  constexpr int NW = (16 * 4 * cpr + 255) / 256;                // CB <= 4
+  uint4 wv[NW];
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    const int i = tid + 256 * k;
+    const int wr = i / cpr, ch = i - wr * cpr;                  // wr = tap * CB + cb
     const int tap = wr / CB, cb = wr - tap * CB;
-    *reinterpret_cast<uint4*>(Wl + wr * rowB + ch * 16) =
-        *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(w + ((long long)tap * a.CBT + cb) * Cs) + ch * 16);
+    wv[k] = make_uint4(0, 0, 0, 0);
+    if (i < 16 * CB * cpr)
+      wv[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(w + ((long long)tap * a.CBT + cb) * Cs) + ch * 16);
+  }
+#pragma unroll
+  for (int k = 0; k < NF; ++k) {
+    const int i = tid + 256 * k;
+    const int hr = i / cpr, ch = i - hr * cpr;
+    if (i < UP_HALO * UP_HALO * cpr) *reinterpret_cast<uint4*>(Fl + hr * rowB + ch * 16) = fv[k];
+  }
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    const int i = tid + 256 * k;
+    const int wr = i / cpr, ch = i - wr * cpr;
+    if (i < 16 * CB * cpr) *reinterpret_cast<uint4*>(Wl + wr * rowB + ch * 16) = wv[k];
   }
   __syncthreads();
 
