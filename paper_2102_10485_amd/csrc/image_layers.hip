@@ -91,12 +91,30 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
   const int npix = Hb * Hb;
   if (a.img) {
     const T* img = static_cast<const T*>(a.img) + ((long long)a.seg * a.seg_samples + j) * npix * CB;
-    for (int t = threadIdx.x; t < npix * CB; t += 256) tile[t] = img[t];
+    const int bytes = npix * CB * (int)sizeof(T);
+    if (bytes % 16 == 0) {                           // every sample then starts on a 16-byte boundary
+      const uint4* src = reinterpret_cast<const uint4*>(img);
+      uint4* dst = reinterpret_cast<uint4*>(tile);
+      for (int t = threadIdx.x; t < bytes / 16; t += 256) dst[t] = src[t];
+    } else {
+      for (int t = threadIdx.x; t < npix * CB; t += 256) tile[t] = img[t];
+    }
   } else {
-    const float* real = a.real + (long long)a.perm[j] * CB * npix;     // NCHW fp32
-    for (int t = threadIdx.x; t < npix * CB; t += 256) {
-      const int cb = t / npix, p = t - cb * npix;
-      tile[p * CB + cb] = from_float<T>(real[t]);
+    const float* real = a.real + (long long)a.perm[j] * CB * npix;     // NCHW fp32; npix is a multiple of 4
+    const int nq = npix >> 2;
+    if ((reinterpret_cast<uintptr_t>(a.real) & 15) != 0) {             // caller's buffer not 16-byte aligned: scalar loads
+      for (int t = threadIdx.x; t < npix * CB; t += 256) {
+        const int cb = t / npix, p = t - cb * npix;
+        tile[p * CB + cb] = from_float<T>(real[t]);
+      }
+    } else
+    for (int t = threadIdx.x; t < CB * nq; t += 256) {
+      const int cb = t / nq, p = 4 * (t - cb * nq);
+      const float4 v = reinterpret_cast<const float4*>(real)[t];
+      tile[p * CB + cb] = from_float<T>(v.x);
+      tile[(p + 1) * CB + cb] = from_float<T>(v.y);
+      tile[(p + 2) * CB + cb] = from_float<T>(v.z);
+      tile[(p + 3) * CB + cb] = from_float<T>(v.w);
     }
   }
   __syncthreads();
