@@ -26,6 +26,8 @@ SPECS = {
     # small nets for unit tests (channel counts that still span MFMA tiles)
     "tiny": dict(cond_g=4, cond_d=4, z_dim=12, img_c=1, img_hw=8, g_h0=2, g_ch=[64, 64], d_ch=[64, 128]),
     "tiny3": dict(cond_g=0, cond_d=3, z_dim=20, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 64], d_ch=[64, 128, 64]),
+    # one conditional pair over twenty labels (the paper's single-pair DC-CGAN at test size)
+    "tiny20": dict(cond_g=20, cond_d=20, z_dim=12, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 64], d_ch=[64, 128, 64]),
     "tiny0": dict(cond_g=0, cond_d=0, z_dim=20, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 128], d_ch=[128, 64, 64]),
     "micro": dict(cond_g=2, cond_d=2, z_dim=3, img_c=1, img_hw=4, g_h0=1, g_ch=[3, 2], d_ch=[2, 3]),
 }

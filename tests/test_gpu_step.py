@@ -165,6 +165,19 @@ def test_three_steps(prec, spec_name, K, nlab):
     p.close()
 
 
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+def test_single_conditional_pair_over_twenty_labels(prec):
+    """The paper's DC-CGAN comparison system (Tables 3 and 4) at test size: one pair, the label of every sample as a
+    one-hot on G's input and as label maps on D's input; the weight gradients of a single model are split over rows."""
+    p = Pair("tiny20", 1, 20, 96, prec, drift=True)
+    rng = np.random.default_rng(8)
+    for s, n in enumerate([96, 50]):
+        lab = rng.integers(0, 20, n)
+        p.step(*batch(p.spec, lab, 500 + s))
+        p.compare("step %d" % s)
+    p.close()
+
+
 def test_empty_model_bad_label_and_empty_batch():
     torch = U.torch_mod()
     p = Pair("tiny", 4, 4, 32, binding.FP32)
