@@ -49,6 +49,7 @@ struct Tile {
 typedef Tile<256, 256, 2, 4, 128, 2> TileBig;    // 512 threads, wave tile 128 x 64, 128 KiB of LDS
 typedef Tile<256, 128, 4, 2, 64, 3> TileMid;     // 512 threads, wave tile 64 x 64, 72 KiB of LDS
 typedef Tile<128, 128, 2, 2, 64, 3> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model), 48 KiB of LDS
+typedef Tile<256, 64, 4, 1, 64, 3> TileNarrow;   // 256 threads, wave tile 64 x 64, for layers with 64 output channels, 60 KiB
 
 int conv_tile_rows(int n_out, long long rows_per_model_hint) {
   if (rows_per_model_hint > 0 && rows_per_model_hint <= 128) return TileSmall::BM;
@@ -526,6 +527,7 @@ static void launch_one(ConvArgs a, hipStream_t st) {
 template <typename T, int MODE, int EPI>
 static void launch_wide(const ConvArgs& a, hipStream_t st) {
   if (a.tile_rows == TileSmall::BM) return launch_one<T, MODE, EPI, TileSmall>(a, st);
+  if (a.N <= TileNarrow::BN) return launch_one<T, MODE, EPI, TileNarrow>(a, st);
   if (a.N % 256 == 0) return launch_one<T, MODE, EPI, TileBig>(a, st);
   return launch_one<T, MODE, EPI, TileMid>(a, st);
 }
@@ -556,9 +558,9 @@ void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
 const char* conv_variant_name(int mode, int epi, const ConvArgs& a) {
   static const char* modes[3] = {"down", "up", "dense"};
   static const char* epis[3] = {"", "+actbwd", "+lrelu"};
-  static char names[3][3][3][48];
-  const int tile = a.tile_rows == TileSmall::BM ? 2 : (a.N % 256 == 0 ? 0 : 1);
-  static const char* tiles[3] = {"256x256", "256x128", "128x128"};
+  static char names[3][3][4][48];
+  const int tile = a.tile_rows == TileSmall::BM ? 2 : (a.N <= TileNarrow::BN ? 3 : (a.N % 256 == 0 ? 0 : 1));
+  static const char* tiles[4] = {"256x256", "256x128", "128x128", "256x64"};
   char* n = names[mode][epi][tile];
   if (!n[0]) snprintf(n, 48, "gemm_%s%s<%s>", modes[mode], epis[epi], tiles[tile]);
   return n;
