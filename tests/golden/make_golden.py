@@ -25,7 +25,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 # config -> (models checked, steps, param snapshots after these steps)
 PLAN = {
     0: dict(models=[0], steps=5, snaps=[1, 5], single=True),
-    1: dict(models=[0, 9], steps=20, snaps=[1, 5, 20], single=True),
+    1: dict(models=[0, 9], steps=50, snaps=[1, 5, 50], single=True),
     2: dict(models=[0, 49, 99], steps=3, snaps=[3], single=True),
     3: dict(models=[0, 7], steps=3, snaps=[3], single=True),
     4: dict(models="zipf", steps=3, snaps=[3], single=True),
