@@ -151,7 +151,7 @@ struct Scope {
     if (c->prof_detail && detail) name = c->prof_names.insert(std::string(name) + detail).first->c_str();
     ProfEntry e; e.name = name; e.flops = flops; e.bytes = bytes;
     for (hipEvent_t* ev : {&e.e0, &e.e1}) {          // events are reused across profiling sessions
-      if (c->event_pool.empty()) hipEventCreate(ev);
+      if (c->event_pool.empty()) hipEventCreateWithFlags(ev, hipEventDisableSystemFence);   // device-side timing only: no system-scope fence
       else { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
     }
     hipEventRecord(e.e0, c->st);
