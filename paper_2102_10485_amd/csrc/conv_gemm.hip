@@ -49,7 +49,8 @@ struct Tile {
 typedef Tile<256, 256, 2, 4, 128, 2> TileBig;    // 512 threads, wave tile 128 x 64, 128 KiB of LDS
 typedef Tile<256, 128, 4, 2, 64, 3> TileMid;     // 512 threads, wave tile 64 x 64, 72 KiB of LDS
 typedef Tile<128, 128, 2, 2, 64, 3> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model), 48 KiB of LDS
-typedef Tile<256, 64, 4, 1, 64, 3> TileNarrow;   // 256 threads, wave tile 64 x 64, for layers with 64 output channels, 60 KiB
+typedef Tile<256, 64, 4, 1, 128, 2> TileNarrow;  // 256 threads, wave tile 64 x 64, for layers with 64 output channels:
+                                                 // 128-byte chunks, two buffers of 40 KiB, so two blocks still share a CU
 
 int conv_tile_rows(int n_out, long long rows_per_model_hint) {
   if (rows_per_model_hint > 0 && rows_per_model_hint <= 128) return TileSmall::BM;
