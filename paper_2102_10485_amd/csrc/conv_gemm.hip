@@ -15,8 +15,9 @@
 // v_mfma_f32_32x32x2_f32 (fp32 storage) from 16-byte LDS reads; accumulation is fp32 in both cases.
 // Forward-type kernel: K-chunks of KB bytes per row travel global -> LDS directly (buffer_load_dwordx4 ... lds, no
 // registers in between) into a ring of NST buffers while the MFMAs of the current chunk run.  The 256 x 256 tile uses
-// KB = 128 with two buffers (one block per CU); the narrower tiles use KB = 64 with three, which leaves room for two
-// blocks per CU so that one block's epilogue and barriers hide behind the other's MFMAs.  The 16-byte chunk c of row
+// KB = 128 with two buffers (one block per CU); the 256 x 128 and 128 x 128 tiles use KB = 64 with three, which leaves
+// room for two blocks per CU so that one block's epilogue and barriers hide behind the other's MFMAs; the 256 x 64
+// tile fits two blocks per CU with KB = 128 and two buffers.  The 16-byte chunk c of row
 // R sits at position c ^ ((R / (256/KB)) % (KB/16)), which keeps both the 1 KiB-per-wave copies and the MFMA operand
 // reads conflict-free.  Weight-gradient kernels: bf16 copies tiles in memory layout and transposes while reading LDS;
 // fp32 goes global -> registers (transposes) -> LDS, row stride 144 bytes.
