@@ -105,3 +105,39 @@ def test_probes_report_plausible_ceilings():
     assert 500.0 < bf < 2600.0          # published dense bf16 peak: 2.5 PFLOP/s
     assert 30.0 < fp < 170.0            # published fp32 matrix peak: 157.3 TFLOP/s
     assert 1000.0 < cp < 8200.0         # published HBM peak: 8 TB/s
+
+
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+@pytest.mark.parametrize("cin,cout,hs,groups", [(128, 128, 8, [3, 0, 2]), (128, 64, 16, [2, 1])])
+def test_upsample_conv3_runs_on_the_transposed_convolution_engine(ctxs, prec, cin, cout, hs, groups):
+    """The generator blocks the paper prints (Table 1: Upsample x2, then Conv k3 s1 p1) on the grouped k4 s2 p1
+    transposed-convolution kernel with the summed taps W4 = A W3 A^T; reference: the oracle's literal upsampling
+    followed by its 3 x 3 convolution."""
+    from oracle import paper_nets as P
+    torch = U.torch_mod()
+    g = ctxs[prec]
+    bf = prec == binding.BF16
+    rng = np.random.default_rng(cin + cout + hs)
+    n = int(sum(groups))
+    offs = np.concatenate([[0], np.cumsum(groups)]).astype(np.int32)
+    G = len(groups)
+    w3 = rng.normal(0, 0.05, (G, cout, cin, 3, 3))                       # [cout][cin][ky][kx] per group
+    A = np.array([[0, 0, 1], [0, 1, 1], [1, 1, 0], [1, 0, 0]], float)
+    w4 = U.round_to(np.einsum("ak,goikl,bl->gabio", A, w3, A), bf)       # [group][ky4][kx4][cin][cout], storage rounding
+    small = U.round_to(rng.normal(0, 1, (n, cin, hs, hs)), bf)
+    w_up = np.ascontiguousarray(w4.transpose(0, 1, 2, 4, 3)).reshape(G, 16, cout, cin)   # the kernel's [tap][cb][cs]
+    d_offs = U.dev(offs)
+    d_small = U.dev(U.pack(small.transpose(0, 2, 3, 1), bf))
+    d_w = U.dev(U.pack(w_up, bf))
+    out = torch.zeros(n * 4 * hs * hs * cout, dtype=torch.int16 if bf else torch.float32, device="cuda")
+    g.op_conv_up(d_small.data_ptr(), d_w.data_ptr(), out.data_ptr(), d_offs.data_ptr(), G, n, cout, cin, hs)
+    got = U.unpack(out, bf, (n, 2 * hs, 2 * hs, cout)).transpose(0, 3, 1, 2)
+    # the summed taps are rounded to the storage type before the multiplication: the reference uses the same
+    # rounded W4 through the pinned identity, and the literal form with the unrounded W3 bounds the difference
+    ref4 = np.concatenate([O.conv_transpose2d(small[offs[i]:offs[i + 1]], w4[i].transpose(2, 3, 0, 1), None)
+                           for i in range(G) if groups[i]])
+    lit = np.concatenate([O.conv2d(P.upsample2(small[offs[i]:offs[i + 1]]), w3[i], None, 3, 1, 1)
+                          for i in range(G) if groups[i]])
+    tol = tolerance(prec)
+    assert np.max(np.abs(got - ref4)) <= tol * np.max(np.abs(ref4))
+    assert np.max(np.abs(got - lit)) <= (2e-5 if not bf else 2e-2) * np.max(np.abs(lit))
