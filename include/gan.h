@@ -194,6 +194,25 @@ gan_status gan_op_conv_up(gan_ctx* ctx, const void* small_in, const void* w_up, 
 gan_status gan_op_conv_wgrad(gan_ctx* ctx, const void* big, const void* small_in, float* dw, const int32_t* offs,
                              int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs);
 
+/* Single operations of the networks exactly as printed in Tables 1 and 2 (Section 4), synchronous like the ones above.
+   These are building blocks; the training step for those networks is not part of this library yet.
+
+   gan_op_dropout: in place on a DEVICE tensor [n_samples][h][w][ch] of the context's storage type whose samples are
+     grouped by model (offs: DEVICE int32 [n_groups + 1]): element <- element * keep / (1 - p) (Table 2: Dropout(0.25)).
+     keep comes from Philox-4x32-10 (Salmon et al., SC'11): counter = (index low, index high, layer + 256 * pass_id,
+     step), key = (seed low, seed high ^ group), index = ((n * ch + c) * h + y) * w + x with n counted inside the group;
+     keep iff (first output word >> 8) >= ceil(p * 2^24).  The backward pass is the same call on the gradient.
+     layer in [0, 255]; p in [0, 1).
+   gan_op_w3_to_w4: the weights that turn "Upsample(2) then Conv k3 s1 p1" (Table 1) into the k4 s2 p1 transposed
+     convolution of gan_op_conv_up: per axis, tap t of the 4-tap filter is the sum of the 3-tap filter's taps in
+     S(t), S = {2}, {1, 2}, {0, 1}, {0}.  w3: DEVICE fp32 [n_groups][3*3][cb][cs]; w4: DEVICE storage type
+     [n_groups][4*4][cb][cs]; w4t: the same with cb and cs exchanged (the layout gan_op_conv_down reads).
+   gan_op_dw4_to_dw3: the adjoint map for the weight gradient, DEVICE fp32 [n_groups][16][cb][cs] -> [n_groups][9][cb][cs]. */
+gan_status gan_op_dropout(gan_ctx* ctx, void* x, const int32_t* offs, int32_t n_groups, int32_t n_samples, int32_t ch,
+                          int32_t h, int32_t w, float p, uint64_t seed, int32_t step, int32_t layer, int32_t pass_id);
+gan_status gan_op_w3_to_w4(gan_ctx* ctx, const float* w3, void* w4, void* w4t, int32_t n_groups, int32_t cb, int32_t cs);
+gan_status gan_op_dw4_to_dw3(gan_ctx* ctx, const float* dw4, float* dw3, int32_t n_groups, int32_t cb, int32_t cs);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,6 +76,10 @@ def load_library():
     L.gan_op_conv_down.argtypes = op
     L.gan_op_conv_up.argtypes = op
     L.gan_op_conv_wgrad.argtypes = op
+    L.gan_op_dropout.argtypes = [_VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
+                                 C.c_int32, C.c_int32, C.c_int32]
+    L.gan_op_w3_to_w4.argtypes = [_VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32]
+    L.gan_op_dw4_to_dw3.argtypes = [_VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32]
     L.gan_sample.argtypes = [_VP, C.POINTER(C.c_double), _VP, _VP, C.c_int32, _VP, _VP, C.c_int32]
     L.gan_anova_f.argtypes = [_VP, _VP, _VP, C.c_int32, C.POINTER(C.c_double)]
     L.gan_probe_mfma.argtypes = [C.c_int32, _VP, C.POINTER(C.c_double)]
@@ -243,3 +247,12 @@ class Gan:
 
     def op_conv_wgrad(self, big, small_in, dw, offs, n_groups, n_samples, cb, cs, hs):
         self._check(self.lib.gan_op_conv_wgrad(self.h, big, small_in, dw, offs, n_groups, n_samples, cb, cs, hs))
+
+    def op_dropout(self, x, offs, n_groups, n_samples, ch, h, w, p, seed, step, layer, pass_id):
+        self._check(self.lib.gan_op_dropout(self.h, x, offs, n_groups, n_samples, ch, h, w, p, seed, step, layer, pass_id))
+
+    def op_w3_to_w4(self, w3, w4, w4t, n_groups, cb, cs):
+        self._check(self.lib.gan_op_w3_to_w4(self.h, w3, w4, w4t, n_groups, cb, cs))
+
+    def op_dw4_to_dw3(self, dw4, dw3, n_groups, cb, cs):
+        self._check(self.lib.gan_op_dw4_to_dw3(self.h, dw4, dw3, n_groups, cb, cs))

@@ -1207,4 +1207,35 @@ gan_status gan_op_conv_wgrad(gan_ctx* c, const void* big, const void* small_in, 
   return s;
 }
 
+gan_status gan_op_dropout(gan_ctx* c, void* x, const int32_t* offs, int32_t n_groups, int32_t n_samples, int32_t ch, int32_t h,
+                          int32_t w, float p, uint64_t seed, int32_t step, int32_t layer, int32_t pass_id) {
+  if (!c || !x || !offs || n_groups < 1 || n_samples < 0 || ch < 1 || h < 1 || w < 1 || step < 0 || layer < 0 || layer > 255 ||
+      pass_id < 0)
+    return GAN_E_ARG;
+  if (!(p >= 0.f && p < 1.f)) return fail(c, GAN_E_ARG, "dropout probability outside [0, 1)");
+  if (c->bf16) launch_dropout<bf16_t>(static_cast<bf16_t*>(x), offs, n_groups, n_samples, ch, h, w, p, seed, step, layer, pass_id, c->st);
+  else launch_dropout<float>(static_cast<float*>(x), offs, n_groups, n_samples, ch, h, w, p, seed, step, layer, pass_id, c->st);
+  gan_status s = sync(c);
+  const hipError_t e = hipGetLastError();
+  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
+  return s;
+}
+gan_status gan_op_w3_to_w4(gan_ctx* c, const float* w3, void* w4, void* w4t, int32_t n_groups, int32_t cb, int32_t cs) {
+  if (!c || !w3 || !w4 || !w4t || n_groups < 1 || cb < 1 || cs < 1) return GAN_E_ARG;
+  if (c->bf16) launch_w3_to_w4<bf16_t>(w3, static_cast<bf16_t*>(w4), static_cast<bf16_t*>(w4t), n_groups, cb, cs, c->st);
+  else launch_w3_to_w4<float>(w3, static_cast<float*>(w4), static_cast<float*>(w4t), n_groups, cb, cs, c->st);
+  gan_status s = sync(c);
+  const hipError_t e = hipGetLastError();
+  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
+  return s;
+}
+gan_status gan_op_dw4_to_dw3(gan_ctx* c, const float* dw4, float* dw3, int32_t n_groups, int32_t cb, int32_t cs) {
+  if (!c || !dw4 || !dw3 || n_groups < 1 || cb < 1 || cs < 1) return GAN_E_ARG;
+  launch_dw4_to_dw3(dw4, dw3, n_groups, cb, cs, c->st);
+  gan_status s = sync(c);
+  const hipError_t e = hipGetLastError();
+  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
+  return s;
+}
+
 }  // extern "C"

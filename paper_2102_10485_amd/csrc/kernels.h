@@ -207,4 +207,17 @@ void launch_draw_labels(const float* u, const double* cdf, int n_labels, int las
 void launch_anova(const int* label_ids, const float* images, int n, int n_labels, int C, int HW, double* x, double* gsum,
                   int* gcnt, double* ssw, hipStream_t st);
 
+// ---- pieces of the networks as printed in the paper's Tables 1 and 2 (paper_layers.hip) ----
+// In-place dropout of an NHWC tensor whose samples are grouped by model (offs[g] .. offs[g+1]): the keep-mask comes
+// from Philox-4x32-10 with counter (element index low, high, layer + 256 * pass, step), key (seed low, seed high ^ g),
+// element index ((n C + c) H + y) W + x, n counted inside the group; kept values are scaled by 1 / (1 - p).
+template <typename T>
+void launch_dropout(T* x, const int* offs, int n_groups, int n, int C, int H, int W, float p, unsigned long long seed, int step,
+                    int layer, int pass_id, hipStream_t st);
+// w4[g][ty*4+tx][cb][cs] = sum of w3[g][ky*3+kx][cb][cs] over ky in S(ty), kx in S(tx), S = {2}, {1,2}, {0,1}, {0}
+// (Upsample x2 + Conv k3 s1 p1 == ConvTranspose k4 s2 p1 with these taps); w4t is the same with cb and cs exchanged.
+template <typename T>
+void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st);
+void launch_dw4_to_dw3(const float* dw4, float* dw3, int n_groups, int cb, int cs, hipStream_t st);   // the adjoint map
+
 }  // namespace gan

@@ -1,0 +1,119 @@
+// Pieces of the networks exactly as the paper's Tables 1 and 2 print them that the k4 s2 p1 engine does not have:
+// the dropout mask (a counter-based generator, so that any other implementation can reproduce it bit for bit) and the
+// two small linear maps that let "Upsample x2, then Conv k3 s1 p1" run as a k4 s2 p1 transposed convolution.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace gan {
+
+// Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3", SC'11), from
+// its definition: a round maps (c0, c1, c2, c3) to (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0));
+// the key is advanced by the two Weyl constants between rounds.  Returns the first output word.
+__device__ inline unsigned philox4x32_10_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1) {
+  constexpr unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) { k0 += W0; k1 += W1; }
+    const unsigned hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const unsigned hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+  }
+  return c0;
+}
+
+// x[j][y][x][c] (rows grouped by model: group g holds samples offs[g] .. offs[g+1]) <- x * keep / (1 - p), where
+// keep(element) = (word0 >> 8) >= thr with thr = ceil(p 2^24), counter = (index low, index high, layer + 256 pass,
+// step), key = (seed low, seed high ^ group), index = ((n C + c) H + y) W + x, n = j - offs[g].
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_kernel(T* __restrict__ x, const int* __restrict__ offs, int n_groups, long long total,
+                                                      int C, int H, int W, unsigned thr, float scale, unsigned seed_lo,
+                                                      unsigned seed_hi, unsigned c2, unsigned step) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int c = (int)(e % C);
+  const long long pix = e / C;
+  const int xw = (int)(pix % W);
+  const int y = (int)((pix / W) % H);
+  const int j = (int)(pix / ((long long)W * H));
+  int lo = 0, hi = n_groups;                       // group of sample j: offs[lo] <= j < offs[lo + 1]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (offs[mid] <= j) lo = mid; else hi = mid;
+  }
+  if (j >= offs[n_groups]) return;                 // rows past the routed samples are left alone
+  const unsigned long long lin = (((unsigned long long)(j - offs[lo]) * C + c) * H + y) * W + xw;
+  const unsigned w0 = philox4x32_10_word0((unsigned)lin, (unsigned)(lin >> 32), c2, step, seed_lo, seed_hi ^ (unsigned)lo);
+  x[e] = (w0 >> 8) >= thr ? from_float<T>(to_float(x[e]) * scale) : from_float<T>(0.f);
+}
+template <typename T>
+void launch_dropout(T* x, const int* offs, int n_groups, int n, int C, int H, int W, float p, unsigned long long seed, int step,
+                    int layer, int pass_id, hipStream_t st) {
+  const long long total = (long long)n * H * W * C;
+  if (total == 0) return;
+  if (!(p >= 0.f && p < 1.f) || n_groups < 1) abort();
+  const double t = ceil((double)p * 16777216.0);
+  hipLaunchKernelGGL((dropout_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, offs, n_groups, total, C, H, W,
+                     (unsigned)t, 1.0f / (1.0f - p), (unsigned)(seed & 0xffffffffull), (unsigned)(seed >> 32),
+                     (unsigned)(layer + 256 * pass_id), (unsigned)step);
+}
+template void launch_dropout<float>(float*, const int*, int, int, int, int, int, float, unsigned long long, int, int, int, hipStream_t);
+template void launch_dropout<bf16_t>(bf16_t*, const int*, int, int, int, int, int, float, unsigned long long, int, int, int, hipStream_t);
+
+// Upsample x2 + Conv k3 s1 p1 as ConvTranspose k4 s2 p1: per axis, tap t4 of the transposed convolution is the sum of
+// the 3-tap filter's taps in S(t4), S(0) = {2}, S(1) = {1, 2}, S(2) = {0, 1}, S(3) = {0}.
+__device__ inline void taps_of(int t4, int& first, int& count) {
+  first = t4 == 0 ? 2 : (t4 == 1 ? 1 : 0);
+  count = (t4 == 1 || t4 == 2) ? 2 : 1;
+}
+// w3: fp32 [G][9][cb][cs] ; w4: T [G][16][cb][cs] ; w4t: T [G][16][cs][cb]
+template <typename T>
+__global__ __launch_bounds__(256) void w3_to_w4_kernel(const float* __restrict__ w3, T* __restrict__ w4, T* __restrict__ w4t,
+                                                       long long total, int cb, int cs) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;      // (g, tap16, cb, cs)
+  if (idx >= total) return;
+  const int s = (int)(idx % cs);
+  const int b = (int)((idx / cs) % cb);
+  const int t = (int)((idx / ((long long)cs * cb)) % 16);
+  const long long g = idx / ((long long)cs * cb * 16);
+  int y0, ny, x0, nx;
+  taps_of(t >> 2, y0, ny);
+  taps_of(t & 3, x0, nx);
+  float v = 0.f;
+  for (int ky = y0; ky < y0 + ny; ++ky)
+    for (int kx = x0; kx < x0 + nx; ++kx) v += w3[((g * 9 + ky * 3 + kx) * cb + b) * cs + s];
+  w4[idx] = from_float<T>(v);
+  w4t[((g * 16 + t) * cs + s) * cb + b] = from_float<T>(v);
+}
+template <typename T>
+void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st) {
+  const long long total = (long long)n_groups * 16 * cb * cs;
+  if (total == 0) return;
+  hipLaunchKernelGGL((w3_to_w4_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w3, w4, w4t, total, cb, cs);
+}
+template void launch_w3_to_w4<float>(const float*, float*, float*, int, int, int, hipStream_t);
+template void launch_w3_to_w4<bf16_t>(const float*, bf16_t*, bf16_t*, int, int, int, hipStream_t);
+
+// the adjoint map: dw3[ky][kx] = sum of dw4[t4y][t4x] over the t4 whose sets contain ky / kx.  fp32 [G][16][cb][cs] -> [G][9][cb][cs]
+__global__ __launch_bounds__(256) void dw4_to_dw3_kernel(const float* __restrict__ dw4, float* __restrict__ dw3, long long total,
+                                                         int cb, int cs) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;      // (g, tap9, cb, cs)
+  if (idx >= total) return;
+  const long long inner = idx % ((long long)cb * cs);
+  const int t = (int)((idx / ((long long)cb * cs)) % 9);
+  const long long g = idx / ((long long)cb * cs * 9);
+  const int ky = t / 3, kx = t - 3 * ky;
+  // 3-tap index k belongs to S(3 - k) and S(2 - k)
+  float v = 0.f;
+  for (int ay = 2 - ky; ay <= 3 - ky; ++ay)
+    for (int ax = 2 - kx; ax <= 3 - kx; ++ax) v += dw4[((g * 16 + ay * 4 + ax) * cb) * cs + inner];
+  dw3[idx] = v;
+}
+void launch_dw4_to_dw3(const float* dw4, float* dw3, int n_groups, int cb, int cs, hipStream_t st) {
+  const long long total = (long long)n_groups * 9 * cb * cs;
+  if (total == 0) return;
+  hipLaunchKernelGGL(dw4_to_dw3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, dw4, dw3, total, cb, cs);
+}
+
+}  // namespace gan
