@@ -19,20 +19,20 @@ PEAK = {"mfma_bf16": 2500.0, "mfma_fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFL
 # the same counters read for the 1 GiB elementwise probe (fetch x 2.0, write x 1.0).  Valid only for the kernel sources they
 # were taken with: `sources` is the digest of csrc/ at that time, and the roofline reports null traffic when it differs.
 MEASURED_TRAFFIC = {
-    "sources": "d40696a45a8c03d2",
+    "sources": "839af48075ebf15b",
     "workload": "config 2 bf16",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "kib_per_launch": {     # kernel family -> (FETCH_SIZE, WRITE_SIZE)
         "gemm_dense<128x128>": (103327, 108800),
         "gemm_up<256x256>": (346947, 274133),
-        "gemm_up<256x128>": (187951, 416000),
-        "gemm_dense+lrelu<256x128>": (154549, 614400),
-        "gemm_down<256x256>": (362671, 207200),
-        "wgrad<256x256>": (345712, 512000),
-        "gemm_up+actbwd<256x128>": (608534, 614400),
+        "gemm_up<256x128>": (187980, 416000),
+        "gemm_dense+lrelu<256x128>": (154550, 614400),
+        "gemm_down<256x256>": (362669, 207200),
+        "wgrad<256x256>": (345711, 512000),
+        "gemm_up+actbwd<256x128>": (608793, 614400),
         "wgrad<64x128>": (460872, 25600),
-        "gemm_dense<256x128>": (103359, 409600),
-        "wgrad<256x128>": (52083, 409600),
+        "gemm_dense<256x128>": (103356, 409600),
+        "wgrad<256x128>": (52074, 409600),
     },
 }
 
