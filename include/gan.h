@@ -168,6 +168,25 @@ gan_status gan_sample(gan_ctx* ctx, const double* prior, const float* u, const f
    Returns GAN_E_STATE (and F = 0) when fewer than two labels occur or there are not more images than labels. */
 gan_status gan_anova_f(gan_ctx* ctx, const int32_t* label_ids, const float* images, int32_t n, double* F);
 
+/* ---- for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+   that forbid hipMalloc) ------------------------------------------------------------------------------------------
+   gan_anova_f_static computes what gan_anova_f computes, without a context and without any device allocation: its
+   intermediate results (per-image channel means, per-label sums, counts and squared deviations) live in a static
+   device array of about 2.1 MiB that every device the library runs on holds until the process ends (its address is
+   looked up once per device, at the first call with that device current).  The caller passes the shape that a context
+   would carry.  label_ids: DEVICE int32 [n]; images: DEVICE fp32 [n, img_c, img_hw, img_hw]; F: HOST double [img_c];
+   hip_stream: a hipStream_t (0 = the null stream), synchronised before returning.
+   Limits: n <= GAN_ANOVA_STATIC_MAX_IMAGES, n_labels <= GAN_ANOVA_STATIC_MAX_LABELS, img_c <= 4; anything larger
+   returns GAN_E_SHAPE.  Other errors as gan_anova_f (GAN_E_STATE and F = 0 when fewer than two labels occur or there
+   are not more images than labels).  gan_static_last_error() gives the text of the last error of this entry point.
+   All calls on one device share that device's array: calls that overlap on one device (different streams or threads)
+   race; calls in sequence need no clearing, every element read is written first by the same call. */
+#define GAN_ANOVA_STATIC_MAX_IMAGES 65536
+#define GAN_ANOVA_STATIC_MAX_LABELS 1024
+gan_status gan_anova_f_static(const int32_t* label_ids, const float* images, int32_t n, int32_t n_labels, int32_t img_c,
+                              int32_t img_hw, void* hip_stream, double* F);
+const char* gan_static_last_error(void);
+
 /* ---- what the chip delivers to the simplest kernels (Section 5 of the paper reports GPU usage only; these give the
    achievable ceilings the step's kernels are reported against, next to the published peaks) -------------- */
 /* TFLOP/s of a register-only MFMA loop in the arithmetic of `precision` (bf16 inputs, or fp32), every CU busy.

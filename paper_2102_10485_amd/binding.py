@@ -82,10 +82,24 @@ def load_library():
     L.gan_op_dw4_to_dw3.argtypes = [_VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32]
     L.gan_sample.argtypes = [_VP, C.POINTER(C.c_double), _VP, _VP, C.c_int32, _VP, _VP, C.c_int32]
     L.gan_anova_f.argtypes = [_VP, _VP, _VP, C.c_int32, C.POINTER(C.c_double)]
+    L.gan_anova_f_static.argtypes = [_VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP, C.POINTER(C.c_double)]
+    L.gan_static_last_error.restype = C.c_char_p
     L.gan_probe_mfma.argtypes = [C.c_int32, _VP, C.POINTER(C.c_double)]
     L.gan_probe_copy.argtypes = [C.c_int64, _VP, C.POINTER(C.c_double)]
     _lib = L
     return L
+
+
+def anova_f_static(label_ids_ptr, images_ptr, n, n_labels, img_c, img_hw, stream=0):
+    """gan_anova_f without a context and without device allocations (static scratch array); returns (status, F)."""
+    F = np.zeros(max(img_c, 1), np.float64)
+    st = load_library().gan_anova_f_static(label_ids_ptr, images_ptr, n, n_labels, img_c, img_hw, stream,
+                                           F.ctypes.data_as(C.POINTER(C.c_double)))
+    return st, F[:max(img_c, 0)]
+
+
+def static_last_error():
+    return (load_library().gan_static_last_error() or b"").decode()
 
 
 def probe_mfma(precision, stream=0):

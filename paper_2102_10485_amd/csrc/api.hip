@@ -12,6 +12,7 @@
 #include <string>
 #include <vector>
 
+#include "anova_host.h"
 #include "kernels.h"
 
 using namespace gan;
@@ -993,23 +994,8 @@ gan_status gan_anova_f(gan_ctx* c, const int32_t* label_ids, const float* images
       hipMemcpy(ssw.data(), c->an_ssw, ssw.size() * sizeof(double), hipMemcpyDeviceToHost) != hipSuccess ||
       hipMemcpy(gcnt.data(), c->an_gcnt, gcnt.size() * sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
     return fail(c, GAN_E_HIP, "analysis of variance failed on the device");
-  int kk = 0;
-  long long nn = 0;
-  for (int k = 0; k < K; ++k) { kk += gcnt[(size_t)k] > 0; nn += gcnt[(size_t)k]; }
-  if (kk < 2 || nn <= kk) return fail(c, GAN_E_STATE, "fewer than two labels present, or not more images than labels");
-  for (int ch = 0; ch < C; ++ch) {
-    double all = 0.0;
-    for (int k = 0; k < K; ++k) all += gsum[(size_t)k * C + ch];
-    const double grand = all / (double)nn;
-    double ssb = 0.0, sw = 0.0;
-    for (int k = 0; k < K; ++k) {
-      if (gcnt[(size_t)k] == 0) continue;
-      const double mk = gsum[(size_t)k * C + ch] / (double)gcnt[(size_t)k];
-      ssb += (double)gcnt[(size_t)k] * (mk - grand) * (mk - grand);
-      sw += ssw[(size_t)k * C + ch];
-    }
-    F[ch] = (ssb / (double)(kk - 1)) / (sw / (double)(nn - kk));
-  }
+  if (!anova_f_from_sums(gsum.data(), ssw.data(), gcnt.data(), K, C, F))
+    return fail(c, GAN_E_STATE, "fewer than two labels present, or not more images than labels");
   return GAN_OK;
 }
 
