@@ -10,7 +10,8 @@
  * through the updated D, its backward pass, Adam on theta_G.
  *
  * Conventions
- *  - Every function returns a gan_status and never throws or aborts.
+ *  - Every function returns a gan_status and never throws or aborts: a shape the kernels do not support is
+ *    refused with GAN_E_SHAPE before anything is launched (gan_last_error has the reason).
  *  - "DEVICE" pointers are HIP device pointers owned by the caller (for
  *    example a torch tensor's data_ptr()); "HOST" pointers are ordinary host
  *    memory.  The context owns parameters, Adam moments, BatchNorm running
@@ -126,12 +127,17 @@ gan_status gan_get_params(gan_ctx* ctx, int32_t which, int32_t model, float* dst
 gan_status gan_set_params(gan_ctx* ctx, int32_t which, int32_t model, const float* src, int64_t n);
 /* Adam first / second moments (may be NULL) and step count of one model. */
 gan_status gan_get_opt_state(gan_ctx* ctx, int32_t which, int32_t model, float* m, float* v, int64_t* t);
+/* Restore what gan_get_opt_state returned (resuming from a checkpoint): moments in the parameter order (either may be
+   NULL: left as it is) and the step count t >= 0 that the next update increments. */
+gan_status gan_set_opt_state(gan_ctx* ctx, int32_t which, int32_t model, const float* m, const float* v, int64_t t);
 /* Gradients used by the last update of this model (same order as the parameters). */
 gan_status gan_get_grads(gan_ctx* ctx, int32_t which, int32_t model, float* dst, int64_t n);
 /* BatchNorm running statistics, concatenated over the network's BN layers. */
 gan_status gan_bn_count(const gan_ctx* ctx, int32_t which, int64_t* per_model);
 gan_status gan_get_bn_running(gan_ctx* ctx, int32_t which, int32_t model, float* mean, float* var, int64_t n);
-/* Routing of the last step: perm[j] = caller index of the j-th sample in model-major order (stable within a
+gan_status gan_set_bn_running(gan_ctx* ctx, int32_t which, int32_t model, const float* mean, const float* var, int64_t n);
+/* Routing of the last training step (gan_generate and gan_sample route into buffers of their own and change neither
+   this nor the counts gan_get_losses reports): perm[j] = caller index of the j-th sample in model-major order (stable within a
    model), offs[k]..offs[k+1] = model k's rows.  HOST int32 [n of that step] and [n_models + 1]. */
 gan_status gan_get_routing(gan_ctx* ctx, int32_t* perm, int32_t* offs);
 /* Text of the last error on this context (never NULL). */

@@ -97,6 +97,9 @@ def lib(real=np.float64):
         _lib.oracle_get_routing.argtypes = [C.c_void_p, _I, _I]
         _lib.oracle_eval_losses.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
         _lib.oracle_eval_grads.argtypes = [C.c_void_p, C.c_int, _I, _D, _D, C.c_int32, _D, _D]
+        _lib.oracle_set_bf16_emulation.argtypes = [C.c_void_p, C.c_int]
+        _lib.oracle_round_bf16.argtypes = [creal]
+        _lib.oracle_round_bf16.restype = creal
         _loaded[real] = _lib
     return _loaded[real]
 
@@ -137,8 +140,10 @@ def make_config(spec, n_models, n_labels, hyper=None):
 
 
 class Oracle:
-    def __init__(self, spec, n_models, n_labels, hyper=None, real=np.float64):
-        """real=np.float64 is the oracle; np.float32 runs the same loops in single precision."""
+    def __init__(self, spec, n_models, n_labels, hyper=None, real=np.float64, emulate_bf16=False):
+        """real=np.float64 is the oracle; np.float32 runs the same loops in single precision.
+        emulate_bf16: round the tensors a 16-bit-storage implementation stores (see gan_oracle.h); a diagnostic
+        reference next to the plain algorithm, never its replacement."""
         self.real = real
         self.L = lib(real)
         self.cfg = make_config(spec, n_models, n_labels, hyper)
@@ -148,6 +153,8 @@ class Oracle:
             raise ValueError("oracle_create failed: %d" % rc)
         self.n_models = n_models
         self.img_shape = (spec["img_c"], spec["img_hw"], spec["img_hw"])
+        if emulate_bf16:
+            assert self.L.oracle_set_bf16_emulation(self.h, 1) == 0
 
     def close(self):
         if self.h:
@@ -247,6 +254,11 @@ class Oracle:
 
 
 # ---- single operations on numpy arrays (NCHW) ------------------------------
+
+def round_bf16(x):
+    """The emulation's rounding of one value (via single precision, to nearest even)."""
+    return float(lib().oracle_round_bf16(float(x)))
+
 
 def conv2d(X, W, bias=None, k=4, s=2, p=1):
     X, W, bias = _f64(X), _f64(W), _f64(bias)

@@ -424,7 +424,39 @@ struct oracle_ctx {
   oreal *jd, *jg;                /* last losses per model */
   int32_t *counts, *perm, *offs;
   int32_t last_n, n_bad;
+  int emul;                      /* bf16-storage emulation (see oracle_set_bf16_emulation); 0 = the plain algorithm */
 };
+
+/* ---- bf16-storage emulation -------------------------------------------------------------------------------
+   A 16-bit storage format with the sign, the 8 exponent bits and the top 7 mantissa bits of an IEEE single
+   ("bfloat16"); conversion from a single rounds to nearest, ties to even.  A value held in a wider type is first
+   rounded to single (that is what an fp32 accumulator holds), then to the 16-bit format. */
+oreal oracle_round_bf16(oreal x) {
+  union { float f; uint32_t u; } c;
+  c.f = (float)x;
+  if ((c.u & 0x7fffffffu) > 0x7f800000u) return x;          /* NaN stays NaN */
+  c.u += 0x7fffu + ((c.u >> 16) & 1u);
+  c.u &= 0xffff0000u;
+  return (oreal)c.f;
+}
+static void qv(const oracle_ctx* c, oreal* x, int64_t n) {
+  if (!c->emul) return;
+  for (int64_t i = 0; i < n; ++i) x[i] = oracle_round_bf16(x[i]);
+}
+/* The weights as a 16-bit-storage implementation multiplies them: a copy of theta with the weights of layers
+   [0, nl) rounded (biases and BatchNorm parameters stay as they are).  NULL when emulation is off. */
+static oreal* shadow_weights(const oracle_ctx* c, const net_t* net, const oreal* th, int nl) {
+  if (!c->emul) return NULL;
+  oreal* q = (oreal*)malloc(sizeof(oreal) * (size_t)net->nparams);
+  memcpy(q, th, sizeof(oreal) * (size_t)net->nparams);
+  for (int i = 0; i < nl; ++i) qv(c, q + net->L[i].w, net->L[i].nw);
+  return q;
+}
+int oracle_set_bf16_emulation(oracle_ctx* c, int on) {
+  if (!c) return -1;
+  c->emul = on ? 1 : 0;
+  return 0;
+}
 
 static void build_nets(oracle_ctx* c) {
   const oracle_config* f = &c->cfg;
@@ -600,28 +632,40 @@ static void bn_layer(const oracle_ctx* c, const layer_t* l, const oreal* th, con
                      oreal* mean, oreal* var, int b, int C, int HW,
                      oreal* rm, oreal* rv, int update_running, int use_running) {
   if (use_running) {
+    qv(c, (oreal*)x, (int64_t)b * C * HW);            /* emulation: the stored tensor is what gets normalised */
     oracle_bn_eval(x, th + l->gamma, th + l->beta, (oreal)c->cfg.bn_eps, rm + l->rs, rv + l->rs, y, b, C, HW);
     return;
   }
   oracle_bn_train(x, th + l->gamma, th + l->beta, (oreal)c->cfg.bn_eps, y, mean, var, b, C, HW);
+  if (c->emul) {
+    /* the statistics above come from the accumulators; what is stored, and normalised, is the rounded tensor */
+    qv(c, (oreal*)x, (int64_t)b * C * HW);
+    oracle_bn_eval(x, th + l->gamma, th + l->beta, (oreal)c->cfg.bn_eps, mean, var, y, b, C, HW);
+  }
   if (update_running)
     oracle_bn_running_update(rm + l->rs, rv + l->rs, mean, var, (oreal)c->cfg.bn_momentum, C, (int64_t)b * HW);
 }
 
-/* G: [z ; onehot] -> linear -> BN -> ReLU -> {convT -> BN -> ReLU}* -> convT(+bias) -> tanh */
+/* G: [z ; onehot] -> linear -> BN -> ReLU -> {convT -> BN -> ReLU}* -> convT(+bias) -> tanh
+   Emulation (c->emul): the input, the weights the contractions read, and every tensor a layer hands to the next
+   are rounded to the 16-bit format; sums, statistics, biases and BatchNorm parameters are not. */
 static void g_forward(const oracle_ctx* c, const oreal* th, cache_t* k, oreal* rm, oreal* rv,
                       int update_running, int use_running) {
   const net_t* G = &c->G;
   const int b = k->b;
   const layer_t* l = &G->L[0];
   const int C0 = c->cfg.g_ch[0], hw0 = c->cfg.g_h0 * c->cfg.g_h0;
-  oracle_linear(k->in, th + l->w, NULL, k->pre[0], b, l->cin, l->cout);      /* [b, C0*h0*h0] == [b,C0,h0,h0] */
+  oreal* thq = shadow_weights(c, G, th, G->nlayers);
+  const oreal* tw = thq ? thq : th;                                          /* where the contractions read weights */
+  qv(c, k->in, (int64_t)b * l->cin);
+  oracle_linear(k->in, tw + l->w, NULL, k->pre[0], b, l->cin, l->cout);      /* [b, C0*h0*h0] == [b,C0,h0,h0] */
   bn_layer(c, l, th, k->pre[0], k->act[0], k->mean[0], k->var[0], b, C0, hw0, rm, rv, update_running, use_running);
   oracle_leaky_relu(k->act[0], k->act[0], (int64_t)b * C0 * hw0, (oreal)0);
+  qv(c, k->act[0], (int64_t)b * C0 * hw0);
   for (int i = 1; i < G->nlayers; ++i) {
     l = &G->L[i];
     const int64_t e = (int64_t)b * l->cout * l->hout * l->hout;
-    oracle_conv_transpose2d(k->act[i - 1], th + l->w, l->bias >= 0 ? th + l->bias : NULL, k->pre[i],
+    oracle_conv_transpose2d(k->act[i - 1], tw + l->w, l->bias >= 0 ? th + l->bias : NULL, k->pre[i],
                             b, l->cin, l->hin, l->hin, l->cout, KSZ, STR, PAD);
     if (l->gamma >= 0) {
       bn_layer(c, l, th, k->pre[i], k->act[i], k->mean[i], k->var[i], b, l->cout, l->hout * l->hout, rm, rv,
@@ -630,24 +674,32 @@ static void g_forward(const oracle_ctx* c, const oreal* th, cache_t* k, oreal* r
     } else {
       oracle_tanh(k->pre[i], k->act[i], e);
     }
+    qv(c, k->act[i], e);
   }
+  free(thq);
 }
 
-/* Given dfake = d cost / d G(z), fill g (all of G's parameter gradients). */
+/* Given dfake = d cost / d G(z), fill g (all of G's parameter gradients).
+   Emulation: every activation gradient that is stored between two operations is rounded (after the tanh derivative,
+   after each data gradient, after each BatchNorm backward); parameter gradients are not. */
 static void g_backward(const oracle_ctx* c, const oreal* th, const cache_t* k, const oreal* dfake, oreal* g) {
   const net_t* G = &c->G;
   const int b = k->b;
   const int last = G->nlayers - 1;
   int64_t e = layer_out_elems(G, last, b);
+  oreal* thq = shadow_weights(c, G, th, G->nlayers);
+  const oreal* tw = thq ? thq : th;
   oreal* dcur = (oreal*)malloc(sizeof(oreal) * (size_t)e);
   oracle_tanh_bwd(k->act[last], dfake, dcur, e);                 /* gradient w.r.t. the last layer's pre-activation */
+  qv(c, dcur, e);
   for (int i = last; i >= 1; --i) {
     const layer_t* l = &G->L[i];
     const int64_t ein = layer_out_elems(G, i - 1, b);
     oreal* dprev = (oreal*)malloc(sizeof(oreal) * (size_t)ein);
-    oracle_conv_transpose2d_bwd(k->act[i - 1], th + l->w, dcur, dprev, g + l->w, l->bias >= 0 ? g + l->bias : NULL,
+    oracle_conv_transpose2d_bwd(k->act[i - 1], tw + l->w, dcur, dprev, g + l->w, l->bias >= 0 ? g + l->bias : NULL,
                                 b, l->cin, l->hin, l->hin, l->cout, KSZ, STR, PAD);
     free(dcur);
+    qv(c, dprev, ein);
     /* dprev is w.r.t. act[i-1] = ReLU(BN(pre[i-1])) */
     const layer_t* lp = &G->L[i - 1];
     const int Cp = (i - 1 == 0) ? c->cfg.g_ch[0] : lp->cout;
@@ -658,24 +710,70 @@ static void g_backward(const oracle_ctx* c, const oreal* th, const cache_t* k, c
     oracle_bn_bwd(k->pre[i - 1], th + lp->gamma, k->mean[i - 1], k->var[i - 1], (oreal)c->cfg.bn_eps, dbn, dprev,
                   g + lp->gamma, g + lp->beta, b, Cp, HWp);
     free(dbn);
+    qv(c, dprev, ein);
     dcur = dprev;
   }
   const layer_t* l0 = &G->L[0];
-  oracle_linear_bwd(k->in, th + l0->w, dcur, NULL, g + l0->w, NULL, b, l0->cin, l0->cout);
+  oracle_linear_bwd(k->in, tw + l0->w, dcur, NULL, g + l0->w, NULL, b, l0->cin, l0->cout);
   free(dcur);
+  free(thq);
 }
 
-/* D: conv(+bias) -> LReLU -> {conv -> BN -> LReLU}* -> flatten -> linear(+bias); logits in act[last] */
+/* Emulation of the first convolution's label planes.  A one-hot label plane is constant over the image, so its part
+   of the output at (oy, ox) is the sum of that channel's taps that fall inside the image; a 16-bit-storage
+   implementation holds that sum (one per border class of the position) and the bias as stored values.  Adds
+   round(sum of valid taps of the sample's label channel) + round(bias) to Y, whose convolution ran over the image
+   channels only. */
+static void add_label_planes_emul(const oracle_ctx* c, const layer_t* l, const oreal* th, const cache_t* k, oreal* Y) {
+  const int C = c->cfg.img_c, cd = c->cfg.cond_d, H = l->hin, Ho = l->hout;
+  const int HW = H * H;
+  for (int r = 0; r < k->b; ++r) {
+    int y = -1;                                        /* the label plane that is one for this sample */
+    for (int j = 0; j < cd; ++j)
+      if (k->in[((int64_t)r * (C + cd) + C + j) * HW] != (oreal)0) y = j;
+    for (int co = 0; co < l->cout; ++co)
+      for (int oy = 0; oy < Ho; ++oy)
+        for (int ox = 0; ox < Ho; ++ox) {
+          oreal sum = 0;
+          if (y >= 0)
+            for (int ky = 0; ky < KSZ; ++ky)
+              for (int kx = 0; kx < KSZ; ++kx) {
+                const int iy = oy * STR - PAD + ky, ix = ox * STR - PAD + kx;
+                if (iy < 0 || iy >= H || ix < 0 || ix >= H) continue;
+                sum += th[l->w + (((int64_t)co * l->cin + C + y) * KSZ + ky) * KSZ + kx];
+              }
+          Y[(((int64_t)r * l->cout + co) * Ho + oy) * Ho + ox] += oracle_round_bf16(sum) + oracle_round_bf16(th[l->bias + co]);
+        }
+  }
+}
+
+/* D: conv(+bias) -> LReLU -> {conv -> BN -> LReLU}* -> flatten -> linear(+bias); logits in act[last].
+   Emulation: as in g_forward; the final linear layer reads the unrounded weights (it is not a 16-bit contraction). */
 static void d_forward(const oracle_ctx* c, const oreal* th, cache_t* k, oreal* rm, oreal* rv, int update_running) {
   const net_t* D = &c->D;
   const int b = k->b;
   const oreal slope = (oreal)c->cfg.leaky_slope;
   const oreal* cur = k->in;
+  oreal* thq = shadow_weights(c, D, th, D->nlayers - 1);
+  const oreal* tw = thq ? thq : th;
+  if (c->emul) {
+    const layer_t* l0 = &D->L[0];
+    qv(c, k->in, (int64_t)b * l0->cin * l0->hin * l0->hin);
+    /* the label planes are handled by add_label_planes_emul: take their taps out of the convolution */
+    for (int co = 0; co < l0->cout; ++co)
+      for (int ci = c->cfg.img_c; ci < l0->cin; ++ci)
+        for (int t = 0; t < KSZ * KSZ; ++t) thq[l0->w + ((int64_t)co * l0->cin + ci) * KSZ * KSZ + t] = 0;
+  }
   for (int j = 0; j < D->nlayers - 1; ++j) {
     const layer_t* l = &D->L[j];
     const int64_t e = (int64_t)b * l->cout * l->hout * l->hout;
-    oracle_conv2d(cur, th + l->w, l->bias >= 0 ? th + l->bias : NULL, k->pre[j], b, l->cin, l->hin, l->hin, l->cout,
-                  KSZ, STR, PAD);
+    if (c->emul && j == 0) {
+      oracle_conv2d(cur, tw + l->w, NULL, k->pre[j], b, l->cin, l->hin, l->hin, l->cout, KSZ, STR, PAD);
+      add_label_planes_emul(c, l, th, k, k->pre[j]);
+    } else {
+      oracle_conv2d(cur, tw + l->w, l->bias >= 0 ? th + l->bias : NULL, k->pre[j], b, l->cin, l->hin, l->hin, l->cout,
+                    KSZ, STR, PAD);
+    }
     if (l->gamma >= 0) {
       bn_layer(c, l, th, k->pre[j], k->act[j], k->mean[j], k->var[j], b, l->cout, l->hout * l->hout, rm, rv,
                update_running, 0);
@@ -687,25 +785,34 @@ static void d_forward(const oracle_ctx* c, const oreal* th, cache_t* k, oreal* r
     } else {
       oracle_leaky_relu(k->pre[j], k->act[j], e, slope);
     }
+    qv(c, k->act[j], e);
     cur = k->act[j];
   }
   const int last = D->nlayers - 1;
   const layer_t* l = &D->L[last];
   oracle_linear(cur, th + l->w, th + l->bias, k->pre[last], b, l->cin, 1);
   memcpy(k->act[last], k->pre[last], sizeof(oreal) * (size_t)b);
+  free(thq);
 }
 
-/* Accumulates (+=) parameter gradients into g; if dinput != NULL also returns d/d(network input). */
+/* Accumulates (+=) parameter gradients into g; if dinput != NULL also returns d/d(network input).
+   Emulation: a stored activation gradient is rounded once, after the last operation applied to it before it is
+   stored: the gradient handed to a BatchNorm layer right after the data-gradient contraction, the gradient handed to
+   the first convolution after its LeakyReLU derivative, the gradient of the network input not at all (the caller
+   multiplies it by the tanh derivative first). */
 static void d_backward(const oracle_ctx* c, const oreal* th, const cache_t* k, const oreal* ds, oreal* g,
                        oreal* dinput) {
   const net_t* D = &c->D;
   const int b = k->b;
   const oreal slope = (oreal)c->cfg.leaky_slope;
   const int last = D->nlayers - 1;
+  oreal* thq = shadow_weights(c, D, th, D->nlayers - 1);
+  const oreal* tw = thq ? thq : th;
   oreal* gl = (oreal*)calloc((size_t)D->nparams, sizeof(oreal));   /* this pass's gradients */
   const layer_t* l = &D->L[last];
   oreal* dcur = (oreal*)malloc(sizeof(oreal) * (size_t)((int64_t)b * l->cin));
   oracle_linear_bwd(k->act[last - 1], th + l->w, ds, dcur, gl + l->w, gl + l->bias, b, l->cin, 1);
+  qv(c, dcur, (int64_t)b * l->cin);
   for (int j = last - 1; j >= 0; --j) {
     l = &D->L[j];
     const int64_t e = (int64_t)b * l->cout * l->hout * l->hout;
@@ -720,18 +827,21 @@ static void d_backward(const oracle_ctx* c, const oreal* th, const cache_t* k, c
     } else {
       oracle_leaky_relu_bwd(k->pre[j], dcur, dpre, e, slope);
     }
+    qv(c, dpre, e);
     free(dcur);
     const oreal* xin = (j == 0) ? k->in : k->act[j - 1];
     const int64_t ein = (int64_t)b * l->cin * l->hin * l->hin;
     oreal* dprev = NULL;
     if (j > 0 || dinput) dprev = (j == 0) ? dinput : (oreal*)malloc(sizeof(oreal) * (size_t)ein);
-    oracle_conv2d_bwd(xin, th + l->w, dpre, dprev, gl + l->w, l->bias >= 0 ? gl + l->bias : NULL,
+    oracle_conv2d_bwd(xin, tw + l->w, dpre, dprev, gl + l->w, l->bias >= 0 ? gl + l->bias : NULL,
                       b, l->cin, l->hin, l->hin, l->cout, KSZ, STR, PAD);
     free(dpre);
+    if (j >= 1 && D->L[j - 1].gamma >= 0) qv(c, dprev, ein);       /* consumed by a BatchNorm backward as stored */
     dcur = (j == 0) ? NULL : dprev;
   }
   for (int64_t i = 0; i < D->nparams; ++i) g[i] += gl[i];
   free(gl);
+  free(thq);
 }
 
 /* Build the inputs of one model from the flat batch: rows idx[0..b). */

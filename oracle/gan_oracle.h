@@ -96,6 +96,26 @@ int  oracle_eval_grads(oracle_ctx* ctx, int model, const int32_t* label_ids, con
                        const oreal* real_batch, int32_t n, oreal* gD, oreal* gG);
 int  oracle_threads(void);
 
+/* ---- bf16-storage emulation (a diagnostic reference, not the definition of the method) ---------------------
+   With the switch on, the step rounds -- to the 16-bit format with a single's sign, exponent and top 7 mantissa bits,
+   round to nearest even, via single precision -- exactly the tensors a 16-bit-storage implementation keeps in that
+   format, and nothing else:
+     * the network inputs (z with its one-hot part, the real images) and the generated images;
+     * the weights read by the linear layer of G and by every (transposed) convolution -- per element, except the
+       one-hot label planes of D's first convolution, whose taps enter as one rounded sum per output position (the
+       sum of the taps inside the image) next to the rounded bias; D's final linear layer reads unrounded weights;
+     * every layer output as stored: the pre-normalisation tensor (BatchNorm statistics are taken before that
+       rounding, the normalisation reads the rounded tensor) and the activated tensor;
+     * every stored activation gradient: after the tanh derivative, after D's linear layer, after each BatchNorm
+       backward, after each data-gradient contraction (for the tensor feeding D's first convolution: after its
+       LeakyReLU derivative).
+   Sums, BatchNorm statistics, costs, parameter gradients, Adam and the master parameters are left in oreal.
+   Off (the default) the code path is the plain algorithm, bit for bit.  Pinned by: the rounding function against
+   the format's definition (ties, specials), switch-off identity, representability of the stored outputs, and the
+   distance to the plain result staying within the format's error. */
+int   oracle_set_bf16_emulation(oracle_ctx* ctx, int on);
+oreal oracle_round_bf16(oreal x);
+
 /* ---- single operations (for pins and for per-kernel parity tests) ------ */
 void oracle_conv2d(const oreal* X, const oreal* W, const oreal* bias, oreal* Y,
                    int N, int Cin, int H, int Wd, int Cout, int k, int s, int p);

@@ -65,6 +65,8 @@ def load_library():
     L.gan_set_params.argtypes = [_VP, C.c_int32, C.c_int32, _FP, C.c_int64]
     L.gan_get_grads.argtypes = [_VP, C.c_int32, C.c_int32, _FP, C.c_int64]
     L.gan_get_opt_state.argtypes = [_VP, C.c_int32, C.c_int32, _FP, _FP, _I64P]
+    L.gan_set_opt_state.argtypes = [_VP, C.c_int32, C.c_int32, _FP, _FP, C.c_int64]
+    L.gan_set_bn_running.argtypes = [_VP, C.c_int32, C.c_int32, _FP, _FP, C.c_int64]
     L.gan_get_bn_running.argtypes = [_VP, C.c_int32, C.c_int32, _FP, _FP, C.c_int64]
     L.gan_get_routing.argtypes = [_VP, _IP, _IP]
     L.gan_last_error.argtypes = [_VP]
@@ -227,6 +229,16 @@ class Gan:
         m, v, t = np.empty(P, np.float32), np.empty(P, np.float32), C.c_int64()
         self._check(self.lib.gan_get_opt_state(self.h, which, model, _fp(m), _fp(v), C.byref(t)))
         return m, v, t.value
+
+    def set_opt_state(self, which, model, m, v, t):
+        m = None if m is None else np.ascontiguousarray(m, np.float32)
+        v = None if v is None else np.ascontiguousarray(v, np.float32)
+        self._check(self.lib.gan_set_opt_state(self.h, which, model, None if m is None else _fp(m),
+                                               None if v is None else _fp(v), int(t)))
+
+    def set_bn_running(self, which, model, mean, var):
+        mean, var = np.ascontiguousarray(mean, np.float32), np.ascontiguousarray(var, np.float32)
+        self._check(self.lib.gan_set_bn_running(self.h, which, model, _fp(mean), _fp(var), mean.size))
 
     def get_bn_running(self, which, model):
         B = self.bn_count(which)

@@ -17,6 +17,12 @@
 
 using namespace gan;
 
+namespace gan {
+static thread_local const char* g_launch_error = nullptr;
+void launch_fail(const char* msg) { if (!g_launch_error) g_launch_error = msg; }
+const char* take_launch_error() { const char* e = g_launch_error; g_launch_error = nullptr; return e; }
+}  // namespace gan
+
 namespace {
 
 inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
@@ -65,7 +71,8 @@ struct gan_ctx {
   int L = 0, NB = 0;
   Net G, D;
   GeomTable geoms;
-  RouteBuffers rb;
+  RouteBuffers rb;                 // the set the launch helpers use (the training step's, except inside gan_generate)
+  RouteBuffers rb_gen;             // gan_generate / gan_sample route into this one
   // workspace (storage type unless noted)
   void *zin = nullptr, *xd = nullptr, *dimg = nullptr, *bufA = nullptr, *bufB = nullptr;
   std::vector<void*> gpre, gact, dpre, dact;
@@ -104,6 +111,15 @@ gan_status fail(gan_ctx* c, gan_status s, const std::string& msg) {
   return s;
 }
 
+// After a call has enqueued its launches: a refused launch (shape the kernels do not support) or a HIP launch error.
+gan_status launch_status(gan_ctx* c) {
+  const char* refused = take_launch_error();
+  const hipError_t e = hipGetLastError();
+  if (refused) return fail(c, GAN_E_SHAPE, refused);
+  if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("launch failed: ") + hipGetErrorString(e));
+  return GAN_OK;
+}
+
 bool dev_alloc(gan_ctx* c, void** p, size_t bytes) {
   if (bytes == 0) bytes = 16;
   if (hipMalloc(p, bytes) != hipSuccess) { (void)hipGetLastError(); return false; }
@@ -129,8 +145,8 @@ const int* tpre_of(gan_ctx* c, int rps, int tile_rows) {
   for (int i = 0; i < c->geoms.n; ++i)
     if (c->geoms.rps[i] == rps && c->geoms.tile_rows[i] == tile_rows) g = i;
   if (g < 0) {   // every geometry a launch uses is registered at create; anything else would read an unbuilt prefix
-    fprintf(stderr, "gan: tile geometry (%d, %d) was not registered\n", rps, tile_rows);
-    abort();
+    launch_fail("a launch asked for a tile geometry that was not registered when the context was created");
+    return nullptr;   // the launchers refuse a null prefix array
   }
   return c->rb.tpre + (long long)g * (c->L + 1);
 }
@@ -749,18 +765,21 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) reg(4 * c->G.conv[i].Hs * c->G.conv[i].Hs, BN_RED_ROWS);
     for (size_t j = 1; j < c->D.conv.size(); ++j) reg(c->D.conv[j].Hs * c->D.conv[j].Hs, BN_RED_ROWS);
   }
+  // two sets of routing buffers: the training step's (what gan_get_losses / gan_get_routing report) and one for
+  // gan_generate / gan_sample, so that generating between a step and its queries changes nothing they return
   RouteBuffers& rb = c->rb;
-  ok = ok && dev_alloc(c, (void**)&rb.cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&rb.counts, (size_t)L * 4) &&
-       dev_alloc(c, (void**)&rb.offs, (size_t)(L + 1) * 4) && dev_alloc(c, (void**)&rb.perm, (size_t)NB * 4) &&
-       dev_alloc(c, (void**)&rb.sample_model, (size_t)NB * 4) && dev_alloc(c, (void**)&rb.sample_slot, (size_t)NB * 4) &&
-       dev_alloc(c, (void**)&rb.tpre, (size_t)MAX_GEOMS * (L + 1) * 4) && dev_alloc(c, (void**)&rb.flags, 16) &&
-       dev_alloc(c, (void**)&rb.order, (size_t)L * 4);
-  {
+  for (RouteBuffers* r : {&c->rb, &c->rb_gen}) {
+    ok = ok && dev_alloc(c, (void**)&r->cnt, (size_t)ROUTE_CHUNKS * L * 4) && dev_alloc(c, (void**)&r->counts, (size_t)L * 4) &&
+         dev_alloc(c, (void**)&r->offs, (size_t)(L + 1) * 4) && dev_alloc(c, (void**)&r->perm, (size_t)NB * 4) &&
+         dev_alloc(c, (void**)&r->sample_model, (size_t)NB * 4) && dev_alloc(c, (void**)&r->sample_slot, (size_t)NB * 4) &&
+         dev_alloc(c, (void**)&r->tpre, (size_t)MAX_GEOMS * (L + 1) * 4) && dev_alloc(c, (void**)&r->order, (size_t)L * 4);
     int mx = 1;
     for (int g = 0; g < c->geoms.n; ++g) mx = std::max(mx, ub_tiles(c, NB, c->geoms.rps[g], c->geoms.tile_rows[g]));
-    rb.tmodel_stride = mx;
-    ok = ok && dev_alloc(c, (void**)&rb.tmodel, (size_t)c->geoms.n * mx * 4);
+    r->tmodel_stride = mx;
+    ok = ok && dev_alloc(c, (void**)&r->tmodel, (size_t)c->geoms.n * mx * 4);
   }
+  ok = ok && dev_alloc(c, (void**)&rb.flags, 16);
+  c->rb_gen.flags = rb.flags;                  // one sticky out-of-range flag for both
   const long long img_elems = (long long)cfg->img_hw * cfg->img_hw * cfg->img_c;
   long long max_act = img_elems;
   ok = ok && dev_alloc(c, &c->zin, (size_t)NB * c->G.Kp * es) && dev_alloc(c, &c->xd, (size_t)2 * NB * img_elems * es) &&
@@ -913,11 +932,10 @@ gan_status gan_train_step(gan_ctx* c, const int32_t* label_ids, const float* noi
     hipMemsetAsync(c->loss_g, 0, (size_t)c->L * 4, c->st);
     return GAN_OK;
   }
+  (void)take_launch_error();
   if (c->bf16) train_step<bf16_t>(c, label_ids, noise, real_batch, n);
   else train_step<float>(c, label_ids, noise, real_batch, n);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("launch failed: ") + hipGetErrorString(e));
-  return GAN_OK;
+  return launch_status(c);
 }
 
 gan_status gan_generate(gan_ctx* c, const int32_t* label_ids, const float* noise, int32_t n, float* out_images,
@@ -927,8 +945,10 @@ gan_status gan_generate(gan_ctx* c, const int32_t* label_ids, const float* noise
   if (n == 0) return GAN_OK;
   if (!label_ids || !noise || !out_images) return fail(c, GAN_E_ARG, "null pointer");
   if (c->shadows_dirty) refresh_shadows(c);
-  c->last_n = n;
+  (void)take_launch_error();
   const gan_config& f = c->cfg;
+  const RouteBuffers train_rb = c->rb;         // the launch helpers read c->rb: point them at the generate set
+  c->rb = c->rb_gen;
   if (c->bf16) {
     route_and_stage<bf16_t>(c, label_ids, noise, nullptr, n);
     g_forward<bf16_t>(c, n, use_running_stats != 0, false);
@@ -940,9 +960,8 @@ gan_status gan_generate(gan_ctx* c, const int32_t* label_ids, const float* noise
     launch_unstage<float>((const float*)c->xd + (long long)n * f.img_hw * f.img_hw * f.img_c, out_images, n, c->L, f.img_c,
                           f.img_hw, c->rb, c->st);
   }
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(c, GAN_E_HIP, std::string("launch failed: ") + hipGetErrorString(e));
-  return GAN_OK;
+  c->rb = train_rb;
+  return launch_status(c);
 }
 
 gan_status gan_sample(gan_ctx* c, const double* prior, const float* u, const float* noise, int32_t n, float* out_images,
@@ -1082,6 +1101,39 @@ gan_status gan_set_params(gan_ctx* c, int32_t which, int32_t model, const float*
   return GAN_OK;
 }
 
+static gan_status write_block(gan_ctx* c, Net& net, int model, float* dev_base, const float* src) {
+  std::vector<float> tmp((size_t)net.P, 0.f);
+  for (long long i = 0; i < net.Pext; ++i) tmp[(size_t)net.ext2int[(size_t)i]] = src[i];
+  if (hipMemcpy(dev_base + (long long)model * net.P, tmp.data(), (size_t)net.P * 4, hipMemcpyHostToDevice) != hipSuccess)
+    return fail(c, GAN_E_HIP, "copy failed");
+  return GAN_OK;
+}
+
+gan_status gan_set_opt_state(gan_ctx* c, int32_t which, int32_t model, const float* m, const float* v, int64_t t) {
+  if (!c || which < 0 || which > 1 || model < 0 || model >= c->L || t < 0 || t > 0x7fffffff) return GAN_E_ARG;
+  Net& net = which == 0 ? c->G : c->D;
+  gan_status s = sync(c);
+  if (s == GAN_OK && m) s = write_block(c, net, model, net.m, m);
+  if (s == GAN_OK && v) s = write_block(c, net, model, net.v, v);
+  if (s == GAN_OK) {
+    const int tt = (int)t;
+    if (hipMemcpy(net.t + model, &tt, 4, hipMemcpyHostToDevice) != hipSuccess) return fail(c, GAN_E_HIP, "copy failed");
+  }
+  return s;
+}
+
+gan_status gan_set_bn_running(gan_ctx* c, int32_t which, int32_t model, const float* mean, const float* var, int64_t n) {
+  if (!c || !mean || !var || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
+  Net& net = which == 0 ? c->G : c->D;
+  if (n != net.nbn) return fail(c, GAN_E_ARG, "wrong element count");
+  gan_status s = sync(c);
+  if (s != GAN_OK) return s;
+  if (hipMemcpy(net.run_mean + (long long)model * net.nbn, mean, (size_t)n * 4, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(net.run_var + (long long)model * net.nbn, var, (size_t)n * 4, hipMemcpyHostToDevice) != hipSuccess)
+    return fail(c, GAN_E_HIP, "copy failed");
+  return GAN_OK;
+}
+
 gan_status gan_get_bn_running(gan_ctx* c, int32_t which, int32_t model, float* mean, float* var, int64_t n) {
   if (!c || !mean || !var || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
   Net& net = which == 0 ? c->G : c->D;
@@ -1143,6 +1195,13 @@ gan_status gan_profile_read(gan_ctx* c, int32_t cap, const char** names, int64_t
 }
 
 // ---- single operations ------------------------------------------------------------------------------------
+// enqueue, wait, and report: a refused launch, a launch error, or a failure while running
+static gan_status finish_op(gan_ctx* c) {
+  const gan_status launched = launch_status(c);
+  const gan_status s = sync(c);
+  return launched != GAN_OK ? launched : s;
+}
+
 static gan_status op_common(gan_ctx* c, const int32_t* offs, int n_groups, int rps, int tile_rows, int** tpre_out) {
   int* tp = nullptr;
   if (hipMalloc((void**)&tp, (size_t)(n_groups + 1) * 4) != hipSuccess) return fail(c, GAN_E_OOM, "tile prefix alloc");
@@ -1151,10 +1210,19 @@ static gan_status op_common(gan_ctx* c, const int32_t* offs, int n_groups, int r
   return GAN_OK;
 }
 
+// what the GEMM kernels address with 32-bit byte offsets: one segment of an operand
+static bool fits_32bit(long long samples, long long side, long long channels, size_t es) {
+  return samples * side * side * channels * (long long)es < (1LL << 31);
+}
+
 static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, void* Out, const int32_t* offs, int n_groups,
                           int n_samples, int C, int N, int Hin, int Hr, long long wstride) {
-  if (!c || !A || !W || !Out || !offs || n_groups < 1 || n_samples < 0) return GAN_E_ARG;
-  if (C % 64 || N < 1) return fail(c, GAN_E_SHAPE, "channels must be multiples of 64");
+  if (!c || !A || !W || !Out || !offs || n_groups < 1 || n_samples < 0 || Hr < 1) return GAN_E_ARG;
+  if (C < 64 || N < 64 || C % 64 || N % 64) return fail(c, GAN_E_SHAPE, "channel counts must be multiples of 64");
+  if (!fits_32bit(n_samples, Hin, C, esize(c)) || !fits_32bit(n_samples, 2 * Hr, N, esize(c)) ||
+      16LL * C * N * (long long)esize(c) >= (1LL << 31))
+    return fail(c, GAN_E_SHAPE, "an operand of 2 GiB or more (the kernels use 32-bit byte offsets)");
+  (void)take_launch_error();
   int* tp = nullptr;
   const int tr = conv_tile_rows(N, (long long)n_samples * Hr * Hr / n_groups);
   gan_status s = op_common(c, offs, n_groups, Hr * Hr, tr, &tp);
@@ -1164,10 +1232,8 @@ static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, vo
   a.seg_first = 0; a.nseg = 1; a.seg_samples = n_samples; a.C = C; a.N = N; a.Hin = Hin; a.Hr = Hr;
   a.ub_tiles = (int)(((long long)n_samples * Hr * Hr) / tr) + n_groups; a.slope = 0.f; a.tile_rows = tr;
   if (c->bf16) launch_conv<bf16_t>(mode, EPI_NONE, a, c->st); else launch_conv<float>(mode, EPI_NONE, a, c->st);
-  s = sync(c);
+  s = finish_op(c);
   (void)hipFree(tp);
-  const hipError_t e = hipGetLastError();
-  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
   return s;
 }
 
@@ -1181,16 +1247,16 @@ gan_status gan_op_conv_up(gan_ctx* c, const void* small_in, const void* w_up, vo
 }
 gan_status gan_op_conv_wgrad(gan_ctx* c, const void* big, const void* small_in, float* dw, const int32_t* offs,
                              int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs) {
-  if (!c || !big || !small_in || !dw || !offs || n_groups < 1 || n_samples < 0) return GAN_E_ARG;
-  if ((16 * cb) % 128 || cb % 8 || cs % 8) return fail(c, GAN_E_SHAPE, "unsupported channel counts");
+  if (!c || !big || !small_in || !dw || !offs || n_groups < 1 || n_samples < 0 || hs < 1) return GAN_E_ARG;
+  if (cb < 8 || cs < 8 || (16 * cb) % 128 || cb % 8 || cs % 8) return fail(c, GAN_E_SHAPE, "unsupported channel counts");
+  if (!fits_32bit(n_samples, 2 * hs, cb, esize(c)) || !fits_32bit(n_samples, hs, cs, esize(c)))
+    return fail(c, GAN_E_SHAPE, "an operand of 2 GiB or more (the kernels use 32-bit byte offsets)");
+  (void)take_launch_error();
   WgradArgs a = {};
   a.Big = big; a.Small = small_in; a.dW = dw; a.offs = offs; a.dw_stride = (long long)16 * cb * cs;
   a.L = n_groups; a.nseg = 1; a.seg_samples = n_samples; a.Cb = cb; a.Cs = cs; a.Hs = hs; a.ntaps = 16; a.ksplit = 1;
   if (c->bf16) launch_wgrad<bf16_t>(a, c->st); else launch_wgrad<float>(a, c->st);
-  gan_status s = sync(c);
-  const hipError_t e = hipGetLastError();
-  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
-  return s;
+  return finish_op(c);
 }
 
 gan_status gan_op_dropout(gan_ctx* c, void* x, const int32_t* offs, int32_t n_groups, int32_t n_samples, int32_t ch, int32_t h,
@@ -1199,29 +1265,23 @@ gan_status gan_op_dropout(gan_ctx* c, void* x, const int32_t* offs, int32_t n_gr
       pass_id < 0)
     return GAN_E_ARG;
   if (!(p >= 0.f && p < 1.f)) return fail(c, GAN_E_ARG, "dropout probability outside [0, 1)");
+  (void)take_launch_error();
   if (c->bf16) launch_dropout<bf16_t>(static_cast<bf16_t*>(x), offs, n_groups, n_samples, ch, h, w, p, seed, step, layer, pass_id, c->st);
   else launch_dropout<float>(static_cast<float*>(x), offs, n_groups, n_samples, ch, h, w, p, seed, step, layer, pass_id, c->st);
-  gan_status s = sync(c);
-  const hipError_t e = hipGetLastError();
-  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
-  return s;
+  return finish_op(c);
 }
 gan_status gan_op_w3_to_w4(gan_ctx* c, const float* w3, void* w4, void* w4t, int32_t n_groups, int32_t cb, int32_t cs) {
   if (!c || !w3 || !w4 || !w4t || n_groups < 1 || cb < 1 || cs < 1) return GAN_E_ARG;
+  (void)take_launch_error();
   if (c->bf16) launch_w3_to_w4<bf16_t>(w3, static_cast<bf16_t*>(w4), static_cast<bf16_t*>(w4t), n_groups, cb, cs, c->st);
   else launch_w3_to_w4<float>(w3, static_cast<float*>(w4), static_cast<float*>(w4t), n_groups, cb, cs, c->st);
-  gan_status s = sync(c);
-  const hipError_t e = hipGetLastError();
-  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
-  return s;
+  return finish_op(c);
 }
 gan_status gan_op_dw4_to_dw3(gan_ctx* c, const float* dw4, float* dw3, int32_t n_groups, int32_t cb, int32_t cs) {
   if (!c || !dw4 || !dw3 || n_groups < 1 || cb < 1 || cs < 1) return GAN_E_ARG;
+  (void)take_launch_error();
   launch_dw4_to_dw3(dw4, dw3, n_groups, cb, cs, c->st);
-  gan_status s = sync(c);
-  const hipError_t e = hipGetLastError();
-  if (s == GAN_OK && e != hipSuccess) return fail(c, GAN_E_HIP, hipGetErrorString(e));
-  return s;
+  return finish_op(c);
 }
 
 }  // extern "C"

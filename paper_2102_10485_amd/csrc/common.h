@@ -33,6 +33,11 @@ template <> __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
   return r;
 }
 
+// A host launcher that finds its assumptions violated records the reason and launches nothing; the library call in
+// progress then returns an error status with this text (nothing in the library ends the process).
+void launch_fail(const char* msg);
+const char* take_launch_error();   // the first reason recorded on this thread since the last call, or nullptr
+
 enum ConvMode { MODE_DOWN = 0, MODE_UP = 1, MODE_DENSE = 2 };
 enum Epilogue { EPI_NONE = 0, EPI_ACT_BWD = 1, EPI_LRELU = 2 };
 enum Act { ACT_RELU = 0, ACT_LRELU = 1 };

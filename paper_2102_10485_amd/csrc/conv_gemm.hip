@@ -517,7 +517,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
 
 template <typename T, int MODE, int EPI, typename TL>
 static void launch_one(ConvArgs a, hipStream_t st) {
-  if (a.tile_rows != TL::BM) abort();            // the tile prefix array must have been built for this tile height
+  if (a.tile_rows != TL::BM) return launch_fail("GEMM: the tile prefix array was built for another tile height");
   a.hr_shift = log2_or_neg(a.Hr);
   const int NT = (a.N + TL::BN - 1) / TL::BN;
   const long long blocks = ((long long)a.ub_tiles * NT * a.nseg * (MODE == MODE_UP ? 4 : 1) + 7) / 8 * 8;
@@ -540,21 +540,21 @@ void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
   // the kernel's assumptions, checked before anything is launched
   if (!a.A || !a.W || !a.Out || !a.offs || !a.tpre || a.N < 1 || a.w_nstride < a.N || a.C % (128 / (int)sizeof(T)) != 0 ||
       (epi == EPI_ACT_BWD && !a.Aux))
-    abort();
-  if (a.N < 64) abort();                        // image-side outputs have their own kernel
+    return launch_fail("GEMM: null operand, or channel counts that are not whole 128-byte lines");
+  if (a.N < 64) return launch_fail("GEMM: fewer than 64 output channels (image-side outputs have their own kernel)");
   {
     // the loaders address one model's slice of A and one weight block with 32-bit byte offsets
     const long long side = mode == MODE_DENSE ? a.Hr : a.Hin;
     if ((long long)a.seg_samples * side * side * a.C * (long long)sizeof(T) >= (1LL << 31) ||
         16LL * a.w_nstride * a.C * (long long)sizeof(T) >= (1LL << 31))
-      abort();
+      return launch_fail("GEMM: one segment of the gathered tensor, or one weight block, is 2 GiB or larger");
   }
   if (mode == MODE_DOWN && epi == EPI_NONE) return launch_wide<T, MODE_DOWN, EPI_NONE>(a, st);
   if (mode == MODE_UP && epi == EPI_NONE) return launch_wide<T, MODE_UP, EPI_NONE>(a, st);
   if (mode == MODE_UP && epi == EPI_ACT_BWD) return launch_wide<T, MODE_UP, EPI_ACT_BWD>(a, st);
   if (mode == MODE_DENSE && epi == EPI_NONE) return launch_wide<T, MODE_DENSE, EPI_NONE>(a, st);
   if (mode == MODE_DENSE && epi == EPI_LRELU) return launch_wide<T, MODE_DENSE, EPI_LRELU>(a, st);
-  abort();   // a combination no caller uses
+  launch_fail("GEMM: (mode, epilogue) combination without an instantiation");
 }
 // Name of the kernel instantiation launch_conv picks (for per-kernel timing): mode, epilogue, tile.
 const char* conv_variant_name(int mode, int epi, const ConvArgs& a) {
@@ -1004,7 +1004,7 @@ static void launch_wgrad_one(WgradArgs a, hipStream_t st) {
     // 32-bit byte offsets inside one model's slice of either operand
     const long long side = a.ntaps == 1 ? a.Hs : 2 * a.Hs;
     if ((long long)a.seg_samples * side * side * a.Cb * 2 >= (1LL << 31) || (long long)a.seg_samples * a.Hs * a.Hs * a.Cs * 2 >= (1LL << 31))
-      abort();
+      return launch_fail("weight gradient: one segment of an operand is 2 GiB or larger");
     hipLaunchKernelGGL((wgrad_tr_kernel<TL>), dim3((unsigned)blocks), dim3(TL::NT), 0, st, a);
   } else {
     hipLaunchKernelGGL((wgrad_kernel<T, TL>), dim3((unsigned)blocks), dim3(TL::NT), 0, st, a);
@@ -1015,7 +1015,7 @@ template <typename T>
 void launch_wgrad(const WgradArgs& a, hipStream_t st) {
   if (!a.Big || !a.Small || !a.dW || !a.offs || a.Cb % 8 || a.Cs % 8 || (a.ntaps != 1 && a.ntaps != 16) || a.ksplit < 1 ||
       (a.ksplit > 1 && a.split_stride <= 0))
-    abort();
+    return launch_fail("weight gradient: null operand, channel counts that are not multiples of 8, or a bad row split");
   if (a.ntaps * a.Cb <= 64) return launch_wgrad_one<T, TileWgImg>(a, st);
   if (a.Cs % 256 == 0) return launch_wgrad_one<T, TileBig>(a, st);
   return launch_wgrad_one<T, TileMid>(a, st);

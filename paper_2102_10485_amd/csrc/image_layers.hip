@@ -437,11 +437,12 @@ __global__ __launch_bounds__(256) void up_img_kernel(UpImgArgs a) {
 }
 template <typename T> void launch_up_img(const UpImgArgs& a, hipStream_t st) {
   if (a.n == 0) return;
-  if (!a.feat || !a.w || !a.out || a.CB < 1 || a.CB > 4 || (a.Cs != 64 && a.Cs != 128) || (a.mode == 1 && !a.bias) || (a.mode == 2 && !a.aux)) abort();
+  if (!a.feat || !a.w || !a.out || a.CB < 1 || a.CB > 4 || (a.Cs != 64 && a.Cs != 128) || (a.mode == 1 && !a.bias) || (a.mode == 2 && !a.aux))
+    return launch_fail("image-side transposed convolution: null operand, more than 4 image channels, or feature channels other than 64 / 128");
   const int tiles = (a.Hs + UP_TS - 1) / UP_TS;
   const int rowB = a.Cs * (int)sizeof(T) + 16;
   const size_t lds = (size_t)(UP_HALO * UP_HALO + 16 * a.CB) * rowB;
-  if (lds > 160 * 1024) abort();
+  if (lds > 160 * 1024) return launch_fail("image-side transposed convolution: tile does not fit the LDS");
   if (a.Cs == 64) {
     hipLaunchKernelGGL((up_img_kernel<T, 64>), dim3(tiles * tiles, a.n), dim3(256), lds, st, a);
   } else if (a.Cs == 128) {
@@ -449,8 +450,6 @@ template <typename T> void launch_up_img(const UpImgArgs& a, hipStream_t st) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_img_kernel<T, 128>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds);
     hipLaunchKernelGGL((up_img_kernel<T, 128>), dim3(tiles * tiles, a.n), dim3(256), lds, st, a);
-  } else {
-    abort();
   }
 }
 template void launch_up_img<float>(const UpImgArgs&, hipStream_t);

@@ -52,7 +52,7 @@ void launch_dropout(T* x, const int* offs, int n_groups, int n, int C, int H, in
                     int layer, int pass_id, hipStream_t st) {
   const long long total = (long long)n * H * W * C;
   if (total == 0) return;
-  if (!(p >= 0.f && p < 1.f) || n_groups < 1) abort();
+  if (!(p >= 0.f && p < 1.f) || n_groups < 1) return launch_fail("dropout: probability outside [0, 1), or no group");
   const double t = ceil((double)p * 16777216.0);
   hipLaunchKernelGGL((dropout_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, offs, n_groups, total, C, H, W,
                      (unsigned)t, 1.0f / (1.0f - p), (unsigned)(seed & 0xffffffffull), (unsigned)(seed >> 32),

@@ -102,7 +102,8 @@ __global__ __launch_bounds__(256) void sum_splits_kernel(const float* __restrict
   *reinterpret_cast<float4*>(dW + (long long)l * dw_stride + 4 * i) = s;
 }
 void launch_sum_splits(const float* part, float* dW, long long dw_stride, long long size, int L, int nsplit, hipStream_t st) {
-  if (size % 4 != 0 || dw_stride % 4 != 0 || ((uintptr_t)dW & 15) != 0 || ((uintptr_t)part & 15) != 0) abort();
+  if (size % 4 != 0 || dw_stride % 4 != 0 || ((uintptr_t)dW & 15) != 0 || ((uintptr_t)part & 15) != 0)
+    return launch_fail("sum of row splits: sizes and pointers must be multiples of 16 bytes");
   const long long tot = size / 4 * L;
   if (tot == 0) return;
   hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, part, dW, dw_stride, size / 4, L, nsplit);
@@ -329,6 +330,7 @@ void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const
                                   int groups, int tile_rows, int gemm_rps, hipStream_t st) {
   const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
   if (tot == 0) return;
+  if (!tpre || !partial) return launch_fail("BatchNorm statistics: no tile prefix array or no partial sums");
   hipLaunchKernelGGL(bn_stats_from_partial_kernel, dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
                      groups, tile_rows, gemm_rps);
 }
@@ -517,8 +519,9 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_final_kernel(NormArgs a, co
 template <typename T>
 void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, const int* tmodel, int ub_tiles, float* partial, hipStream_t st) {
   if (a.nseg == 0 || ub_tiles == 0) return;
+  if (!tpre) return launch_fail("BatchNorm backward: no tile prefix array");
   const int cg = a.C / Vec16<T>::N;
-  if (cg < 1 || cg > 256) abort();                  // one thread per 16 bytes of a row
+  if (cg < 1 || cg > 256) return launch_fail("BatchNorm backward: one thread per 16 bytes of a row needs at most 256 of them");
   const size_t lds = (size_t)2 * (256 / cg) * a.C * sizeof(float);
   hipLaunchKernelGGL((bn_bwd_reduce_kernel<T>), dim3(ub_tiles, a.nseg), dim3(256), lds, st, a, tpre, tmodel, ub_tiles, partial);
   const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
@@ -747,7 +750,7 @@ __global__ void head_bwd_w_final_kernel(HeadArgs a) {
   else a.db[(long long)l * a.pstride] = s;
 }
 template <typename T> void launch_head_bwd_w(const HeadArgs& a, hipStream_t st) {
-  if (a.K % 4 != 0 || (a.rsplit > 1 && !a.part)) abort();
+  if (a.K % 4 != 0 || (a.rsplit > 1 && !a.part)) return launch_fail("linear head: feature count not a multiple of 4, or no buffer for the row splits");
   const int rsplit = a.rsplit > 1 ? a.rsplit : 1;
   hipLaunchKernelGGL((head_bwd_w_kernel<T>), dim3((a.K + 1023) / 1024, a.L, rsplit), dim3(256), 0, st, a);
   if (rsplit > 1) {
@@ -873,21 +876,21 @@ __global__ __launch_bounds__(256) void adam_tile_kernel(AdamArgs a) {
 template <typename T>
 void launch_adam(AdamArgs a, hipStream_t st) {
   // regions sorted by offset are the caller's job; the gaps between them cover the rest of [0, P)
-  if (a.nregions < 0 || a.nregions > ADAM_MAX_REGIONS || a.P % 8) abort();
+  if (a.nregions < 0 || a.nregions > ADAM_MAX_REGIONS || a.P % 8) return launch_fail("Adam: too many weight regions, or a parameter block that is not a multiple of 8");
   long long pos = 0;
   a.ngaps = 0;
   a.reg_tile0[0] = 0;
   a.gap_blk0[0] = 0;
   for (int r = 0; r <= a.nregions; ++r) {
     const long long lo = r < a.nregions ? a.reg_w[r] : a.P;
-    if (lo < pos || lo % 4) abort();
+    if (lo < pos || lo % 4) return launch_fail("Adam: weight regions must be sorted and 16-byte aligned");
     if (lo > pos) {
       a.gap_lo[a.ngaps] = pos; a.gap_hi[a.ngaps] = lo;
       a.gap_blk0[a.ngaps + 1] = a.gap_blk0[a.ngaps] + (int)((lo - pos + 1023) / 1024);
       ++a.ngaps;
     }
     if (r < a.nregions) {
-      if (a.reg_cb[r] % 64 || a.reg_cs[r] % 64 || !a.shadow_t) abort();
+      if (a.reg_cb[r] % 64 || a.reg_cs[r] % 64 || !a.shadow_t) return launch_fail("Adam: tiled regions need channel counts that are multiples of 64");
       a.reg_tile0[r + 1] = a.reg_tile0[r] + 16 * (a.reg_cb[r] / 64) * (a.reg_cs[r] / 64);
       pos = lo + 16LL * a.reg_cb[r] * a.reg_cs[r];
     }
