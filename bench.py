@@ -144,6 +144,99 @@ def other_rows(args, torch, binding, work, gan, prec, prec_name, d_lab, d_real, 
     print(json.dumps(out_j))
 
 
+def build_workload(args, config, torch, binding, synth, prec_name, single_pair=None):
+    """Context, resident inputs and description of one workload."""
+    work = synth.Workload(config)
+    prec = binding.BF16 if prec_name == "bf16" else binding.FP32
+    n = work.n
+    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
+    spec, n_models, n_labels, descr = work.spec, work.n_models, work.n_labels, DESCR[config]
+    img_lab = lab                              # the classes the real images are drawn from
+    if single_pair:
+        spec, n_models = dict(work.spec), 1
+        if single_pair == "cgan":
+            n_labels = max(work.n_labels, 2)
+            spec["cond_g"] = spec["cond_d"] = n_labels
+            # one model owns the whole batch, and the library addresses one model's slice of any tensor with 32-bit
+            # byte offsets; the largest slice is the patch matrix of D's first layer
+            kc = -(-(16 * spec["img_c"] + 9 * n_labels + 1) // 64) * 64
+            row_bytes = kc * (2 if prec_name == "bf16" else 4) * (spec["img_hw"] // 2) ** 2
+            n = min(n, ((1 << 31) - 1) // row_bytes // 64 * 64)
+            descr = "one conditional pair (all %d labels) of config %d's widths, batch %d" % (n_labels, config, n)
+        else:
+            n_labels = 1
+            spec["cond_g"] = spec["cond_d"] = 0
+            descr = "one unconditional pair of config %d's widths, batch %d" % (config, n)
+            lab = np.zeros_like(lab)
+        lab, img_lab = lab[:n], img_lab[:n]
+    cfg = binding.make_config(spec, n_models, n_labels, n, prec, seed=work.seed)
+    gan = binding.Gan(cfg, torch.cuda.current_stream().cuda_stream)
+    d_lab = torch.from_numpy(lab).cuda()
+    d_real = torch.from_numpy(work.images(img_lab)).cuda()
+    d_noise = [torch.from_numpy(work.noise()[:n].copy()).cuda() for _ in range(4)]
+    torch.cuda.synchronize()
+    return dict(work=work, gan=gan, prec=prec, n=n, n_models=n_models, descr=descr, d_lab=d_lab, d_real=d_real, d_noise=d_noise)
+
+
+def time_steps(torch, w, steps, warmup):
+    """W warm-up steps, then K steps between two synchronisations: milliseconds per step (no per-kernel timing on)."""
+    gan, n = w["gan"], w["n"]
+
+    def step(i):
+        gan.train_step(w["d_lab"].data_ptr(), w["d_noise"][i % 4].data_ptr(), w["d_real"].data_ptr(), n)
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    jd, jg, cnt = gan.get_losses()
+    assert np.all(np.isfinite(jd)) and np.all(np.isfinite(jg)) and int(cnt.sum()) == n
+    return 1e3 * dt / steps
+
+
+def kernel_timings(torch, w, steps, detail=False, gemm_only=False):
+    """`steps` more steps with HIP events around the launches on the library's stream: per kernel family the launches
+    per step, milliseconds, and the algorithmic flops and bytes those launches stood for."""
+    gan, n = w["gan"], w["n"]
+    gan.profile_enable(True, detail=detail, gemm_only=gemm_only)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        gan.train_step(w["d_lab"].data_ptr(), w["d_noise"][i % 4].data_ptr(), w["d_real"].data_ptr(), n)
+    torch.cuda.synchronize()
+    ms_instr = 1e3 * (time.perf_counter() - t0) / steps
+    prof = gan.profile_read()
+    gan.profile_enable(False)
+    kern = {}
+    for name, r in prof.items():
+        kern[name] = {"launches_per_step": r["launches"] / steps, "ms_per_step": r["ms"] / steps,
+                      "avg_launch_ms": r["ms"] / max(r["launches"], 1),
+                      "tflops": r["flops"] / (r["ms"] * 1e9) if r["ms"] > 0 else 0.0,
+                      "gbps": r["bytes"] / (r["ms"] * 1e6) if r["ms"] > 0 else 0.0,
+                      "flops_per_launch": r["flops"] / max(r["launches"], 1), "bytes_per_launch": r["bytes"] / max(r["launches"], 1)}
+    return kern, ms_instr
+
+
+def is_mfma(name):
+    return name.startswith("gemm_") or name.startswith("wgrad")
+
+
+def mfma_summary(kern, peak):
+    gemm = [k for k in kern if is_mfma(k)]
+    ms = sum(kern[k]["ms_per_step"] for k in gemm)
+    fl = sum(kern[k]["flops_per_launch"] * kern[k]["launches_per_step"] for k in gemm)
+    return {"tflops": fl / (ms * 1e9), "frac_of_peak": fl / (ms * 1e9) / peak, "ms_per_step": ms}
+
+
+# the bandwidth-bound kernel families reported against the HBM peak (algorithmic bytes: every input read once, every
+# output written once, in the storage type; Adam: 28 B per parameter plus the storage-type copies)
+ELEMENTWISE = ("adam", "bn_apply", "bn_bwd_reduce", "bn_bwd_apply", "im2col", "up_img", "head_fwd", "head_bwd_data", "head_bwd_w",
+               "stage", "transpose_w")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -152,10 +245,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 0-4 (default: 2, the largest)")
     ap.add_argument("--precision", choices=["fp32", "bf16"], default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-profile", action="store_true", help="do not time individual kernels (no roofline object)")
-    ap.add_argument("--detail", action="store_true", help="time every kernel, one line per layer shape (analysis runs)")
-    ap.add_argument("--all-kernels", action="store_true",
-                    help="time every kernel, not only the MFMA ones (two stream-draining events per launch: slower steps)")
+    ap.add_argument("--no-profile", action="store_true", help="no per-kernel timing pass (no roofline object)")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the short runs of the other workloads (`configs` object)")
+    ap.add_argument("--detail", action="store_true", help="per-kernel pass with one line per layer shape (analysis runs)")
     ap.add_argument("--row", choices=["train", "sample", "anova"], default="train",
                     help="train (default): the training step; sample: mixture sampling (Eq. 5) of images_per_step images per "
                          "call; anova: the per-channel F-statistic of one batch")
@@ -177,110 +269,91 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP library has no CPU fallback")
     torch.cuda.set_device(0)
-    work = synth.Workload(args.config)
-    prec_name = args.precision or work.precision
-    prec = binding.BF16 if prec_name == "bf16" else binding.FP32
-    n = work.n
-    lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
-    spec, n_models, n_labels, descr = work.spec, work.n_models, work.n_labels, DESCR[args.config]
-    img_lab = lab                              # the classes the real images are drawn from
-    if args.single_pair:
-        if args.row != "train":
-            sys.exit("bench.py: --single-pair goes with the train row")
-        spec, n_models = dict(work.spec), 1
-        if args.single_pair == "cgan":
-            n_labels = max(work.n_labels, 2)
-            spec["cond_g"] = spec["cond_d"] = n_labels
-            # one model owns the whole batch, and the library addresses one model's slice of any tensor with 32-bit
-            # byte offsets; the largest slice is the patch matrix of D's first layer
-            kc = -(-(16 * spec["img_c"] + 9 * n_labels + 1) // 64) * 64
-            row_bytes = kc * (2 if prec_name == "bf16" else 4) * (spec["img_hw"] // 2) ** 2
-            n = min(n, ((1 << 31) - 1) // row_bytes // 64 * 64)
-            descr = "one conditional pair (all %d labels) of config %d's widths, batch %d" % (n_labels, args.config, n)
-        else:
-            n_labels = 1
-            spec["cond_g"] = spec["cond_d"] = 0
-            descr = "one unconditional pair of config %d's widths, batch %d" % (args.config, n)
-            lab = np.zeros_like(lab)
-        lab, img_lab = lab[:n], img_lab[:n]
-    cfg = binding.make_config(spec, n_models, n_labels, n, prec, seed=work.seed)
-    gan = binding.Gan(cfg, torch.cuda.current_stream().cuda_stream)
-
-    d_lab = torch.from_numpy(lab).cuda()
-    d_real = torch.from_numpy(work.images(img_lab)).cuda()
-    d_noise = [torch.from_numpy(work.noise()[:n].copy()).cuda() for _ in range(4)]
-    torch.cuda.synchronize()
+    if args.single_pair and args.row != "train":
+        sys.exit("bench.py: --single-pair goes with the train row")
+    prec_name = args.precision or synth.Workload(args.config).precision
+    w = build_workload(args, args.config, torch, binding, synth, prec_name, args.single_pair)
+    work, gan, n = w["work"], w["gan"], w["n"]
 
     if args.row != "train":
-        return other_rows(args, torch, binding, work, gan, prec, prec_name, d_lab, d_real, d_noise, n)
+        return other_rows(args, torch, binding, work, gan, w["prec"], prec_name, w["d_lab"], w["d_real"], w["d_noise"], n)
 
-    def step(i):
-        gan.train_step(d_lab.data_ptr(), d_noise[i % 4].data_ptr(), d_real.data_ptr(), n)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
     if args.copy_probe:
+        time_steps(torch, w, 1, 1)
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         dst = torch.empty_like(src)
         torch.add(src, 1.0, out=dst)      # one elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_profile:
-        gan.profile_enable(True, detail=args.detail, gemm_only=not (args.detail or args.all_kernels))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    jd, jg, cnt = gan.get_losses()
-    assert np.all(np.isfinite(jd)) and np.all(np.isfinite(jg)) and int(cnt.sum()) == n
-
+    # the timed region: K steps with nothing but the step's own launches in the stream
+    ms_per_step = time_steps(torch, w, args.steps, args.warmup)
     out = {
-        "metric": "training images/sec (G+D step, all labels)", "value": n * args.steps / dt, "unit": "images/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "metric": "training images/sec (G+D step, all labels)", "value": n * 1e3 / ms_per_step, "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": prec_name, "data": "synthetic",
-        "config": {"workload": descr + (", %s" % prec_name), "n_models": n_models, "images_per_step": n,
+        "config": {"workload": w["descr"] + (", %s" % prec_name), "n_models": w["n_models"], "images_per_step": n,
                    "batch_sizes": "min %d / median %d / max %d" % (work.batch_sizes.min(), np.median(work.batch_sizes),
                                                                   work.batch_sizes.max()) if not args.single_pair else str(n)},
     }
+    peak = PEAK["mfma_bf16"] if prec_name == "bf16" else PEAK["mfma_fp32"]
     if not args.no_profile:
-        prof = gan.profile_read()
-        gan.profile_enable(False)
-        kern = {}
-        for name, r in prof.items():
-            per = r["ms"] / max(r["launches"], 1)
-            kern[name] = {"launches_per_step": r["launches"] / args.steps, "ms_per_step": r["ms"] / args.steps,
-                          "avg_launch_ms": per,
-                          "tflops": r["flops"] / (r["ms"] * 1e9) if r["ms"] > 0 else 0.0,
-                          "gbps": r["bytes"] / (r["ms"] * 1e6) if r["ms"] > 0 else 0.0}
+        # the same K steps again with HIP events on the library's stream around the MFMA launches (the roofline's
+        # launch durations), then a few with events around every launch (the bandwidth-bound families)
+        kern, ms_instr = kernel_timings(torch, w, args.steps, detail=args.detail, gemm_only=not args.detail)
         if args.detail:
             for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_per_step"]):
                 print("%-44s %5.1f launches %8.3f ms/step %8.1f TFLOP/s %8.1f GB/s" % (k, v["launches_per_step"], v["ms_per_step"], v["tflops"], v["gbps"]), file=sys.stderr)
-        gemm = [k for k in kern if k.startswith("gemm_") or k.startswith("wgrad")]
+        gemm = [k for k in kern if is_mfma(k)]
         dom = max(gemm, key=lambda k: kern[k]["ms_per_step"])
-        peak = PEAK["mfma_bf16"] if prec_name == "bf16" else PEAK["mfma_fp32"]
+        traffic = measured_traffic(dom, "config %d %s" % (args.config, prec_name))
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": kern[dom]["tflops"], "peak": peak,
-                           "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / peak,
-                           "traffic": measured_traffic(dom, "config %d %s" % (args.config, prec_name)),
-                           "traffic_unit": "HBM bytes per launch (counters)",
-                           "algorithmic_bytes": prof[dom]["bytes"] / max(prof[dom]["launches"], 1),
-                           "avg_launch_ms": kern[dom]["avg_launch_ms"]}
-        gemm_ms = sum(kern[k]["ms_per_step"] for k in gemm)
-        gemm_fl = sum(prof[k]["flops"] for k in gemm) / args.steps
-        out["conv_mfma"] = {"tflops": gemm_fl / (gemm_ms * 1e9), "frac_of_peak": gemm_fl / (gemm_ms * 1e9) / peak,
-                            "ms_per_step": gemm_ms}
+                           "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / peak, "traffic": traffic,
+                           "traffic_unit": "HBM bytes per launch",
+                           "traffic_source": ("stored hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                                              "command with these kernel sources, profiles/hbm_traffic_config2_bf16.md), not measured by "
+                                              "this run") if traffic is not None else
+                                             "none: the kernel sources changed since the counters were taken",
+                           "algorithmic_flops_per_launch": kern[dom]["flops_per_launch"],
+                           "algorithmic_bytes": kern[dom]["bytes_per_launch"],
+                           "avg_launch_ms": kern[dom]["avg_launch_ms"],
+                           "timing": "HIP events on the library's stream around every launch of this kernel in %d steps that repeat the "
+                                     "timed region (%.3f ms/step with the events in the stream)" % (args.steps, ms_instr)}
+        out["conv_mfma"] = mfma_summary(kern, peak)
+        allk, ms_all = kernel_timings(torch, w, min(args.steps, 5))
+        out["elementwise"] = {k: {"launches_per_step": round(v["launches_per_step"], 2), "ms_per_step": round(v["ms_per_step"], 4),
+                                  "gbps": round(v["gbps"], 1), "frac_of_hbm_peak": round(v["gbps"] / PEAK["hbm"], 4)}
+                              for k, v in sorted(allk.items(), key=lambda kv: -kv[1]["ms_per_step"]) if k in ELEMENTWISE}
+        out["elementwise_note"] = ("algorithmic bytes (inputs read once, outputs written once, storage type; Adam 28 B per parameter + "
+                                   "storage copies) / HIP-event time, against 8 TB/s; %d steps with events around every launch" % min(args.steps, 5))
         # the same figures against what the simplest kernels reach on this chip (register-only MFMA loop, plain copy)
-        mfma_meas = binding.probe_mfma(prec, torch.cuda.current_stream().cuda_stream)
+        mfma_meas = binding.probe_mfma(w["prec"], torch.cuda.current_stream().cuda_stream)
         copy_meas = binding.probe_copy(1 << 30, torch.cuda.current_stream().cuda_stream)
         out["measured_ceilings"] = {"mfma_loop_tflops": mfma_meas, "device_copy_gbps": copy_meas,
                                     "roofline_frac_of_mfma_loop": kern[dom]["tflops"] / mfma_meas,
-                                    "conv_mfma_frac_of_mfma_loop": gemm_fl / (gemm_ms * 1e9) / mfma_meas}
-        out["kernels"] = {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(kern.items(),
-                                                                                        key=lambda kv: -kv[1]["ms_per_step"])}
-        out["kernel_ms_sum"] = sum(v["ms_per_step"] for v in kern.values())
+                                    "conv_mfma_frac_of_mfma_loop": out["conv_mfma"]["tflops"] / mfma_meas}
+        out["kernels"] = {k: {kk: round(vv, 4) for kk, vv in v.items() if not kk.endswith("_per_launch")}
+                          for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_per_step"])}
     gan.close()
+    del w
+    if not args.no_profile and not args.no_other_configs and not args.single_pair and args.config == 2:
+        # the other workloads and the comparison systems, a few steps each (parity-test cases, not the headline)
+        others = {}
+        runs = [("config 0 fp32", 0, "fp32", None), ("config 1 fp32", 1, "fp32", None), ("config 1 bf16", 1, "bf16", None),
+                ("config 3 bf16", 3, "bf16", None), ("config 4 bf16", 4, "bf16", None),
+                ("single pair gan (config 2 widths) bf16", 2, "bf16", "gan"), ("single pair cgan (config 2 widths) bf16", 2, "bf16", "cgan")]
+        for name, cfg_id, pn, sp in runs:
+            torch.cuda.empty_cache()
+            ww = build_workload(args, cfg_id, torch, binding, synth, pn, sp)
+            ms = time_steps(torch, ww, 10, 3)
+            kk, _ = kernel_timings(torch, ww, 5, gemm_only=True)
+            pk = PEAK["mfma_bf16"] if pn == "bf16" else PEAK["mfma_fp32"]
+            mm = mfma_summary(kk, pk)
+            others[name] = {"workload": ww["descr"], "ms_per_step": round(ms, 4), "images_per_s": round(ww["n"] * 1e3 / ms, 1),
+                            "conv_mfma_tflops": round(mm["tflops"], 2), "conv_mfma_frac_of_peak": round(mm["frac_of_peak"], 4),
+                            "mfma_peak_tflops": pk}
+            ww["gan"].close()
+            del ww
+        out["configs"] = others
     if not args.no_cpu_baseline and not args.single_pair:
         out["cpu_baseline"] = cpu_baseline(synth.Workload(args.config))
     print(json.dumps(out))

@@ -85,6 +85,8 @@ def lib(real=np.float64):
         _lib.oracle_set_params.argtypes = [C.c_void_p, C.c_int, C.c_int, _D]
         _lib.oracle_get_grads.argtypes = [C.c_void_p, C.c_int, C.c_int, _D]
         _lib.oracle_get_opt_state.argtypes = [C.c_void_p, C.c_int, C.c_int, _D, _D, C.POINTER(C.c_int64)]
+        _lib.oracle_set_opt_state.argtypes = [C.c_void_p, C.c_int, C.c_int, _D, _D, C.c_int64]
+        _lib.oracle_set_bn_running.argtypes = [C.c_void_p, C.c_int, C.c_int, _D, _D]
         _lib.oracle_get_bn_running.argtypes = [C.c_void_p, C.c_int, C.c_int, _D, _D]
         _lib.oracle_train_step.argtypes = [C.c_void_p, _I, _D, _D, C.c_int32, C.c_int32]
         _lib.oracle_generate.argtypes = [C.c_void_p, _I, _D, C.c_int32, _D, C.c_int32, C.c_int32]
@@ -193,6 +195,24 @@ class Oracle:
         m, v, t = np.empty(P, self.real), np.empty(P, self.real), C.c_int64()
         assert self.L.oracle_get_opt_state(self.h, which, model, _d(m), _d(v), C.byref(t)) == 0
         return m, v, t.value
+
+    def set_opt_state(self, which, model, m, v, t):
+        m, v = np.ascontiguousarray(m, self.real), np.ascontiguousarray(v, self.real)
+        assert self.L.oracle_set_opt_state(self.h, which, model, _d(m), _d(v), int(t)) == 0
+
+    def set_bn_running(self, which, model, mean, var):
+        mean, var = np.ascontiguousarray(mean, self.real), np.ascontiguousarray(var, self.real)
+        assert self.L.oracle_set_bn_running(self.h, which, model, _d(mean), _d(var)) == 0
+
+    def get_state(self, model):
+        """Everything a step of one model starts from: per network (params, m, v, t, running mean, running var)."""
+        return [(self.get_params(w, model),) + self.get_opt_state(w, model) + self.get_bn_running(w, model) for w in (0, 1)]
+
+    def set_state(self, model, state):
+        for w, (th, m, v, t, rm, rv) in enumerate(state):
+            self.set_params(w, model, th)
+            self.set_opt_state(w, model, m, v, t)
+            self.set_bn_running(w, model, rm, rv)
 
     def get_bn_running(self, which, model):
         B = self.bn_count(which)

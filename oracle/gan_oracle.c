@@ -578,6 +578,21 @@ int oracle_get_opt_state(const oracle_ctx* c, int which, int model, oreal* m, or
   if (t) *t = (which == 0 ? c->tG : c->tD)[model];
   return 0;
 }
+int oracle_set_opt_state(oracle_ctx* c, int which, int model, const oreal* m, const oreal* v, int64_t t) {
+  if (model < 0 || model >= c->cfg.n_models || t < 0) return -1;
+  const int64_t P = oracle_param_count(c, which);
+  if (m) memcpy((which == 0 ? c->mG : c->mD) + model * P, m, P * sizeof(oreal));
+  if (v) memcpy((which == 0 ? c->vG : c->vD) + model * P, v, P * sizeof(oreal));
+  (which == 0 ? c->tG : c->tD)[model] = t;
+  return 0;
+}
+int oracle_set_bn_running(oracle_ctx* c, int which, int model, const oreal* mean, const oreal* var) {
+  if (model < 0 || model >= c->cfg.n_models) return -1;
+  const int64_t B = oracle_bn_count(c, which);
+  memcpy((which == 0 ? c->rmG : c->rmD) + model * B, mean, B * sizeof(oreal));
+  memcpy((which == 0 ? c->rvG : c->rvD) + model * B, var, B * sizeof(oreal));
+  return 0;
+}
 int oracle_get_grads(const oracle_ctx* c, int which, int model, oreal* dst) {
   if (model < 0 || model >= c->cfg.n_models) return -1;
   const int64_t P = oracle_param_count(c, which);

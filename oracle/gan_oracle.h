@@ -74,6 +74,9 @@ int64_t oracle_param_count(const oracle_ctx* ctx, int which /*0 = G, 1 = D*/);
 int  oracle_get_params(const oracle_ctx* ctx, int which, int model, oreal* dst);
 int  oracle_set_params(oracle_ctx* ctx, int which, int model, const oreal* src);
 int  oracle_get_opt_state(const oracle_ctx* ctx, int which, int model, oreal* m, oreal* v, int64_t* t);
+/* restore a saved state (m, v may be NULL: left as they are); t is the number of updates taken so far */
+int  oracle_set_opt_state(oracle_ctx* ctx, int which, int model, const oreal* m, const oreal* v, int64_t t);
+int  oracle_set_bn_running(oracle_ctx* ctx, int which, int model, const oreal* mean, const oreal* var);
 int  oracle_get_grads(const oracle_ctx* ctx, int which, int model, oreal* dst); /* of the last step */
 /* BN running statistics, concatenated over the BN layers of the network: mean then var */
 int64_t oracle_bn_count(const oracle_ctx* ctx, int which);

@@ -327,11 +327,12 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   }
 
   const unsigned lds0 = (unsigned)(uintptr_t)smem;     // LDS byte address of the buffers
-  auto load_chunk = [&](int kc, int stage) {
-    // K order, fastest first: the chunks of one 128-byte line; the taps whose gathers land on the same input pixels
-    // shifted by one (down: the 4 taps of a (ky%2, kx%2) class, up: the phase's 4 taps), which find their rows in
-    // L2; the channel line; (down) the class.
-    int tap, cc;
+  // K-chunk kc -> which tap it gathers and the wave-uniform byte offsets it adds to a row's base offsets.
+  // K order, fastest first: the chunks of one 128-byte line; the taps whose gathers land on the same input pixels
+  // shifted by one (down: the 4 taps of a (ky%2, kx%2) class, up: the phase's 4 taps), which find their rows in
+  // L2; the channel line; (down) the class.
+  auto chunk_offsets = [&](int kc, int& tap, unsigned& a_delta, unsigned& w_delta) {
+    int cc;
     if (MODE == MODE_DOWN) {
       const int part = kc % LINES, j4 = (kc / LINES) & 3, rest = kc / (4 * LINES);
       const int cls = rest / cpl;
@@ -357,8 +358,13 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     } else {
       dy = 0; dx = 0; wtap = 0;
     }
-    const unsigned a_delta = (unsigned)(((dy * Hin + dx) * C + cc * BK) * SZ);    // wave-uniform
-    const unsigned w_delta = (unsigned)((wtap * wns * C + cc * BK) * SZ);
+    a_delta = (unsigned)(((dy * Hin + dx) * C + cc * BK) * SZ);    // wave-uniform
+    w_delta = (unsigned)((wtap * wns * C + cc * BK) * SZ);
+  };
+  auto load_chunk = [&](int kc, int stage) {
+    int tap;
+    unsigned a_delta, w_delta;
+    chunk_offsets(kc, tap, a_delta, w_delta);
     const unsigned a_dst = lds0 + (stage * BM + wave * (1024 / KB)) * KB;        // + pass * RPP rows
     const unsigned b_dst = lds0 + (NST * BM + stage * BN + wave * (1024 / KB)) * KB;
 #pragma unroll
@@ -368,7 +374,6 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     for (int i = 0; i < PB; ++i)
       load16_to_lds(w_rsrc, bcol[i] != NO_ROW ? bcol[i] + w_delta : NO_ROW, b_dst + i * RPP * KB);
   };
-
   floatx16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)

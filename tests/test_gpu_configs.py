@@ -3,18 +3,38 @@ oracle results (tests/golden/config*.npz, written by tests/golden/make_golden.py
 
 The label models are independent (Eq. 5), so the oracle is run for a few of them (first / last, or largest /
 median / smallest batch) while the GPU steps all of them; routing is checked bit for bit for every sample.
+
+First step (every implementation takes it from the same seeded state): costs and parameters at the stated tolerance
+against the fp64 oracle (1e-4 fp32 storage, 2e-2 bf16 storage); the gradients, sampled per tensor, against the fp64
+oracle (fp32 storage) or its bf16-storage emulation (bf16 storage), bounded as tests/parity.py derives; Adam's
+arithmetic (the oracle's Adam applied to the GPU's own sampled gradient must give the GPU's moments and update).
+
+Later steps run free.  The iteration amplifies rounding (Adam's sign-like step, the two players feeding each other):
+the stored results include the oracle in single precision (f32) and the emulation with single-precision sums (e32),
+and their distance to f64 / e64 at a step is how far apart two correct implementations of that storage type are
+there.  The bound on a cost or on the parameters at a later step is the stated tolerance (fp32 storage) or 1e-3
+against the emulation (bf16 storage) where that distance is below it, otherwise 3 x the largest such distance seen
+up to that step (3: the spread between two realisations of the same process).  The distance to the plain oracle is
+printed next to the stated 2e-2 for bf16 storage.
 """
 import os
 
 import numpy as np
 import pytest
 
+import oracle as O
 from paper_2102_10485_amd import binding, synth
 from tests import gpu_util as U
+from tests import parity as P
 from tests.golden import make_golden as MG
 
 pytestmark = pytest.mark.gpu
 GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+SPREAD = 3.0
+
+
+def rel(a, b):
+    return abs(a - b) / abs(b)
 
 
 def run_config(config, precision):
@@ -27,18 +47,34 @@ def run_config(config, precision):
     work = synth.Workload(config)
     models = [int(m) for m in gold["models"]]
     assert np.array_equal(gold["batch_sizes"], work.batch_sizes)
-    prec = binding.BF16 if precision == "bf16" else binding.FP32
-    tol = 2e-2 if precision == "bf16" else 1e-4
+    bf = precision == "bf16"
+    prec = binding.BF16 if bf else binding.FP32
+    tol = 2e-2 if bf else 1e-4
+    ref_tag, near_tag = ("e64", "e32") if bf else ("f64", "f32")      # what later steps follow, and its companion
     gan = binding.Gan(binding.make_config(work.spec, work.n_models, work.n_labels, work.n, prec),
                       torch.cuda.current_stream().cuda_stream)
+    theta0 = {}
     for l in range(work.n_models):
         for which in (0, 1):
-            gan.set_params(which, l, work.params(which, l))
+            p = work.params(which, l)
+            gan.set_params(which, l, p)
+            if l in models:
+                theta0[(l, which)] = p.astype(np.float64)
     pos = {which: MG.sample_positions(work.spec, which) for which in (0, 1)}
     lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
     d_lab = torch.from_numpy(lab).cuda()
-    worst, failures, table = {}, [], []
-    env = {"loss": 0.0, "param": 0.0}
+    failures, table = [], []
+    env = {"cost": 0.0, "theta": 0.0}
+
+    def check(step, l, name, err, bound):
+        table.append((step, l, name, err, bound))
+        if not np.isfinite(err) or (bound is not None and err > bound):
+            failures.append((config, precision, step, l, name, float(err), bound))
+
+    def sampled(tag, kind, step, l, which):
+        key = "%s_g_%d_%d_%s" if kind == "g" else "%s_p_" + str(step) + "_%d_%d_%s"
+        return {name: gold[key % (tag, l, which, name)] for name in pos[which]}
+
     for step in range(1, plan["steps"] + 1):
         z, x = work.noise(), work.images(lab)
         dz, dx = torch.from_numpy(z).cuda(), torch.from_numpy(x).cuda()
@@ -51,57 +87,74 @@ def run_config(config, precision):
             mdl = lab if work.n_models > 1 else np.zeros_like(lab)
             assert np.array_equal(perm, np.argsort(mdl, kind="stable"))
             assert np.array_equal(offs, np.concatenate([[0], np.cumsum(np.bincount(mdl, minlength=work.n_models))]))
-
-        # From the second iteration on the bound is widened where the iteration itself amplifies rounding.  The
-        # distance of the single-precision oracle from the fp64 oracle measures that amplification; it fluctuates
-        # from step to step and quantity to quantity, so its running maximum over the steps so far (over the checked
-        # models and both costs) is used: fp32 storage 10 x that envelope (another fp32 summation order), bf16
-        # storage 50 x (its rounding unit is 2^16 coarser).  The first iteration is always held to the stated bound.
-        if plan["single"]:
-            for i in range(len(models)):
-                for name in ("jd", "jg"):
-                    ref = gold["f64_%s_%d" % (name, step)][i]
-                    env["loss"] = max(env["loss"], abs(gold["f32_%s_%d" % (name, step)][i] - ref) / abs(ref))
-
-        def bound(drift, kind="loss"):
-            if step >= 2 and plan["single"]:
-                return max(tol, (10.0 if precision == "fp32" else 50.0) * max(drift, env[kind]))
-            return tol
-
+        # how far apart two correct implementations are at this step (running maximum over steps, models, both costs)
+        for i in range(len(models)):
+            for c in ("jd", "jg"):
+                env["cost"] = max(env["cost"], rel(gold["%s_%s_%d" % (near_tag, c, step)][i], gold["%s_%s_%d" % (ref_tag, c, step)][i]))
+        later = max(1e-3 if bf else tol, SPREAD * env["cost"])
         for i, l in enumerate(models):
-            for name, got in (("jd", jd[l]), ("jg", jg[l])):
-                ref = gold["f64_%s_%d" % (name, step)][i]
-                drift = abs(gold["f32_%s_%d" % (name, step)][i] - ref) / abs(ref) if plan["single"] else 0.0
-                err = abs(got - ref) / abs(ref)
-                worst[name] = max(worst.get(name, 0), err)
-                table.append((step, l, name, float(got), float(ref), err, drift))
-                if err > bound(drift):
-                    failures.append((config, step, l, name, float(got), float(ref), err, drift))
-        if step in plan["snaps"]:
+            for c, got in (("jd", jd[l]), ("jg", jg[l])):
+                plain = rel(got, gold["f64_%s_%d" % (c, step)][i])
+                if step == 1:
+                    check(step, l, c + " vs plain", plain, tol)                     # the stated tolerance, per step
+                else:
+                    check(step, l, c + " vs plain", plain, None if bf else later)
+                if bf:
+                    check(step, l, c + " vs emulation", rel(got, gold["e64_%s_%d" % (c, step)][i]), later)
+        if step == 1:
+            first_step_checks(gan, gold, models, pos, theta0, bf, check, sampled)
+        elif step in plan["snaps"]:
             for l in models:
                 for which in (0, 1):
                     th = gan.get_params(which, l)
-                    all_got, all_ref, all_f32 = [], [], []
-                    for name, idx in pos[which].items():
-                        ref = gold["f64_p_%d_%d_%d_%s" % (step, l, which, name)]
-                        f32 = gold["f32_p_%d_%d_%d_%s" % (step, l, which, name)] if plan["single"] else ref
-                        got = th[idx]
-                        floor = 0.02 * np.sqrt(idx.size)
-                        err = U.rel_l2(got, ref, floor=floor)
-                        if err > max(bound(U.rel_l2(f32, ref, floor=floor), "param"), U.one_flip(idx.size)):
-                            failures.append((config, step, l, which, name, err, U.rel_l2(f32, ref, floor=floor)))
-                        all_got.append(got); all_ref.append(ref); all_f32.append(f32)
-                    g, r, s = (np.concatenate(a) for a in (all_got, all_ref, all_f32))
-                    err = U.rel_l2(g, r)
-                    worst["params"] = max(worst.get("params", 0), err)
-                    table.append((step, l, "params%d" % which, 0.0, 0.0, err, U.rel_l2(s, r)))
-                    if err > bound(U.rel_l2(s, r), "param"):
-                        failures.append((config, step, l, which, "params", err, U.rel_l2(s, r)))
+                    ref, near = sampled(ref_tag, "p", step, l, which), sampled(near_tag, "p", step, l, which)
+                    cat = lambda d: np.concatenate([d[n] for n in pos[which]])
+                    got = np.concatenate([th[pos[which][n]] for n in pos[which]])
+                    t0 = np.concatenate([theta0[(l, which)][pos[which][n]] for n in pos[which]])
+                    env["theta"] = max(env["theta"], P.rel_l2(cat(near), cat(ref)))
+                    check(step, l, "GD"[which] + ".theta", P.rel_l2(got, cat(ref)), max(1e-3 if bf else tol, SPREAD * env["theta"]))
+                    if bf:
+                        check(step, l, "GD"[which] + ".theta vs plain", P.rel_l2(got, cat(sampled("f64", "p", step, l, which))), None)
+                    # the displacement since the start, against the reference's: a path that stopped updating is 1.0 off
+                    d_near = P.rel_l2(cat(near) - t0, cat(ref) - t0)
+                    check(step, l, "GD"[which] + ".moved", P.rel_l2(got - t0, cat(ref) - t0), max(0.1, SPREAD * d_near))
     gan.close()
-    for row in table:
-        print("config %d %s step %d model %d %-8s got %.6g ref %.6g err %.2e (fp32-oracle drift %.2e)" % ((config, precision) + row))
-    print("config %d %s worst relative errors: %s" % (config, precision, worst))
+    for step, l, name, err, bound in table:
+        print("config %d %s step %d model %d %-24s %.2e (bound %s)" % (config, precision, step, l, name, err,
+                                                                       "%.1e" % bound if bound is not None else "-"))
     assert not failures, failures
+
+
+def first_step_checks(gan, gold, models, pos, theta0, bf, check, sampled):
+    """Gradients, Adam's arithmetic, update and parameters after the first step, on the sampled positions."""
+    ref_tag, near_tag = ("e64", "e32") if bf else ("f64", "f32")
+    cat = lambda d, which: np.concatenate([d[n] for n in pos[which]])
+    # the scale of the gradient bound: the companion implementation's distance, largest over the checked models
+    d_grad = max(P.rel_l2(cat(sampled(near_tag, "g", 1, l, w), w), cat(sampled(ref_tag, "g", 1, l, w), w)) for l in models for w in (0, 1))
+    g_bound = max(5e-3 if bf else 5e-4, SPREAD * d_grad)
+    for l in models:
+        for which in (0, 1):
+            net = "GD"[which]
+            g, th = gan.get_grads(which, l), gan.get_params(which, l)
+            m, v, t = gan.get_opt_state(which, l)
+            assert t == 1
+            g_ref = sampled(ref_tag, "g", 1, l, which)
+            gn = np.linalg.norm(cat(g_ref, which)) / np.sqrt(cat(g_ref, which).size)
+            for name, idx in pos[which].items():
+                check(1, l, "%s.grad[%s]" % (net, name), P.rel_l2(g[idx], g_ref[name], floor=1e-3 * gn * np.sqrt(idx.size)), 2.0 * g_bound)
+            allidx = np.concatenate([pos[which][n] for n in pos[which]])
+            check(1, l, net + ".grad", P.rel_l2(g[allidx], cat(g_ref, which)), g_bound)
+            if bf:
+                check(1, l, net + ".grad vs plain", P.rel_l2(g[allidx], cat(sampled("f64", "g", 1, l, which), which)), None)
+            # Adam on the GPU's own gradient from the seeded state (zero moments, t = 1)
+            t0 = theta0[(l, which)][allidx]
+            th_e, m_e, v_e = O.adam(t0, np.zeros_like(t0), np.zeros_like(t0), g[allidx].astype(np.float64), 1)
+            check(1, l, net + ".adam.m", P.rel_l2(m[allidx], m_e), 1e-5)
+            check(1, l, net + ".adam.v", P.rel_l2(v[allidx], v_e), 1e-4)
+            check(1, l, net + ".adam.update", P.rel_l2(th[allidx] - t0, th_e - t0), 1e-3)
+            p_ref = cat(sampled(ref_tag, "p", 1, l, which), which)
+            check(1, l, net + ".update", P.rel_l2(th[allidx] - t0, p_ref - t0), min(3.0 * np.sqrt(g_bound), 0.5))
+            check(1, l, net + ".theta vs plain", P.rel_l2(th[allidx], cat(sampled("f64", "p", 1, l, which), which)), 2e-2 if bf else 1e-4)
 
 
 def test_config0_fp32():
@@ -130,3 +183,38 @@ def test_config3_bf16():
 
 def test_config4_bf16_ragged():
     run_config(4, "bf16")
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_config1_all_200_steps(precision):
+    """Config 1 states 200 steps.  Parity is followed for 50 (above): beyond that the oracle's own single- and
+    double-precision builds disagree by more than the costs themselves.  The full 200 are run here twice: every cost
+    finite and positive throughout, routing exact at the last step, and the two runs bit-identical."""
+    torch = U.torch_mod()
+    prec = binding.BF16 if precision == "bf16" else binding.FP32
+    finals = []
+    for rep in range(2):
+        work = synth.Workload(1)
+        gan = binding.Gan(binding.make_config(work.spec, work.n_models, work.n_labels, work.n, prec),
+                          torch.cuda.current_stream().cuda_stream)
+        for l in range(work.n_models):
+            for which in (0, 1):
+                gan.set_params(which, l, work.params(which, l))
+        lab = work.labels()
+        d_lab = torch.from_numpy(lab).cuda()
+        costs = []
+        for step in range(200):
+            dz, dx = torch.from_numpy(work.noise()).cuda(), torch.from_numpy(work.images(lab)).cuda()
+            gan.train_step(d_lab.data_ptr(), dz.data_ptr(), dx.data_ptr(), work.n)
+            if step % 10 == 9:
+                jd, jg, cnt = gan.get_losses()
+                costs.append(np.concatenate([jd, jg]))
+                assert np.all(np.isfinite(costs[-1])) and np.all(costs[-1] > 0), (step, costs[-1])
+        perm, offs = gan.get_routing(work.n)
+        assert np.array_equal(perm, np.argsort(lab, kind="stable"))
+        assert all(gan.get_opt_state(w, l)[2] == 200 for w in (0, 1) for l in (0, work.n_models - 1))
+        finals.append((np.array(costs), [gan.get_params(w, l) for w in (0, 1) for l in range(work.n_models)]))
+        gan.close()
+    assert np.array_equal(finals[0][0], finals[1][0])
+    for a, b in zip(finals[0][1], finals[1][1]):
+        assert np.array_equal(a, b)

@@ -1,15 +1,16 @@
 """Whole-step parity of the HIP library against the CPU oracle on identical seeded inputs (GPU).
 
-Tolerances: fp32 storage 1e-4 relative, bf16 storage (fp32 master weights) 2e-2 relative, on the per-step costs
-and on the parameters; label routing is compared bit for bit.  Parameters are compared as relative L2 norms, per
-network (strict) and per tensor with the denominator floored at the initialisation scale 0.02 per element
-(tensors that start at zero move by about lr per step, so they carry no relative precision of their own).
+Every step is compared FROM THE SAME STATE: before a step the oracle's state (parameters, Adam moments and step
+counts, BatchNorm running statistics) is loaded into the HIP context through its checkpoint calls, both take the
+step, and costs, gradients, moments, updates, parameters and running statistics are compared (tests/parity.py says
+which quantity catches what).  The stated tolerances -- 1e-4 for fp32 storage, 2e-2 for bf16 storage with fp32 master
+weights, both against the plain fp64 oracle -- are per step; the bf16 path is also held to the oracle's bf16-storage
+emulation, which rounds the same tensors, at 1e-3.  Label routing is compared bit for bit.
 
-The two-player iteration amplifies rounding from step to step (Adam divides by the root of the second moment, so
-a parameter whose gradient is near zero moves by about lr in a direction decided by the last bits).  The oracle's
-own loops compiled in single precision drift from the double-precision result by more than 1e-4 after two or
-three iterations.  From the second iteration on the fp32 bound is therefore max(1e-4, 10 x that drift), the drift
-being measured in the same test on the same inputs; the first iteration is always held to 1e-4.
+(Why from the same state: Adam divides by the root of the second moment, so a parameter whose gradient is within
+rounding of zero moves by about lr in a direction the last bits decide, and the two-player iteration feeds that back;
+the oracle's own loops compiled in single precision are 1.2e-4 away from its fp64 result after three free-running
+steps.  Free-running trajectories are followed in tests/test_gpu_configs.py.)
 """
 import numpy as np
 import pytest
@@ -17,6 +18,7 @@ import pytest
 import oracle as O
 from paper_2102_10485_amd import binding, synth
 from tests import gpu_util as U
+from tests import parity as P
 
 pytestmark = pytest.mark.gpu
 
@@ -24,9 +26,9 @@ TOL = {binding.FP32: 1e-4, binding.BF16: 2e-2}
 
 
 class Pair:
-    """The HIP context and the oracle with identical parameters."""
+    """The HIP context, the plain oracle and (bf16 storage) the emulating oracle, stepped from identical states."""
 
-    def __init__(self, spec_name, n_models, n_labels, max_n, prec, seed=3, oracle_models=None, drift=False):
+    def __init__(self, spec_name, n_models, n_labels, max_n, prec, seed=3, oracle_models=None):
         torch = U.torch_mod()
         self.torch = torch
         self.spec = synth.SPECS[spec_name]
@@ -35,10 +37,15 @@ class Pair:
         self.gpu = binding.Gan(binding.make_config(self.spec, n_models, n_labels, max_n, prec),
                                torch.cuda.current_stream().cuda_stream)
         self.orc = O.Oracle(self.spec, n_models, n_labels)
-        # the same loops in single precision, to measure how far plain fp32 arithmetic drifts (fp32 runs only)
-        self.o32 = O.Oracle(self.spec, n_models, n_labels, real=np.float32) if (drift and prec == binding.FP32) else None
+        self.emu = O.Oracle(self.spec, n_models, n_labels, emulate_bf16=True) if prec == binding.BF16 else None
+        # the same emulation with single-precision sums: how far apart two correct bf16-storage implementations are
+        self.emu32 = O.Oracle(self.spec, n_models, n_labels, emulate_bf16=True, real=np.float32) if self.emu else None
+        # fp32 storage: the oracle's loops in single precision, for the same purpose
+        self.o32 = O.Oracle(self.spec, n_models, n_labels, real=np.float32) if prec == binding.FP32 else None
         self.nsteps = 0
         self.models = list(range(n_models)) if oracle_models is None else list(oracle_models)
+        self.before = {}
+        self.report = []
         for l in range(n_models):
             rng = np.random.default_rng([seed, l])
             for which in (0, 1):
@@ -47,61 +54,84 @@ class Pair:
                 self.gpu.set_params(which, l, p)
                 if l in self.models:
                     self.orc.set_params(which, l, p)
+                    if self.emu:
+                        self.emu.set_params(which, l, p)
+                        self.emu32.set_params(which, l, p)
                     if self.o32:
                         self.o32.set_params(which, l, p)
 
-    def step(self, lab, z, x):
+    def _load_state(self, l, state):
+        for w, (th, m, v, t, rm, rv) in enumerate(state):
+            self.gpu.set_params(w, l, th)
+            self.gpu.set_opt_state(w, l, m, v, t)
+            self.gpu.set_bn_running(w, l, rm, rv)
+        if self.emu:
+            self.emu.set_state(l, state)
+            self.emu32.set_state(l, state)
+        if self.o32:
+            self.o32.set_state(l, state)
+
+    def step(self, lab, z, x, same_state=True):
         t = self.torch
+        for l in self.models:
+            state = self.orc.get_state(l)
+            # the HIP context keeps fp32 master values: start all sides from the values it can hold
+            state = [tuple(np.asarray(a, np.float32).astype(np.float64) if isinstance(a, np.ndarray) else a for a in net)
+                     for net in state]
+            if same_state:
+                self.orc.set_state(l, state)
+                self._load_state(l, state)
+            self.before[l] = dict(params=[state[0][0], state[1][0]], m=[state[0][1], state[1][1]],
+                                  v=[state[0][2], state[1][2]], t=[state[0][3], state[1][3]])
         self.keep = (t.from_numpy(np.ascontiguousarray(lab, np.int32)).cuda(),
                      t.from_numpy(np.ascontiguousarray(z, np.float32)).cuda(),
                      t.from_numpy(np.ascontiguousarray(x, np.float32)).cuda())
         self.gpu.train_step(self.keep[0].data_ptr(), self.keep[1].data_ptr(), self.keep[2].data_ptr(), len(lab))
         for l in self.models:
             self.orc.train_step(lab, z.astype(np.float64), x.astype(np.float64), only_model=l)
+            if self.emu:
+                self.emu.train_step(lab, z.astype(np.float64), x.astype(np.float64), only_model=l)
+                self.emu32.train_step(lab, z, x, only_model=l)
             if self.o32:
                 self.o32.train_step(lab, z, x, only_model=l)
         self.nsteps += 1
 
-    def bound(self, drift):
-        """Tolerance for one quantity: the stated one, widened from the second iteration on by the measured drift."""
-        tol = TOL[self.prec]
-        if self.o32 is None or self.nsteps < 2:
-            return tol
-        return max(tol, 10.0 * drift)
-
     def compare(self, what=""):
-        tol = TOL[self.prec]
-        jd, jg, cnt = self.gpu.get_losses()
-        ojd, ojg, ocnt = self.orc.get_losses()
-        sjd, sjg, _ = self.o32.get_losses() if self.o32 else (ojd, ojg, None)
+        """The step just taken, model by model, against the plain oracle (and the emulation for bf16 storage)."""
+        cnt, ocnt = self.gpu.get_losses()[2], self.orc.get_losses()[2]
         assert np.array_equal(cnt, ocnt)
-        worst = 0.0
+        fails = []
+        live = [l for l in self.models if ocnt[l] > 0]
+        if self.emu and live:
+            e64 = {l: P.snapshot(self.emu, l) for l in live}
+            emu_bounds = P.emulation_bounds([(P.snapshot(self.emu32, l), e64[l]) for l in live])
+        refs = {l: P.snapshot(self.orc, l) for l in live}
+        plain_bounds = P.BF16_VS_PLAIN
+        if self.o32 and live:
+            plain_bounds = P.fp32_bounds([(P.snapshot(self.o32, l), refs[l]) for l in live])
         for l in self.models:
             if ocnt[l] == 0:
+                jd, jg = self.gpu.get_losses()[:2]
                 assert jd[l] == 0 and jg[l] == 0
                 continue
-            b = self.bound(abs(sjd[l] - ojd[l]) / abs(ojd[l]))
-            assert abs(jd[l] - ojd[l]) <= b * abs(ojd[l]), (what, "J_D", l, jd[l], ojd[l], b)
-            b = self.bound(abs(sjg[l] - ojg[l]) / abs(ojg[l]))
-            assert abs(jg[l] - ojg[l]) <= b * abs(ojg[l]), (what, "J_G", l, jg[l], ojg[l], b)
-            for which in (0, 1):
-                got, ref = self.gpu.get_params(which, l), self.orc.get_params(which, l)
-                sng = self.o32.get_params(which, l) if self.o32 else ref
-                e = U.rel_l2(got, ref)
-                worst = max(worst, e)
-                b = self.bound(U.rel_l2(sng, ref))
-                assert e <= b, (what, "params", which, l, e, b)
-                per = U.tensor_errors(self.spec, which, got, ref, 0.02)
-                dr = U.tensor_errors(self.spec, which, sng, ref, 0.02)
-                numel = {k: int(np.prod(sh)) for k, (_, sh) in synth.param_slices(self.spec, which).items()}
-                bad = {k: (v, self.bound(dr[k])) for k, v in per.items()
-                       if v > max(self.bound(dr[k]), U.one_flip(numel[k]))}
-                assert not bad, (what, which, l, bad)
-        return worst
+            got = P.snapshot(self.gpu, l)
+            tag = "%s model %d" % (what, l)
+            f, rows = P.compare_step(self.spec, self.before[l], got, refs[l], plain_bounds, tag + " vs plain", adam=O.adam)
+            fails += f
+            self.report += rows
+            if self.emu:
+                f, rows = P.compare_step(self.spec, self.before[l], got, e64[l], emu_bounds, tag + " vs emulation")
+                fails += f
+                self.report += rows
+        assert not fails, fails
 
     def close(self):
+        print(P.format_rows(self.report))
         self.gpu.close()
         self.orc.close()
+        if self.emu:
+            self.emu.close()
+            self.emu32.close()
         if self.o32:
             self.o32.close()
 
@@ -116,7 +146,7 @@ def batch(spec, labels, seed):
 
 @pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
 def test_first_step_gradients_and_routing(prec):
-    """One step, three ragged models: routing bit-exact, gradients of both networks, costs, parameters."""
+    """One step, three ragged models: routing bit-exact; costs, gradients, moments, updates, parameters."""
     p = Pair("tiny3", 3, 3, 64, prec)
     lab = np.array([2, 0, 1, 1, 2, 0, 0, 2, 1, 2, 2, 0, 2, 2, 1, 2, 2, 2, 0, 2, 2], np.int32)
     lab_, z, x = batch(p.spec, lab, 11)
@@ -124,21 +154,6 @@ def test_first_step_gradients_and_routing(prec):
     perm, offs = p.gpu.get_routing(len(lab))
     operm, ooffs = p.orc.get_routing(len(lab))
     assert np.array_equal(perm, operm) and np.array_equal(offs, ooffs)
-    tol = TOL[prec]
-    for l in range(3):
-        for which in (0, 1):
-            got, ref = p.gpu.get_grads(which, l), p.orc.get_grads(which, l)
-            per = {}
-            for name, (sl, shape) in synth.param_slices(p.spec, which).items():
-                per[name] = U.rel_l2(got[sl], ref[sl], floor=1e-3 * np.linalg.norm(ref))
-            # Gradients are not part of the stated tolerance (costs and parameters are).  In bf16 storage the
-            # activation gradients are rounded to 8 bits of mantissa before sums in which the real and the fake
-            # half nearly cancel (Eq. 3 at initialisation), which amplifies the rounding to several percent of
-            # the small result; fp32 storage runs the same kernels and is held to 1e-3.
-            bad = {k: v for k, v in per.items() if v > (1e-3 if prec == binding.FP32 else 0.25)}
-            assert not bad, (which, l, bad)
-            cos = float(got @ ref / (np.linalg.norm(got) * np.linalg.norm(ref)))
-            assert cos > (0.999999 if prec == binding.FP32 else 0.98), (which, l, cos)
     p.compare("step1")
     p.close()
 
@@ -146,21 +161,16 @@ def test_first_step_gradients_and_routing(prec):
 @pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
 @pytest.mark.parametrize("spec_name,K,nlab", [("tiny", 1, 4), ("tiny", 4, 4), ("tiny0", 2, 2)])
 def test_three_steps(prec, spec_name, K, nlab):
-    """Mixed labels in one conditional pair, one pair per label, and an unconditional family; three iterations."""
-    p = Pair(spec_name, K, nlab, 80, prec, drift=True)
+    """Mixed labels in one conditional pair, one pair per label, and an unconditional family; three iterations, each
+    from the oracle's state (so the second and third start with non-zero moments and moved statistics)."""
+    p = Pair(spec_name, K, nlab, 80, prec)
     rng = np.random.default_rng(5)
     for s in range(3):
         n = [37, 80, 52][s]
         lab = rng.integers(0, nlab, n)
         p.step(*batch(p.spec, lab, 100 + s))
         p.compare("step %d" % s)
-    # BatchNorm running statistics after three updates each (three per step in D)
     for l in range(K):
-        for which in (0, 1):
-            gm, gv = p.gpu.get_bn_running(which, l)
-            om, ov = p.orc.get_bn_running(which, l)
-            assert U.rel_l2(gm, om, floor=1e-2 * np.sqrt(om.size)) <= TOL[prec] * 5
-            assert U.rel_l2(gv, ov) <= TOL[prec] * 5
         assert p.gpu.get_opt_state(0, l)[2] == p.orc.get_opt_state(0, l)[2] == 3
     p.close()
 
@@ -169,12 +179,41 @@ def test_three_steps(prec, spec_name, K, nlab):
 def test_single_conditional_pair_over_twenty_labels(prec):
     """The paper's DC-CGAN comparison system (Tables 3 and 4) at test size: one pair, the label of every sample as a
     one-hot on G's input and as label maps on D's input; the weight gradients of a single model are split over rows."""
-    p = Pair("tiny20", 1, 20, 96, prec, drift=True)
+    p = Pair("tiny20", 1, 20, 96, prec)
     rng = np.random.default_rng(8)
     for s, n in enumerate([96, 50]):
         lab = rng.integers(0, 20, n)
         p.step(*batch(p.spec, lab, 500 + s))
         p.compare("step %d" % s)
+    p.close()
+
+
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+def test_single_unconditional_pair(prec):
+    """The paper's DC-GAN comparison system (Tables 1 and 2) at test size: one pair, no label anywhere (one label,
+    no conditioning), a batch of several hundred so that every weight gradient is split over rows and summed in a
+    fixed order; the second batch is ragged against the splits."""
+    p = Pair("tiny0", 1, 1, 320, prec)
+    for s, n in enumerate([320, 203]):
+        p.step(*batch(p.spec, np.zeros(n, np.int32), 700 + s))
+        p.compare("step %d" % s)
+    p.close()
+
+
+def test_free_running_steps_keep_the_stated_tolerance_while_it_means_something():
+    """Three steps with no state reloaded in between, fp32 storage: the costs and parameters stay within 1e-4 of the
+    fp64 oracle for the first two steps (the third is past where the oracle's own single-precision build holds it)."""
+    p = Pair("tiny", 4, 4, 80, binding.FP32)
+    rng = np.random.default_rng(5)
+    for s in range(2):
+        lab = rng.integers(0, 4, [37, 80][s])
+        p.step(*batch(p.spec, lab, 100 + s), same_state=False)
+        jd, jg, _ = p.gpu.get_losses()
+        ojd, ojg, _ = p.orc.get_losses()
+        assert np.all(np.abs(jd - ojd) <= 1e-4 * np.abs(ojd)) and np.all(np.abs(jg - ojg) <= 1e-4 * np.abs(ojg))
+        for l in range(4):
+            for which in (0, 1):
+                assert P.rel_l2(p.gpu.get_params(which, l), p.orc.get_params(which, l)) <= 1e-4
     p.close()
 
 
@@ -275,7 +314,7 @@ def test_generate(prec):
 def test_config0_five_steps_fp32():
     """The 28x28x1 conditional pair, batch 64, one label, five iterations, fp32."""
     w = synth.Workload(0)
-    p = Pair("mnist", 1, 10, 64, binding.FP32, drift=True)
+    p = Pair("mnist", 1, 10, 64, binding.FP32)
     for s in range(5):
         lab = w.labels(single_label=3)
         p.step(lab, w.noise(), w.images(lab))
