@@ -206,6 +206,20 @@ __device__ inline void decode_row(int r, int H, int rps, int sh, int& n, int& y,
     x = rem - y * H;
   }
 }
+// Row order of the forward-type kernel inside a model: pixel row y slowest, then the sample, then x.  A tile of
+// consecutive rows then covers few pixel rows (one, when samples * H is a multiple of the tile height), and the taps
+// that fall above or below the map for all of them are skipped as whole K-chunks.  row_block = samples * H.
+__device__ inline void decode_row_yfirst(int r, int H, int row_block, int sh, int& n, int& y, int& x) {
+  y = r / row_block;
+  const int rem = r - y * row_block;
+  if (sh >= 0) {
+    n = rem >> sh;
+    x = rem & (H - 1);
+  } else {
+    n = rem / H;
+    x = rem - n * H;
+  }
+}
 static int log2_or_neg(int v) {
   for (int s = 0; s < 30; ++s)
     if ((1 << s) == v) return s;
@@ -224,6 +238,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   unsigned char* const Bs = smem + NST * BM * KB;      // buffer s at Bs + s * BN * KB
   constexpr int BK = KB / (int)sizeof(T);              // elements of K per chunk
   constexpr int LINES = 128 / KB;                      // chunks per 128-byte line
+  constexpr int LINES_ = LINES;
   constexpr int EPV = 16 / (int)sizeof(T);
   constexpr int LPT = PA + PB;                         // loads per thread per chunk
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -269,9 +284,28 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   const int py = phase >> 1, px = phase & 1;
 
   constexpr int SZ = (int)sizeof(T);
-  const int ntaps = (MODE == MODE_DOWN) ? 16 : (MODE == MODE_UP ? 4 : 1);
-  const int nk = ntaps * C / BK;
   const int cpl = C * SZ / 128;   // 128-byte channel lines per tap
+  // Pixel rows this tile covers (rows are ordered y, sample, x) and the taps that are inside the map for at least
+  // one of them: a tap row that is outside for the whole tile contributes zeros only and its K-chunks are skipped.
+  const int row_block = (s1 - s0) * Hr;
+  int cnt_lo = 4, cnt_hi = 4;     // down: valid taps of the classes with ky even / odd ; up: cnt_lo = valid taps
+  bool first_gone = false;        // the skipped taps are the first ones of their group (otherwise the last ones)
+  if (MODE != MODE_DENSE) {
+    const int y_lo = m0 / row_block, y_hi = (min(m0 + BM, Mrows) - 1) / row_block;
+    const bool top_only = y_hi == 0, bottom_only = y_lo == Hr - 1;          // only the first / last pixel row
+    if (MODE == MODE_DOWN) {
+      if (top_only) cnt_lo = 2;                      // ky = 0 reads row -1
+      if (bottom_only) cnt_hi = 2;                   // ky = 3 reads row Hin
+      first_gone = top_only;
+    } else {
+      // phase py = 0 gathers rows y and y - 1, py = 1 rows y + 1 and y (tap index a = 0, 1 in this order)
+      if (py == 0 && top_only) cnt_lo = 2;           // a = 1 (row y - 1) is gone: the last ones
+      if (py == 1 && bottom_only) { cnt_lo = 2; first_gone = true; }   // a = 0 (row y + 1) is gone
+    }
+  }
+  const int chunks_per_tap = cpl * LINES_;
+  const int nk = (MODE == MODE_DOWN) ? 2 * (cnt_lo + cnt_hi) * chunks_per_tap
+                                     : (MODE == MODE_UP ? cnt_lo * chunks_per_tap : C / BK);
   const int wns = p.w_nstride;   // rows per tap in the weight block (N, or more when only some rows are used)
   // this model's slice of the gathered tensor (one segment) and its weight block, as bounds-checked buffers
   const int nsamp = s1 - s0;
@@ -299,7 +333,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
         amask[i] = 1;
       } else {
         int n, y, x;
-        decode_row(r, Hr, rps, p.hr_shift, n, y, x);
+        decode_row_yfirst(r, Hr, row_block, p.hr_shift, n, y, x);
         const int by = (MODE == MODE_DOWN) ? 2 * y - 1 : y, bx = (MODE == MODE_DOWN) ? 2 * x - 1 : x;
         apix[i] = (unsigned)((((n * Hin + by) * Hin + bx) * C + chunk * EPV) * SZ);     // may wrap below zero: masked
         if (MODE == MODE_DOWN) {             // tap (ky, kx) is inside iff row by + ky and column bx + kx are: separable
@@ -310,7 +344,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
           for (int k = 0; k < 4; ++k)
             if ((unsigned)(by + k) < (unsigned)Hin) amask[i] |= xm << (4 * k);
         } else {
-          for (int t = 0; t < ntaps; ++t) {
+          for (int t = 0; t < 4; ++t) {
             const int dy = py == 0 ? ((t >> 1) == 0 ? 0 : -1) : ((t >> 1) == 0 ? 1 : 0);
             const int dx = px == 0 ? ((t & 1) == 0 ? 0 : -1) : ((t & 1) == 0 ? 1 : 0);
             const int iy = by + dy, ix = bx + dx;
@@ -334,13 +368,26 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   auto chunk_offsets = [&](int kc, int& tap, unsigned& a_delta, unsigned& w_delta) {
     int cc;
     if (MODE == MODE_DOWN) {
-      const int part = kc % LINES, j4 = (kc / LINES) & 3, rest = kc / (4 * LINES);
-      const int cls = rest / cpl;
-      cc = (rest - cls * cpl) * LINES + part;
+      // classes 0, 1 hold the taps with ky in {0, 2}, classes 2, 3 those with ky in {1, 3}; a class keeps cnt taps
+      const int per_lo = cnt_lo * chunks_per_tap;                 // chunks of one class with ky even
+      int cls, rest;
+      if (kc < 2 * per_lo) { cls = kc >= per_lo ? 1 : 0; rest = kc - cls * per_lo; }
+      else { const int k2 = kc - 2 * per_lo, per_hi = cnt_hi * chunks_per_tap; cls = k2 >= per_hi ? 3 : 2; rest = k2 - (cls - 2) * per_hi; }
+      const int cnt = cls < 2 ? cnt_lo : cnt_hi;
+      const int part = rest % LINES, jr = rest / LINES;
+      const int j = cnt == 4 ? (jr & 3) : (jr & 1);
+      const int line = cnt == 4 ? (jr >> 2) : (jr >> 1);
+      // the two taps left in a class of two are its kx pair at the one valid ky: ky = 2 (top tile, even class) or
+      // ky = 1 (bottom tile, odd class)
+      const int j4 = cnt == 4 ? j : j + ((cls < 2) ? 2 : 0);
+      cc = line * LINES + part;
       tap = (((cls >> 1) + 2 * (j4 >> 1)) << 2) + (cls & 1) + 2 * (j4 & 1);
     } else if (MODE == MODE_UP) {
-      cc = (kc / (4 * LINES)) * LINES + kc % LINES;
-      tap = (kc / LINES) & 3;
+      const int part = kc % LINES, jr = kc / LINES;
+      const int j = cnt_lo == 4 ? (jr & 3) : (jr & 1);
+      const int line = cnt_lo == 4 ? (jr >> 2) : (jr >> 1);
+      cc = line * LINES + part;
+      tap = cnt_lo == 4 ? j : j + (first_gone ? 2 : 0);
     } else {
       cc = kc;
       tap = 0;
@@ -401,13 +448,14 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     const int r = m0 + t;
     long long o = -1;
     if (r < Mrows) {
-      if (MODE == MODE_UP) {
-        int n, y, x;
-        decode_row(r, Hr, rps, p.hr_shift, n, y, x);
-        const int Hb = 2 * Hr;
-        o = ((sample_base + n) * Hb + (2 * y + py)) * Hb + (2 * x + px);
-      } else {
+      if (MODE == MODE_DENSE) {
         o = sample_base * rps + r;
+      } else {
+        int n, y, x;
+        decode_row_yfirst(r, Hr, row_block, p.hr_shift, n, y, x);
+        const int Hb = 2 * Hr;
+        if (MODE == MODE_UP) o = ((sample_base + n) * Hb + (2 * y + py)) * Hb + (2 * x + px);
+        else o = ((sample_base + n) * Hr + y) * Hr + x;
       }
     }
     orow[t] = o;
@@ -834,6 +882,14 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
   // offset: everything that depends on the row is computed once, and a chunk only adds a wave-uniform offset
   // (sample n0, pixel row y0 of the chunk's first row) and re-tests the vertical border.
   const bool fast = p.ntaps == 1 || (p.hs_shift >= 0 && Hs <= 64);
+  // Reduction order "pixel row first" (y, sample, x) for the models whose samples * H rows per pixel row are whole
+  // chunks: a chunk then lies inside one pixel row y0, the vertical border test is the same for the whole chunk, and
+  // the chunks of the one pixel row whose tap row ky falls outside the map (y0 = 0 for ky = 0, y0 = H - 1 for
+  // ky = 3) hold zeros only and are skipped.  The tile's taps share one ky (4 * Cb >= BM).  The choice depends on the
+  // model's own sample count only.
+  const int rb = (s1 - s0) * Hs;                    // rows per pixel row
+  const bool yfirst = p.ntaps == 16 && fast && rb % WG_KR == 0 && 4 * Cb >= BM && Cb % 8 == 0 && (BM % Cb == 0 || Cb % BM == 0);
+  const int ky_tile = (mt * BM / Cb) >> 2;
   unsigned fa_off[PA], fb_off[PB];
   int fa_iy[PA];                   // 2 * (y inside the chunk) - 1 + ky ; a large value marks a lane that never loads
 #pragma unroll
@@ -845,6 +901,15 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
       if (p.ntaps == 1) {
         fa_off[i] = (unsigned)((c * Cb + cA) * 2);
         fa_iy[i] = 0;
+      } else if (yfirst) {
+        // row c of a chunk: sample n0 + c / H, x = c % H, pixel row y0 (chunk-uniform)
+        const int sh = p.hs_shift;
+        const int ni = c >> sh, xi = c & (Hs - 1);
+        const int ix = 2 * xi - 1 + kxA;
+        if ((unsigned)ix < (unsigned)Hb) {
+          fa_iy[i] = kyA - 1;
+          fa_off[i] = (unsigned)((((ni * Hb + fa_iy[i]) * Hb + ix) * Cb + cA) * 2);    // may wrap below zero: masked
+        }
       } else if (fast) {
         const int sh = p.hs_shift;
         const int ni = c >> (2 * sh), rem = c & (rps - 1);
@@ -858,7 +923,11 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
     }
   }
 #pragma unroll
-  for (int i = 0; i < PB; ++i) fb_off[i] = (unsigned)(((rowB0 + i * RPB) * Cs + cB) * 2);
+  for (int i = 0; i < PB; ++i) {
+    const int c = rowB0 + i * RPB;
+    if (yfirst) fb_off[i] = (unsigned)((((c >> p.hs_shift) * rps + (c & (Hs - 1))) * Cs + cB) * 2);
+    else fb_off[i] = (unsigned)((c * Cs + cB) * 2);
+  }
 
   auto load_chunk = [&](int seg, int k0, int stage) {
     const long long sb = (long long)seg * p.seg_samples + s0;
@@ -867,11 +936,17 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
     const unsigned a_dst = lds0 + stage * STAGE_A + wave * 1024;
     const unsigned b_dst = lds0 + 2 * STAGE_A + stage * STAGE_B + wave * 1024;
     const int left = r_hi - k0;                 // rows of this chunk that exist
+    unsigned b_delta = (unsigned)(k0 * Cs * 2);
     if (fast) {
       unsigned a_delta;
       int y2 = 0;
       if (p.ntaps == 1) {
         a_delta = (unsigned)(k0 * Cb * 2);
+      } else if (yfirst) {
+        const int y0 = k0 / rb, n0 = (k0 - y0 * rb) >> p.hs_shift;
+        a_delta = (unsigned)(((n0 * Hb + 2 * y0) * Hb) * Cb * 2);
+        y2 = 2 * y0;
+        b_delta = (unsigned)(((n0 * Hs + y0) * Hs) * Cs * 2);
       } else {
         const int n0 = k0 >> (2 * p.hs_shift), y0 = (k0 & (rps - 1)) >> p.hs_shift;
         a_delta = (unsigned)(((n0 * Hb + 2 * y0) * Hb) * Cb * 2);
@@ -896,7 +971,6 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
         load16_to_lds(a_rsrc, off, a_dst + i * NT_ * 16);
       }
     }
-    const unsigned b_delta = (unsigned)(k0 * Cs * 2);
 #pragma unroll
     for (int i = 0; i < PB; ++i)
       load16_to_lds(b_rsrc, (rowB0 + i * RPB < left && okB) ? fb_off[i] + b_delta : NO_ROW, b_dst + i * NT_ * 16);
@@ -944,18 +1018,27 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
     }
   };
 
-  // chunks of all segments as one sequence
-  const int per_seg = r_hi > r_lo ? (r_hi - r_lo + WG_KR - 1) / WG_KR : 0;
+  // chunks of all segments as one sequence; in pixel-row-first order the chunks [bad0, bad0 + nbad) of every segment
+  // (the pixel row whose tap row is outside the map) are left out
+  const int per_seg_all = r_hi > r_lo ? (r_hi - r_lo + WG_KR - 1) / WG_KR : 0;
+  int bad0 = 0, nbad = 0;
+  if (yfirst && per_seg_all > 0 && (ky_tile == 0 || ky_tile == 3)) {
+    const int yb = ky_tile == 0 ? 0 : Hs - 1;
+    const int lo = max(yb * rb, r_lo), hi = min((yb + 1) * rb, r_hi);      // rows of that pixel row inside this block's share
+    if (hi > lo) { bad0 = (lo - r_lo) / WG_KR; nbad = (hi - lo) / WG_KR; } // both multiples of the chunk height
+  }
+  const int per_seg = per_seg_all - nbad;
   const int nchunks = per_seg * p.nseg;
+  auto chunk_row = [&](int cin) { return r_lo + (cin < bad0 ? cin : cin + nbad) * WG_KR; };
   if (nchunks > 0) {
-    load_chunk(0, r_lo, 0);
+    load_chunk(0, chunk_row(0), 0);
     wait_vm0();
     __syncthreads();
     int seg = 0, cin = 0;
     for (int c = 0; c < nchunks; ++c) {
       if (c + 1 < nchunks) {
         if (++cin == per_seg) { cin = 0; ++seg; }
-        load_chunk(seg, r_lo + cin * WG_KR, (c + 1) & 1);
+        load_chunk(seg, chunk_row(cin), (c + 1) & 1);
       }
       mma_chunk(c & 1);
       wait_vm0();
