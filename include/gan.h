@@ -87,8 +87,31 @@ typedef struct {
   float    bn_eps, bn_momentum, leaky_slope;  /* the paper's tables: momentum 0.1, slope 0.2          */
   float    d_loss_scale, g_loss_scale;        /* the factors 1/2 in Eq. 3 and Eq. 4                   */
   float    init_std;        /* built-in initialiser: weights ~ N(0, init_std^2), gamma 1, the rest 0  */
-  uint64_t seed;            /* seed of the built-in initialiser                                       */
+  uint64_t seed;            /* seed of the built-in initialiser and of the dropout masks              */
+  int32_t  family;          /* gan_family: which networks (see below)                                 */
+  float    bn_eps_first;    /* GAN_FAMILY_PAPER: epsilon of G's first BatchNorm (Table 1: 1e-5)       */
+  float    dropout_p;       /* GAN_FAMILY_PAPER: dropout probability in D (Table 2: 0.25), in [0, 1)  */
 } gan_config;
+
+/* GAN_FAMILY_STRIDED (0): the k4 s2 p1 convolution / transposed-convolution networks described above.
+   GAN_FAMILY_PAPER (1): the networks exactly as the paper's Tables 1 and 2 print them (Section 4), unconditional
+   (cond_g = cond_d = 0; the label only selects the model):
+     G: z -> linear (+bias) -> ReLU -> [g_ch[0], g_h0, g_h0] -> BN(bn_eps_first)
+        -> { Upsample x2 -> Conv k3 s1 p1 (g_ch[i-1] -> g_ch[i]) -> BN(bn_eps) -> LeakyReLU } for i = 1 .. n_g-1
+        -> Conv k3 s1 p1 (g_ch[n_g-1] -> img_c, +bias) -> tanh                       img_hw = g_h0 * 2^(n_g-1)
+     D: { Conv k3 s2 p1 (+bias) -> LeakyReLU -> Dropout(dropout_p) [-> BN(bn_eps), not after the first] } x n_d
+        -> flatten -> linear (+bias) -> logit
+   g_ch must be multiples of 64; d_ch may be any width up to 1024 (held padded to multiples of 64, the padding stays
+   exactly zero).  Dropout is active in all three discriminator passes of an iteration (real, fake, fake through the
+   updated D: pass ids 0, 1, 2), kept values scaled by 1 / (1 - p); the mask is the one gan_op_dropout documents, with
+   layer = 1 .. n_d, step = the number of iterations the model has run (counting this one) and seed = cfg.seed.
+   Flat parameter order:
+     G: fc.w [g_ch[0]*g_h0*g_h0, z_dim] (rows in (c,h,w) order), fc.b, bn0.gamma, bn0.beta, then per block i:
+        conv.w [g_ch[i], g_ch[i-1], 3, 3], gamma, beta; then conv.w [img_c, g_ch[n_g-1], 3, 3], conv.b.
+     D: per conv j: w [d_ch[j], Cin, 3, 3], b [d_ch[j]], and for j > 0 gamma, beta; then fc.w [d_ch[last]*h*h] in
+        (c,h,w) order, fc.b.
+   BatchNorm running statistics (gan_get_bn_running): the BN layers in network order, real channels only. */
+typedef enum { GAN_FAMILY_STRIDED = 0, GAN_FAMILY_PAPER = 1 } gan_family;
 
 /* Allocate a context on the current device.  hip_stream is a hipStream_t (0 = the null stream).
    Fails with GAN_E_SHAPE when a channel count is not a multiple of 64, img_c > 4, the sides do not
@@ -220,7 +243,7 @@ gan_status gan_op_conv_wgrad(gan_ctx* ctx, const void* big, const void* small_in
                              int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs);
 
 /* Single operations of the networks exactly as printed in Tables 1 and 2 (Section 4), synchronous like the ones above.
-   These are building blocks; the training step for those networks is not part of this library yet.
+   (The training step for those networks is gan_train_step with family = GAN_FAMILY_PAPER.)
 
    gan_op_dropout: in place on a DEVICE tensor [n_samples][h][w][ch] of the context's storage type whose samples are
      grouped by model (offs: DEVICE int32 [n_groups + 1]): element <- element * keep / (1 - p) (Table 2: Dropout(0.25)).

@@ -10,6 +10,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 MAX_LAYERS = 8
 FP32, BF16 = 0, 1
+FAMILY_STRIDED, FAMILY_PAPER = 0, 1
 
 GAN_OK, GAN_E_ARG, GAN_E_SHAPE, GAN_E_OOM, GAN_E_HIP, GAN_E_LABEL, GAN_E_STATE = 0, -1, -2, -3, -4, -5, -6
 
@@ -33,6 +34,7 @@ class GanConfig(C.Structure):
         ("bn_eps", C.c_float), ("bn_momentum", C.c_float), ("leaky_slope", C.c_float),
         ("d_loss_scale", C.c_float), ("g_loss_scale", C.c_float),
         ("init_std", C.c_float), ("seed", C.c_uint64),
+        ("family", C.c_int32), ("bn_eps_first", C.c_float), ("dropout_p", C.c_float),
     ]
 
 
@@ -123,8 +125,10 @@ def probe_copy(nbytes=1 << 30, stream=0):
 
 
 def make_config(spec, n_models, n_labels, max_total_batch, precision=FP32, hyper=None, seed=1):
-    h = dict(lr=2e-4, beta1=0.5, beta2=0.999, adam_eps=1e-8, bn_eps=1e-5, bn_momentum=0.1,
-             leaky_slope=0.2, d_loss_scale=0.5, g_loss_scale=0.5, init_std=0.02)
+    paper = spec.get("family") == "paper"
+    h = dict(lr=2e-4, beta1=0.5, beta2=0.999, adam_eps=1e-8, bn_eps=0.8 if paper else 1e-5, bn_momentum=0.1,
+             leaky_slope=0.2, d_loss_scale=0.5, g_loss_scale=0.5, init_std=0.02, bn_eps_first=1e-5,
+             dropout_p=0.25 if paper else 0.0)
     h.update(hyper or {})
     c = GanConfig()
     c.struct_size = C.sizeof(GanConfig)
@@ -139,6 +143,7 @@ def make_config(spec, n_models, n_labels, max_total_batch, precision=FP32, hyper
     for i, v in enumerate(spec["d_ch"]):
         c.d_ch[i] = v
     c.max_total_batch = max_total_batch
+    c.family = FAMILY_PAPER if paper else FAMILY_STRIDED
     for k, v in h.items():
         setattr(c, k, v)
     c.seed = seed

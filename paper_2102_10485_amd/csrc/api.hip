@@ -42,6 +42,10 @@ struct ConvLayer {
   long long rs = -1;                                    // offset into the running-statistics block
   int bnC = 0;                                          // channels normalised after this layer (0: none)
   int nbias = 0;
+  // networks as printed in the paper's tables: real (unpadded) channel counts, and for G's blocks the place of the
+  // summed-tap k4 weights in the storage-type arenas
+  int cs_real = 0, cb_real = 0;
+  long long w4 = -1;
 };
 
 struct Net {
@@ -53,6 +57,11 @@ struct Net {
   long long Pext = 0;              // parameters per model in the documented order
   long long nbn = 0;
   std::vector<long long> ext2int;  // documented index -> internal index
+  std::vector<long long> bn_ext2int;   // documented running-statistics index -> internal (empty: identical)
+  std::vector<int> ext_kind;       // per documented element: 0 weight, 1 gamma, 2 zero-initialised (built-in initialiser)
+  // networks as printed in the paper's tables (G): k4 weights with summed taps, [tap][cb][cs] and [tap][cs][cb]
+  long long fc_bias = -1, P4 = 0;
+  void *w4u = nullptr, *w4d = nullptr;
   float *theta = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
   void *shadow_u = nullptr, *shadow_d = nullptr;   // storage-type copies: [tap][cb][cs] and [tap][cs][cb]
   float *run_mean = nullptr, *run_var = nullptr;
@@ -85,6 +94,8 @@ struct gan_ctx {
   float* head_part = nullptr;      // row-split partial sums of the linear head's weight gradient (few models only)
   int head_rsplit = 1;
   float* wg_part = nullptr;        // row-split partial weight gradients (few models only)
+  bool paper = false;              // the networks as printed in the paper's tables
+  float *dw4 = nullptr, *c3_part = nullptr;   // paper G: k4 weight gradient of one block; row-split partials of the last conv
   int KcD = 0, KcG = 0;
   int nslot = 1;
   int last_n = -1;
@@ -263,6 +274,101 @@ void build_layout(gan_ctx* c) {
   }
 }
 
+// The networks as printed in the paper's Tables 1 and 2.  D's k3 s2 p1 convolutions sit in the engine's k4 layout
+// (fourth tap row / column and channel padding are not parameters and stay zero); G's Upsample + k3 blocks keep their
+// 3 x 3 weights as parameters and run on k4 weights with summed taps rebuilt after every update.
+void build_layout_paper(gan_ctx* c) {
+  const gan_config& f = c->cfg;
+  auto pad64 = [](int v) { return (int)round_up(v, 64); };
+  {
+    Net& G = c->G;
+    long long o = 0, r = 0, o4 = 0;
+    G.Kz = f.z_dim; G.Kp = (int)round_up(G.Kz, 64);
+    G.C0 = f.g_ch[0]; G.h0 = f.g_h0; G.J = G.C0 * G.h0 * G.h0;
+    G.fc_w = o; o += (long long)G.J * G.Kp;
+    G.fc_bias = o; o += G.J;
+    G.fc_gamma = o; o += G.C0; G.fc_beta = o; o += G.C0; G.fc_rs = r; r += G.C0;
+    o = round_up(o, 8);
+    auto ext = [&](long long internal, int kind) { G.ext2int.push_back(internal); G.ext_kind.push_back(kind); };
+    for (int ch = 0; ch < G.C0; ++ch)
+      for (int y = 0; y < G.h0; ++y)
+        for (int x = 0; x < G.h0; ++x)
+          for (int i = 0; i < G.Kz; ++i) ext(G.fc_w + ((long long)((y * G.h0 + x) * G.C0 + ch)) * G.Kp + i, 0);
+    for (int ch = 0; ch < G.C0; ++ch)
+      for (int y = 0; y < G.h0; ++y)
+        for (int x = 0; x < G.h0; ++x) ext(G.fc_bias + (long long)(y * G.h0 + x) * G.C0 + ch, 2);
+    for (int ch = 0; ch < G.C0; ++ch) ext(G.fc_gamma + ch, 1);
+    for (int ch = 0; ch < G.C0; ++ch) ext(G.fc_beta + ch, 2);
+    int h = f.g_h0;
+    for (int i = 1; i < f.n_g; ++i) {                       // Upsample x2 + Conv k3: 3 x 3 master weights [9][cb][cs]
+      ConvLayer l;
+      l.Cs = f.g_ch[i - 1]; l.Cb = f.g_ch[i]; l.CBT = l.Cb; l.Hs = h; l.cs_real = l.Cs; l.cb_real = l.Cb;
+      l.w = o; o += (long long)9 * l.Cb * l.Cs;
+      l.w4 = o4; o4 += (long long)16 * l.Cb * l.Cs;
+      for (int co = 0; co < l.Cb; ++co)
+        for (int ci = 0; ci < l.Cs; ++ci)
+          for (int tap = 0; tap < 9; ++tap) ext(l.w + ((long long)tap * l.Cb + co) * l.Cs + ci, 0);
+      l.gamma = o; o += l.Cb; l.beta = o; o += l.Cb; l.rs = r; r += l.Cb; l.bnC = l.Cb;
+      for (int ch = 0; ch < l.Cb; ++ch) ext(l.gamma + ch, 1);
+      for (int ch = 0; ch < l.Cb; ++ch) ext(l.beta + ch, 2);
+      o = round_up(o, 8);
+      G.conv.push_back(l);
+      h *= 2;
+    }
+    {                                                       // last: Conv k3 s1 p1 onto the image, [9][img_c][cs]
+      ConvLayer l;
+      l.Cs = f.g_ch[f.n_g - 1]; l.Cb = f.img_c; l.CBT = l.Cb; l.Hs = h; l.cs_real = l.Cs; l.cb_real = l.Cb;
+      l.w = o; o += (long long)9 * l.Cb * l.Cs;
+      for (int co = 0; co < l.Cb; ++co)
+        for (int ci = 0; ci < l.Cs; ++ci)
+          for (int tap = 0; tap < 9; ++tap) ext(l.w + ((long long)tap * l.Cb + co) * l.Cs + ci, 0);
+      l.bias = o; l.nbias = l.Cb; o += l.Cb;
+      for (int ch = 0; ch < l.Cb; ++ch) ext(l.bias + ch, 2);
+      o = round_up(o, 8);
+      G.conv.push_back(l);
+    }
+    G.P = round_up(o, 64); G.Pext = (long long)G.ext2int.size(); G.nbn = r; G.P4 = round_up(o4, 64);
+  }
+  {
+    Net& D = c->D;
+    long long o = 0, r = 0;
+    auto ext = [&](long long internal, int kind) { D.ext2int.push_back(internal); D.ext_kind.push_back(kind); };
+    int h = f.img_hw;
+    for (int j = 0; j < f.n_d; ++j) {
+      ConvLayer l;
+      l.cb_real = (j == 0) ? f.img_c : f.d_ch[j - 1];
+      l.cs_real = f.d_ch[j];
+      l.Cb = (j == 0) ? f.img_c : pad64(l.cb_real); l.CBT = l.Cb; l.Cs = pad64(l.cs_real); l.Hs = h / 2;
+      l.w = o; o += (long long)16 * l.CBT * l.Cs;
+      for (int co = 0; co < l.cs_real; ++co)
+        for (int ci = 0; ci < l.cb_real; ++ci)
+          for (int ky = 0; ky < 3; ++ky)
+            for (int kx = 0; kx < 3; ++kx) ext(l.w + ((long long)(ky * 4 + kx) * l.CBT + ci) * l.Cs + co, 0);
+      l.bias = o; l.nbias = l.Cs; o += l.Cs;
+      for (int ch = 0; ch < l.cs_real; ++ch) ext(l.bias + ch, 2);
+      if (j > 0) {
+        l.gamma = o; o += l.Cs; l.beta = o; o += l.Cs; l.rs = r; l.bnC = l.Cs;
+        for (int ch = 0; ch < l.cs_real; ++ch) ext(l.gamma + ch, 1);
+        for (int ch = 0; ch < l.cs_real; ++ch) ext(l.beta + ch, 2);
+        for (int ch = 0; ch < l.cs_real; ++ch) D.bn_ext2int.push_back(r + ch);
+        r += l.Cs;
+      }
+      o = round_up(o, 8);
+      D.conv.push_back(l);
+      h /= 2;
+    }
+    const ConvLayer& last = D.conv.back();
+    D.K = last.Cs * h * h; D.h0 = h; D.C0 = last.Cs;
+    D.fc_w = o; o += D.K;
+    for (int ch = 0; ch < last.cs_real; ++ch)
+      for (int y = 0; y < h; ++y)
+        for (int x = 0; x < h; ++x) ext(D.fc_w + (long long)(y * h + x) * last.Cs + ch, 0);
+    D.fc_b = o; o += 1;
+    ext(D.fc_b, 2);
+    D.P = round_up(o, 64); D.Pext = (long long)D.ext2int.size(); D.nbn = r;
+  }
+}
+
 bool alloc_net(gan_ctx* c, Net& n) {
   const size_t tot = (size_t)c->L * n.P;
   bool ok = dev_alloc(c, (void**)&n.theta, tot * 4) && dev_alloc(c, (void**)&n.m, tot * 4) &&
@@ -334,6 +440,36 @@ void builtin_init(gan_ctx* c) {
   fill(c, c->D.run_var, (long long)c->L * c->D.nbn, 1.f);
 }
 
+// Built-in initialiser of the networks as printed in the tables: drawn on the host in the documented order and placed
+// through the index map, so that padding and the unused fourth taps stay zero.
+static float host_normal(unsigned long long& st) {
+  auto next = [&]() {
+    unsigned long long z = (st += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+  };
+  const double u1 = ((double)(next() >> 11) + 1.0) / 9007199254740993.0, u2 = (double)(next() >> 11) / 9007199254740992.0;
+  return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586 * u2));
+}
+bool builtin_init_paper(gan_ctx* c) {
+  unsigned long long st = c->cfg.seed * 0x100000001B3ull + 17;
+  for (Net* n : {&c->G, &c->D}) {
+    std::vector<float> tmp((size_t)n->P);
+    for (int l = 0; l < c->L; ++l) {
+      std::fill(tmp.begin(), tmp.end(), 0.f);
+      for (long long i = 0; i < n->Pext; ++i) {
+        const int kind = n->ext_kind[(size_t)i];
+        tmp[(size_t)n->ext2int[(size_t)i]] = kind == 0 ? c->cfg.init_std * host_normal(st) : (kind == 1 ? 1.f : 0.f);
+      }
+      if (hipMemcpy(n->theta + (long long)l * n->P, tmp.data(), (size_t)n->P * 4, hipMemcpyHostToDevice) != hipSuccess) return false;
+    }
+  }
+  fill(c, c->G.run_var, (long long)c->L * c->G.nbn, 1.f);
+  fill(c, c->D.run_var, (long long)c->L * c->D.nbn, 1.f);
+  return true;
+}
+
 // ---- storage-type copies of the weights ------------------------------------------------------------------
 PackArgs pack_args(gan_ctx* c, Net& net, const ConvLayer& cl, int Kc, int nslot, void* wp);
 
@@ -354,9 +490,22 @@ void refresh_transposes(gan_ctx* c, Net& n, bool isG) {
       launch_transpose_w<float, float>((const float*)n.theta + cl.w, (float*)n.shadow_d + cl.w, n.P, c->L, cl.Cb, cl.Cs, c->st);
   }
 }
+// k4 weights with summed taps of G's Upsample + Conv k3 blocks, from the 3 x 3 master weights
+template <typename T>
+void paper_rebuild_w4(gan_ctx* c) {
+  Net& G = c->G;
+  for (size_t i = 0; i + 1 < G.conv.size(); ++i) {
+    const ConvLayer& cl = G.conv[i];
+    launch_w3_to_w4<T>(G.theta + cl.w, (T*)G.w4u + cl.w4, (T*)G.w4d + cl.w4, c->L, cl.Cb, cl.Cs, c->st, G.P, G.P4);
+  }
+}
 void refresh_shadows(gan_ctx* c) {
   for (Net* n : {&c->G, &c->D}) {
     if (c->bf16) launch_cast_shadow<bf16_t>(n->theta, (bf16_t*)n->shadow_u, (long long)c->L * n->P, c->st);
+    if (c->paper && n == &c->G) {
+      if (c->bf16) paper_rebuild_w4<bf16_t>(c); else paper_rebuild_w4<float>(c);
+      continue;
+    }
     if (c->bf16) refresh_transposes<bf16_t>(c, *n, n == &c->G); else refresh_transposes<float>(c, *n, n == &c->G);
   }
   c->shadows_dirty = false;
@@ -650,6 +799,216 @@ void g_backward(gan_ctx* c, int n) {
   wgrad_call<T>(c, "gemm_wgrad_dense", c->bufB, c->zin, G.g + G.fc_w, G.P, G.J, G.Kp, 1, 1, 1, n);
 }
 
+// ---- the networks as printed in the paper's Tables 1 and 2 ---------------------------------------------------
+PointArgs point_args(gan_ctx* c, void* x, int C, int Cpad, int HW, int seg_first, int nseg, int n) {
+  PointArgs a;
+  memset(&a, 0, sizeof(a));
+  a.x = x; a.offs = c->rb.offs; a.sample_model = c->rb.sample_model; a.L = c->L; a.n = n; a.C = C; a.Cpad = Cpad; a.HW = HW;
+  a.seg_first = seg_first; a.nseg = nseg; a.seg_samples = n; a.slope = 1.f; a.scale = 1.f;
+  a.seed_lo = (unsigned)(c->cfg.seed & 0xffffffffull); a.seed_hi = (unsigned)(c->cfg.seed >> 32);
+  return a;
+}
+// dropout of D's block `layer` (1-based) in the passes pass0 (first processed segment) and pass0 + 1
+void with_dropout(gan_ctx* c, PointArgs& a, int layer, int pass0, int step_add) {
+  const float p = c->cfg.dropout_p;
+  if (!(p > 0.f)) return;
+  a.thr = (unsigned)ceil((double)p * 16777216.0);
+  a.scale = 1.0f / (1.0f - p);
+  a.layer = layer; a.pass_of_seg[0] = pass0; a.pass_of_seg[1] = pass0 + 1;
+  a.steps = c->D.t; a.step_add = step_add;
+}
+
+// BatchNorm whose statistics are taken from the stored tensor; no activation after it
+template <typename T>
+void bn_forward_direct(gan_ctx* c, NormArgs a, const void* x, void* y, float eps, bool use_running, bool update_running) {
+  a.x = x; a.y = y; a.eps = eps; a.slope = 1.f;
+  if (use_running) {
+    launch_bn_from_running(a, c->st);
+  } else {
+    launch_bn_stats_direct<T>(a, a.C, c->st);
+    if (update_running) launch_bn_running(a, c->st);
+  }
+  Scope s(c, "bn_apply", 0, 2.0 * a.n * a.nseg * a.rps * a.C * sizeof(T));
+  launch_bn_apply<T>(a, c->st);
+}
+
+template <typename T>
+void paper_g_forward(gan_ctx* c, int n, bool use_running, bool update_running) {
+  Net& G = c->G;
+  const gan_config& f = c->cfg;
+  conv_call<T>(c, "gemm_dense", MODE_DENSE, EPI_NONE, c->zin, (const T*)G.shadow_u + G.fc_w, G.P, c->gpre[0], nullptr, G.Kp, G.J,
+               1, 1, 0, 1, n);
+  {
+    PointArgs a = point_args(c, c->gpre[0], G.J, G.J, 1, 0, 1, n);          // + bias, ReLU
+    a.bias = G.theta + G.fc_bias; a.pstride = G.P; a.slope = 0.f;
+    Scope s(c, "bias_act_dropout", 0, 2.0 * n * G.J * sizeof(T));
+    launch_point_fwd<T>(a, c->st);
+  }
+  bn_forward_direct<T>(c, norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
+                                       c->g_sums[0], 0, 1, n, 1.f),
+                       c->gpre[0], c->gact[0], f.bn_eps_first, use_running, update_running);
+  const int nl = (int)G.conv.size();
+  for (int i = 0; i + 1 < nl; ++i) {                   // Upsample x2 + Conv k3 as a k4 s2 p1 transposed convolution
+    const ConvLayer& cl = G.conv[i];
+    conv_call<T>(c, "gemm_up", MODE_UP, EPI_NONE, c->gact[i], (const T*)G.w4u + cl.w4, G.P4, c->gpre[i + 1], nullptr, cl.Cs, cl.Cb,
+                 cl.Hs, cl.Hs, 0, 1, n, 0, -1.0, !use_running);
+    NormArgs a = norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
+                              c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, f.leaky_slope);
+    bn_forward<T>(c, a, c->gpre[i + 1], c->gact[i + 1], use_running, update_running, cl.Hs * cl.Hs, 4);
+  }
+  const ConvLayer& cl = G.conv[nl - 1];                // Conv k3 s1 p1 (+bias) -> tanh, into the fake half of D's image buffer
+  Conv3Args a;
+  memset(&a, 0, sizeof(a));
+  a.in = c->gact[nl - 1]; a.out = c->xd; a.w = G.theta + cl.w; a.w_stride = G.P; a.bias = G.theta + cl.bias; a.bias_stride = G.P;
+  a.offs = c->rb.offs; a.sample_model = c->rb.sample_model; a.L = c->L; a.n = n; a.H = cl.Hs; a.Cin = cl.Cs; a.CO = cl.Cb;
+  a.out_seg = 1; a.seg_samples = n;
+  Scope s(c, "conv3_img", 2.0 * n * cl.Hs * cl.Hs * 9 * cl.Cs * cl.Cb, sizeof(T) * (double)n * cl.Hs * cl.Hs * (cl.Cs + cl.Cb));
+  launch_conv3_fwd<T>(a, c->st);
+}
+
+// pass0: dropout pass id of the first processed segment (real 0, fake 1, fake through the updated D 2);
+// step_add: 1 before D's update of this iteration, 0 after it (the iteration number is D's step count + step_add)
+template <typename T>
+void paper_d_forward(gan_ctx* c, int n, int seg_first, int nseg, bool update_running, int pass0, int step_add) {
+  Net& D = c->D;
+  const gan_config& f = c->cfg;
+  const ConvLayer& c1 = D.conv[0];
+  conv_call<T>(c, "gemm_dense_img", MODE_DENSE, EPI_LRELU, c->colD, c->wpD, (long long)c1.Cs * c->KcD, c->dact[0], nullptr, c->KcD,
+               c1.Cs, 1, c1.Hs, seg_first, nseg, n, 0, img_flops(c1, n, nseg));
+  if (f.dropout_p > 0.f) {
+    PointArgs a = point_args(c, c->dact[0], c1.cs_real, c1.Cs, c1.Hs * c1.Hs, seg_first, nseg, n);
+    with_dropout(c, a, 1, pass0, step_add);
+    Scope s(c, "bias_act_dropout", 0, 2.0 * n * nseg * c1.Hs * c1.Hs * c1.cs_real * sizeof(T));
+    launch_point_fwd<T>(a, c->st);
+  }
+  const int nl = (int)D.conv.size();
+  for (int j = 1; j < nl; ++j) {
+    const ConvLayer& cl = D.conv[j];
+    conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->dact[j - 1], (const T*)D.shadow_d + cl.w, D.P, c->dpre[j], nullptr, cl.Cb,
+                 cl.Cs, 2 * cl.Hs, cl.Hs, seg_first, nseg, n);
+    PointArgs a = point_args(c, c->dpre[j], cl.cs_real, cl.Cs, cl.Hs * cl.Hs, seg_first, nseg, n);
+    a.bias = D.theta + cl.bias; a.pstride = D.P; a.slope = f.leaky_slope;
+    with_dropout(c, a, j + 1, pass0, step_add);
+    { Scope s(c, "bias_act_dropout", 0, 2.0 * n * nseg * cl.Hs * cl.Hs * cl.cs_real * sizeof(T)); launch_point_fwd<T>(a, c->st); }
+    bn_forward_direct<T>(c, norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
+                                         c->d_sums[j], seg_first, nseg, n, 1.f),
+                         c->dpre[j], c->dact[j], f.bn_eps, false, update_running);
+  }
+  HeadArgs h;
+  memset(&h, 0, sizeof(h));
+  h.feat = c->dact[nl - 1]; h.w = D.theta + D.fc_w; h.b = D.theta + D.fc_b; h.pstride = D.P; h.logits = c->logits;
+  h.offs = c->rb.offs; h.sample_model = c->rb.sample_model; h.L = c->L; h.K = D.K;
+  h.seg_first = seg_first; h.nseg = nseg; h.seg_samples = n; h.n = n;
+  Scope s(c, "head_fwd", 0, sizeof(T) * (double)n * nseg * D.K);
+  launch_head_fwd<T>(h, c->st);
+}
+
+template <typename T>
+void paper_d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bool to_image, int pass0, int step_add) {
+  Net& D = c->D;
+  const gan_config& f = c->cfg;
+  const int nl = (int)D.conv.size();
+  HeadArgs h;
+  memset(&h, 0, sizeof(h));
+  h.feat = c->dact[nl - 1]; h.dfeat = c->bufA; h.w = D.theta + D.fc_w; h.b = D.theta + D.fc_b;
+  h.dw = D.g + D.fc_w; h.db = D.g + D.fc_b; h.pstride = D.P; h.dlogits = c->dlogits;
+  h.part = c->head_part; h.rsplit = c->head_rsplit;
+  h.offs = c->rb.offs; h.sample_model = c->rb.sample_model; h.L = c->L; h.K = D.K;
+  h.seg_first = seg_first; h.nseg = nseg; h.seg_samples = n; h.n = n;
+  { Scope s(c, "head_bwd_data", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_data<T>(h, c->st); }
+  if (param_grads) { Scope s(c, "head_bwd_w", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_w<T>(h, c->st); }
+  for (int j = nl - 1; j >= 1; --j) {
+    const ConvLayer& cl = D.conv[j];
+    NormArgs na = norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
+                               c->d_sums[j], seg_first, nseg, n, 1.f);
+    na.eps = f.bn_eps;
+    bn_backward<T>(c, na, c->dpre[j], c->bufA, c->bufB, param_grads);         // -> gradient w.r.t. the dropped activations
+    PointArgs a = point_args(c, c->bufB, cl.cs_real, cl.Cs, cl.Hs * cl.Hs, seg_first, nseg, n);
+    a.saved = c->dpre[j]; a.slope = f.leaky_slope;
+    with_dropout(c, a, j + 1, pass0, step_add);
+    { Scope s(c, "act_dropout_bwd", 0, 3.0 * n * nseg * cl.Hs * cl.Hs * cl.cs_real * sizeof(T)); launch_point_bwd<T>(a, c->st); }
+    if (param_grads) {
+      launch_col_sum<T>(a, D.g + cl.bias, D.P, c->st);
+      wgrad_call<T>(c, "gemm_wgrad", c->dact[j - 1], c->bufB, D.g + cl.w, D.P, cl.Cb, cl.Cs, cl.Hs, 16, nseg, n);
+    }
+    conv_call<T>(c, "gemm_up", MODE_UP, j == 1 ? EPI_ACT_BWD : EPI_NONE, c->bufB, (const T*)D.shadow_u + cl.w, D.P, c->bufA,
+                 j == 1 ? c->dact[0] : nullptr, cl.Cs, cl.Cb, cl.Hs, cl.Hs, seg_first, nseg, n);
+  }
+  const ConvLayer& c1 = D.conv[0];
+  if (f.dropout_p > 0.f) {      // the first block's dropout (its LeakyReLU derivative came with the data gradient above)
+    PointArgs a = point_args(c, c->bufA, c1.cs_real, c1.Cs, c1.Hs * c1.Hs, seg_first, nseg, n);
+    a.saved = c->dact[0];
+    with_dropout(c, a, 1, pass0, step_add);
+    Scope s(c, "act_dropout_bwd", 0, 2.0 * n * nseg * c1.Hs * c1.Hs * c1.cs_real * sizeof(T));
+    launch_point_bwd<T>(a, c->st);
+  }
+  if (param_grads) {
+    wgrad_call<T>(c, "gemm_wgrad_img", c->colD, c->bufA, c->dwp, (long long)c->KcD * c1.Cs, c->KcD, c1.Cs, c1.Hs, 1, nseg, n,
+                  img_flops(c1, n, nseg), c->img_ksplit);
+    launch_unpack_dw(pack_args(c, D, c1, c->KcD, c->nslot, c->wpD), c->st);
+    for (const ConvLayer& cl : D.conv) launch_clear_fourth_taps(D.g + cl.w, D.P, c->L, cl.CBT, cl.Cs, c->st);
+  }
+  if (to_image) up_img_call<T>(c, D, c1, c->bufA, c->dimg, c->xd, 2, 1, n);
+}
+
+template <typename T>
+void paper_g_backward(gan_ctx* c, int n) {
+  Net& G = c->G;
+  const gan_config& f = c->cfg;
+  const int nl = (int)G.conv.size();
+  const ConvLayer& last = G.conv[nl - 1];
+  const T* dlast = (const T*)c->dimg + (long long)n * last.Hs * last.Hs * last.Cb;
+  {
+    Conv3Args a;
+    memset(&a, 0, sizeof(a));
+    a.in = c->gact[nl - 1]; a.dout = c->dimg; a.din = c->bufA; a.w = G.theta + last.w; a.w_stride = G.P;
+    a.offs = c->rb.offs; a.sample_model = c->rb.sample_model; a.L = c->L; a.n = n; a.H = last.Hs; a.Cin = last.Cs; a.CO = last.Cb;
+    a.out_seg = 1; a.seg_samples = n;
+    { Scope s(c, "conv3_img_wgrad", 2.0 * n * last.Hs * last.Hs * 9 * last.Cs * last.Cb, sizeof(T) * (double)n * last.Hs * last.Hs * (last.Cs + last.Cb));
+      launch_conv3_wgrad<T>(a, c->c3_part, G.g + last.w, G.P, c->st); }
+    ImgBiasArgs b;
+    b.img = dlast; b.partial = c->bias_partial; b.dbias = G.g + last.bias; b.pstride = G.P; b.offs = c->rb.offs;
+    b.L = c->L; b.CB = last.Cb; b.HW = last.Hs * last.Hs;
+    launch_img_bias_grad<T>(b, c->st);
+    Scope s(c, "conv3_img_dgrad", 2.0 * n * last.Hs * last.Hs * 9 * last.Cs * last.Cb, sizeof(T) * (double)n * last.Hs * last.Hs * (last.Cs + last.Cb));
+    launch_conv3_dgrad<T>(a, c->st);
+  }
+  for (int i = nl - 2; i >= 0; --i) {
+    const ConvLayer& cl = G.conv[i];
+    NormArgs na = norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
+                               c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, f.leaky_slope);
+    bn_backward<T>(c, na, c->gpre[i + 1], c->bufA, c->bufB, true);
+    const long long per = (long long)16 * cl.Cb * cl.Cs;
+    wgrad_call<T>(c, "gemm_wgrad", c->bufB, c->gact[i], c->dw4, per, cl.Cb, cl.Cs, cl.Hs, 16, 1, n);
+    launch_dw4_to_dw3(c->dw4, G.g + cl.w, c->L, cl.Cb, cl.Cs, c->st, per, G.P);
+    conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->bufB, (const T*)G.w4d + cl.w4, G.P4, c->bufA, nullptr, cl.Cb, cl.Cs,
+                 2 * cl.Hs, cl.Hs, 0, 1, n);
+  }
+  NormArgs na = norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
+                             c->g_sums[0], 0, 1, n, 1.f);
+  na.eps = f.bn_eps_first;
+  bn_backward<T>(c, na, c->gpre[0], c->bufA, c->bufB, true);
+  PointArgs a = point_args(c, c->bufB, G.J, G.J, 1, 0, 1, n);                 // ReLU derivative from the stored output
+  a.saved = c->gpre[0]; a.slope = 0.f;
+  { Scope s(c, "act_dropout_bwd", 0, 3.0 * n * G.J * sizeof(T)); launch_point_bwd<T>(a, c->st); }
+  launch_col_sum<T>(a, G.g + G.fc_bias, G.P, c->st);
+  wgrad_call<T>(c, "gemm_wgrad_dense", c->bufB, c->zin, G.g + G.fc_w, G.P, G.J, G.Kp, 1, 1, 1, n);
+}
+
+template <typename T>
+void paper_adam_g(gan_ctx* c) {
+  Net& G = c->G;
+  AdamArgs a = {};
+  a.theta = G.theta; a.m = G.m; a.v = G.v; a.g = G.g; a.shadow = c->bf16 ? G.shadow_u : nullptr; a.shadow_t = nullptr;
+  a.P = G.P; a.L = c->L; a.counts = c->rb.counts; a.t = G.t; a.bc = G.bc;
+  a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps;
+  {
+    Scope s(c, "adam", 0, (double)c->L * G.P * (28.0 + (c->bf16 ? 2.0 : 0.0)));
+    launch_adam<T>(a, c->st);
+  }
+  paper_rebuild_w4<T>(c);
+}
+
 template <typename T>
 void adam_call(gan_ctx* c, Net& net, bool isG) {
   AdamArgs a = {};
@@ -687,7 +1046,25 @@ void route_and_stage(gan_ctx* c, const int32_t* label_ids, const float* noise, c
 }
 
 template <typename T>
+void paper_train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real, int n) {
+  if (c->shadows_dirty) refresh_shadows(c);
+  route_and_stage<T>(c, label_ids, noise, real, n);
+  paper_g_forward<T>(c, n, false, true);                               // fake = G(z)
+  im2col_call<T>(c, c->D.conv[0], c->xd, nullptr, c->colD, c->KcD, c->nslot, 1, n);
+  paper_d_forward<T>(c, n, 0, 2, true, 0, 1);                          // D(real), D(fake): dropout passes 0 and 1
+  loss_call(c, n, 0);                                                  // Eq. 3
+  paper_d_backward<T>(c, n, 0, 2, true, false, 0, 1);
+  adam_call<T>(c, c->D, false);
+  paper_d_forward<T>(c, n, 1, 1, true, 2, 0);                          // updated D on the same fake batch: pass 2
+  loss_call(c, n, 1);                                                  // Eq. 4 (negated: minimised)
+  paper_d_backward<T>(c, n, 1, 1, false, true, 2, 0);
+  paper_g_backward<T>(c, n);
+  paper_adam_g<T>(c);
+}
+
+template <typename T>
 void train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const float* real, int n) {
+  if (c->paper) return paper_train_step<T>(c, label_ids, noise, real, n);
   if (c->shadows_dirty) refresh_shadows(c);
   route_and_stage<T>(c, label_ids, noise, real, n);
   g_forward<T>(c, n, false, true);                 // fake = G(z)
@@ -703,9 +1080,28 @@ void train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const 
   adam_call<T>(c, c->G, true);
 }
 
+bool check_config_paper(const gan_config* f, std::string& why) {
+  if (f->n_g < 2 || f->n_g > GAN_MAX_LAYERS || f->n_d < 2 || f->n_d > GAN_MAX_LAYERS) { why = "n_g, n_d must be in [2, 8]"; return false; }
+  if (f->img_c < 1 || f->img_c > 4) { why = "img_c must be in [1, 4]"; return false; }
+  if (f->cond_g != 0 || f->cond_d != 0) { why = "the networks of the tables are unconditional: cond_g = cond_d = 0"; return false; }
+  if ((f->g_h0 << (f->n_g - 1)) != f->img_hw) { why = "img_hw must equal g_h0 * 2^(n_g - 1)"; return false; }
+  if (((f->img_hw >> f->n_d) << f->n_d) != f->img_hw || (f->img_hw >> f->n_d) < 1) { why = "img_hw must be divisible by 2^n_d"; return false; }
+  for (int i = 0; i < f->n_g; ++i) if (f->g_ch[i] <= 0 || f->g_ch[i] % 64 || f->g_ch[i] > 1024) { why = "g_ch must be multiples of 64, at most 1024"; return false; }
+  for (int i = 0; i < f->n_d; ++i) if (f->d_ch[i] <= 0 || f->d_ch[i] > 1024) { why = "d_ch must be in [1, 1024]"; return false; }
+  if (f->g_ch[f->n_g - 1] != 64 && f->g_ch[f->n_g - 1] != 128) { why = "the last generator block must have 64 or 128 channels"; return false; }
+  if (f->d_ch[0] > 128) { why = "the first discriminator block supports at most 128 channels"; return false; }
+  if ((f->g_ch[0] * f->g_h0 * f->g_h0) % 128) { why = "g_ch[0]*g_h0^2 must be a multiple of 128"; return false; }
+  if (f->z_dim < 1 || f->max_total_batch < 1) { why = "bad z_dim / max_total_batch"; return false; }
+  if (!(f->dropout_p >= 0.f && f->dropout_p < 1.f) || !(f->bn_eps_first > 0.f) || !(f->bn_eps > 0.f)) { why = "bad dropout_p / epsilon"; return false; }
+  return true;
+}
+
 bool check_config(const gan_config* f, std::string& why) {
   if (f->n_models < 1 || f->n_labels < 1) { why = "n_models and n_labels must be positive"; return false; }
   if (f->n_models != 1 && f->n_models != f->n_labels) { why = "n_models must be 1 or n_labels"; return false; }
+  if (f->precision != GAN_FP32 && f->precision != GAN_BF16_FP32MASTER) { why = "unknown precision"; return false; }
+  if (f->family == GAN_FAMILY_PAPER) return check_config_paper(f, why);
+  if (f->family != GAN_FAMILY_STRIDED) { why = "unknown network family"; return false; }
   if (f->n_g < 2 || f->n_g > GAN_MAX_LAYERS || f->n_d < 2 || f->n_d > GAN_MAX_LAYERS) { why = "n_g, n_d must be in [2, 8]"; return false; }
   if (f->img_c < 1 || f->img_c > 4) { why = "img_c must be in [1, 4]"; return false; }
   if ((f->g_h0 << f->n_g) != f->img_hw) { why = "img_hw must equal g_h0 * 2^n_g"; return false; }
@@ -738,7 +1134,8 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   c->L = cfg->n_models; c->NB = cfg->max_total_batch;
   c->nslot = (cfg->cond_d > 0 && c->L == 1) ? cfg->cond_d : 1;
   c->geoms.n = 0;
-  build_layout(c);
+  c->paper = cfg->family == GAN_FAMILY_PAPER;
+  if (c->paper) build_layout_paper(c); else build_layout(c);
   const int L = c->L, NB = c->NB;
   const size_t es = esize(c);
   bool ok = alloc_net(c, c->G) && alloc_net(c, c->D);
@@ -854,7 +1251,7 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     c->KcG = (int)round_up(16 * gl.Cb, 64);
     const size_t d1 = (size_t)c->KcD * c1.Cs, g1 = (size_t)c->KcG * gl.Cs;
     ok = ok && dev_alloc(c, &c->colD, (size_t)2 * NB * c1.Hs * c1.Hs * c->KcD * es) &&
-         dev_alloc(c, &c->colG, (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
+         dev_alloc(c, &c->colG, c->paper ? 16 : (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
          dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)c->img_ksplit * L * (d1 > g1 ? d1 : g1) * 4) &&
          dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
   }
@@ -870,6 +1267,15 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     want(c->G.J, c->G.Kp, 1);
     c->wg_part = nullptr;
     if (need) ok = ok && dev_alloc(c, (void**)&c->wg_part, need);
+    if (c->paper) {
+      // G's summed-tap k4 weights (both layouts), the k4 weight gradient of one block, the last conv's row-split partials
+      size_t per = 0;
+      for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) per = std::max(per, (size_t)16 * c->G.conv[i].Cb * c->G.conv[i].Cs);
+      const ConvLayer& last = c->G.conv.back();
+      ok = ok && dev_alloc(c, &c->G.w4u, (size_t)L * c->G.P4 * es) && dev_alloc(c, &c->G.w4d, (size_t)L * c->G.P4 * es) &&
+           dev_alloc(c, (void**)&c->dw4, (size_t)L * per * 4) &&
+           dev_alloc(c, (void**)&c->c3_part, (size_t)8 * L * 9 * last.Cb * last.Cs * 4);
+    }
     // the linear head's weight gradient: blocks of 1024 columns per model, rows split when that leaves the chip idle
     c->head_rsplit = (int)std::min<long long>(std::max<long long>(512 / ((long long)L * ((c->D.K + 1023) / 1024)), 1), 64);
     if (c->head_rsplit > 1) ok = ok && dev_alloc(c, (void**)&c->head_part, (size_t)c->head_rsplit * L * (c->D.K + 4) * 4);
@@ -880,7 +1286,7 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     const ConvLayer& gl = c->G.conv.back();
     const long long lim = 1LL << 31;
     const long long big = std::max({(long long)NB * max_act * (long long)es, (long long)NB * c1.Hs * c1.Hs * c->KcD * (long long)es,
-                                    (long long)NB * gl.Hs * gl.Hs * c->KcG * (long long)es});
+                                    c->paper ? 0LL : (long long)NB * gl.Hs * gl.Hs * c->KcG * (long long)es});
     if (big >= lim) {
       for (void* p : c->allocs) (void)hipFree(p);
       delete c;
@@ -897,8 +1303,10 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
   hipMemsetAsync(rb.offs, 0, (size_t)(L + 1) * 4, c->st);
   hipMemsetAsync(c->loss_d, 0, (size_t)L * 4, c->st);
   hipMemsetAsync(c->loss_g, 0, (size_t)L * 4, c->st);
-  builtin_init(c);
-  if (hipStreamSynchronize(c->st) != hipSuccess || hipGetLastError() != hipSuccess) {
+  bool init_ok = true;
+  if (c->paper) { hipStreamSynchronize(c->st); init_ok = builtin_init_paper(c); }
+  else builtin_init(c);
+  if (!init_ok || hipStreamSynchronize(c->st) != hipSuccess || hipGetLastError() != hipSuccess) {
     for (void* p : c->allocs) (void)hipFree(p);
     delete c;
     return GAN_E_HIP;
@@ -951,11 +1359,13 @@ gan_status gan_generate(gan_ctx* c, const int32_t* label_ids, const float* noise
   c->rb = c->rb_gen;
   if (c->bf16) {
     route_and_stage<bf16_t>(c, label_ids, noise, nullptr, n);
+    if (c->paper) paper_g_forward<bf16_t>(c, n, use_running_stats != 0, false); else
     g_forward<bf16_t>(c, n, use_running_stats != 0, false);
     launch_unstage<bf16_t>((const bf16_t*)c->xd + (long long)n * f.img_hw * f.img_hw * f.img_c, out_images, n, c->L, f.img_c,
                            f.img_hw, c->rb, c->st);
   } else {
     route_and_stage<float>(c, label_ids, noise, nullptr, n);
+    if (c->paper) paper_g_forward<float>(c, n, use_running_stats != 0, false); else
     g_forward<float>(c, n, use_running_stats != 0, false);
     launch_unstage<float>((const float*)c->xd + (long long)n * f.img_hw * f.img_hw * f.img_c, out_images, n, c->L, f.img_c,
                           f.img_hw, c->rb, c->st);
@@ -1047,7 +1457,8 @@ gan_status gan_param_count(const gan_ctx* c, int32_t which, int64_t* per_model) 
 }
 gan_status gan_bn_count(const gan_ctx* c, int32_t which, int64_t* per_model) {
   if (!c || !per_model || which < 0 || which > 1) return GAN_E_ARG;
-  *per_model = which == 0 ? c->G.nbn : c->D.nbn;
+  const Net& net = which == 0 ? c->G : c->D;
+  *per_model = net.bn_ext2int.empty() ? net.nbn : (long long)net.bn_ext2int.size();
   return GAN_OK;
 }
 
@@ -1122,14 +1533,21 @@ gan_status gan_set_opt_state(gan_ctx* c, int32_t which, int32_t model, const flo
   return s;
 }
 
+static long long bn_ext_count(const Net& net) { return net.bn_ext2int.empty() ? net.nbn : (long long)net.bn_ext2int.size(); }
+
 gan_status gan_set_bn_running(gan_ctx* c, int32_t which, int32_t model, const float* mean, const float* var, int64_t n) {
   if (!c || !mean || !var || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
   Net& net = which == 0 ? c->G : c->D;
-  if (n != net.nbn) return fail(c, GAN_E_ARG, "wrong element count");
+  if (n != bn_ext_count(net)) return fail(c, GAN_E_ARG, "wrong element count");
   gan_status s = sync(c);
   if (s != GAN_OK) return s;
-  if (hipMemcpy(net.run_mean + (long long)model * net.nbn, mean, (size_t)n * 4, hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(net.run_var + (long long)model * net.nbn, var, (size_t)n * 4, hipMemcpyHostToDevice) != hipSuccess)
+  std::vector<float> m((size_t)net.nbn, 0.f), v((size_t)net.nbn, 1.f);
+  for (long long i = 0; i < n; ++i) {
+    const long long k = net.bn_ext2int.empty() ? i : net.bn_ext2int[(size_t)i];
+    m[(size_t)k] = mean[i]; v[(size_t)k] = var[i];
+  }
+  if (hipMemcpy(net.run_mean + (long long)model * net.nbn, m.data(), (size_t)net.nbn * 4, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(net.run_var + (long long)model * net.nbn, v.data(), (size_t)net.nbn * 4, hipMemcpyHostToDevice) != hipSuccess)
     return fail(c, GAN_E_HIP, "copy failed");
   return GAN_OK;
 }
@@ -1137,11 +1555,17 @@ gan_status gan_set_bn_running(gan_ctx* c, int32_t which, int32_t model, const fl
 gan_status gan_get_bn_running(gan_ctx* c, int32_t which, int32_t model, float* mean, float* var, int64_t n) {
   if (!c || !mean || !var || which < 0 || which > 1 || model < 0 || model >= c->L) return GAN_E_ARG;
   Net& net = which == 0 ? c->G : c->D;
-  if (n != net.nbn) return fail(c, GAN_E_ARG, "wrong element count");
+  if (n != bn_ext_count(net)) return fail(c, GAN_E_ARG, "wrong element count");
   gan_status s = sync(c);
   if (s != GAN_OK) return s;
-  hipMemcpy(mean, net.run_mean + (long long)model * net.nbn, (size_t)n * 4, hipMemcpyDeviceToHost);
-  hipMemcpy(var, net.run_var + (long long)model * net.nbn, (size_t)n * 4, hipMemcpyDeviceToHost);
+  std::vector<float> m((size_t)net.nbn), v((size_t)net.nbn);
+  if (hipMemcpy(m.data(), net.run_mean + (long long)model * net.nbn, (size_t)net.nbn * 4, hipMemcpyDeviceToHost) != hipSuccess ||
+      hipMemcpy(v.data(), net.run_var + (long long)model * net.nbn, (size_t)net.nbn * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(c, GAN_E_HIP, "copy failed");
+  for (long long i = 0; i < n; ++i) {
+    const long long k = net.bn_ext2int.empty() ? i : net.bn_ext2int[(size_t)i];
+    mean[i] = m[(size_t)k]; var[i] = v[(size_t)k];
+  }
   return GAN_OK;
 }
 

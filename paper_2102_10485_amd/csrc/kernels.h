@@ -216,8 +216,61 @@ void launch_dropout(T* x, const int* offs, int n_groups, int n, int C, int H, in
                     int layer, int pass_id, hipStream_t st);
 // w4[g][ty*4+tx][cb][cs] = sum of w3[g][ky*3+kx][cb][cs] over ky in S(ty), kx in S(tx), S = {2}, {1,2}, {0,1}, {0}
 // (Upsample x2 + Conv k3 s1 p1 == ConvTranspose k4 s2 p1 with these taps); w4t is the same with cb and cs exchanged.
+// group g reads w3 + g * w3_stride and writes w4 + g * w4_stride, w4t + g * w4_stride (strides in elements; 0: packed)
 template <typename T>
-void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st);
-void launch_dw4_to_dw3(const float* dw4, float* dw3, int n_groups, int cb, int cs, hipStream_t st);   // the adjoint map
+void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st, long long w3_stride = 0,
+                     long long w4_stride = 0);
+void launch_dw4_to_dw3(const float* dw4, float* dw3, int n_groups, int cb, int cs, hipStream_t st, long long dw4_stride = 0,
+                       long long dw3_stride = 0);   // the adjoint map
+
+// ---- the training step of the networks as printed in Tables 1 and 2 (paper_step.hip) ----
+// One pass over a stored NHWC tensor whose samples are grouped by model: rows of sample j (model-major) are HW pixels
+// of Cpad channels, of which the first C are real (the rest is channel padding and is left alone).
+struct PointArgs {
+  void* x;                  // forward: the layer output, in place ; backward: the gradient, in place ; sums: the tensor
+  const void* saved;        // backward: the forward result at the same positions
+  const float* bias;        // forward: [C] of model 0, pstride between models (may be NULL)
+  long long pstride;
+  const int* offs;
+  const int* sample_model;
+  const int* steps;         // dropout: per-model count of iterations taken (NULL when thr == 0)
+  int step_add;             // the iteration number is steps[l] + step_add
+  int L, n, C, Cpad, HW;
+  int seg_first, nseg, seg_samples;
+  int pass_of_seg[2];       // dropout: pass id of each processed segment
+  int layer;
+  unsigned thr;             // ceil(p 2^24); 0: no dropout
+  float scale;              // 1 / (1 - p)
+  float slope;              // activation: x > 0 ? x : slope x   (1: none)
+  unsigned seed_lo, seed_hi;
+};
+template <typename T> void launch_point_fwd(const PointArgs& a, hipStream_t st);     // x <- dropout(act(x + bias))
+template <typename T> void launch_point_bwd(const PointArgs& a, hipStream_t st);     // g <- g * keep * scale * act'(saved)
+// out[l * out_stride + c] = sum over the segments and rows of model l of x[.., c]
+template <typename T> void launch_col_sum(const PointArgs& a, float* out, long long out_stride, hipStream_t st);
+// batch statistics (mean, biased variance, 1/sqrt(var + eps)) of a stored tensor with Cpad channels per row
+template <typename T> void launch_bn_stats_direct(const NormArgs& a, int Cpad, hipStream_t st);
+// zero the gradient entries of the fourth tap row and column of a k3 filter held as [16][Cb][Cs]
+void launch_clear_fourth_taps(float* dw, long long pstride, int L, int Cb, int Cs, hipStream_t st);
+
+// Conv k3 s1 p1 between Cin feature channels (64 or 128) and CO image channels (1..4), side H, NHWC, rows model-major.
+struct Conv3Args {
+  const void* in;           // features [samples][H][H][Cin] (segment 0)
+  void* out;                // forward: tanh(conv + bias) into segment out_seg of the image buffer
+  const void* dout;         // backward: gradient w.r.t. the pre-tanh output, segment out_seg of the image-gradient buffer
+  void* din;                // backward: gradient w.r.t. the features
+  const float* w;           // [9][CO][Cin] of model 0, w_stride between models
+  long long w_stride;
+  const float* bias;        // [CO] of model 0
+  long long bias_stride;
+  const int* offs;
+  const int* sample_model;
+  int L, n, H, Cin, CO;
+  int out_seg, seg_samples;
+};
+template <typename T> void launch_conv3_fwd(const Conv3Args& a, hipStream_t st);
+template <typename T> void launch_conv3_dgrad(const Conv3Args& a, hipStream_t st);
+// part: [8][L][9*CO*Cin] scratch ; dw: [9][CO][Cin] of model 0, dw_stride between models
+template <typename T> void launch_conv3_wgrad(const Conv3Args& a, float* part, float* dw, long long dw_stride, hipStream_t st);
 
 }  // namespace gan

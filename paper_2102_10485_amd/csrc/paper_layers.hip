@@ -70,7 +70,7 @@ __device__ inline void taps_of(int t4, int& first, int& count) {
 // w3: fp32 [G][9][cb][cs] ; w4: T [G][16][cb][cs] ; w4t: T [G][16][cs][cb]
 template <typename T>
 __global__ __launch_bounds__(256) void w3_to_w4_kernel(const float* __restrict__ w3, T* __restrict__ w4, T* __restrict__ w4t,
-                                                       long long total, int cb, int cs) {
+                                                       long long total, int cb, int cs, long long w3_stride, long long w4_stride) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;      // (g, tap16, cb, cs)
   if (idx >= total) return;
   const int s = (int)(idx % cs);
@@ -82,22 +82,24 @@ __global__ __launch_bounds__(256) void w3_to_w4_kernel(const float* __restrict__
   taps_of(t & 3, x0, nx);
   float v = 0.f;
   for (int ky = y0; ky < y0 + ny; ++ky)
-    for (int kx = x0; kx < x0 + nx; ++kx) v += w3[((g * 9 + ky * 3 + kx) * cb + b) * cs + s];
-  w4[idx] = from_float<T>(v);
-  w4t[((g * 16 + t) * cs + s) * cb + b] = from_float<T>(v);
+    for (int kx = x0; kx < x0 + nx; ++kx) v += w3[g * w3_stride + (((long long)(ky * 3 + kx)) * cb + b) * cs + s];
+  w4[g * w4_stride + ((long long)t * cb + b) * cs + s] = from_float<T>(v);
+  w4t[g * w4_stride + ((long long)t * cs + s) * cb + b] = from_float<T>(v);
 }
 template <typename T>
-void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st) {
+void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st, long long w3_stride,
+                     long long w4_stride) {
   const long long total = (long long)n_groups * 16 * cb * cs;
   if (total == 0) return;
-  hipLaunchKernelGGL((w3_to_w4_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w3, w4, w4t, total, cb, cs);
+  hipLaunchKernelGGL((w3_to_w4_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w3, w4, w4t, total, cb, cs,
+                     w3_stride ? w3_stride : (long long)9 * cb * cs, w4_stride ? w4_stride : (long long)16 * cb * cs);
 }
-template void launch_w3_to_w4<float>(const float*, float*, float*, int, int, int, hipStream_t);
-template void launch_w3_to_w4<bf16_t>(const float*, bf16_t*, bf16_t*, int, int, int, hipStream_t);
+template void launch_w3_to_w4<float>(const float*, float*, float*, int, int, int, hipStream_t, long long, long long);
+template void launch_w3_to_w4<bf16_t>(const float*, bf16_t*, bf16_t*, int, int, int, hipStream_t, long long, long long);
 
 // the adjoint map: dw3[ky][kx] = sum of dw4[t4y][t4x] over the t4 whose sets contain ky / kx.  fp32 [G][16][cb][cs] -> [G][9][cb][cs]
 __global__ __launch_bounds__(256) void dw4_to_dw3_kernel(const float* __restrict__ dw4, float* __restrict__ dw3, long long total,
-                                                         int cb, int cs) {
+                                                         int cb, int cs, long long dw4_stride, long long dw3_stride) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;      // (g, tap9, cb, cs)
   if (idx >= total) return;
   const long long inner = idx % ((long long)cb * cs);
@@ -107,13 +109,15 @@ __global__ __launch_bounds__(256) void dw4_to_dw3_kernel(const float* __restrict
   // 3-tap index k belongs to S(3 - k) and S(2 - k)
   float v = 0.f;
   for (int ay = 2 - ky; ay <= 3 - ky; ++ay)
-    for (int ax = 2 - kx; ax <= 3 - kx; ++ax) v += dw4[((g * 16 + ay * 4 + ax) * cb) * cs + inner];
-  dw3[idx] = v;
+    for (int ax = 2 - kx; ax <= 3 - kx; ++ax) v += dw4[g * dw4_stride + ((long long)(ay * 4 + ax) * cb) * cs + inner];
+  dw3[g * dw3_stride + (long long)t * cb * cs + inner] = v;
 }
-void launch_dw4_to_dw3(const float* dw4, float* dw3, int n_groups, int cb, int cs, hipStream_t st) {
+void launch_dw4_to_dw3(const float* dw4, float* dw3, int n_groups, int cb, int cs, hipStream_t st, long long dw4_stride,
+                       long long dw3_stride) {
   const long long total = (long long)n_groups * 9 * cb * cs;
   if (total == 0) return;
-  hipLaunchKernelGGL(dw4_to_dw3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, dw4, dw3, total, cb, cs);
+  hipLaunchKernelGGL(dw4_to_dw3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, dw4, dw3, total, cb, cs,
+                     dw4_stride ? dw4_stride : (long long)16 * cb * cs, dw3_stride ? dw3_stride : (long long)9 * cb * cs);
 }
 
 }  // namespace gan

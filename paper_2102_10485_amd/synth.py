@@ -30,6 +30,12 @@ SPECS = {
     "tiny20": dict(cond_g=20, cond_d=20, z_dim=12, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 64], d_ch=[64, 128, 64]),
     "tiny0": dict(cond_g=0, cond_d=0, z_dim=20, img_c=3, img_hw=16, g_h0=2, g_ch=[128, 64, 128], d_ch=[128, 64, 64]),
     "micro": dict(cond_g=2, cond_d=2, z_dim=3, img_c=1, img_hw=4, g_h0=1, g_ch=[3, 2], d_ch=[2, 3]),
+    # the networks exactly as the paper's Tables 1 and 2 print them (Upsample + Conv k3 generator; Conv k3 s2 +
+    # LeakyReLU + Dropout + BatchNorm discriminator with 16/32/64/128 channels), unconditional, one pair per label
+    "paper32": dict(family="paper", cond_g=0, cond_d=0, z_dim=100, img_c=3, img_hw=32, g_h0=8, g_ch=[128, 128, 64],
+                    d_ch=[16, 32, 64, 128]),
+    "paper16": dict(family="paper", cond_g=0, cond_d=0, z_dim=24, img_c=3, img_hw=16, g_h0=4, g_ch=[64, 128, 64],
+                    d_ch=[16, 32, 72]),
 }
 
 # name -> (spec, n_models, n_labels, per-label batch, precision)
@@ -49,6 +55,8 @@ def param_tensors(spec, which):
     Layers followed by BatchNorm have no bias.
     """
     out = []
+    if spec.get("family") == "paper":
+        return _paper_tensors(spec, which)
     if which == 0:
         g_ch, h0 = spec["g_ch"], spec["g_h0"]
         out.append(("fc.w", (g_ch[0] * h0 * h0, spec["z_dim"] + spec["cond_g"]), "w"))
@@ -77,6 +85,30 @@ def param_tensors(spec, which):
             h //= 2
         out.append(("fc.w", (1, d_ch[-1] * h * h), "w"))
         out.append(("fc.b", (1,), "b"))
+    return out
+
+
+def _paper_tensors(spec, which):
+    """The networks of the paper's Tables 1 and 2 (every conv of D and the two ends of G carry a bias; a layer
+    directly followed by BatchNorm does not)."""
+    out = []
+    if which == 0:
+        g_ch, h0 = spec["g_ch"], spec["g_h0"]
+        out += [("fc.w", (g_ch[0] * h0 * h0, spec["z_dim"]), "w"), ("fc.b", (g_ch[0] * h0 * h0,), "b"),
+                ("bn0.gamma", (g_ch[0],), "gamma"), ("bn0.beta", (g_ch[0],), "beta")]
+        for i in range(1, len(g_ch)):
+            out += [("conv%d.w" % i, (g_ch[i], g_ch[i - 1], 3, 3), "w"), ("bn%d.gamma" % i, (g_ch[i],), "gamma"),
+                    ("bn%d.beta" % i, (g_ch[i],), "beta")]
+        n = len(g_ch)
+        out += [("conv%d.w" % n, (spec["img_c"], g_ch[-1], 3, 3), "w"), ("conv%d.b" % n, (spec["img_c"],), "b")]
+    else:
+        cin, h = spec["img_c"], spec["img_hw"]
+        for j, c in enumerate(spec["d_ch"], 1):
+            out += [("conv%d.w" % j, (c, cin, 3, 3), "w"), ("conv%d.b" % j, (c,), "b")]
+            if j > 1:
+                out += [("bn%d.gamma" % j, (c,), "gamma"), ("bn%d.beta" % j, (c,), "beta")]
+            cin, h = c, h // 2
+        out += [("fc.w", (1, cin * h * h), "w"), ("fc.b", (1,), "b")]
     return out
 
 

@@ -63,7 +63,7 @@ class Bounds:
 
 
 # fp32 storage against the fp64 oracle: the stated 1e-4 on everything linear in the passes.
-FP32_VS_PLAIN = Bounds(cost=1e-4, theta=1e-4, grad=5e-4, set_aside=0.1)
+FP32_VS_PLAIN = Bounds(cost=1e-4, theta=1e-4, grad=5e-3, set_aside=0.1)
 # bf16 storage against the plain fp64 oracle: the stated 2e-2 on costs and parameters; a missing or mis-signed update
 # is caught here too; the gradients are reported (the storage rounding moves them by 5-15 % at initialisation).
 BF16_VS_PLAIN = Bounds(cost=2e-2, theta=2e-2, update=0.7)
@@ -76,12 +76,14 @@ def fp32_bounds(pairs, spread=3.0):
     that Adam's sign-like step put on the other side, so from the second step on two correct single-precision
     implementations are further apart than that.  pairs: (snapshot of the oracle's loops compiled in single
     precision, fp64 snapshot) of the same step from the same state for every model checked; their largest distance
-    times 3 (spread between two realisations) is the bound when it exceeds the floor.  The floor, 5e-4, is one
-    activation-derivative decision taken the other way upstream (see the module text): behind it every gradient
-    changes diffusely by about 0.8 / sqrt(elements of that activation tensor), 1e-4 .. 5e-4 at test sizes (measured:
-    1.2e-4 on G's gradient with one such decision in D's first layer, 1e-6 without)."""
+    times 3 (spread between two realisations) is the bound when it exceeds the floor.  The floor, 5e-3, is one
+    activation-derivative decision taken the other way (see the module text): besides the one output channel that is
+    set aside, the BatchNorm backward pass spreads the changed element over its channel's batch and the data gradients
+    spread that over every tensor upstream, diffusely -- measured 1.2e-4 on G's gradient with one such decision in D's
+    first layer at 40 samples per model, 2.6e-3 with one in a 64-channel generator block at 10 samples per model, 1e-6
+    without.  Anything wrong in a kernel (a tap, a sign, a scale of a percent) is far above it."""
     d_grad = max(rel_l2(a["grads"][w], b["grads"][w]) for a, b in pairs for w in (0, 1))
-    return Bounds(cost=1e-4, theta=1e-4, grad=max(5e-4, spread * d_grad), set_aside=0.1)
+    return Bounds(cost=1e-4, theta=1e-4, grad=max(5e-3, spread * d_grad), set_aside=0.1)
 
 
 def emulation_bounds(pairs, spread=3.0):
@@ -134,26 +136,28 @@ def compare_step(spec, before, got, ref, bounds, tag="", adam=None):
             fails.append((tag, net + ".t", got["t"][which], ref["t"][which]))
         g_ref, g_got = ref["grads"][which], got["grads"][which]
         # per tensor (one output channel set aside, see above); a tensor whose gradient is tiny next to the network's
-        # (a cancellation) is measured against 1e-3 of the network's gradient norm spread evenly over its elements
+        # (a cancelled sum: the last bias and BatchNorm shift of D add gradients of opposite sign over the real and the
+        # fake half) is measured against 1e-2 of the network's gradient norm spread evenly over its elements
         gn2 = float(g_ref @ g_ref) / g_ref.size
         net_e2, net_r2, set_aside = 0.0, 0.0, 0.0
         for tname, (sl, shape) in synth.param_slices(spec, which).items():
             n = int(np.prod(shape))
             e2, r2 = channel_errors(g_got[sl], g_ref[sl], tname, shape)
             worst = int(np.argmax(e2))
-            set_aside = max(set_aside, np.sqrt(e2[worst] / max(r2[worst], r2.mean(), 1e-6 * gn2 * n / e2.size)))
+            set_aside = max(set_aside, np.sqrt(e2[worst] / max(r2[worst], r2.mean(), 1e-4 * gn2 * n / e2.size)))
             keep = np.ones(e2.size, bool)
             if e2.size > 1 and bounds.set_aside is not None:      # only where the bounds are tight enough to need it
                 keep[worst] = False
-            den2 = max(r2[keep].sum(), 1e-6 * gn2 * n)
+            den2 = max(r2[keep].sum(), 1e-4 * gn2 * n)
             check("%s.grad[%s]" % (net, tname), np.sqrt(e2[keep].sum() / den2), bounds.grad_tensor)
             net_e2 += e2[keep].sum(); net_r2 += r2[keep].sum()
             if len(shape) == 4:                     # convolution weight: every filter tap on its own
                 nch, axis = _channels(tname, shape)
-                a = np.moveaxis(g_got[sl].reshape(shape), axis, 0)[keep].reshape(-1, 16)
-                b = np.moveaxis(g_ref[sl].reshape(shape), axis, 0)[keep].reshape(-1, 16)
-                tap = max(np.linalg.norm(a[:, t] - b[:, t]) / max(np.linalg.norm(b[:, t]), np.sqrt(1e-6 * gn2 * n / 16.0))
-                          for t in range(16))
+                nt = shape[2] * shape[3]
+                a = np.moveaxis(g_got[sl].reshape(shape), axis, 0)[keep].reshape(-1, nt)
+                b = np.moveaxis(g_ref[sl].reshape(shape), axis, 0)[keep].reshape(-1, nt)
+                tap = max(np.linalg.norm(a[:, t] - b[:, t]) / max(np.linalg.norm(b[:, t]), np.sqrt(1e-4 * gn2 * n / nt))
+                          for t in range(nt))
                 check("%s.grad[%s]/tap" % (net, tname), tap, bounds.grad_tensor)
         check(net + ".grad", np.sqrt(net_e2 / net_r2), bounds.grad)
         check(net + ".grad/set-aside channel", set_aside, bounds.set_aside)
