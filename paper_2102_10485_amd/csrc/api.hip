@@ -111,6 +111,12 @@ struct gan_ctx {
   std::set<std::string> prof_names;
   std::vector<ProfEntry> prof_entries;
   std::vector<hipEvent_t> event_pool;
+  // A second stream (default priority) for the weight gradients and the Adam updates of the convolution weights, which
+  // nothing later in the backward chain waits for: they run beside it and fill the chip where the chain's kernels
+  // leave it idle (tile-count tails, bandwidth-bound passes).  Ordering between the two streams is by events.
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> order_events;
+  size_t order_next = 0;
 };
 
 namespace {
@@ -188,6 +194,24 @@ struct Scope {
   }
   ~Scope() { if (idx >= 0) hipEventRecord(c->prof_entries[idx].e1, c->st); }
 };
+
+// The stream for work that may run beside the caller's stream.  With per-launch timing on, everything stays on the
+// caller's stream, so that every launch is timed alone.
+hipStream_t side_stream(gan_ctx* c) { return (c->prof || !c->side) ? c->st : c->side; }
+// whatever is enqueued on `later` from now on starts after everything enqueued on `earlier` so far
+void order_after(gan_ctx* c, hipStream_t later, hipStream_t earlier) {
+  if (later == earlier) return;
+  if (c->order_next == c->order_events.size()) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return launch_fail("could not create an ordering event");
+    c->order_events.push_back(e);
+  }
+  hipEvent_t e = c->order_events[c->order_next++];
+  hipEventRecord(e, earlier);
+  hipStreamWaitEvent(later, e, 0);
+}
+
+template <typename T> void adam_region_call(gan_ctx* c, const AdamArgs& a, int region, hipStream_t st);
 
 double valid_tap_fraction(int Hs) {   // k4 s2 p1: per axis 2 of the 4*Hs (row, tap) pairs fall outside
   const double f = (4.0 * Hs - 2.0) / (4.0 * Hs);
@@ -550,7 +574,8 @@ int wgrad_ksplit(const gan_ctx* c, int Cb, int Cs, int ntaps) {
 // own split (partials left at dW + split * L * stride).
 template <typename T>
 void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small, float* dW, long long stride, int Cb, int Cs,
-                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0, int ksplit = 0) {
+                int Hs, int ntaps, int nseg, int n, double flops_alg = -1.0, int ksplit = 0, hipStream_t st = nullptr) {
+  if (!st) st = c->st;
   WgradArgs a = {};
   a.Big = Big; a.Small = Small; a.dW = dW; a.offs = c->rb.offs; a.order = c->rb.order; a.dw_stride = stride;
   a.L = c->L; a.nseg = nseg; a.seg_samples = n; a.Cb = Cb; a.Cs = Cs; a.Hs = Hs; a.ntaps = ntaps; a.ksplit = ksplit;
@@ -572,9 +597,9 @@ void wgrad_call(gan_ctx* c, const char* name, const void* Big, const void* Small
   (void)name;
   {
     Scope s(c, wgrad_variant_name(a), flops_alg >= 0 ? flops_alg : 2.0 * rows * Cb * Cs * ntaps * frac, bytes, detail);
-    launch_wgrad<T>(a, c->st);
+    launch_wgrad<T>(a, st);
   }
-  if (auto_split > 1) launch_sum_splits(c->wg_part, dW, stride, layer, c->L, auto_split, c->st);
+  if (auto_split > 1) launch_sum_splits(c->wg_part, dW, stride, layer, c->L, auto_split, st);
 }
 
 template <typename T>
@@ -729,9 +754,12 @@ void loss_call(gan_ctx* c, int n, int mode) {
 
 // Backward through D.  param_grads: fill D's gradient block (both segments summed).  to_image: continue down to
 // d cost / d fake, multiplied by the tanh derivative, into dimg.
+// adam (with param_grads): D's planned update, whose step counts are already advanced; the update of a convolution's
+// weights is enqueued beside the chain as soon as its gradient is complete and its data gradient has read the old ones.
 template <typename T>
-void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bool to_image) {
+void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bool to_image, const AdamArgs* adam = nullptr) {
   Net& D = c->D;
+  hipStream_t side = side_stream(c);
   const float slope = c->cfg.leaky_slope;
   const int nl = (int)D.conv.size();
   HeadArgs h;
@@ -743,16 +771,29 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
   h.seg_first = seg_first; h.nseg = nseg; h.seg_samples = n; h.n = n;
   { Scope s(c, "head_bwd_data", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_data<T>(h, c->st); }
   if (param_grads) { Scope s(c, "head_bwd_w", 0, sizeof(T) * (double)n * nseg * D.K); launch_head_bwd_w<T>(h, c->st); }
+  int pending = -1;                // region of D's planned update whose turn comes next
   for (int j = nl - 1; j >= 1; --j) {
     const ConvLayer& cl = D.conv[j];
+    // in place: the pre-normalisation tensor is not needed again in this step, its gradient takes its place
+    void* dx = c->dpre[j];
     bn_backward<T>(c, norm_args<T>(c, D, cl.Cs, cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->d_mean[j], c->d_var[j], c->d_rstd[j],
                                    c->d_sums[j], seg_first, nseg, n, slope),
-                   c->dpre[j], c->bufA, c->bufB, param_grads);
-    if (param_grads)
-      wgrad_call<T>(c, "gemm_wgrad", c->dact[j - 1], c->bufB, D.g + cl.w, D.P, cl.Cb, cl.Cs, cl.Hs, 16, nseg, n);
+                   c->dpre[j], c->bufA, dx, param_grads);
+    if (param_grads) {
+      // Beside the chain, in this order: the update of the layer above (its data gradient, which read the old weights,
+      // is done; being bandwidth-bound it pairs with the data-gradient GEMM below), then this layer's weight gradient.
+      order_after(c, side, c->st);
+      if (adam && pending >= 0) adam_region_call<T>(c, *adam, pending, side);
+      wgrad_call<T>(c, "gemm_wgrad", c->dact[j - 1], dx, D.g + cl.w, D.P, cl.Cb, cl.Cs, cl.Hs, 16, nseg, n, -1.0, 0, side);
+      pending = j - 1;
+    }
     // data gradient; for the first conv's output the LeakyReLU derivative is applied in the epilogue
-    conv_call<T>(c, "gemm_up", MODE_UP, j == 1 ? EPI_ACT_BWD : EPI_NONE, c->bufB, (const T*)D.shadow_u + cl.w, D.P, c->bufA,
+    conv_call<T>(c, "gemm_up", MODE_UP, j == 1 ? EPI_ACT_BWD : EPI_NONE, dx, (const T*)D.shadow_u + cl.w, D.P, c->bufA,
                  j == 1 ? c->dact[0] : nullptr, cl.Cs, cl.Cb, cl.Hs, cl.Hs, seg_first, nseg, n);
+  }
+  if (param_grads && adam && pending >= 0) {
+    order_after(c, side, c->st);
+    adam_region_call<T>(c, *adam, pending, side);
   }
   const ConvLayer& c1 = D.conv[0];
   if (param_grads) {
@@ -767,8 +808,9 @@ void d_backward(gan_ctx* c, int n, int seg_first, int nseg, bool param_grads, bo
 
 // Backward through G from dimg (fake segment) = d cost / d (pre-tanh output).
 template <typename T>
-void g_backward(gan_ctx* c, int n) {
+void g_backward(gan_ctx* c, int n, const AdamArgs* adam = nullptr) {
   Net& G = c->G;
+  hipStream_t side = side_stream(c);
   const int nl = (int)G.conv.size();
   const ConvLayer& last = G.conv[nl - 1];
   const T* dlast = (const T*)c->dimg + (long long)n * 4 * last.Hs * last.Hs * last.Cb;
@@ -784,19 +826,28 @@ void g_backward(gan_ctx* c, int n) {
     conv_call<T>(c, "gemm_dense_img", MODE_DENSE, EPI_NONE, c->colG, c->wpG, (long long)last.Cs * c->KcG, c->bufA, nullptr, c->KcG,
                  last.Cs, 1, last.Hs, 0, 1, n, 0, img_flops(last, n, 1));
   }
+  int pending = -1;
   for (int i = nl - 2; i >= 0; --i) {
     const ConvLayer& cl = G.conv[i];
+    void* dx = c->gpre[i + 1];     // in place, as in D
     bn_backward<T>(c, norm_args<T>(c, G, cl.Cb, 4 * cl.Hs * cl.Hs, cl.gamma, cl.beta, cl.rs, c->g_mean[i + 1], c->g_var[i + 1],
                                    c->g_rstd[i + 1], c->g_sums[i + 1], 0, 1, n, 0.f),
-                   c->gpre[i + 1], c->bufA, c->bufB, true);
-    wgrad_call<T>(c, "gemm_wgrad", c->bufB, c->gact[i], G.g + cl.w, G.P, cl.Cb, cl.Cs, cl.Hs, 16, 1, n);
-    conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, c->bufB, (const T*)G.shadow_d + cl.w, G.P, c->bufA, nullptr, cl.Cb, cl.Cs,
+                   c->gpre[i + 1], c->bufA, dx, true);
+    order_after(c, side, c->st);
+    if (adam && pending >= 0) adam_region_call<T>(c, *adam, pending, side);      // as in D
+    wgrad_call<T>(c, "gemm_wgrad", dx, c->gact[i], G.g + cl.w, G.P, cl.Cb, cl.Cs, cl.Hs, 16, 1, n, -1.0, 0, side);
+    pending = i;
+    conv_call<T>(c, "gemm_down", MODE_DOWN, EPI_NONE, dx, (const T*)G.shadow_d + cl.w, G.P, c->bufA, nullptr, cl.Cb, cl.Cs,
                  2 * cl.Hs, cl.Hs, 0, 1, n);
   }
   bn_backward<T>(c, norm_args<T>(c, G, G.C0, G.h0 * G.h0, G.fc_gamma, G.fc_beta, G.fc_rs, c->g_mean[0], c->g_var[0], c->g_rstd[0],
                                  c->g_sums[0], 0, 1, n, 0.f),
-                 c->gpre[0], c->bufA, c->bufB, true);
-  wgrad_call<T>(c, "gemm_wgrad_dense", c->bufB, c->zin, G.g + G.fc_w, G.P, G.J, G.Kp, 1, 1, 1, n);
+                 c->gpre[0], c->bufA, c->gpre[0], true);
+  // (row-split partial sums share one scratch area with the weight gradients above: same stream)
+  order_after(c, side, c->st);
+  if (adam && pending >= 0) adam_region_call<T>(c, *adam, pending, side);
+  wgrad_call<T>(c, "gemm_wgrad_dense", c->gpre[0], c->zin, G.g + G.fc_w, G.P, G.J, G.Kp, 1, 1, 1, n, -1.0, 0, side);
+  order_after(c, c->st, side);
 }
 
 // ---- the networks as printed in the paper's Tables 1 and 2 ---------------------------------------------------
@@ -1009,13 +1060,14 @@ void paper_adam_g(gan_ctx* c) {
   paper_rebuild_w4<T>(c);
 }
 
+// The planned update of one network: every convolution weight the GEMM engine also reads in "down" form is a tiled
+// region (the update writes that transposed copy too), in layer order; the rest of the block is the gaps.
 template <typename T>
-void adam_call(gan_ctx* c, Net& net, bool isG) {
+AdamArgs adam_args(gan_ctx* c, Net& net, bool isG) {
   AdamArgs a = {};
   a.theta = net.theta; a.m = net.m; a.v = net.v; a.g = net.g; a.shadow = c->bf16 ? net.shadow_u : nullptr;
   a.P = net.P; a.L = c->L; a.counts = c->rb.counts; a.t = net.t; a.bc = net.bc;
   a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps;
-  // convolution weights the GEMM engine also reads in "down" form: the update writes that transposed copy too
   a.shadow_t = net.shadow_d;
   for (size_t i = 0; i < net.conv.size(); ++i) {
     const bool gemm = isG ? (i + 1 < net.conv.size()) : (i > 0);
@@ -1023,15 +1075,39 @@ void adam_call(gan_ctx* c, Net& net, bool isG) {
     a.reg_w[a.nregions] = net.conv[i].w; a.reg_cb[a.nregions] = net.conv[i].Cb; a.reg_cs[a.nregions] = net.conv[i].Cs;
     ++a.nregions;
   }
+  adam_plan(a);
+  return a;
+}
+// bytes one update moves per element: g, theta, m, v in; theta, m, v out; the storage-type copy
+inline double adam_bytes_per_element(const gan_ctx* c) { return 28.0 + (c->bf16 ? 2.0 : 0.0); }
+template <typename T>
+void adam_region_call(gan_ctx* c, const AdamArgs& a, int region, hipStream_t st) {
+  double elems = 0;
+  for (int r = 0; r < a.nregions; ++r)
+    if (region < 0 || r == region) elems += 16.0 * a.reg_cb[r] * a.reg_cs[r];
+  Scope s(c, "adam", 0, (double)c->L * elems * (adam_bytes_per_element(c) + sizeof(T)));
+  launch_adam_region<T>(a, region, st);
+}
+// what is left of a planned update once the regions are done (or enqueued beside): the gaps, and the packed weights of
+// the image-side layer, rebuilt from the new master weights
+template <typename T>
+void adam_rest_call(gan_ctx* c, Net& net, bool isG, const AdamArgs& a) {
   {
-    double tbytes = 0;
-    for (int r = 0; r < a.nregions; ++r) tbytes += 16.0 * a.reg_cb[r] * a.reg_cs[r] * sizeof(T);
-    Scope s(c, "adam", 0, (double)c->L * (net.P * (28.0 + (c->bf16 ? 2.0 : 0.0)) + tbytes));
-    launch_adam<T>(a, c->st);
+    double elems = 0;
+    for (int r = 0; r < a.ngaps; ++r) elems += (double)(a.gap_hi[r] - a.gap_lo[r]);
+    Scope s(c, "adam", 0, (double)c->L * elems * adam_bytes_per_element(c));
+    launch_adam_gaps(a, c->st);
   }
-  // the image-side layer multiplies a patch matrix: its packed weights are rebuilt from the new master weights
   if (isG) launch_pack_w<T>(pack_args(c, net, net.conv.back(), c->KcG, 0, c->wpG), c->st);
   else launch_pack_w<T>(pack_args(c, net, net.conv.front(), c->KcD, c->nslot, c->wpD), c->st);
+}
+// the whole update on the caller's stream
+template <typename T>
+void adam_call(gan_ctx* c, Net& net, bool isG) {
+  const AdamArgs a = adam_args<T>(c, net, isG);
+  launch_adam_prepare(a, c->st);
+  adam_region_call<T>(c, a, -1, c->st);
+  adam_rest_call<T>(c, net, isG, a);
 }
 
 template <typename T>
@@ -1071,13 +1147,24 @@ void train_step(gan_ctx* c, const int32_t* label_ids, const float* noise, const 
   im2col_call<T>(c, c->D.conv[0], c->xd, nullptr, c->colD, c->KcD, c->nslot, 1, n);   // the fake half of D's input
   d_forward<T>(c, n, 0, 2, true);                  // D(real), D(fake): separate batch statistics per segment
   loss_call(c, n, 0);                              // Eq. 3
-  d_backward<T>(c, n, 0, 2, true, false);
-  adam_call<T>(c, c->D, false);
+  c->order_next = 0;
+  {
+    const AdamArgs aD = adam_args<T>(c, c->D, false);
+    launch_adam_prepare(aD, c->st);
+    d_backward<T>(c, n, 0, 2, true, false, &aD);   // weight gradients and the convolutions' updates beside the chain
+    adam_rest_call<T>(c, c->D, false, aD);
+    order_after(c, c->st, side_stream(c));
+  }
   d_forward<T>(c, n, 1, 1, true);                  // updated D on the same fake batch
   loss_call(c, n, 1);                              // Eq. 4 (negated: minimised)
   d_backward<T>(c, n, 1, 1, false, true);          // only data gradients: theta_D is not G's to move
-  g_backward<T>(c, n);
-  adam_call<T>(c, c->G, true);
+  {
+    const AdamArgs aG = adam_args<T>(c, c->G, true);
+    launch_adam_prepare(aG, c->st);
+    g_backward<T>(c, n, &aG);
+    adam_rest_call<T>(c, c->G, true, aG);
+    order_after(c, c->st, side_stream(c));
+  }
 }
 
 bool check_config_paper(const gan_config* f, std::string& why) {
@@ -1311,6 +1398,10 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     delete c;
     return GAN_E_HIP;
   }
+  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) {
+    (void)hipGetLastError();
+    c->side = nullptr;                         // everything then runs on the caller's stream
+  }
   c->shadows_dirty = true;
   *out = c;
   return GAN_OK;
@@ -1319,6 +1410,8 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
 gan_status gan_destroy(gan_ctx* c) {
   if (!c) return GAN_E_ARG;
   (void)hipStreamSynchronize(c->st);
+  if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+  for (auto& e : c->order_events) hipEventDestroy(e);
   for (auto& e : c->prof_entries) { hipEventDestroy(e.e0); hipEventDestroy(e.e1); }
   for (auto& e : c->event_pool) hipEventDestroy(e);
   for (void* p : c->allocs) (void)hipFree(p);

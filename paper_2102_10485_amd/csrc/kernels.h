@@ -181,9 +181,14 @@ struct AdamArgs {
   int ngaps;
   long long gap_lo[ADAM_MAX_REGIONS + 1], gap_hi[ADAM_MAX_REGIONS + 1];
   int gap_blk0[ADAM_MAX_REGIONS + 2];     // prefix of 1024-element blocks (filled by the launcher)
+  int tile_first, tile_count;             // the 64 x 64 tiles (per model) of a launch over some of the regions
 };
-// T: storage type of the shadows
+// T: storage type of the shadows.  launch_adam does the whole update; the parts below do it piecewise (plan first).
 template <typename T> void launch_adam(AdamArgs a, hipStream_t st);
+bool adam_plan(AdamArgs& a);
+void launch_adam_prepare(const AdamArgs& a, hipStream_t st);
+void launch_adam_gaps(const AdamArgs& a, hipStream_t st);
+template <typename T> void launch_adam_region(AdamArgs a, int region, hipStream_t st);
 template <typename T> void launch_cast_shadow(const float* theta, T* shadow, long long total, hipStream_t st);
 // dst[tap][cs][cb] <- src[tap][cb][cs] for every model (src: T or float master)
 template <typename T, typename S>

@@ -831,74 +831,114 @@ __global__ __launch_bounds__(256) void adam_tile_kernel(AdamArgs a) {
   constexpr int EPV = 16 / (int)sizeof(T);
   constexpr int TSTRIDE = 64 * (int)sizeof(T) + 16;            // bytes per transposed row (64 cb)
   __shared__ __attribute__((aligned(16))) unsigned char tile[64 * TSTRIDE];
-  const int l = blockIdx.y;
-  if (a.counts[l] == 0) return;
-  int r = 0;
-  while (r + 1 < a.nregions && (int)blockIdx.x >= a.reg_tile0[r + 1]) ++r;
-  const int Cb = a.reg_cb[r], Cs = a.reg_cs[r];
-  const int tcs_n = Cs >> 6, tcb_n = Cb >> 6;
-  int q = blockIdx.x - a.reg_tile0[r];
-  const int tcs = q % tcs_n; q /= tcs_n;
-  const int tcb = q % tcb_n;
-  const int tap = q / tcb_n;
-  const long long base = (long long)l * a.P + a.reg_w[r];
-  const float bc1 = a.bc[2 * l], bc2 = a.bc[2 * l + 1];
-  const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+  // a block takes the (tile, model) pairs blockIdx.x, blockIdx.x + gridDim.x, ... of this launch (the launcher's
+  // grid covers them all)
+  const long long items = (long long)a.tile_count * a.L;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    const int l = (int)(item / a.tile_count);
+    if (a.counts[l] == 0) continue;
+    const int bx = (int)(item - (long long)l * a.tile_count) + a.tile_first;
+    int r = 0;
+    while (r + 1 < a.nregions && bx >= a.reg_tile0[r + 1]) ++r;
+    const int Cb = a.reg_cb[r], Cs = a.reg_cs[r];
+    const int tcs_n = Cs >> 6, tcb_n = Cb >> 6;
+    int q = bx - a.reg_tile0[r];
+    const int tcs = q % tcs_n; q /= tcs_n;
+    const int tcb = q % tcb_n;
+    const int tap = q / tcb_n;
+    const long long base = (long long)l * a.P + a.reg_w[r];
+    const float bc1 = a.bc[2 * l], bc2 = a.bc[2 * l + 1];
+    const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = r0 + 16 * i;                                // cb inside the tile
-    const long long o = base + ((long long)tap * Cb + tcb * 64 + row) * Cs + tcs * 64 + c4;
-    const float4 g = ld_stream(a.g + o);
-    float4 th = ld_stream(a.theta + o);
-    float4 m = ld_stream(a.m + o);
-    float4 v = ld_stream(a.v + o);
-    float tt[4];
-    adam_update4(a, bc1, bc2, g, th, m, v, tt);
-    st_stream(a.theta + o, th);
-    st_stream(a.m + o, m);
-    st_stream(a.v + o, v);
-    if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
+    for (int i = 0; i < 4; ++i) {
+      const int row = r0 + 16 * i;                                // cb inside the tile
+      const long long o = base + ((long long)tap * Cb + tcb * 64 + row) * Cs + tcs * 64 + c4;
+      const float4 g = ld_stream(a.g + o);
+      float4 th = ld_stream(a.theta + o);
+      float4 m = ld_stream(a.m + o);
+      float4 v = ld_stream(a.v + o);
+      float tt[4];
+      adam_update4(a, bc1, bc2, g, th, m, v, tt);
+      st_stream(a.theta + o, th);
+      st_stream(a.m + o, m);
+      st_stream(a.v + o, v);
+      if (a.shadow) store4(static_cast<bf16_t*>(a.shadow) + o, tt);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) *reinterpret_cast<T*>(tile + (c4 + e) * TSTRIDE + row * (int)sizeof(T)) = from_float<T>(tt[e]);
-  }
-  __syncthreads();
-  T* dst = static_cast<T*>(a.shadow_t) + base;
-  constexpr int CPR = 64 / EPV;                                 // 16-byte chunks per transposed row
+      for (int e = 0; e < 4; ++e) *reinterpret_cast<T*>(tile + (c4 + e) * TSTRIDE + row * (int)sizeof(T)) = from_float<T>(tt[e]);
+    }
+    __syncthreads();
+    T* dst = static_cast<T*>(a.shadow_t) + base;
+    constexpr int CPR = 64 / EPV;                                 // 16-byte chunks per transposed row
 #pragma unroll
-  for (int i = 0; i < 64 * CPR / 256; ++i) {
-    const int cid = threadIdx.x + 256 * i;
-    const int cs = cid / CPR, ch = cid - cs * CPR;
-    const uint4 val = *reinterpret_cast<const uint4*>(tile + cs * TSTRIDE + ch * 16);
-    *reinterpret_cast<uint4*>(dst + ((long long)tap * Cs + tcs * 64 + cs) * Cb + tcb * 64 + ch * EPV) = val;
+    for (int i = 0; i < 64 * CPR / 256; ++i) {
+      const int cid = threadIdx.x + 256 * i;
+      const int cs = cid / CPR, ch = cid - cs * CPR;
+      const uint4 val = *reinterpret_cast<const uint4*>(tile + cs * TSTRIDE + ch * 16);
+      *reinterpret_cast<uint4*>(dst + ((long long)tap * Cs + tcs * 64 + cs) * Cb + tcb * 64 + ch * EPV) = val;
+    }
+    __syncthreads();                                              // the tile is rewritten by the next pair
   }
 }
 
-template <typename T>
-void launch_adam(AdamArgs a, hipStream_t st) {
-  // regions sorted by offset are the caller's job; the gaps between them cover the rest of [0, P)
-  if (a.nregions < 0 || a.nregions > ADAM_MAX_REGIONS || a.P % 8) return launch_fail("Adam: too many weight regions, or a parameter block that is not a multiple of 8");
+// Fills the launch geometry: the tiled regions (sorted by offset: the caller's job) and the gaps between them, which
+// cover the rest of [0, P).  False (and a launch error) when the regions do not fit the kernels.
+bool adam_plan(AdamArgs& a) {
+  if (a.nregions < 0 || a.nregions > ADAM_MAX_REGIONS || a.P % 8) {
+    launch_fail("Adam: too many weight regions, or a parameter block that is not a multiple of 8");
+    return false;
+  }
   long long pos = 0;
   a.ngaps = 0;
   a.reg_tile0[0] = 0;
   a.gap_blk0[0] = 0;
+  a.tile_first = 0;
   for (int r = 0; r <= a.nregions; ++r) {
     const long long lo = r < a.nregions ? a.reg_w[r] : a.P;
-    if (lo < pos || lo % 4) return launch_fail("Adam: weight regions must be sorted and 16-byte aligned");
+    if (lo < pos || lo % 4) { launch_fail("Adam: weight regions must be sorted and 16-byte aligned"); return false; }
     if (lo > pos) {
       a.gap_lo[a.ngaps] = pos; a.gap_hi[a.ngaps] = lo;
       a.gap_blk0[a.ngaps + 1] = a.gap_blk0[a.ngaps] + (int)((lo - pos + 1023) / 1024);
       ++a.ngaps;
     }
     if (r < a.nregions) {
-      if (a.reg_cb[r] % 64 || a.reg_cs[r] % 64 || !a.shadow_t) return launch_fail("Adam: tiled regions need channel counts that are multiples of 64");
+      if (a.reg_cb[r] % 64 || a.reg_cs[r] % 64 || !a.shadow_t) {
+        launch_fail("Adam: tiled regions need channel counts that are multiples of 64");
+        return false;
+      }
       a.reg_tile0[r + 1] = a.reg_tile0[r] + 16 * (a.reg_cb[r] / 64) * (a.reg_cs[r] / 64);
       pos = lo + 16LL * a.reg_cb[r] * a.reg_cs[r];
     }
   }
+  return true;
+}
+// The three parts of one update of a planned AdamArgs, in any order after the first: the step counts and bias
+// corrections; the gaps; one tiled region (or all of them, region < 0).  Each element is updated by exactly one part.
+void launch_adam_prepare(const AdamArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(adam_prepare_kernel, dim3((a.L + 255) / 256), dim3(256), 0, st, a);
+}
+void launch_adam_gaps(const AdamArgs& a, hipStream_t st) {
   if (a.ngaps > 0) hipLaunchKernelGGL(adam_kernel, dim3((unsigned)a.gap_blk0[a.ngaps], a.L), dim3(256), 0, st, a);
-  if (a.nregions > 0)
-    hipLaunchKernelGGL((adam_tile_kernel<T>), dim3((unsigned)a.reg_tile0[a.nregions], a.L), dim3(256), 0, st, a);
+}
+template <typename T>
+void launch_adam_region(AdamArgs a, int region, hipStream_t st) {
+  if (a.nregions == 0 || region >= a.nregions) return;
+  const int first = region < 0 ? 0 : a.reg_tile0[region];
+  const int last = region < 0 ? a.reg_tile0[a.nregions] : a.reg_tile0[region + 1];
+  a.tile_first = first;
+  a.tile_count = last - first;
+  const long long blocks = (long long)a.tile_count * a.L;
+  if (blocks > 0x7fffffffLL) return launch_fail("Adam: more than 2^31 weight tiles in one launch");
+  if (blocks > 0) hipLaunchKernelGGL((adam_tile_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+}
+template void launch_adam_region<float>(AdamArgs, int, hipStream_t);
+template void launch_adam_region<bf16_t>(AdamArgs, int, hipStream_t);
+
+template <typename T>
+void launch_adam(AdamArgs a, hipStream_t st) {
+  if (!adam_plan(a)) return;
+  launch_adam_prepare(a, st);
+  launch_adam_gaps(a, st);
+  launch_adam_region<T>(a, -1, st);
 }
 template void launch_adam<float>(AdamArgs, hipStream_t);
 template void launch_adam<bf16_t>(AdamArgs, hipStream_t);
