@@ -104,7 +104,7 @@ def other_rows(args, torch, binding, work, gan, prec, prec_name, d_lab, d_real, 
         labels = torch.empty(n, dtype=torch.int32, device="cuda")
 
         def call(i):
-            gan.sample(prior, d_u.data_ptr(), d_noise[i % 4].data_ptr(), n, out.data_ptr(), labels.data_ptr(), 1)
+            gan.sample(prior, d_u.data_ptr(), d_noise[i % 2].data_ptr(), n, out.data_ptr(), labels.data_ptr(), 1)
         metric, unit = "mixture samples/sec (class draw + per-label generators, running statistics)", "images/s"
     else:
         def call(i):
@@ -144,13 +144,15 @@ def other_rows(args, torch, binding, work, gan, prec, prec_name, d_lab, d_real, 
     print(json.dumps(out_j))
 
 
-def build_workload(args, config, torch, binding, synth, prec_name, single_pair=None):
-    """Context, resident inputs and description of one workload."""
-    work = synth.Workload(config)
+def build_workload(args, config, torch, binding, synth, prec_name, single_pair=None, spec_name=None):
+    """Context, resident inputs and description of one workload (spec_name: config's label models with other networks)."""
+    work = synth.Workload(config, spec=spec_name)
     prec = binding.BF16 if prec_name == "bf16" else binding.FP32
     n = work.n
     lab = work.labels(single_label=3) if work.n_models == 1 else work.labels()
     spec, n_models, n_labels, descr = work.spec, work.n_models, work.n_labels, DESCR[config]
+    if spec_name:
+        descr += ", networks '%s'" % spec_name
     img_lab = lab                              # the classes the real images are drawn from
     if single_pair:
         spec, n_models = dict(work.spec), 1
@@ -173,7 +175,7 @@ def build_workload(args, config, torch, binding, synth, prec_name, single_pair=N
     gan = binding.Gan(cfg, torch.cuda.current_stream().cuda_stream)
     d_lab = torch.from_numpy(lab).cuda()
     d_real = torch.from_numpy(work.images(img_lab)).cuda()
-    d_noise = [torch.from_numpy(work.noise()[:n].copy()).cuda() for _ in range(4)]
+    d_noise = [torch.from_numpy(work.noise()[:n].copy()).cuda() for _ in range(2)]
     torch.cuda.synchronize()
     return dict(work=work, gan=gan, prec=prec, n=n, n_models=n_models, descr=descr, d_lab=d_lab, d_real=d_real, d_noise=d_noise)
 
@@ -183,7 +185,7 @@ def time_steps(torch, w, steps, warmup):
     gan, n = w["gan"], w["n"]
 
     def step(i):
-        gan.train_step(w["d_lab"].data_ptr(), w["d_noise"][i % 4].data_ptr(), w["d_real"].data_ptr(), n)
+        gan.train_step(w["d_lab"].data_ptr(), w["d_noise"][i % 2].data_ptr(), w["d_real"].data_ptr(), n)
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -205,7 +207,7 @@ def kernel_timings(torch, w, steps, detail=False, gemm_only=False):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        gan.train_step(w["d_lab"].data_ptr(), w["d_noise"][i % 4].data_ptr(), w["d_real"].data_ptr(), n)
+        gan.train_step(w["d_lab"].data_ptr(), w["d_noise"][i % 2].data_ptr(), w["d_real"].data_ptr(), n)
     torch.cuda.synchronize()
     ms_instr = 1e3 * (time.perf_counter() - t0) / steps
     prof = gan.profile_read()
@@ -255,6 +257,9 @@ def main():
                     help="train row on the paper's comparison systems instead of the label models: ONE pair of the same widths over "
                          "the same flat batch -- cgan: conditioned on the label of every sample (Tables 3 and 4); gan: unconditional "
                          "(Tables 1 and 2)")
+    ap.add_argument("--networks", choices=["paper32"], default=None,
+                    help="train row with the config's labels and batches but other networks: paper32 = the generator and "
+                         "discriminator exactly as the paper's Tables 1 and 2 print them (32x32x3)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="before the timed region, run one elementwise kernel over 1 GiB (reads 1 GiB, writes 1 GiB: known traffic for scaling "
                          "hardware byte counters)")
@@ -272,7 +277,7 @@ def main():
     if args.single_pair and args.row != "train":
         sys.exit("bench.py: --single-pair goes with the train row")
     prec_name = args.precision or synth.Workload(args.config).precision
-    w = build_workload(args, args.config, torch, binding, synth, prec_name, args.single_pair)
+    w = build_workload(args, args.config, torch, binding, synth, prec_name, args.single_pair, args.networks)
     work, gan, n = w["work"], w["gan"], w["n"]
 
     if args.row != "train":
@@ -335,15 +340,20 @@ def main():
                           for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_per_step"])}
     gan.close()
     del w
-    if not args.no_profile and not args.no_other_configs and not args.single_pair and args.config == 2:
+    if not args.no_profile and not args.no_other_configs and not args.single_pair and not args.networks and args.config == 2:
         # the other workloads and the comparison systems, a few steps each (parity-test cases, not the headline)
         others = {}
-        runs = [("config 0 fp32", 0, "fp32", None), ("config 1 fp32", 1, "fp32", None), ("config 1 bf16", 1, "bf16", None),
-                ("config 3 bf16", 3, "bf16", None), ("config 4 bf16", 4, "bf16", None),
-                ("single pair gan (config 2 widths) bf16", 2, "bf16", "gan"), ("single pair cgan (config 2 widths) bf16", 2, "bf16", "cgan")]
-        for name, cfg_id, pn, sp in runs:
+        runs = [("config 0 fp32", 0, "fp32", None, None), ("config 1 fp32", 1, "fp32", None, None), ("config 1 bf16", 1, "bf16", None, None),
+                ("config 2 fp32", 2, "fp32", None, None),
+                ("config 3 bf16", 3, "bf16", None, None), ("config 4 bf16", 4, "bf16", None, None),
+                ("single pair gan (config 2 widths) bf16", 2, "bf16", "gan", None),
+                ("single pair cgan (config 2 widths) bf16", 2, "bf16", "cgan", None),
+                # config 2's label models with the networks exactly as the paper's Tables 1 and 2 print them
+                ("paper networks (Tables 1-2), config 2 labels and batch, bf16", 2, "bf16", None, "paper32"),
+                ("paper networks (Tables 1-2), config 2 labels and batch, fp32", 2, "fp32", None, "paper32")]
+        for name, cfg_id, pn, sp, spec_name in runs:
             torch.cuda.empty_cache()
-            ww = build_workload(args, cfg_id, torch, binding, synth, pn, sp)
+            ww = build_workload(args, cfg_id, torch, binding, synth, pn, sp, spec_name)
             ms = time_steps(torch, ww, 10, 3)
             kk, _ = kernel_timings(torch, ww, 5, gemm_only=True)
             pk = PEAK["mfma_bf16"] if pn == "bf16" else PEAK["mfma_fp32"]
@@ -354,7 +364,7 @@ def main():
             ww["gan"].close()
             del ww
         out["configs"] = others
-    if not args.no_cpu_baseline and not args.single_pair:
+    if not args.no_cpu_baseline and not args.single_pair and not args.networks:
         out["cpu_baseline"] = cpu_baseline(synth.Workload(args.config))
     print(json.dumps(out))
 

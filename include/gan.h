@@ -166,6 +166,16 @@ gan_status gan_get_routing(gan_ctx* ctx, int32_t* perm, int32_t* offs);
 /* Text of the last error on this context (never NULL). */
 const char* gan_last_error(const gan_ctx* ctx);
 
+/* Replayable steps (enable = 1; off by default): a gan_train_step call whose three device pointers and n equal those
+   of one of the last eight distinct calls is captured into a HIP graph once and replayed from then on (same kernels,
+   same order, same results bit for bit; the eight most recently used argument sets are kept).  For callers whose host
+   thread, not the device, limits the step rate: a replay is one host call instead of a hundred and more launches; on
+   an idle host it is no faster than the launches.  enable = 0: plain launches again (also the case while per-launch
+   timing is on).  The caller's buffers are read when the step runs, as always. */
+gan_status gan_use_graphs(gan_ctx* ctx, int32_t enable);
+/* Number of training steps of this context that ran as graph replays so far (HOST int64). */
+gan_status gan_graph_replays(const gan_ctx* ctx, int64_t* n);
+
 /* ---- profiling ------------------------------------------------------------------------------------ */
 /* Time kernel launches of the next steps with HIP events on the context's stream: enable = 1 every launch, one
    family per kernel instantiation; 2 every launch, one family per layer shape; 3 only the MFMA kernels (GEMM and

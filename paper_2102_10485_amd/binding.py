@@ -74,6 +74,8 @@ def load_library():
     L.gan_last_error.argtypes = [_VP]
     L.gan_last_error.restype = C.c_char_p
     L.gan_profile_enable.argtypes = [_VP, C.c_int32]
+    L.gan_use_graphs.argtypes = [_VP, C.c_int32]
+    L.gan_graph_replays.argtypes = [_VP, C.POINTER(C.c_int64)]
     L.gan_profile_read.argtypes = [_VP, C.c_int32, C.POINTER(C.c_char_p), _I64P, C.POINTER(C.c_double),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), _IP]
     op = [_VP, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
@@ -255,6 +257,14 @@ class Gan:
         perm, offs = np.empty(max(n, 1), np.int32), np.empty(self.n_models + 1, np.int32)
         self._check(self.lib.gan_get_routing(self.h, perm.ctypes.data_as(_IP), offs.ctypes.data_as(_IP)))
         return perm[:n], offs
+
+    def graph_replays(self):
+        n = C.c_int64(0)
+        self._check(self.lib.gan_graph_replays(self.h, C.byref(n)))
+        return int(n.value)
+
+    def use_graphs(self, on=True):
+        self._check(self.lib.gan_use_graphs(self.h, 1 if on else 0))
 
     def profile_enable(self, on=True, detail=False, gemm_only=False):
         level = 0 if not on else (2 if detail else (3 if gemm_only else 1))

@@ -275,7 +275,8 @@ struct Conv3Args {
 };
 template <typename T> void launch_conv3_fwd(const Conv3Args& a, hipStream_t st);
 template <typename T> void launch_conv3_dgrad(const Conv3Args& a, hipStream_t st);
-// part: [8][L][9*CO*Cin] scratch ; dw: [9][CO][Cin] of model 0, dw_stride between models
+// part: [conv3_wgrad_splits(L)][L][9*CO*Cin] scratch ; dw: [9][CO][Cin] of model 0, dw_stride between models
+int conv3_wgrad_splits(int L);
 template <typename T> void launch_conv3_wgrad(const Conv3Args& a, float* part, float* dw, long long dw_stride, hipStream_t st);
 
 }  // namespace gan
