@@ -75,6 +75,7 @@ def load_library():
     L.gan_last_error.restype = C.c_char_p
     L.gan_profile_enable.argtypes = [_VP, C.c_int32]
     L.gan_use_graphs.argtypes = [_VP, C.c_int32]
+    L.gan_use_second_stream.argtypes = [_VP, C.c_int32]
     L.gan_graph_replays.argtypes = [_VP, C.POINTER(C.c_int64)]
     L.gan_profile_read.argtypes = [_VP, C.c_int32, C.POINTER(C.c_char_p), _I64P, C.POINTER(C.c_double),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), _IP]
@@ -262,6 +263,9 @@ class Gan:
         n = C.c_int64(0)
         self._check(self.lib.gan_graph_replays(self.h, C.byref(n)))
         return int(n.value)
+
+    def use_second_stream(self, on=True):
+        self._check(self.lib.gan_use_second_stream(self.h, 1 if on else 0))
 
     def use_graphs(self, on=True):
         self._check(self.lib.gan_use_graphs(self.h, 1 if on else 0))

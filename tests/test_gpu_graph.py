@@ -1,6 +1,7 @@
-"""Replayed steps (HIP graph) against plain launches: same kernels, so every replay must equal the plain-launch result
-bit for bit.  Two contexts take the same steps from the same parameters, one replaying (gan_use_graphs), one not
-(the default).  The inputs live in the same device buffers throughout and are overwritten before every step (labels
+"""The optional ways to run a step -- replayed as a HIP graph, with the weight gradients and weight updates on a
+second stream, or both -- against plain launches on one stream (the default): same kernels, so every step must equal
+the plain result bit for bit.  Four contexts take the same steps from the same parameters: replaying
+(gan_use_graphs), second stream (gan_use_second_stream), both, neither.  The inputs live in the same device buffers throughout and are overwritten before every step (labels
 too: the routing is rebuilt on the device inside the replay); between the steps the program does its own eager work
 -- host queries, a generate call on the replaying context, torch kernels -- and synchronises."""
 import numpy as np
@@ -20,8 +21,12 @@ def test_replays_equal_plain_launches(spec_name, precision):
     prec = binding.BF16 if precision == "bf16" else binding.FP32
     rng = np.random.default_rng(77)
     st = torch.cuda.current_stream().cuda_stream
-    ctxs = [binding.Gan(binding.make_config(spec, K, K, n, prec, seed=5), st) for _ in range(2)]
+    ctxs = [binding.Gan(binding.make_config(spec, K, K, n, prec, seed=5), st) for _ in range(4)]
     ctxs[0].use_graphs(True)
+    ctxs[1].use_second_stream(True)
+    ctxs[2].use_second_stream(True)
+    ctxs[2].use_graphs(True)
+    plain = ctxs[3]
     for l in range(K):
         for which in (0, 1):
             p = synth.init_params(spec, which, np.random.default_rng([9, which, l]))
@@ -43,15 +48,16 @@ def test_replays_equal_plain_launches(spec_name, precision):
         for g in ctxs:
             g.train_step(d_lab.data_ptr(), d_z.data_ptr(), d_x.data_ptr(), n)
         torch.cuda.synchronize()
-        a, b = ctxs[0].get_losses(), ctxs[1].get_losses()
-        for u, v in zip(a, b):
-            assert np.array_equal(u, v), (step, u, v)
-        for l in range(K):
-            for which in (0, 1):
-                assert np.array_equal(ctxs[0].get_params(which, l), ctxs[1].get_params(which, l)), (step, l, which)
-                ma, va, ta = ctxs[0].get_opt_state(which, l)
-                mb, vb, tb = ctxs[1].get_opt_state(which, l)
-                assert ta == tb and np.array_equal(ma, mb) and np.array_equal(va, vb), (step, l, which)
+        b = plain.get_losses()
+        for k, g in enumerate(ctxs[:3]):
+            for u, v in zip(g.get_losses(), b):
+                assert np.array_equal(u, v), (step, k, u, v)
+            for l in range(K):
+                for which in (0, 1):
+                    assert np.array_equal(g.get_params(which, l), plain.get_params(which, l)), (step, k, l, which)
+                    ma, va, ta = g.get_opt_state(which, l)
+                    mb, vb, tb = plain.get_opt_state(which, l)
+                    assert ta == tb and np.array_equal(ma, mb) and np.array_equal(va, vb), (step, k, l, which)
         assert np.array_equal(ctxs[0].get_routing(n)[0], np.argsort(lab, kind="stable"))
         # eager work between the replays
         junk.add_(1.0).mul_(0.5)
@@ -63,7 +69,7 @@ def test_replays_equal_plain_launches(spec_name, precision):
             for g in ctxs:
                 g.set_params(0, 0, p)
         torch.cuda.synchronize()
-    # the first call ran as plain launches, the second was captured: six replays; none in the other context
-    assert ctxs[0].graph_replays() == 6 and ctxs[1].graph_replays() == 0
+    # the first call ran as plain launches, the second was captured: six replays; none where replays are off
+    assert [g.graph_replays() for g in ctxs] == [6, 0, 6, 0]
     for g in ctxs:
         g.close()
