@@ -42,25 +42,3 @@ def unpack(t, bf16, shape):
     if bf16:
         return from_bf16_bits(a.view(np.uint16)).reshape(shape)
     return a.reshape(shape)
-
-
-def rel_l2(a, b, floor=0.0):
-    a, b = np.asarray(a, np.float64).ravel(), np.asarray(b, np.float64).ravel()
-    den = max(np.linalg.norm(b), floor)
-    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a - b)
-
-
-def tensor_errors(spec, which, got, ref, scale_floor):
-    """Per-tensor relative L2, the denominator floored at scale_floor * sqrt(numel)."""
-    out = {}
-    for name, (sl, shape) in synth.param_slices(spec, which).items():
-        n = int(np.prod(shape))
-        out[name] = rel_l2(got[sl], ref[sl], floor=scale_floor * np.sqrt(n))
-    return out
-
-
-def one_flip(numel, lr=2e-4, scale=0.02):
-    """Relative L2 (against the floored norm scale*sqrt(numel)) of ONE element landing on the other side of an
-    Adam step: on the first steps every parameter moves by about lr*sign(g), and an element whose gradient is below
-    rounding noise legitimately takes either sign.  Per-tensor checks allow one such element (x1.1 for slack)."""
-    return 1.1 * 2.0 * lr / (scale * np.sqrt(numel))
