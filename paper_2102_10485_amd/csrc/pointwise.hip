@@ -463,7 +463,27 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(NormArgs a, const in
     sgx[e] = 0.f;
   }
   if (rl < RL) {
-    for (long long r = r0 + rl; r < r1; r += RL) {
+    // four rows per trip: eight 16-byte loads in flight per thread (the sums stay in row order)
+    long long r = r0 + rl;
+    for (; r + 3 * RL < r1; r += 4 * RL) {
+      float v[4][EPV], d[4][EPV];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        loadv(x + (r + k * RL) * a.C, v[k]);
+        loadv(dy + (r + k * RL) * a.C, d[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+          const float xh = (v[k][e] - mu[e]) * rs[e];
+          const float u = ga[e] * xh + be[e];
+          const float gg = u > 0.f ? d[k][e] : d[k][e] * a.slope;
+          sg[e] += gg;
+          sgx[e] += gg * xh;
+        }
+    }
+    for (; r < r1; r += RL) {
       float v[EPV], d[EPV];
       loadv(x + r * a.C, v);
       loadv(dy + r * a.C, d);

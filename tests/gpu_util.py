@@ -42,3 +42,9 @@ def unpack(t, bf16, shape):
     if bf16:
         return from_bf16_bits(a.view(np.uint16)).reshape(shape)
     return a.reshape(shape)
+
+
+def rel_l2(a, b, floor=0.0):
+    a, b = np.asarray(a, np.float64).ravel(), np.asarray(b, np.float64).ravel()
+    den = max(np.linalg.norm(b), floor)
+    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a - b)
