@@ -255,6 +255,10 @@ gan_status gan_probe_copy(int64_t bytes, void* hip_stream, double* gbps);
      up   : big[n,Y,X,cb]    = sum_{ky,kx,cs : Y=2y-1+ky, X=2x-1+kx} small[n,y,x,cs] * w[ky,kx,cb,cs]  (convT forward, conv dgrad)
      wgrad: dw[ky,kx,cb,cs]  = sum_{n,y,x} big[n,2y-1+ky,2x-1+kx,cb] * small[n,y,x,cs]
    n_groups models, group g uses weight block g.  n_samples = offs[n_groups] must be given by the caller. */
+/* Which of the forward-type GEMM's tile shapes gan_op_conv_down / gan_op_conv_up use from now on: rows = 64, 128 or
+   256 rows per tile (with 256 the width follows the output channels: 64, 128 or 256 columns), 0 = chosen from the
+   problem size as inside a training step.  Lets a test run one case through every instantiation. */
+gan_status gan_op_tile_rows(gan_ctx* ctx, int32_t rows);
 gan_status gan_op_conv_down(gan_ctx* ctx, const void* big, const void* w_down, void* small_out, const int32_t* offs,
                             int32_t n_groups, int32_t n_samples, int32_t cb, int32_t cs, int32_t hs);
 gan_status gan_op_conv_up(gan_ctx* ctx, const void* small_in, const void* w_up, void* big_out, const int32_t* offs,

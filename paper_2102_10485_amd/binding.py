@@ -75,6 +75,7 @@ def load_library():
     L.gan_last_error.restype = C.c_char_p
     L.gan_profile_enable.argtypes = [_VP, C.c_int32]
     L.gan_use_graphs.argtypes = [_VP, C.c_int32]
+    L.gan_op_tile_rows.argtypes = [_VP, C.c_int32]
     L.gan_use_second_stream.argtypes = [_VP, C.c_int32]
     L.gan_graph_replays.argtypes = [_VP, C.POINTER(C.c_int64)]
     L.gan_profile_read.argtypes = [_VP, C.c_int32, C.POINTER(C.c_char_p), _I64P, C.POINTER(C.c_double),
@@ -284,6 +285,9 @@ class Gan:
                 for i in range(n.value)}
 
     # single operations (device pointers as integers)
+    def op_tile_rows(self, rows):
+        self._check(self.lib.gan_op_tile_rows(self.h, rows))
+
     def op_conv_down(self, big, w_down, small_out, offs, n_groups, n_samples, cb, cs, hs):
         self._check(self.lib.gan_op_conv_down(self.h, big, w_down, small_out, offs, n_groups, n_samples, cb, cs, hs))
 

@@ -134,6 +134,7 @@ struct gan_ctx {
   struct StepArgs { const void *lab, *noise, *real; int n; };
   std::vector<StepArgs> seen;      // the last eight distinct argument sets that ran as plain launches
   unsigned long long calls = 0, replays = 0;
+  int op_tile_rows = 0;            // single-operation entry points: tile height forced by the caller (0: chosen as in a step)
 };
 
 namespace {
@@ -187,7 +188,7 @@ const int* tpre_of(gan_ctx* c, int rps, int tile_rows) {
 // tile height for a layer: from the average rows per model at the sizing batch (fixed at create, so the prefix
 // arrays built at every routing match)
 int layer_tile_rows(const gan_ctx* c, int n_out, int rps) {
-  return conv_tile_rows(n_out, (long long)c->NB * rps / c->L);
+  return conv_tile_rows(n_out, (long long)c->NB * rps / c->L, c->L);
 }
 int ub_tiles(const gan_ctx* c, int n, int rps, int tile_rows) {
   return (int)(((long long)n * rps) / tile_rows) + (n < c->L ? n : c->L);
@@ -646,7 +647,7 @@ void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running
   if (use_running) {
     launch_bn_from_running(a, c->st);
   } else {
-    const int tr = layer_tile_rows(c, a.C, gemm_rps);
+    const int tr = layer_tile_rows(c, a.C * col_groups, gemm_rps);     // the tile height of the GEMM that left the partials (N = C * col_groups)
     launch_bn_stats_from_partial(a, c->stat_partial, tpre_of(c, gemm_rps, tr), ub_tiles(c, a.n, gemm_rps, tr), gemm_phases, col_groups, tr,
                                  gemm_rps, c->st);
     if (update_running) launch_bn_running(a, c->st);
@@ -1871,7 +1872,7 @@ static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, vo
     return fail(c, GAN_E_SHAPE, "an operand of 2 GiB or more (the kernels use 32-bit byte offsets)");
   (void)take_launch_error();
   int* tp = nullptr;
-  const int tr = conv_tile_rows(N, (long long)n_samples * Hr * Hr / n_groups);
+  const int tr = c->op_tile_rows ? c->op_tile_rows : conv_tile_rows(N, (long long)n_samples * Hr * Hr / n_groups, n_groups);
   gan_status s = op_common(c, offs, n_groups, Hr * Hr, tr, &tp);
   if (s != GAN_OK) return s;
   ConvArgs a = {};
@@ -1882,6 +1883,13 @@ static gan_status op_conv(gan_ctx* c, int mode, const void* A, const void* W, vo
   s = finish_op(c);
   (void)hipFree(tp);
   return s;
+}
+
+gan_status gan_op_tile_rows(gan_ctx* c, int32_t rows) {
+  if (!c) return GAN_E_ARG;
+  if (rows != 0 && rows != 64 && rows != 128 && rows != 256) return fail(c, GAN_E_ARG, "tile heights are 64, 128 and 256 (0: automatic)");
+  c->op_tile_rows = rows;
+  return GAN_OK;
 }
 
 gan_status gan_op_conv_down(gan_ctx* c, const void* big, const void* w_down, void* small_out, const int32_t* offs,

@@ -93,6 +93,6 @@ const char* wgrad_variant_name(const WgradArgs& a);
 int wgrad_tiles_per_model(int ntaps, int Cb, int Cs);
 
 // rows per M-tile the forward-type kernel will use for n_out output channels and about rows_per_model rows
-int conv_tile_rows(int n_out, long long rows_per_model_hint);
+int conv_tile_rows(int n_out, long long rows_per_model_hint, int n_models);
 
 }  // namespace gan

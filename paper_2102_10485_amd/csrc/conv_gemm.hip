@@ -52,8 +52,15 @@ typedef Tile<256, 128, 4, 2, 64, 3> TileMid;     // 512 threads, wave tile 64 x 
 typedef Tile<128, 128, 2, 2, 64, 3> TileSmall;   // 256 threads, wave tile 64 x 64 (few rows per model), 48 KiB of LDS
 typedef Tile<256, 64, 4, 1, 128, 2> TileNarrow;  // 256 threads, wave tile 64 x 64, for layers with 64 output channels:
                                                  // 128-byte chunks, two buffers of 40 KiB, so two blocks still share a CU
+typedef Tile<64, 64, 2, 2, 64, 3> TileTiny;      // 256 threads, wave tile 32 x 32, 24 KiB of LDS: workloads so small that
+                                                 // the larger tiles would leave most of the chip without a block
 
-int conv_tile_rows(int n_out, long long rows_per_model_hint) {
+int conv_tile_rows(int n_out, long long rows_per_model_hint, int n_models) {
+  // fewer than 128 tiles of 256 rows x 128 columns in a launch of one segment: the chip has 256 units to fill
+  if (rows_per_model_hint > 0 && n_models > 0) {
+    const long long tiles = n_models * ((rows_per_model_hint + 255) / 256) * ((n_out + 127) / 128);
+    if (tiles < 128) return TileTiny::BM;
+  }
   if (rows_per_model_hint > 0 && rows_per_model_hint <= 128) return TileSmall::BM;
   return TileBig::BM;
 }
@@ -116,6 +123,8 @@ __device__ inline void lds_wait(u32x4 (&a)[TM], u32x4 (&b)[TN]) {
     asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]) : "n"(N) : "memory");
   else if constexpr (TM == 2 && TN == 2)
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]) : "n"(N) : "memory");
+  else if constexpr (TM == 1 && TN == 1)
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a[0]), "+v"(b[0]) : "n"(N) : "memory");
   else
     static_assert(TM == 4 && TN == 2, "add the operand list for this wave tile");
 }
@@ -581,6 +590,7 @@ static void launch_one(ConvArgs a, hipStream_t st) {
 
 template <typename T, int MODE, int EPI>
 static void launch_wide(const ConvArgs& a, hipStream_t st) {
+  if (a.tile_rows == TileTiny::BM) return launch_one<T, MODE, EPI, TileTiny>(a, st);
   if (a.tile_rows == TileSmall::BM) return launch_one<T, MODE, EPI, TileSmall>(a, st);
   if (a.N <= TileNarrow::BN) return launch_one<T, MODE, EPI, TileNarrow>(a, st);
   if (a.N % 256 == 0) return launch_one<T, MODE, EPI, TileBig>(a, st);
@@ -613,9 +623,9 @@ void launch_conv(int mode, int epi, const ConvArgs& a, hipStream_t st) {
 const char* conv_variant_name(int mode, int epi, const ConvArgs& a) {
   static const char* modes[3] = {"down", "up", "dense"};
   static const char* epis[3] = {"", "+actbwd", "+lrelu"};
-  static char names[3][3][4][48];
-  const int tile = a.tile_rows == TileSmall::BM ? 2 : (a.N <= TileNarrow::BN ? 3 : (a.N % 256 == 0 ? 0 : 1));
-  static const char* tiles[4] = {"256x256", "256x128", "128x128", "256x64"};
+  static char names[3][3][5][48];
+  const int tile = a.tile_rows == TileTiny::BM ? 4 : (a.tile_rows == TileSmall::BM ? 2 : (a.N <= TileNarrow::BN ? 3 : (a.N % 256 == 0 ? 0 : 1)));
+  static const char* tiles[5] = {"256x256", "256x128", "128x128", "256x64", "64x64"};
   char* n = names[mode][epi][tile];
   if (!n[0]) snprintf(n, 48, "gemm_%s%s<%s>", modes[mode], epis[epi], tiles[tile]);
   return n;

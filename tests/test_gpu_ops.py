@@ -47,11 +47,16 @@ def tolerance(prec):
     return 2e-5 if prec == binding.FP32 else 1e-2
 
 
+@pytest.mark.parametrize("tile_rows", [0, 64, 128, 256])
 @pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
 @pytest.mark.parametrize("cb,cs,hs,groups", CASES)
-def test_conv_down_up_wgrad(ctxs, prec, cb, cs, hs, groups):
+def test_conv_down_up_wgrad(ctxs, prec, cb, cs, hs, groups, tile_rows):
+    """tile_rows: the forward-type kernel's tile height (0: as a training step would choose for this size, which is
+    the smallest tile at these sizes); with 256 the width follows the output channels (64, 128 or 256 columns), so the
+    cases together run every tile instantiation."""
     torch = U.torch_mod()
     g = ctxs[prec]
+    g.op_tile_rows(tile_rows)
     bf = prec == binding.BF16
     rng = np.random.default_rng(cb * 1000 + cs + hs)
     n = int(sum(groups))
@@ -116,6 +121,7 @@ def test_upsample_conv3_runs_on_the_transposed_convolution_engine(ctxs, prec, ci
     from oracle import paper_nets as P
     torch = U.torch_mod()
     g = ctxs[prec]
+    g.op_tile_rows(0)
     bf = prec == binding.BF16
     rng = np.random.default_rng(cin + cout + hs)
     n = int(sum(groups))
