@@ -35,8 +35,12 @@ def test_single_operations_refuse_shapes_the_kernels_do_not_support():
     # null pointers and negative sizes are argument errors
     assert g.lib.gan_op_conv_down(g.h, 0, p, p, o, 1, 4, 64, 64, 4) == binding.GAN_E_ARG
     assert g.lib.gan_op_conv_down(g.h, p, p, p, o, 1, -1, 64, 64, 4) == binding.GAN_E_ARG
-    # and the context still works afterwards
-    g.op_conv_down(p, p, p, o, 1, 4, 64, 64, 4)
+    # a tile height the kernels do not have
+    assert g.lib.gan_op_tile_rows(g.h, 96) == binding.GAN_E_ARG
+    # and the context still works afterwards, with every tile height there is
+    for rows in (64, 128, 256, 0):
+        g.op_tile_rows(rows)
+        g.op_conv_down(p, p, p, o, 1, 4, 64, 64, 4)
     g.close()
 
 
