@@ -78,91 +78,118 @@ __global__ __launch_bounds__(256) void im2col_kernel(Im2colArgs a) {
   }
   store8(static_cast<T*>(a.out) + (((long long)a.seg * a.seg_samples + j) * rps + pix) * a.Kc + m0, v);
 }
-// Same result, one block per sample: the sample's image goes through LDS once (NHWC, storage type), and every thread
-// keeps the (tap, channel) decoding of its 8 columns while it walks down the sample's patch rows.
+// Same result, one block per sample: the sample's image goes through LDS once (NHWC, storage type, with a one-pixel
+// border of zeros so that no tap needs a bounds test), and every thread keeps the decoding of its 8 columns -- for a
+// tap column the offset of its element from the patch's first one -- while it walks down the sample's patch rows.
 template <typename T>
 __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  T* tile = reinterpret_cast<T*>(lds_raw);                       // [Hb][Hb][CB]
+  T* tile = reinterpret_cast<T*>(lds_raw);                       // [Hb + 2][Hb + 2][CB]
   const int j = blockIdx.x;
   if (j >= a.offs[a.L]) return;
   const int g8 = a.Kc >> 3;
   const int rps = a.Hs * a.Hs, Hb = 2 * a.Hs, CB = a.CB;
-  const int npix = Hb * Hb;
+  const int npix = Hb * Hb, Hp = Hb + 2;
+  // the border: rows 0 and Hp - 1, columns 0 and Hp - 1
+  for (int t = threadIdx.x; t < 4 * Hp * CB; t += 256) {
+    const int side = t / (Hp * CB), r = t - side * (Hp * CB);
+    const int q = r / CB, cb = r - q * CB;
+    const int py = side == 0 ? 0 : (side == 1 ? Hp - 1 : q), px = side < 2 ? q : (side == 2 ? 0 : Hp - 1);
+    tile[(py * Hp + px) * CB + cb] = from_float<T>(0.f);
+  }
   if (a.img) {
     const T* img = static_cast<const T*>(a.img) + ((long long)a.seg * a.seg_samples + j) * npix * CB;
-    const int bytes = npix * CB * (int)sizeof(T);
-    if (bytes % 16 == 0) {                           // every sample then starts on a 16-byte boundary
-      const uint4* src = reinterpret_cast<const uint4*>(img);
-      uint4* dst = reinterpret_cast<uint4*>(tile);
-      for (int t = threadIdx.x; t < bytes / 16; t += 256) dst[t] = src[t];
-    } else {
-      for (int t = threadIdx.x; t < npix * CB; t += 256) tile[t] = img[t];
+    for (int t = threadIdx.x; t < npix * CB; t += 256) {
+      const int pxl = t / CB, cb = t - pxl * CB;
+      const int py = pxl / Hb, px = pxl - py * Hb;
+      tile[((py + 1) * Hp + px + 1) * CB + cb] = img[t];
     }
   } else {
     const float* real = a.real + (long long)a.perm[j] * CB * npix;     // NCHW fp32; npix is a multiple of 4
     const int nq = npix >> 2;
     if ((reinterpret_cast<uintptr_t>(a.real) & 15) != 0) {             // caller's buffer not 16-byte aligned: scalar loads
       for (int t = threadIdx.x; t < npix * CB; t += 256) {
-        const int cb = t / npix, p = t - cb * npix;
-        tile[p * CB + cb] = from_float<T>(real[t]);
+        const int cb = t / npix, pxl = t - cb * npix;
+        const int py = pxl / Hb, px = pxl - py * Hb;
+        tile[((py + 1) * Hp + px + 1) * CB + cb] = from_float<T>(real[t]);
       }
     } else
     for (int t = threadIdx.x; t < CB * nq; t += 256) {
-      const int cb = t / nq, p = 4 * (t - cb * nq);
+      const int cb = t / nq, pxl = 4 * (t - cb * nq);
       const float4 v = reinterpret_cast<const float4*>(real)[t];
-      tile[p * CB + cb] = from_float<T>(v.x);
-      tile[(p + 1) * CB + cb] = from_float<T>(v.y);
-      tile[(p + 2) * CB + cb] = from_float<T>(v.z);
-      tile[(p + 3) * CB + cb] = from_float<T>(v.w);
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {                                    // (four pixels of a row, unless Hb % 4 == 2)
+        const int py = (pxl + k) / Hb, px = pxl + k - py * Hb;
+        tile[((py + 1) * Hp + px + 1) * CB + cb] = from_float<T>(vv[k]);
+      }
     }
   }
   __syncthreads();
   const int ntap = 16 * CB;
   const int slot = a.nslot > 0 ? a.sample_slot[j] : 0;
   T* out = static_cast<T*>(a.out) + ((long long)a.seg * a.seg_samples + j) * rps * a.Kc;
-  int cur = -1;
-  int dyv[8], dxv[8], cbv[8], kind[8];            // kind: 0 tap, 1 zero, 2 one, 3 + class: label-map indicator of this class
-  for (int t = threadIdx.x; t < rps * g8; t += 256) {
-    const int pix = t / g8, g = t - pix * g8;
-    if (g != cur) {                                // fixed per thread whenever 256 is a multiple of g8
-      cur = g;
+  // A thread keeps its group of 8 columns (256 is a multiple of the groups per row: the launcher checks) and walks
+  // down the patch rows in steps of 256 / g8; the row's (y, x) is carried along instead of divided out, and the values
+  // travel as stored (no conversion): the kernel is bound by its vector instructions otherwise.
+  const int g = (int)threadIdx.x % g8, pstep = 256 / g8;
+  int off[8], kind[8];            // kind: 0 tap (off: element offset from the patch's corner), 1 zero, 2 one, 3 + class: label-map indicator of this class
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int m = g * 8 + e;
+    off[e] = 0; kind[e] = 1;
+    if (m < ntap) {
+      const int tap = m / CB, cb = m - tap * CB;
+      off[e] = ((tap >> 2) * Hp + (tap & 3)) * CB + cb; kind[e] = 0;
+    } else if (a.nslot > 0) {
+      const int q = m - ntap;
+      if (q < 9 * a.nslot) { if (q / 9 == slot) kind[e] = 3 + q % 9; }
+      else if (q == 9 * a.nslot) kind[e] = 2;
+    }
+  }
+  const bool plain = kind[0] == 0 && kind[7] == 0;      // all eight are taps (the kinds are ordered along a row)
+  const T one = from_float<T>(1.f), zero = from_float<T>(0.f);
+  int pix = (int)threadIdx.x / g8;
+  int y = pix / a.Hs, x = pix - y * a.Hs;
+  for (; pix < rps; pix += pstep) {
+    const T* corner = tile + (2 * y * Hp + 2 * x) * CB;        // padded position of input pixel (2y - 1, 2x - 1)
+    T v[8];
+    if (plain) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = corner[off[e]];
+    } else {
+      const int cls = pos_class(y, x, a.Hs);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int m = g * 8 + e;
-        dyv[e] = 0; dxv[e] = 0; cbv[e] = 0; kind[e] = 1;
-        if (m < ntap) {
-          const int tap = m / CB;
-          cbv[e] = m - tap * CB; dyv[e] = (tap >> 2) - 1; dxv[e] = (tap & 3) - 1; kind[e] = 0;
-        } else if (a.nslot > 0) {
-          const int q = m - ntap;
-          if (q < 9 * a.nslot) { if (q / 9 == slot) kind[e] = 3 + q % 9; }
-          else if (q == 9 * a.nslot) kind[e] = 2;
-        }
+        const T tapv = corner[off[e]];
+        v[e] = kind[e] == 0 ? tapv : ((kind[e] == 2 || kind[e] == 3 + cls) ? one : zero);
       }
     }
-    const int y = pix / a.Hs, x = pix - y * a.Hs;
-    const int cls = pos_class(y, x, a.Hs);
-    float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float val = 0.f;
-      if (kind[e] == 0) {
-        const int iy = 2 * y + dyv[e], ix = 2 * x + dxv[e];
-        if ((unsigned)iy < (unsigned)Hb && (unsigned)ix < (unsigned)Hb) val = to_float(tile[(iy * Hb + ix) * CB + cbv[e]]);
-      } else if (kind[e] == 2 || kind[e] == 3 + cls) {
-        val = 1.f;
-      }
-      v[e] = val;
+    T* dst = out + (long long)pix * a.Kc + g * 8;
+    if constexpr (sizeof(T) == 2) {
+      uint4 pk;
+      pk.x = (unsigned)v[0].v | ((unsigned)v[1].v << 16);
+      pk.y = (unsigned)v[2].v | ((unsigned)v[3].v << 16);
+      pk.z = (unsigned)v[4].v | ((unsigned)v[5].v << 16);
+      pk.w = (unsigned)v[6].v | ((unsigned)v[7].v << 16);
+      *reinterpret_cast<uint4*>(dst) = pk;
+    } else {
+      float* d = reinterpret_cast<float*>(dst);
+      const float* f = reinterpret_cast<const float*>(v);
+      *reinterpret_cast<float4*>(d) = make_float4(f[0], f[1], f[2], f[3]);
+      *reinterpret_cast<float4*>(d + 4) = make_float4(f[4], f[5], f[6], f[7]);
     }
-    store8(out + (long long)pix * a.Kc + g * 8, v);
+    x += pstep;
+    while (x >= a.Hs) { x -= a.Hs; ++y; }
   }
 }
 template <typename T> void launch_im2col(const Im2colArgs& a, hipStream_t st) {
   const long long tot = (long long)a.n * a.Hs * a.Hs * (a.Kc / 8);
   if (tot == 0) return;
-  const size_t lds = (size_t)4 * a.Hs * a.Hs * a.CB * sizeof(T);
-  if (lds <= 64 * 1024) {
+  const size_t lds = (size_t)(2 * a.Hs + 2) * (2 * a.Hs + 2) * a.CB * sizeof(T);
+  if (lds <= 64 * 1024 && 256 % (a.Kc / 8) == 0) {
+    if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&im2col_sample_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL((im2col_sample_kernel<T>), dim3((unsigned)a.n), dim3(256), lds, st, a);
     return;
   }
@@ -301,8 +328,9 @@ template void launch_img_bias_grad<bf16_t>(const ImgBiasArgs&, hipStream_t);
 // Transposed convolution onto the image (or the data gradient of D's first convolution, which is the same
 // operation): img[n, 2y+py, 2x+px][cb] = sum over the 4 taps of that phase and cs of feat[n, y+dy, x+dx][cs] * w[tap][cb][cs].
 // One block = an 8 x 8 patch of feature pixels of one sample with its 1-pixel halo held in LDS, so every feature
-// row is read from memory once for all 4 phases x 4 taps; wave p computes output phase p on MFMA with the (at
-// most 4) image channels as the N side of a 32 x 32 tile.  Epilogue: bias + tanh, or times (1 - y^2).
+// row is read from memory once for all 4 phases x 4 taps; the (phase, image channel) pairs -- at most 16 -- are the N
+// side of a 32 x 32 MFMA tile, and the block's four waves share the reduction over the 3 x 3 neighbourhood.
+// Epilogue: bias + tanh, or times (1 - y^2).
 // ---------------------------------------------------------------------------------------------------------
 __device__ inline void up_mma(floatx16& acc, const uint4& a, const uint4& b, bf16_t) {
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
@@ -353,7 +381,7 @@ __global__ __launch_bounds__(256) void up_img_kernel(UpImgArgs a) {
   for (int k = 0; k < NW; ++k) {
     const int i = tid + 256 * k;
     const int wr = i / cpr, ch = i - wr * cpr;                  // wr = tap * CB + cb
-    const int tap = wr / CB, cb = wr - tap * CB;
+    const int tap = (int)(((unsigned)wr * (65536u / (unsigned)CB + 1u)) >> 16), cb = wr - tap * CB;   // wr / CB, wr < 64
     wv[k] = make_uint4(0, 0, 0, 0);
     if (i < 16 * CB * cpr)
       wv[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(w + ((long long)tap * a.CBT + cb) * Cs) + ch * 16);
@@ -372,64 +400,77 @@ __global__ __launch_bounds__(256) void up_img_kernel(UpImgArgs a) {
   }
   __syncthreads();
 
-  const int py = wave >> 1, px = wave & 1;                    // this wave's output phase
+  // One product for all four output phases: columns = (phase, image channel) -- 4 * CB of the MFMA tile's 32 --, rows =
+  // the patch's 64 pixels, K = (neighbour pixel, feature channel) over the 3 x 3 neighbourhood; a neighbour at offset
+  // (dy, dx) meets output phase (py, px) through filter tap ky = 1, 2 (dy = 0), 3 (dy = -1, py = 0) or 0 (dy = +1,
+  // py = 1), likewise kx, and not at all otherwise (those lanes multiply zeros).  The four waves share the feature
+  // channels: wave w takes K-steps [w, w + 1) * ksteps / 4 of every neighbour, so everything but a lane's weight row
+  // is a compile-time offset.
   const int r = lane & 31, h = lane >> 5;
+  const int NC = 4 * CB;
+  const unsigned mCB = 65536u / (unsigned)CB + 1u;            // i / CB == (i * mCB) >> 16 for the small i below
+  const int ph = (int)(((unsigned)r * mCB) >> 16), cbn = r - ph * CB;
+  const int py = ph >> 1, px = ph & 1;
   floatx16 acc[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   constexpr int ksteps = Cs * (int)sizeof(T) / 32;            // 32 bytes of K per MFMA step (16 per lane half)
+  constexpr int kpw = ksteps / 4;
+  static_assert(ksteps % 4 == 0, "K-steps per wave");
+  const int kbase = __builtin_amdgcn_readfirstlane(wave) * (kpw * 32) + h * 16;
+  const unsigned char* frow0[2];
 #pragma unroll
-  for (int tp = 0; tp < 4; ++tp) {
-    const int ta = tp >> 1, tb = tp & 1;
-    const int dy = py == 0 ? (ta == 0 ? 0 : -1) : (ta == 0 ? 1 : 0);
-    const int dx = px == 0 ? (tb == 0 ? 0 : -1) : (tb == 0 ? 1 : 0);
-    const int ky = py == 0 ? (ta == 0 ? 1 : 3) : (ta == 0 ? 0 : 2);
-    const int kx = px == 0 ? (tb == 0 ? 1 : 3) : (tb == 0 ? 0 : 2);
-    const unsigned char* wrow = Wl + ((ky * 4 + kx) * CB + (r < CB ? r : 0)) * rowB + h * 16;
-    const unsigned char* frow[2];
+  for (int t = 0; t < 2; ++t) {
+    const int q = t * 32 + r;                                 // pixel of the patch: (q / 8, q % 8)
+    frow0[t] = Fl + ((q / UP_TS + 1) * UP_HALO + (q % UP_TS + 1)) * rowB + kbase;
+  }
+  const unsigned char* wcol = Wl + cbn * rowB + kbase;        // + tap * CB rows
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int q = t * 32 + r;                               // pixel of the patch: (q / 8, q % 8)
-      frow[t] = Fl + ((q / UP_TS + 1 + dy) * UP_HALO + (q % UP_TS + 1 + dx)) * rowB + h * 16;
-    }
+  for (int nb = 0; nb < 9; ++nb) {
+    const int dy = nb / 3 - 1, dx = nb % 3 - 1;               // compile-time after unrolling
+    const int ky = dy == 0 ? (py == 0 ? 1 : 2) : (dy < 0 ? (py == 0 ? 3 : -1) : (py == 1 ? 0 : -1));
+    const int kx = dx == 0 ? (px == 0 ? 1 : 2) : (dx < 0 ? (px == 0 ? 3 : -1) : (px == 1 ? 0 : -1));
+    const bool has = r < NC && ky >= 0 && kx >= 0;
+    const unsigned char* brow = wcol + (has ? (ky * 4 + kx) * CB * rowB : 0);
 #pragma unroll
-    for (int ks = 0; ks < ksteps; ++ks) {
-      uint4 b = make_uint4(0, 0, 0, 0);
-      if (r < CB) b = *reinterpret_cast<const uint4*>(wrow + ks * 32);
+    for (int k = 0; k < kpw; ++k) {
+      uint4 b = *reinterpret_cast<const uint4*>(brow + k * 32);
+      if (!has) b = make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const uint4 av = *reinterpret_cast<const uint4*>(frow[t] + ks * 32);
+        const uint4 av = *reinterpret_cast<const uint4*>(frow0[t] + (dy * UP_HALO + dx) * rowB + k * 32);
         up_mma(acc[t], av, b, T());
       }
     }
   }
-  // epilogue: only the first CB columns (lanes) of each MFMA tile are real.  Pass them through LDS so that all
-  // 256 threads share the (1 - y^2) / tanh work and write whole output rows.
-  __syncthreads();                                            // the halo tile is no longer read
-  float* ep = reinterpret_cast<float*>(Fl);                   // [2*UP_TS rows][2*UP_TS cols][4]
-  if (r < CB) {
+  // epilogue: each wave leaves its partial sums of the real columns in LDS (the halo tile and the weights are no longer
+  // read); all 256 threads then add the four, share the (1 - y^2) / tanh work and write whole output rows.
+  __syncthreads();
+  float* ep = reinterpret_cast<float*>(lds);                  // [4 waves][64 pixels][NC]
+  if (r < NC) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int q = t * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-        const int Yl = 2 * (q / UP_TS) + py, Xl = 2 * (q % UP_TS) + px;
-        ep[(Yl * 2 * UP_TS + Xl) * 4 + r] = acc[t][e];
+        ep[(wave * 64 + q) * NC + r] = acc[t][e];
       }
   }
   __syncthreads();
   T* out = static_cast<T*>(a.out);
   const T* aux = static_cast<const T*>(a.aux);
   const int rowlen = 2 * UP_TS * CB;                          // contiguous output elements per patch row
+  const unsigned mRow = 65536u / (unsigned)rowlen + 1u;       // exact for i < 1024, rowlen <= 64
   for (int i = tid; i < 2 * UP_TS * rowlen; i += 256) {
-    const int Yl = i / rowlen, rem = i - Yl * rowlen;
-    const int Xl = rem / CB, cb = rem - Xl * CB;
+    const int Yl = (int)(((unsigned)i * mRow) >> 16), rem = i - Yl * rowlen;
+    const int Xl = (int)(((unsigned)rem * mCB) >> 16), cb = rem - Xl * CB;
     const int Y = 2 * y0 + Yl, X = 2 * x0 + Xl;
     if (Y >= Hb || X >= Hb) continue;
     const long long o = ((sample * Hb + Y) * Hb + X) * CB + cb;
-    float v = ep[(Yl * 2 * UP_TS + Xl) * 4 + cb];
+    const int q = (Yl >> 1) * UP_TS + (Xl >> 1), col = ((Yl & 1) * 2 + (Xl & 1)) * CB + cb;
+    float v = (ep[q * NC + col] + ep[(64 + q) * NC + col]) + (ep[(128 + q) * NC + col] + ep[(192 + q) * NC + col]);
     if (a.mode == 1) v = tanhf(v + a.bias[(long long)l * a.bias_stride + cb]);
     else if (a.mode == 2) { const float yv = to_float(aux[o]); v *= (1.f - yv * yv); }
     out[o] = from_float<T>(v);

@@ -85,7 +85,11 @@ def fp32_bounds(pairs, spread=3.0):
     first layer at 40 samples per model, 2.6e-3 with one in a 64-channel generator block at 10 samples per model, 1e-6
     without.  Anything wrong in a kernel (a tap, a sign, a scale of a percent) is far above it."""
     d_grad = max(rel_l2(a["grads"][w], b["grads"][w]) for a, b in pairs for w in (0, 1))
-    return Bounds(cost=1e-4, theta=1e-4, grad=max(5e-3, spread * d_grad), set_aside=0.1)
+    # The parameters follow the gradient through Adam's sign-like first steps: where the single-precision build of the
+    # oracle itself takes such a decision the other way, its parameters leave the 1e-4 too (every element whose
+    # gradient changed sign moves by 2 lr), and the same spread applies.
+    d_theta = max(rel_l2(a["params"][w], b["params"][w]) for a, b in pairs for w in (0, 1))
+    return Bounds(cost=1e-4, theta=max(1e-4, spread * d_theta), grad=max(5e-3, spread * d_grad), set_aside=0.1)
 
 
 def emulation_bounds(pairs, spread=3.0):
