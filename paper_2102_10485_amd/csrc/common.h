@@ -27,11 +27,28 @@ __host__ __device__ inline unsigned short f32_to_bf16_bits(float f) {
 }
 template <typename T> __host__ __device__ inline T from_float(float f);
 template <> __host__ __device__ inline float from_float<float>(float f) { return f; }
+// On the device the conversion is the hardware's (v_cvt_pk_bf16_f32, round to nearest even like the function above);
+// the software rounding costs six vector instructions per element, which made several kernels instruction-bound.
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef float gan_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 gan_bf16x2 __attribute__((ext_vector_type(2)));
+__host__ __device__ inline unsigned pack2_bf16(float lo, float hi) {
+  const gan_f32x2 v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, gan_bf16x2));
+}
+template <> __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
+  bf16_t r;
+  r.v = __builtin_bit_cast(unsigned short, (__bf16)f);
+  return r;
+}
+#else
+__host__ __device__ inline unsigned pack2_bf16(float lo, float hi) { return (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16); }
 template <> __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
   bf16_t r;
   r.v = f32_to_bf16_bits(f);
   return r;
 }
+#endif
 
 // A host launcher that finds its assumptions violated records the reason and launches nothing; the library call in
 // progress then returns an error status with this text (nothing in the library ends the process).

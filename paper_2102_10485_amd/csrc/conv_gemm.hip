@@ -565,9 +565,11 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
               if (!(to_float(aa[k]) > 0.f)) vf[k] *= p.slope;
           }
           uint4 vraw;
-          T* vv = reinterpret_cast<T*>(&vraw);
-#pragma unroll
-          for (int k = 0; k < EPV; ++k) vv[k] = from_float<T>(vf[k]);
+          if constexpr (sizeof(T) == 2) {
+            vraw = make_uint4(pack2_bf16(vf[0], vf[1]), pack2_bf16(vf[2], vf[3]), pack2_bf16(vf[4], vf[5]), pack2_bf16(vf[6], vf[7]));
+          } else {
+            vraw = make_uint4(__float_as_uint(vf[0]), __float_as_uint(vf[1]), __float_as_uint(vf[2]), __float_as_uint(vf[3]));
+          }
           *reinterpret_cast<uint4*>(Out + o * N + col) = vraw;
         }
       }

@@ -35,10 +35,10 @@ __device__ inline void store8(float* p, const float (&v)[8]) {
 }
 __device__ inline void store8(bf16_t* p, const float (&v)[8]) {
   uint4 t;
-  t.x = (unsigned)f32_to_bf16_bits(v[0]) | ((unsigned)f32_to_bf16_bits(v[1]) << 16);
-  t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
-  t.z = (unsigned)f32_to_bf16_bits(v[4]) | ((unsigned)f32_to_bf16_bits(v[5]) << 16);
-  t.w = (unsigned)f32_to_bf16_bits(v[6]) | ((unsigned)f32_to_bf16_bits(v[7]) << 16);
+  t.x = pack2_bf16(v[0], v[1]);
+  t.y = pack2_bf16(v[2], v[3]);
+  t.z = pack2_bf16(v[4], v[5]);
+  t.w = pack2_bf16(v[6], v[7]);
   *reinterpret_cast<uint4*>(p) = t;
 }
 
@@ -125,60 +125,63 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
       }
     }
   }
-  __syncthreads();
-  const int ntap = 16 * CB;
+  const int ntap = 16 * CB;                        // a multiple of 8: a group of 8 columns is all taps or none
   const int slot = a.nslot > 0 ? a.sample_slot[j] : 0;
   T* out = static_cast<T*>(a.out) + ((long long)a.seg * a.seg_samples + j) * rps * a.Kc;
+  // The columns after the taps (label-map indicators, the constant one, padding) depend on the pixel only through its
+  // position class: their 9 possible rows are written once, behind the image tile.
+  const int gtap = ntap >> 3, gsp = g8 - gtap;     // groups of tap columns, of the others
+  T* special = tile + Hp * Hp * CB + ((16 - ((Hp * Hp * CB * (int)sizeof(T)) & 15)) & 15) / (int)sizeof(T);   // 16-byte aligned; [9][gsp * 8]
+  for (int t = threadIdx.x; t < 9 * gsp * 8; t += 256) {
+    const int cls = t / (gsp * 8), q = t - cls * (gsp * 8);          // q: column - ntap
+    float val = 0.f;
+    if (a.nslot > 0) {
+      if (q < 9 * a.nslot) val = (q / 9 == slot && q % 9 == cls) ? 1.f : 0.f;
+      else if (q == 9 * a.nslot) val = 1.f;
+    }
+    special[t] = from_float<T>(val);
+  }
+  __syncthreads();
   // A thread keeps its group of 8 columns (256 is a multiple of the groups per row: the launcher checks) and walks
   // down the patch rows in steps of 256 / g8; the row's (y, x) is carried along instead of divided out, and the values
   // travel as stored (no conversion): the kernel is bound by its vector instructions otherwise.
   const int g = (int)threadIdx.x % g8, pstep = 256 / g8;
-  int off[8], kind[8];            // kind: 0 tap (off: element offset from the patch's corner), 1 zero, 2 one, 3 + class: label-map indicator of this class
+  int off[8];                                      // tap columns: element offset from the patch's corner
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int m = g * 8 + e;
-    off[e] = 0; kind[e] = 1;
-    if (m < ntap) {
-      const int tap = m / CB, cb = m - tap * CB;
-      off[e] = ((tap >> 2) * Hp + (tap & 3)) * CB + cb; kind[e] = 0;
-    } else if (a.nslot > 0) {
-      const int q = m - ntap;
-      if (q < 9 * a.nslot) { if (q / 9 == slot) kind[e] = 3 + q % 9; }
-      else if (q == 9 * a.nslot) kind[e] = 2;
-    }
+    const int tap = m / CB, cb = m - tap * CB;
+    off[e] = m < ntap ? ((tap >> 2) * Hp + (tap & 3)) * CB + cb : 0;
   }
-  const bool plain = kind[0] == 0 && kind[7] == 0;      // all eight are taps (the kinds are ordered along a row)
-  const T one = from_float<T>(1.f), zero = from_float<T>(0.f);
+  const bool taps = g < gtap;
+  constexpr int VB = 8 * (int)sizeof(T);           // bytes of a group
   int pix = (int)threadIdx.x / g8;
   int y = pix / a.Hs, x = pix - y * a.Hs;
   for (; pix < rps; pix += pstep) {
-    const T* corner = tile + (2 * y * Hp + 2 * x) * CB;        // padded position of input pixel (2y - 1, 2x - 1)
-    T v[8];
-    if (plain) {
+    uint4 pk[VB / 16];
+    if (taps) {
+      const T* corner = tile + (2 * y * Hp + 2 * x) * CB;      // padded position of input pixel (2y - 1, 2x - 1)
+      T v[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = corner[off[e]];
-    } else {
-      const int cls = pos_class(y, x, a.Hs);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const T tapv = corner[off[e]];
-        v[e] = kind[e] == 0 ? tapv : ((kind[e] == 2 || kind[e] == 3 + cls) ? one : zero);
+      if constexpr (sizeof(T) == 2) {
+        pk[0].x = (unsigned)v[0].v | ((unsigned)v[1].v << 16);
+        pk[0].y = (unsigned)v[2].v | ((unsigned)v[3].v << 16);
+        pk[0].z = (unsigned)v[4].v | ((unsigned)v[5].v << 16);
+        pk[0].w = (unsigned)v[6].v | ((unsigned)v[7].v << 16);
+      } else {
+        const unsigned* u = reinterpret_cast<const unsigned*>(v);
+        pk[0] = make_uint4(u[0], u[1], u[2], u[3]);
+        pk[VB / 16 - 1] = make_uint4(u[4], u[5], u[6], u[7]);
       }
-    }
-    T* dst = out + (long long)pix * a.Kc + g * 8;
-    if constexpr (sizeof(T) == 2) {
-      uint4 pk;
-      pk.x = (unsigned)v[0].v | ((unsigned)v[1].v << 16);
-      pk.y = (unsigned)v[2].v | ((unsigned)v[3].v << 16);
-      pk.z = (unsigned)v[4].v | ((unsigned)v[5].v << 16);
-      pk.w = (unsigned)v[6].v | ((unsigned)v[7].v << 16);
-      *reinterpret_cast<uint4*>(dst) = pk;
     } else {
-      float* d = reinterpret_cast<float*>(dst);
-      const float* f = reinterpret_cast<const float*>(v);
-      *reinterpret_cast<float4*>(d) = make_float4(f[0], f[1], f[2], f[3]);
-      *reinterpret_cast<float4*>(d + 4) = make_float4(f[4], f[5], f[6], f[7]);
+      const uint4* src = reinterpret_cast<const uint4*>(special + (pos_class(y, x, a.Hs) * gsp + (g - gtap)) * 8);
+#pragma unroll
+      for (int k = 0; k < VB / 16; ++k) pk[k] = src[k];
     }
+    uint4* dst = reinterpret_cast<uint4*>(out + (long long)pix * a.Kc + g * 8);
+#pragma unroll
+    for (int k = 0; k < VB / 16; ++k) dst[k] = pk[k];
     x += pstep;
     while (x >= a.Hs) { x -= a.Hs; ++y; }
   }
@@ -186,8 +189,9 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
 template <typename T> void launch_im2col(const Im2colArgs& a, hipStream_t st) {
   const long long tot = (long long)a.n * a.Hs * a.Hs * (a.Kc / 8);
   if (tot == 0) return;
-  const size_t lds = (size_t)(2 * a.Hs + 2) * (2 * a.Hs + 2) * a.CB * sizeof(T);
-  if (lds <= 64 * 1024 && 256 % (a.Kc / 8) == 0) {
+  // the zero-bordered image tile, then (16-byte aligned) the 9 possible rows of the columns behind the taps
+  const size_t lds = (size_t)(2 * a.Hs + 2) * (2 * a.Hs + 2) * a.CB * sizeof(T) + 16 + (size_t)9 * (a.Kc - 16 * a.CB) * sizeof(T);
+  if (lds <= 64 * 1024 && 256 % (a.Kc / 8) == 0 && a.Kc >= 16 * a.CB) {
     if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&im2col_sample_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL((im2col_sample_kernel<T>), dim3((unsigned)a.n), dim3(256), lds, st, a);

@@ -243,8 +243,8 @@ __device__ inline void store4(float* p, const float (&v)[4]) {
 }
 __device__ inline void store4(bf16_t* p, const float (&v)[4]) {
   uint2 t;
-  t.x = (unsigned)f32_to_bf16_bits(v[0]) | ((unsigned)f32_to_bf16_bits(v[1]) << 16);
-  t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
+  t.x = pack2_bf16(v[0], v[1]);
+  t.y = pack2_bf16(v[2], v[3]);
   *reinterpret_cast<uint2*>(p) = t;
 }
 
@@ -262,10 +262,10 @@ __device__ inline void loadv(const bf16_t* p, float (&v)[8]) {
 __device__ inline void storev(float* p, const float (&v)[4]) { store4(p, v); }
 __device__ inline void storev(bf16_t* p, const float (&v)[8]) {
   uint4 t;
-  t.x = (unsigned)f32_to_bf16_bits(v[0]) | ((unsigned)f32_to_bf16_bits(v[1]) << 16);
-  t.y = (unsigned)f32_to_bf16_bits(v[2]) | ((unsigned)f32_to_bf16_bits(v[3]) << 16);
-  t.z = (unsigned)f32_to_bf16_bits(v[4]) | ((unsigned)f32_to_bf16_bits(v[5]) << 16);
-  t.w = (unsigned)f32_to_bf16_bits(v[6]) | ((unsigned)f32_to_bf16_bits(v[7]) << 16);
+  t.x = pack2_bf16(v[0], v[1]);
+  t.y = pack2_bf16(v[2], v[3]);
+  t.z = pack2_bf16(v[4], v[5]);
+  t.w = pack2_bf16(v[6], v[7]);
   typedef unsigned u4 __attribute__((ext_vector_type(4)));
   u4 q; q.x = t.x; q.y = t.y; q.z = t.z; q.w = t.w;
   __builtin_nontemporal_store(q, reinterpret_cast<u4*>(p));
@@ -700,27 +700,34 @@ void launch_loss(const HeadArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(loss_kernel, dim3(a.L), dim3(256), 0, st, a);
 }
 
-// dfeat[row][k] = dlogit[row] * w[model][k]
+// dfeat[row][k] = dlogit[row] * w[model][k]; a thread takes 8 consecutive k of one row (K is a multiple of 8: the
+// feature maps have whole 64-channel lines), blockIdx.y the segment; 32-bit index arithmetic (the launcher checks).
 template <typename T>
 __global__ __launch_bounds__(256) void head_bwd_data_kernel(HeadArgs a) {
-  const int k4 = a.K / 4;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (long long)a.n * a.nseg * k4) return;
-  const long long wrow = idx / k4;
-  const int k = (int)(idx - wrow * k4) * 4;
-  const int sidx = (int)(wrow / a.n), j = (int)(wrow - (long long)sidx * a.n);
-  if (j >= a.offs[a.L]) return;
+  const unsigned k8 = (unsigned)a.K >> 3;
+  const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+  const unsigned j = idx / k8;
+  if (j >= (unsigned)a.n || (int)j >= a.offs[a.L]) return;
+  const int k = (int)(idx - j * k8) * 8;
   const int l = a.sample_model[j];
-  const long long r = (long long)(a.seg_first + sidx) * a.seg_samples + j;
+  const long long r = (long long)(a.seg_first + (int)blockIdx.y) * a.seg_samples + j;
   const float d = a.dlogits[r];
-  const float4 ww = *reinterpret_cast<const float4*>(a.w + (long long)l * a.pstride + k);
-  const float v[4] = {d * ww.x, d * ww.y, d * ww.z, d * ww.w};
-  store4(static_cast<T*>(a.dfeat) + r * a.K + k, v);
+  const float* w = a.w + (long long)l * a.pstride + k;
+  const float4 w0 = *reinterpret_cast<const float4*>(w), w1 = *reinterpret_cast<const float4*>(w + 4);
+  const float v[8] = {d * w0.x, d * w0.y, d * w0.z, d * w0.w, d * w1.x, d * w1.y, d * w1.z, d * w1.w};
+  T* dst = static_cast<T*>(a.dfeat) + r * a.K + k;
+  if constexpr (sizeof(T) == 2) {
+    storev(dst, v);
+  } else {
+    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
 }
 template <typename T> void launch_head_bwd_data(const HeadArgs& a, hipStream_t st) {
-  const long long tot = (long long)a.n * a.nseg * (a.K / 4);
-  if (tot == 0) return;
-  hipLaunchKernelGGL((head_bwd_data_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+  const long long tot = (long long)a.n * (a.K / 8);
+  if (tot == 0 || a.nseg == 0) return;
+  if (a.K % 8 != 0 || tot + 256 >= (1LL << 32)) return launch_fail("head data gradient: K must be a multiple of 8 and n * K / 8 below 2^32");
+  hipLaunchKernelGGL((head_bwd_data_kernel<T>), dim3((unsigned)((tot + 255) / 256), (unsigned)a.nseg), dim3(256), 0, st, a);
 }
 template void launch_head_bwd_data<float>(const HeadArgs&, hipStream_t);
 template void launch_head_bwd_data<bf16_t>(const HeadArgs&, hipStream_t);
