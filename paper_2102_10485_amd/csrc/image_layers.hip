@@ -283,7 +283,39 @@ __global__ void unpack_dw_kernel(PackArgs a) {
     a.dbias[(long long)l * a.pstride + cs] = dwp_at(a, l, ntap + 9 * a.nslot, cs);
   }
 }
-void launch_unpack_dw(const PackArgs& a, hipStream_t st) {
+// part[0][i] <- part[0][i] + part[1][i] + ... (nsplit blocks of size4 float4 each), in a fixed order: lane group q of
+// a block adds the blocks q, q + 4, ... in turn, then (q0 + q1) + (q2 + q3).  One thread per element would walk the
+// splits one load after the other: with one model and 128 splits that chain alone took 0.13 ms.
+__global__ __launch_bounds__(256) void reduce_splits_kernel(float* __restrict__ part, long long size4, int nsplit) {
+  __shared__ float4 red[4][64];
+  const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const long long i = (long long)blockIdx.x * 64 + c;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < size4) {
+    const float4* p = reinterpret_cast<const float4*>(part) + i;
+#pragma unroll 4
+    for (int k = q; k < nsplit; k += 4) {
+      const float4 t = p[(long long)k * size4];
+      acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    }
+  }
+  red[q][c] = acc;
+  __syncthreads();
+  if (q == 0 && i < size4) {
+    const float4 a0 = red[0][c], a1 = red[1][c], a2 = red[2][c], a3 = red[3][c];
+    reinterpret_cast<float4*>(part)[i] = make_float4((a0.x + a1.x) + (a2.x + a3.x), (a0.y + a1.y) + (a2.y + a3.y),
+                                                      (a0.z + a1.z) + (a2.z + a3.z), (a0.w + a1.w) + (a2.w + a3.w));
+  }
+}
+void launch_unpack_dw(const PackArgs& a0, hipStream_t st) {
+  PackArgs a = a0;
+  const long long block = (long long)a.L * a.Kc * a.Cs;       // floats per split
+  if (a.nsplit > 4 && block % 4 == 0) {
+    // many row splits: add them up with a kernel that has enough threads, in place into the first block
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((block / 4 + 63) / 64)), dim3(256), 0, st, const_cast<float*>(a.dwp), block / 4,
+                       a.nsplit);
+    a.nsplit = 1;
+  }
   const long long tot = (long long)a.L * a.Cs * (16 * a.CB + (a.nslot > 0 ? a.nslot * 16 + 1 : 0));
   hipLaunchKernelGGL(unpack_dw_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
 }

@@ -95,6 +95,7 @@ __global__ __launch_bounds__(256) void sum_splits_kernel(const float* __restrict
   const long long i = idx - (long long)l * size4;
   const float4* p = reinterpret_cast<const float4*>(part) + (long long)l * size4 + i;
   float4 s = p[0];
+#pragma unroll 8
   for (int k = 1; k < nsplit; ++k) {
     const float4 t = p[(long long)k * L * size4];
     s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
@@ -296,7 +297,8 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
   const int seq = nphase * ntiles, per = (seq + RED_SLICES - 1) / RED_SLICES;
   float n = 0.f, mean = 0.f, m2 = 0.f;
   if (c < a.C)
-    for (int q = sl * per; q < min(seq, (sl + 1) * per); ++q) {
+#pragma unroll 4
+    for (int q = sl * per; q < min(seq, (sl + 1) * per); ++q) {     // (unrolled: the loads of four tiles are in flight together)
       const int ph = q / ntiles, t = q - ph * ntiles;
       const float nt = (float)min(tile_rows, rows - t * tile_rows);
       for (int g = 0; g < groups; ++g) {
@@ -772,7 +774,8 @@ __global__ void head_bwd_w_final_kernel(HeadArgs a) {
   const int l = (int)(idx / (a.K + 1)), k = (int)(idx - (long long)l * (a.K + 1));
   if (a.offs[l + 1] == a.offs[l]) return;
   float s = 0.f;
-  for (int sp = 0; sp < a.rsplit; ++sp) s += a.part[((long long)sp * a.L + l) * (a.K + 4) + k];
+#pragma unroll 8
+  for (int sp = 0; sp < a.rsplit; ++sp) s += a.part[((long long)sp * a.L + l) * (a.K + 4) + k];     // loads in flight together, sum in order
   if (k < a.K) a.dw[(long long)l * a.pstride + k] = s;
   else a.db[(long long)l * a.pstride] = s;
 }
