@@ -19,20 +19,20 @@ PEAK = {"mfma_bf16": 2500.0, "mfma_fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFL
 # the same counters read for the 1 GiB elementwise probe (fetch x 2.0, write x 1.0).  Valid only for the kernel sources they
 # were taken with: `sources` is the digest of csrc/ at that time, and the roofline reports null traffic when it differs.
 MEASURED_TRAFFIC = {
-    "sources": "f94790406f3381f3",
+    "sources": "3dd504b0f83f8e06",
     "workload": "config 2 bf16",
     "fetch_scale": 2.000, "write_scale": 1.000,
     "kib_per_launch": {
-        "gemm_dense<128x128>": (103319, 108800),
-        "gemm_up<256x256>": (489686, 274133),
-        "gemm_up<256x128>": (186460, 416000),
-        "gemm_dense+lrelu<256x128>": (154552, 614400),
-        "gemm_down<256x256>": (497628, 207200),
-        "wgrad<256x256>": (421464, 512000),
-        "gemm_up+actbwd<256x128>": (647440, 614400),
+        "gemm_dense<128x128>": (103307, 108800),
+        "gemm_up<256x256>": (490595, 274133),
+        "gemm_up<256x128>": (186425, 416000),
+        "gemm_dense+lrelu<256x128>": (154542, 614400),
+        "gemm_down<256x256>": (498901, 207200),
+        "wgrad<256x256>": (425394, 512000),
+        "gemm_up+actbwd<256x128>": (641929, 614400),
         "wgrad<64x128>": (460882, 25600),
-        "gemm_dense<256x128>": (103354, 409600),
-        "wgrad<256x128>": (52093, 409600),
+        "gemm_dense<256x128>": (103336, 409600),
+        "wgrad<256x128>": (52092, 409600),
     },
 }
 
