@@ -472,55 +472,6 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   __syncthreads();
   T* __restrict__ Out = static_cast<T*>(p.Out);
   const T* __restrict__ Aux = static_cast<const T*>(p.Aux);
-  if (p.stat_partial) {
-    // For the BatchNorm that follows: per column of this tile, the sum of the fp32 results and the sum of squared
-    // deviations from the tile's own column mean (merged across tiles by the pairwise-update formula, which keeps
-    // the variance free of the E[x^2] - mean^2 cancellation).  Fixed order everywhere.
-    float* red = reinterpret_cast<float*>(smem + SMEM - TL::WM * BN * 8);   // [WM][BN][2], at the end of the buffers
-    const int valid_rows = min(BM, Mrows - m0);
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      float s1 = 0.f;
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s1 += acc[tm][tn][e];             // rows past the model's end are exact zeros
-      s1 += __shfl_xor(s1, 32, 64);
-      if (lane < 32) red[(wm * BN + wn * TN * 32 + tn * 32 + lane) * 2] = s1;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      const int c = wn * TN * 32 + tn * 32 + (lane & 31);
-      float tot = 0.f;
-#pragma unroll
-      for (int w = 0; w < TL::WM; ++w) tot += red[(w * BN + c) * 2];
-      const float mean = tot / (float)valid_rows;
-      float s2 = 0.f;
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int rr = wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          const float d = acc[tm][tn][e] - mean;
-          if (rr < valid_rows) s2 += d * d;
-        }
-      s2 += __shfl_xor(s2, 32, 64);
-      if (lane < 32) red[(wm * BN + c) * 2 + 1] = s2;
-    }
-    __syncthreads();
-    for (int c = tid; c < BN; c += TL::NT) {
-      const int col = nt * BN + c;
-      if (col >= N) continue;
-      float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-      for (int w = 0; w < TL::WM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
-      const long long t = ((long long)phase * p.nseg + sidx) * p.ub_tiles + mt;
-      p.stat_partial[(t * N + col) * 2] = s1;
-      p.stat_partial[(t * N + col) * 2 + 1] = s2;
-    }
-    // (the patches below sit after the row table, the sums at the end of the buffers: no barrier needed between them)
-  }
   {
     // Each wave passes its 32 x (TN*32) blocks (fp32) through a private LDS patch so that every lane stores 16
     // contiguous bytes of an output row (full N is a multiple of 64 for these tiles).  The patch belongs to one
@@ -570,12 +521,66 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
           } else {
             vraw = make_uint4(__float_as_uint(vf[0]), __float_as_uint(vf[1]), __float_as_uint(vf[2]), __float_as_uint(vf[3]));
           }
-          *reinterpret_cast<uint4*>(Out + o * N + col) = vraw;
+          {
+            typedef unsigned u4 __attribute__((ext_vector_type(4)));
+            u4 q; q.x = vraw.x; q.y = vraw.y; q.z = vraw.z; q.w = vraw.w;
+            __builtin_nontemporal_store(q, reinterpret_cast<u4*>(Out + o * N + col));      // read next by another kernel, never by this one
+          }
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       __builtin_amdgcn_wave_barrier();
     }
+  }
+  if (p.stat_partial) {
+    // For the BatchNorm that follows: per column of this tile, the sum of the fp32 results and the sum of squared
+    // deviations from the tile's own column mean (merged across tiles by the pairwise-update formula, which keeps
+    // the variance free of the E[x^2] - mean^2 cancellation).  Fixed order everywhere.
+    float* red = reinterpret_cast<float*>(smem + SMEM - TL::WM * BN * 8);   // [WM][BN][2], at the end of the buffers
+    const int valid_rows = min(BM, Mrows - m0);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      float s1 = 0.f;
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s1 += acc[tm][tn][e];             // rows past the model's end are exact zeros
+      s1 += __shfl_xor(s1, 32, 64);
+      if (lane < 32) red[(wm * BN + wn * TN * 32 + tn * 32 + lane) * 2] = s1;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int c = wn * TN * 32 + tn * 32 + (lane & 31);
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < TL::WM; ++w) tot += red[(w * BN + c) * 2];
+      const float mean = tot / (float)valid_rows;
+      float s2 = 0.f;
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int rr = wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          const float d = acc[tm][tn][e] - mean;
+          if (rr < valid_rows) s2 += d * d;
+        }
+      s2 += __shfl_xor(s2, 32, 64);
+      if (lane < 32) red[(wm * BN + c) * 2 + 1] = s2;
+    }
+    __syncthreads();
+    for (int c = tid; c < BN; c += TL::NT) {
+      const int col = nt * BN + c;
+      if (col >= N) continue;
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < TL::WM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
+      const long long t = ((long long)phase * p.nseg + sidx) * p.ub_tiles + mt;
+      p.stat_partial[(t * N + col) * 2] = s1;
+      p.stat_partial[(t * N + col) * 2 + 1] = s2;
+    }
+    // (the patches above sit after the row table, the sums at the end of the buffers: no barrier needed between them;
+    // the sums come last so that they are computed while the tile's stores are on their way)
   }
 }
 
