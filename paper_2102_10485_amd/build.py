@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgan_hip.so")
-SOURCES = ["api.hip", "conv_gemm.hip", "pointwise.hip", "image_layers.hip", "paper_layers.hip", "probe.hip", "anova_static.hip", "paper_step.hip"]
+SOURCES = ["api.hip", "conv_gemm.hip", "pointwise.hip", "image_layers.hip", "paper_layers.hip", "probe.hip", "anova_static.hip", "paper_step.hip", "conv3_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 instructions are kept out of all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1089,8 +1089,12 @@ __global__ __launch_bounds__(TL::NT) void wgrad_tr_kernel(WgradArgs p) {
       const int pr = cid / CPRW, pc = cid - pr * CPRW;
       const int m = mt * BM + wm * TM * 32 + tm * 32 + pr;
       const int col = colw + pc * 4;
-      if (m < Mtot && col < Cs)         // Cs is a multiple of 8: a 16-byte chunk is inside or outside
-        *reinterpret_cast<float4*>(dW + (long long)m * Cs + col) = *reinterpret_cast<const float4*>(patch + pr * PSTRIDE + pc * 16);
+      if (m < Mtot && col < Cs) {       // Cs is a multiple of 8: a 16-byte chunk is inside or outside
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const float4 t = *reinterpret_cast<const float4*>(patch + pr * PSTRIDE + pc * 16);
+        f4 q; q.x = t.x; q.y = t.y; q.z = t.z; q.w = t.w;
+        __builtin_nontemporal_store(q, reinterpret_cast<f4*>(dW + (long long)m * Cs + col));   // read next by the update kernel
+      }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
