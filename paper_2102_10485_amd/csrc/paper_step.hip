@@ -82,42 +82,71 @@ template void launch_point_bwd<float>(const PointArgs&, hipStream_t);
 template void launch_point_bwd<bf16_t>(const PointArgs&, hipStream_t);
 
 // Rows of (segment, model): samples offs[l] .. offs[l+1] of segment seg, HW rows each, Cpad channels per row.
-// Block = 16 channels x 16 row lanes; every lane adds its rows in order, then the lanes are added in order.
-constexpr int PS_LANES = 16;
-__device__ inline float lanes_sum(float v, float (*sh)[16], int cx, int rl) {
-  sh[rl][cx] = v;
+// Block = CB_ channels of one (segment,) model: CB_ / EPV channel lanes of 16 bytes x 256 / lanes row lanes; every row
+// lane adds its rows (rl, rl + RL, ...) in order, then the lanes are added in order -- whole 16-byte loads of 64 or
+// 128 contiguous bytes per row instead of one element per thread.
+constexpr int PS_CH = 32;                     // channels per block
+template <typename T> struct PsVec { static constexpr int N = 16 / (int)sizeof(T); };
+template <typename T> __device__ inline void ps_load(const T* p, float (&v)[PsVec<T>::N]) {
+  const uint4 t = *reinterpret_cast<const uint4*>(p);
+  if constexpr (sizeof(T) == 2) {
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+    v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u);
+    v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xffff0000u);
+  } else {
+    v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
+  }
+}
+// sum over the row lanes, in lane order, of every lane's EPV values; result for channel cx (< PS_CH) in the threads
+// with threadIdx.x < PS_CH
+template <int EPV>
+__device__ inline float ps_lanes_sum(const float (&v)[EPV], float* sh, int cl, int rl, int RL) {
+  __syncthreads();                                   // the buffer's previous use is over
+#pragma unroll
+  for (int e = 0; e < EPV; ++e) sh[rl * PS_CH + cl * EPV + e] = v[e];
   __syncthreads();
   float s = 0.f;
-  if (rl == 0)
-    for (int k = 0; k < PS_LANES; ++k) s += sh[k][cx];
-  __syncthreads();
-  return s;       // valid in lane 0
+  if ((int)threadIdx.x < PS_CH)
+    for (int k = 0; k < RL; ++k) s += sh[k * PS_CH + threadIdx.x];
+  return s;
 }
 
-// dbias[l][c] (+)= sum over the segments and rows of g (mode: the segments are added in order inside the block)
+// dbias[l][c] = sum over the segments and rows of g (the segments are added in order inside the block)
 template <typename T>
 __global__ __launch_bounds__(256) void col_sum_kernel(PointArgs a, float* __restrict__ out, long long out_stride) {
-  __shared__ float sh[PS_LANES][16];
-  const int cx = threadIdx.x & 15, rl = threadIdx.x >> 4;
-  const int cblocks = (a.C + 15) / 16;
-  const int c = (blockIdx.x % cblocks) * 16 + cx;
+  constexpr int EPV = PsVec<T>::N, CG = PS_CH / EPV, RL = 256 / CG;
+  __shared__ float sh[RL * PS_CH];
+  const int cl = threadIdx.x % CG, rl = threadIdx.x / CG;
+  const int cblocks = (a.Cpad + PS_CH - 1) / PS_CH;
+  const int c0 = (blockIdx.x % cblocks) * PS_CH;
   const int l = blockIdx.x / cblocks;
   const int cnt = a.offs[l + 1] - a.offs[l];
   if (cnt == 0) return;
   const long long rows = (long long)cnt * a.HW;
+  const bool live = c0 + cl * EPV < a.Cpad;          // Cpad is a multiple of 8: a 16-byte group is inside or outside
   float tot = 0.f;
   for (int s = 0; s < a.nseg; ++s) {
-    const T* g = static_cast<const T*>(a.x) + ((long long)(a.seg_first + s) * a.seg_samples + a.offs[l]) * a.HW * a.Cpad;
-    float acc = 0.f;
-    if (c < a.C)
-      for (long long r = rl; r < rows; r += PS_LANES) acc += to_float(g[r * a.Cpad + c]);
-    tot += lanes_sum(acc, sh, cx, rl);
+    const T* g = static_cast<const T*>(a.x) + ((long long)(a.seg_first + s) * a.seg_samples + a.offs[l]) * a.HW * a.Cpad + c0 + cl * EPV;
+    float acc[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+    if (live)
+      for (long long r = rl; r < rows; r += RL) {
+        float v[EPV];
+        ps_load<T>(g + r * a.Cpad, v);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[e] += v[e];
+      }
+    tot += ps_lanes_sum<EPV>(acc, sh, cl, rl, RL);
   }
-  if (rl == 0 && c < a.C) out[(long long)l * out_stride + c] = tot;
+  const int c = c0 + (int)threadIdx.x;
+  if ((int)threadIdx.x < PS_CH && c < a.C) out[(long long)l * out_stride + c] = tot;
 }
 template <typename T> void launch_col_sum(const PointArgs& a, float* out, long long out_stride, hipStream_t st) {
   if (a.nseg == 0) return;
-  hipLaunchKernelGGL((col_sum_kernel<T>), dim3((unsigned)(a.L * ((a.C + 15) / 16))), dim3(256), 0, st, a, out, out_stride);
+  if (a.Cpad % 8 != 0) return launch_fail("column sums: the channel count of a row must be a multiple of 8");
+  hipLaunchKernelGGL((col_sum_kernel<T>), dim3((unsigned)(a.L * ((a.Cpad + PS_CH - 1) / PS_CH))), dim3(256), 0, st, a, out, out_stride);
 }
 template void launch_col_sum<float>(const PointArgs&, float*, long long, hipStream_t);
 template void launch_col_sum<bf16_t>(const PointArgs&, float*, long long, hipStream_t);
@@ -126,39 +155,56 @@ template void launch_col_sum<bf16_t>(const PointArgs&, float*, long long, hipStr
 // pass), 1 / sqrt(var + eps); written where the BatchNorm passes expect them ([(segment) * L + model][C]).
 template <typename T>
 __global__ __launch_bounds__(256) void bn_stats_direct_kernel(NormArgs a, int Cpad) {
-  __shared__ float sh[PS_LANES][16];
-  __shared__ float mean_sh[16];
-  const int cx = threadIdx.x & 15, rl = threadIdx.x >> 4;
-  const int cblocks = (a.C + 15) / 16;
-  const int c = (blockIdx.x % cblocks) * 16 + cx;
+  constexpr int EPV = PsVec<T>::N, CG = PS_CH / EPV, RL = 256 / CG;
+  __shared__ float sh[RL * PS_CH];
+  __shared__ float mean_sh[PS_CH];
+  const int cl = threadIdx.x % CG, rl = threadIdx.x / CG;
+  const int cblocks = (Cpad + PS_CH - 1) / PS_CH;
+  const int c0 = (blockIdx.x % cblocks) * PS_CH;
   const int l = (blockIdx.x / cblocks) % a.L;
   const int sidx = blockIdx.x / (cblocks * a.L);
   const int cnt = a.offs[l + 1] - a.offs[l];
   if (cnt == 0) return;
   const long long rows = (long long)cnt * a.rps;
-  const T* x = static_cast<const T*>(a.x) + ((long long)(a.seg_first + sidx) * a.seg_samples + a.offs[l]) * a.rps * Cpad;
-  float acc = 0.f;
-  if (c < a.C)
-    for (long long r = rl; r < rows; r += PS_LANES) acc += to_float(x[r * Cpad + c]);
-  const float s1 = lanes_sum(acc, sh, cx, rl);
-  if (rl == 0) mean_sh[cx] = s1 / (float)rows;
+  const bool live = c0 + cl * EPV < Cpad;
+  const T* x = static_cast<const T*>(a.x) + ((long long)(a.seg_first + sidx) * a.seg_samples + a.offs[l]) * a.rps * Cpad + c0 + cl * EPV;
+  float acc[EPV];
+#pragma unroll
+  for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+  if (live)
+    for (long long r = rl; r < rows; r += RL) {
+      float v[EPV];
+      ps_load<T>(x + r * Cpad, v);
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) acc[e] += v[e];
+    }
+  const float s1 = ps_lanes_sum<EPV>(acc, sh, cl, rl, RL);
+  if ((int)threadIdx.x < PS_CH) mean_sh[threadIdx.x] = s1 / (float)rows;
   __syncthreads();
-  const float mean = mean_sh[cx];
-  acc = 0.f;
-  if (c < a.C)
-    for (long long r = rl; r < rows; r += PS_LANES) { const float d = to_float(x[r * Cpad + c]) - mean; acc += d * d; }
-  const float s2 = lanes_sum(acc, sh, cx, rl);
-  if (rl == 0 && c < a.C) {
+  float mean[EPV];
+#pragma unroll
+  for (int e = 0; e < EPV; ++e) { mean[e] = mean_sh[cl * EPV + e]; acc[e] = 0.f; }
+  if (live)
+    for (long long r = rl; r < rows; r += RL) {
+      float v[EPV];
+      ps_load<T>(x + r * Cpad, v);
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) { const float d = v[e] - mean[e]; acc[e] += d * d; }
+    }
+  const float s2 = ps_lanes_sum<EPV>(acc, sh, cl, rl, RL);
+  const int c = c0 + (int)threadIdx.x;
+  if ((int)threadIdx.x < PS_CH && c < a.C) {
     const float var = s2 / (float)rows;
     const long long o = (long long)((a.seg_first + sidx) * a.L + l) * a.C + c;
-    a.mean[o] = mean;
+    a.mean[o] = mean_sh[threadIdx.x];
     a.var[o] = var;
     a.rstd[o] = 1.0f / sqrtf(var + a.eps);
   }
 }
 template <typename T> void launch_bn_stats_direct(const NormArgs& a, int Cpad, hipStream_t st) {
-  const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
+  const long long tot = (long long)a.nseg * a.L * ((Cpad + PS_CH - 1) / PS_CH);
   if (tot == 0) return;
+  if (Cpad % 8 != 0) return launch_fail("batch statistics: the channel count of a row must be a multiple of 8");
   hipLaunchKernelGGL((bn_stats_direct_kernel<T>), dim3((unsigned)tot), dim3(256), 0, st, a, Cpad);
 }
 template void launch_bn_stats_direct<float>(const NormArgs&, int, hipStream_t);
