@@ -271,9 +271,10 @@ gan_status gan_op_conv_wgrad(gan_ctx* ctx, const void* big, const void* small_in
 
    gan_op_dropout: in place on a DEVICE tensor [n_samples][h][w][ch] of the context's storage type whose samples are
      grouped by model (offs: DEVICE int32 [n_groups + 1]): element <- element * keep / (1 - p) (Table 2: Dropout(0.25)).
-     keep comes from Philox-4x32-10 (Salmon et al., SC'11): counter = (index low, index high, layer + 256 * pass_id,
-     step), key = (seed low, seed high ^ group), index = ((n * ch + c) * h + y) * w + x with n counted inside the group;
-     keep iff (first output word >> 8) >= ceil(p * 2^24).  The backward pass is the same call on the gradient.
+     keep comes from Philox-4x32-10 (Salmon et al., SC'11): counter = (q low, q high, layer + 256 * pass_id, step) with
+     q = index / 4, key = (seed low, seed high ^ group), index = ((n * ch + c) * h + y) * w + x with n counted inside
+     the group; keep iff (output word number index % 4 >> 8) >= ceil(p * 2^24): four consecutive elements share one
+     evaluation of the generator.  The backward pass is the same call on the gradient.
      layer in [0, 255]; p in [0, 1).
    gan_op_w3_to_w4: the weights that turn "Upsample(2) then Conv k3 s1 p1" (Table 1) into the k4 s2 p1 transposed
      convolution of gan_op_conv_up: per axis, tap t of the 4-tap filter is the sum of the 3-tap filter's taps in

@@ -21,10 +21,11 @@ Readings (the tables do not say):
 The dropout mask must be reproducible bit for bit by any other implementation, so it comes from a counter-based
 generator, Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
 SC'11), written here from its definition:
-    counter = (element index low, element index high, layer + 256 * pass, iteration of the model)
+    counter = (q low, q high, layer + 256 * pass, iteration of the model), q = element index // 4
     key     = (seed low, seed high xor model index)
     element index = ((n * C + c) * H + y) * W + x with n the sample's position among the model's samples (stable order)
-    u = (first output word >> 8) * 2^-24 ;  keep the element iff u >= p.
+    u = (output word number (element index % 4) >> 8) * 2^-24 ;  keep the element iff u >= p
+(all four output words of a counter are used: four consecutive elements share one evaluation of the generator).
 """
 import numpy as np
 
@@ -52,12 +53,14 @@ def philox4x32_10(c0, c1, c2, c3, k0, k1):
 
 def dropout_keep(shape, p, seed, model, step, layer, pass_id):
     """Boolean keep-mask of an [n, C, H, W] tensor of one model (definition in the module header)."""
-    idx = np.arange(int(np.prod(shape)), dtype=np.uint64)
-    lo, hi = (idx & _LO32).astype(np.uint32), (idx >> np.uint64(32)).astype(np.uint32)
+    total = int(np.prod(shape))
+    q = np.arange((total + 3) // 4, dtype=np.uint64)                    # one counter per four consecutive elements
+    lo, hi = (q & _LO32).astype(np.uint32), (q >> np.uint64(32)).astype(np.uint32)
     k0 = np.uint32(seed & 0xFFFFFFFF)
     k1 = np.uint32(((seed >> 32) & 0xFFFFFFFF) ^ model)
-    w0 = philox4x32_10(lo, hi, np.uint32(layer + 256 * pass_id), np.uint32(step), k0, k1)[0]
-    u = (w0 >> np.uint32(8)).astype(np.float64) * (1.0 / 16777216.0)
+    words = philox4x32_10(lo, hi, np.uint32(layer + 256 * pass_id), np.uint32(step), k0, k1)
+    w = np.stack(words, axis=1).reshape(-1)[:total]                      # element i: word i % 4 of counter i // 4
+    u = (w >> np.uint32(8)).astype(np.float64) * (1.0 / 16777216.0)
     return (u >= p).reshape(shape)
 
 

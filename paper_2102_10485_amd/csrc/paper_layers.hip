@@ -9,8 +9,8 @@ namespace gan {
 
 // Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3", SC'11), from
 // its definition: a round maps (c0, c1, c2, c3) to (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0));
-// the key is advanced by the two Weyl constants between rounds.  Returns the first output word.
-__device__ inline unsigned philox4x32_10_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1) {
+// the key is advanced by the two Weyl constants between rounds.  All four output words.
+__device__ inline void philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1, unsigned (&out)[4]) {
   constexpr unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
@@ -20,12 +20,12 @@ __device__ inline unsigned philox4x32_10_word0(unsigned c0, unsigned c1, unsigne
     const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
   }
-  return c0;
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
 // x[j][y][x][c] (rows grouped by model: group g holds samples offs[g] .. offs[g+1]) <- x * keep / (1 - p), where
-// keep(element) = (word0 >> 8) >= thr with thr = ceil(p 2^24), counter = (index low, index high, layer + 256 pass,
-// step), key = (seed low, seed high ^ group), index = ((n C + c) H + y) W + x, n = j - offs[g].
+// keep(element) = (word[index % 4] >> 8) >= thr with thr = ceil(p 2^24), counter = (index / 4 low, high, layer + 256
+// pass, step), key = (seed low, seed high ^ group), index = ((n C + c) H + y) W + x, n = j - offs[g].
 template <typename T>
 __global__ __launch_bounds__(256) void dropout_kernel(T* __restrict__ x, const int* __restrict__ offs, int n_groups, long long total,
                                                       int C, int H, int W, unsigned thr, float scale, unsigned seed_lo,
@@ -44,8 +44,11 @@ __global__ __launch_bounds__(256) void dropout_kernel(T* __restrict__ x, const i
   }
   if (j >= offs[n_groups]) return;                 // rows past the routed samples are left alone
   const unsigned long long lin = (((unsigned long long)(j - offs[lo]) * C + c) * H + y) * W + xw;
-  const unsigned w0 = philox4x32_10_word0((unsigned)lin, (unsigned)(lin >> 32), c2, step, seed_lo, seed_hi ^ (unsigned)lo);
-  x[e] = (w0 >> 8) >= thr ? from_float<T>(to_float(x[e]) * scale) : from_float<T>(0.f);
+  unsigned w[4];
+  philox4x32_10((unsigned)(lin >> 2), (unsigned)(lin >> 34), c2, step, seed_lo, seed_hi ^ (unsigned)lo, w);
+  const unsigned sel = (unsigned)lin & 3u;
+  const unsigned wd = sel == 0 ? w[0] : (sel == 1 ? w[1] : (sel == 2 ? w[2] : w[3]));
+  x[e] = (wd >> 8) >= thr ? from_float<T>(to_float(x[e]) * scale) : from_float<T>(0.f);
 }
 template <typename T>
 void launch_dropout(T* x, const int* offs, int n_groups, int n, int C, int H, int W, float p, unsigned long long seed, int step,

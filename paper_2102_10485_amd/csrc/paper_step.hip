@@ -14,8 +14,8 @@
 
 namespace gan {
 
-__device__ inline unsigned philox_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1) {
-  // Philox-4x32-10 (Salmon et al., SC'11), first output word; same definition as in paper_layers.hip
+__device__ inline void philox4(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1, unsigned (&out)[4]) {
+  // Philox-4x32-10 (Salmon et al., SC'11), all four output words; same definition as in paper_layers.hip
   constexpr unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
@@ -25,20 +25,28 @@ __device__ inline unsigned philox_word0(unsigned c0, unsigned c1, unsigned c2, u
     const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
   }
-  return c0;
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// keep-mask of element (n inside its model, c, pixel) of a [n][C][H][W]-indexed tensor: see gan_op_dropout in gan.h
-__device__ inline bool dropout_keep(const PointArgs& a, int l, int n_local, int c, int pix, int pass_id, unsigned step) {
-  const unsigned long long lin = ((unsigned long long)n_local * a.C + c) * a.HW + pix;
-  const unsigned w0 = philox_word0((unsigned)lin, (unsigned)(lin >> 32), (unsigned)(a.layer + 256 * pass_id), step, a.seed_lo,
-                                   a.seed_hi ^ (unsigned)l);
-  return (w0 >> 8) >= a.thr;
+// the four output words that hold the keep-decisions of elements lin .. lin + 3 (lin a multiple of 4) of a
+// [n][C][H][W]-indexed tensor, or the one of element lin (any lin): see gan_op_dropout in gan.h
+__device__ inline void dropout_words(const PointArgs& a, int l, unsigned long long lin, int pass_id, unsigned step, unsigned (&w)[4]) {
+  philox4((unsigned)(lin >> 2), (unsigned)(lin >> 34), (unsigned)(a.layer + 256 * pass_id), step, a.seed_lo, a.seed_hi ^ (unsigned)l, w);
 }
 
 // forward: x <- dropout(act(x + bias))      (mode 0)
 // backward: g <- g * keep * scale * act'(saved)   (mode 1; saved = the forward result: positive exactly where the
 //           pre-activation was, zero where dropped -- and there the gradient is zero anyway)
+template <typename T, int MODE>
+__device__ inline float point_value(const PointArgs& a, float v, const T* saved, const float* bias, int o, int c) {
+  if (MODE == 0) {
+    if (bias) v += bias[c];
+    v = v > 0.f ? v : v * a.slope;
+  } else {
+    if (!(to_float(saved[o]) > 0.f)) v *= a.slope;
+  }
+  return v;
+}
 template <typename T, int MODE>
 __global__ __launch_bounds__(256) void point_kernel(PointArgs a) {
   const int j = blockIdx.x, sidx = blockIdx.y;
@@ -52,18 +60,38 @@ __global__ __launch_bounds__(256) void point_kernel(PointArgs a) {
   T* x = static_cast<T*>(a.x) + base;
   const T* saved = MODE == 1 ? static_cast<const T*>(a.saved) + base : nullptr;
   const float* bias = (MODE == 0 && a.bias) ? a.bias + (long long)l * a.pstride : nullptr;
-  const int total = a.HW * a.C;
-  for (int t = threadIdx.x; t < total; t += 256) {
-    const int pix = t / a.C, c = t - pix * a.C;
-    const long long o = (long long)pix * a.Cpad + c;
-    float v = to_float(x[o]);
-    if (MODE == 0) {
-      if (bias) v += bias[c];
-      v = v > 0.f ? v : v * a.slope;
-    } else {
-      if (!(to_float(saved[o]) > 0.f)) v *= a.slope;
+  // (pixel, channel) carried along instead of divided out: the kernel is bound by its vector instructions
+  const int dp = 256 / a.C, dc = 256 - dp * a.C;
+  int pix = (int)threadIdx.x / a.C, c = (int)threadIdx.x - pix * a.C;
+  if (a.thr > 0 && (a.HW & 3) == 0) {
+    // a thread takes four consecutive pixels of one channel: consecutive element indices, one generator evaluation
+    const int total = (a.HW >> 2) * a.C;
+    for (int t = threadIdx.x; t < total; t += 256, pix += dp, c += dc) {
+      if (c >= a.C) { c -= a.C; ++pix; }              // pix counts groups of four pixels here
+      unsigned w[4];
+      dropout_words(a, l, ((unsigned long long)n_local * a.C + c) * a.HW + pix * 4, pass_id, step, w);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int o = (pix * 4 + k) * a.Cpad + c;
+        const float v = point_value<T, MODE>(a, to_float(x[o]), saved, bias, o, c);
+        x[o] = from_float<T>((w[k] >> 8) >= a.thr ? v * a.scale : 0.f);
+      }
     }
-    if (a.thr > 0) v = dropout_keep(a, l, n_local, c, pix, pass_id, step) ? v * a.scale : 0.f;
+    return;
+  }
+  const int total = a.HW * a.C;
+  for (int t = threadIdx.x; t < total; t += 256, pix += dp, c += dc) {
+    if (c >= a.C) { c -= a.C; ++pix; }
+    const int o = pix * a.Cpad + c;
+    float v = point_value<T, MODE>(a, to_float(x[o]), saved, bias, o, c);
+    if (a.thr > 0) {
+      const unsigned long long lin = ((unsigned long long)n_local * a.C + c) * a.HW + pix;
+      unsigned w[4];
+      dropout_words(a, l, lin, pass_id, step, w);
+      const unsigned sel = (unsigned)lin & 3u;
+      const unsigned wd = sel == 0 ? w[0] : (sel == 1 ? w[1] : (sel == 2 ? w[2] : w[3]));
+      v = (wd >> 8) >= a.thr ? v * a.scale : 0.f;
+    }
     x[o] = from_float<T>(v);
   }
 }

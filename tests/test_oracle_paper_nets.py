@@ -40,6 +40,16 @@ def test_dropout_mask_properties():
     assert P.dropout_keep(shape, 0.0, 5, 1, 3, 2, 0).all()
     # the mask of a sample does not depend on how many samples follow it
     assert np.array_equal(a[:2], P.dropout_keep((2,) + shape[1:], 0.25, 5, 1, 3, 2, 0))
+    # element i takes output word i % 4 of counter i // 4: the four words of a counter are four different draws (the
+    # decisions inside a group of four are as independent as across groups), a length that is not a multiple of four
+    # just stops early, and the elements 4..7 are the four words of counter 1
+    flat = a.reshape(-1)
+    g = flat.reshape(-1, 4)
+    for u, v in ((0, 1), (1, 2), (2, 3), (0, 3)):
+        assert 0.55 < (g[:, u] == g[:, v]).mean() < 0.70
+    assert np.array_equal(flat[:13], P.dropout_keep((13, 1, 1, 1), 0.25, 5, 1, 3, 2, 0).reshape(-1))
+    words = P.philox4x32_10(1, 0, 2, 3, 5, 1)                                           # counter (1, 0, layer, step), key (seed, model)
+    assert [bool((int(w) >> 8) >= 4194304) for w in words] == [bool(b) for b in flat[4:8]]
 
 
 def test_upsample_and_its_adjoint():
