@@ -15,8 +15,8 @@ __device__ inline void philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsi
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     if (r > 0) { k0 += W0; k1 += W1; }
-    const unsigned hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-    const unsigned hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const unsigned long long p0 = (unsigned long long)M0 * c0, p1 = (unsigned long long)M1 * c2;     // one wide multiply each
+    const unsigned hi0 = (unsigned)(p0 >> 32), lo0 = (unsigned)p0, hi1 = (unsigned)(p1 >> 32), lo1 = (unsigned)p1;
     const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
   }
@@ -70,32 +70,44 @@ __device__ inline void taps_of(int t4, int& first, int& count) {
   first = t4 == 0 ? 2 : (t4 == 1 ? 1 : 0);
   count = (t4 == 1 || t4 == 2) ? 2 : 1;
 }
-// w3: fp32 [G][9][cb][cs] ; w4: T [G][16][cb][cs] ; w4t: T [G][16][cs][cb]
+// w3: fp32 [G][9][cb][cs] ; w4: T [G][16][cb][cs] ; w4t: T [G][16][cs][cb] (written by the tiled transpose afterwards)
+// grid (chunks of cb * cs, 16 taps, G): no index divisions beyond one 32-bit one
 template <typename T>
-__global__ __launch_bounds__(256) void w3_to_w4_kernel(const float* __restrict__ w3, T* __restrict__ w4, T* __restrict__ w4t,
-                                                       long long total, int cb, int cs, long long w3_stride, long long w4_stride) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;      // (g, tap16, cb, cs)
-  if (idx >= total) return;
-  const int s = (int)(idx % cs);
-  const int b = (int)((idx / cs) % cb);
-  const int t = (int)((idx / ((long long)cs * cb)) % 16);
-  const long long g = idx / ((long long)cs * cb * 16);
+__global__ __launch_bounds__(256) void w3_to_w4_kernel(const float* __restrict__ w3, T* __restrict__ w4, int cb, int cs, long long w3_stride,
+                                                       long long w4_stride) {
+  const int inner = blockIdx.x * 256 + threadIdx.x;                       // b * cs + s
+  if (inner >= cb * cs) return;
+  const int t = blockIdx.y;
+  const long long g = blockIdx.z;
   int y0, ny, x0, nx;
   taps_of(t >> 2, y0, ny);
   taps_of(t & 3, x0, nx);
   float v = 0.f;
   for (int ky = y0; ky < y0 + ny; ++ky)
-    for (int kx = x0; kx < x0 + nx; ++kx) v += w3[g * w3_stride + (((long long)(ky * 3 + kx)) * cb + b) * cs + s];
-  w4[g * w4_stride + ((long long)t * cb + b) * cs + s] = from_float<T>(v);
-  w4t[g * w4_stride + ((long long)t * cs + s) * cb + b] = from_float<T>(v);
+    for (int kx = x0; kx < x0 + nx; ++kx) v += w3[g * w3_stride + (long long)(ky * 3 + kx) * cb * cs + inner];
+  w4[g * w4_stride + (long long)t * cb * cs + inner] = from_float<T>(v);
+}
+// w4t[g][t][s][b] = w4[g][t][b][s] for channel counts the tiled transpose does not take (element by element)
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_plain_kernel(const T* __restrict__ w4, T* __restrict__ w4t, int cb, int cs, long long stride) {
+  const int inner = blockIdx.x * 256 + threadIdx.x;
+  if (inner >= cb * cs) return;
+  const int b = inner / cs, s = inner - b * cs;
+  const long long base = (long long)blockIdx.z * stride + (long long)blockIdx.y * cb * cs;
+  w4t[base + (long long)s * cb + b] = w4[base + inner];
 }
 template <typename T>
 void launch_w3_to_w4(const float* w3, T* w4, T* w4t, int n_groups, int cb, int cs, hipStream_t st, long long w3_stride,
                      long long w4_stride) {
-  const long long total = (long long)n_groups * 16 * cb * cs;
-  if (total == 0) return;
-  hipLaunchKernelGGL((w3_to_w4_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w3, w4, w4t, total, cb, cs,
-                     w3_stride ? w3_stride : (long long)9 * cb * cs, w4_stride ? w4_stride : (long long)16 * cb * cs);
+  if (n_groups == 0 || cb == 0 || cs == 0) return;
+  if (n_groups > 65535 || (long long)cb * cs >= (1LL << 31)) return launch_fail("summed-tap weights: more than 65535 groups, or a filter plane of 2^31 elements");
+  const long long s4 = w4_stride ? w4_stride : (long long)16 * cb * cs;
+  hipLaunchKernelGGL((w3_to_w4_kernel<T>), dim3((unsigned)((cb * cs + 255) / 256), 16, (unsigned)n_groups), dim3(256), 0, st, w3, w4, cb, cs,
+                     w3_stride ? w3_stride : (long long)9 * cb * cs, s4);
+  if (w4t) {
+    if (cb % 32 == 0) launch_transpose_w<T, T>(w4, w4t, s4, n_groups, cb, cs, st);      // 32 x 32 tiles through LDS
+    else hipLaunchKernelGGL((transpose_plain_kernel<T>), dim3((unsigned)((cb * cs + 255) / 256), 16, (unsigned)n_groups), dim3(256), 0, st, w4, w4t, cb, cs, s4);
+  }
 }
 template void launch_w3_to_w4<float>(const float*, float*, float*, int, int, int, hipStream_t, long long, long long);
 template void launch_w3_to_w4<bf16_t>(const float*, bf16_t*, bf16_t*, int, int, int, hipStream_t, long long, long long);

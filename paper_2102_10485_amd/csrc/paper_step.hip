@@ -20,8 +20,8 @@ __device__ inline void philox4(unsigned c0, unsigned c1, unsigned c2, unsigned c
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     if (r > 0) { k0 += W0; k1 += W1; }
-    const unsigned hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-    const unsigned hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const unsigned long long p0 = (unsigned long long)M0 * c0, p1 = (unsigned long long)M1 * c2;     // one wide multiply each
+    const unsigned hi0 = (unsigned)(p0 >> 32), lo0 = (unsigned)p0, hi1 = (unsigned)(p1 >> 32), lo1 = (unsigned)p1;
     const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
   }
