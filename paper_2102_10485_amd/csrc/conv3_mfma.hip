@@ -15,6 +15,8 @@
 // fp32 master weights are rounded to T on their way into LDS, as every other layer's weights are in their storage copy.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace gan {
@@ -43,6 +45,8 @@ constexpr int C3_MAXCO = 4;
 constexpr int C3_MAX_SPLITS = 32;
 
 // ---- forward -----------------------------------------------------------------------------------------------------
+// One block per sample: the model's weights go into LDS once, then the sample's patches one after the other, the next
+// patch's halo tile on its way (in registers) while the current one is multiplied.
 template <typename T, int CIN>
 __global__ __launch_bounds__(256) void conv3_fwd_kernel(Conv3Args a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -50,46 +54,38 @@ __global__ __launch_bounds__(256) void conv3_fwd_kernel(Conv3Args a) {
   constexpr int rowB = CIN * SZ + 16;                          // bytes per pixel / weight row in LDS
   constexpr int cpr = CIN * SZ / 16;                           // 16-byte chunks per row
   unsigned char* Fl = lds;                                     // [C3_HALO * C3_HALO][rowB]
-  unsigned char* Wl = lds + C3_HALO * C3_HALO * rowB;          // [9 * CO][rowB]
-  const int j = blockIdx.y;
+  unsigned char* Wl = lds + C3_HALO * C3_HALO * rowB;          // [9 * C3_MAXCO][rowB]
+  float* ep = reinterpret_cast<float*>(Wl + 9 * C3_MAXCO * rowB);   // [4 waves][64 pixels][CO]
+  const int j = blockIdx.x;
   if (j >= a.offs[a.L]) return;
   const int l = a.sample_model[j];
   const int H = a.H, CO = a.CO;
   const int tiles = (H + C3_TS - 1) / C3_TS;
-  const int y0 = (blockIdx.x / tiles) * C3_TS, x0 = (blockIdx.x % tiles) * C3_TS;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const T* in = static_cast<const T*>(a.in) + (long long)j * H * H * CIN;
+  T* out = static_cast<T*>(a.out) + ((long long)a.out_seg * a.seg_samples + j) * H * H * CO;
   constexpr int NF = (C3_HALO * C3_HALO * cpr + 255) / 256;
   uint4 fv[NF];
+  auto fetch = [&](int tile) {
+    const int y0 = (tile / tiles) * C3_TS, x0 = (tile % tiles) * C3_TS;
 #pragma unroll
-  for (int k = 0; k < NF; ++k) {
-    const int i = tid + 256 * k;
-    const int hr = i / cpr, ch = i - hr * cpr;
-    const int y = y0 - 1 + hr / C3_HALO, x = x0 - 1 + hr % C3_HALO;
-    fv[k] = make_uint4(0, 0, 0, 0);
-    if (i < C3_HALO * C3_HALO * cpr && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)H)
-      fv[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(in + ((long long)y * H + x) * CIN) + ch * 16);
-  }
+    for (int k = 0; k < NF; ++k) {
+      const int i = tid + 256 * k;
+      const int hr = i / cpr, ch = i - hr * cpr;
+      const int y = y0 - 1 + hr / C3_HALO, x = x0 - 1 + hr % C3_HALO;
+      fv[k] = make_uint4(0, 0, 0, 0);
+      if (i < C3_HALO * C3_HALO * cpr && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)H)
+        fv[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(in + ((long long)y * H + x) * CIN) + ch * 16);
+    }
+  };
+  fetch(0);
   const float* w = a.w + (long long)l * a.w_stride;            // [9][CO][CIN] fp32
   for (int i = tid; i < 9 * CO * CIN; i += 256) {
     const int row = i / CIN, ci = i - row * CIN;
     *reinterpret_cast<T*>(Wl + row * rowB + ci * SZ) = from_float<T>(w[i]);
   }
-#pragma unroll
-  for (int k = 0; k < NF; ++k) {
-    const int i = tid + 256 * k;
-    const int hr = i / cpr, ch = i - hr * cpr;
-    if (i < C3_HALO * C3_HALO * cpr) *reinterpret_cast<uint4*>(Fl + hr * rowB + ch * 16) = fv[k];
-  }
-  __syncthreads();
-
   const int r = lane & 31, h = lane >> 5;
   const bool colok = r < CO;
-  c3_f16 acc[2];
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   constexpr int ksteps = CIN * SZ / 32, kpw = ksteps / 4;      // the four waves share the feature channels
   static_assert(ksteps % 4 == 0, "K-steps per wave");
   const int kbase = wave * (kpw * 32) + h * 16;
@@ -100,37 +96,55 @@ __global__ __launch_bounds__(256) void conv3_fwd_kernel(Conv3Args a) {
     frow0[t] = Fl + ((q / C3_TS + 1) * C3_HALO + (q % C3_TS + 1)) * rowB + kbase;
   }
   const unsigned char* wcol = Wl + (colok ? r : 0) * rowB + kbase;
+  const unsigned mCO = 65536u / (unsigned)CO + 1u;             // i / CO for i < 256
+  float bias_r[C3_MAXCO];
 #pragma unroll
-  for (int nb = 0; nb < 9; ++nb) {
-    const int dy = nb / 3 - 1, dx = nb % 3 - 1;                // the tap (ky, kx) = (dy + 1, dx + 1) reads pixel p + (dy, dx)
+  for (int co = 0; co < C3_MAXCO; ++co) bias_r[co] = co < CO ? a.bias[(long long)l * a.bias_stride + co] : 0.f;
+  for (int tile = 0; tile < tiles * tiles; ++tile) {
+    const int y0 = (tile / tiles) * C3_TS, x0 = (tile % tiles) * C3_TS;
+    __syncthreads();                                           // the previous patch: multiplied and written out
 #pragma unroll
-    for (int k = 0; k < kpw; ++k) {
-      uint4 b = *reinterpret_cast<const uint4*>(wcol + nb * CO * rowB + k * 32);
-      if (!colok) b = make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const uint4 av = *reinterpret_cast<const uint4*>(frow0[t] + (dy * C3_HALO + dx) * rowB + k * 32);
-        c3_mma(acc[t], av, b, T());
-      }
+    for (int k = 0; k < NF; ++k) {
+      const int i = tid + 256 * k;
+      const int hr = i / cpr, ch = i - hr * cpr;
+      if (i < C3_HALO * C3_HALO * cpr) *reinterpret_cast<uint4*>(Fl + hr * rowB + ch * 16) = fv[k];
     }
-  }
-  __syncthreads();                                             // the tiles are no longer read
-  float* ep = reinterpret_cast<float*>(lds);                   // [4 waves][64 pixels][CO]
-  if (colok) {
+    if (tile + 1 < tiles * tiles) fetch(tile + 1);
+    __syncthreads();
+    c3_f16 acc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) ep[(wave * 64 + t * 32 + c3_acc_row(e, h)) * CO + r] = acc[t][e];
-  }
-  __syncthreads();
-  T* out = static_cast<T*>(a.out) + ((long long)a.out_seg * a.seg_samples + j) * H * H * CO;
-  const unsigned mCO = 65536u / (unsigned)CO + 1u;             // i / CO for i < 256
-  for (int i = tid; i < 64 * CO; i += 256) {
-    const int q = (int)(((unsigned)i * mCO) >> 16), co = i - q * CO;
-    const int y = y0 + q / C3_TS, x = x0 + q % C3_TS;
-    if (y >= H || x >= H) continue;
-    const float v = (ep[q * CO + co] + ep[(64 + q) * CO + co]) + (ep[(128 + q) * CO + co] + ep[(192 + q) * CO + co]);
-    out[((long long)y * H + x) * CO + co] = from_float<T>(tanhf(v + a.bias[(long long)l * a.bias_stride + co]));
+      for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 9; ++nb) {
+      const int dy = nb / 3 - 1, dx = nb % 3 - 1;              // the tap (ky, kx) = (dy + 1, dx + 1) reads pixel p + (dy, dx)
+#pragma unroll
+      for (int k = 0; k < kpw; ++k) {
+        uint4 b = *reinterpret_cast<const uint4*>(wcol + nb * CO * rowB + k * 32);
+        if (!colok) b = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const uint4 av = *reinterpret_cast<const uint4*>(frow0[t] + (dy * C3_HALO + dx) * rowB + k * 32);
+          c3_mma(acc[t], av, b, T());
+        }
+      }
+    }
+    if (colok) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ep[(wave * 64 + t * 32 + c3_acc_row(e, h)) * CO + r] = acc[t][e];
+    }
+    __syncthreads();
+    for (int i = tid; i < 64 * CO; i += 256) {
+      const int q = (int)(((unsigned)i * mCO) >> 16), co = i - q * CO;
+      const int y = y0 + q / C3_TS, x = x0 + q % C3_TS;
+      if (y >= H || x >= H) continue;
+      const float v = (ep[q * CO + co] + ep[(64 + q) * CO + co]) + (ep[(128 + q) * CO + co] + ep[(192 + q) * CO + co]);
+      const float bb = co == 0 ? bias_r[0] : (co == 1 ? bias_r[1] : (co == 2 ? bias_r[2] : bias_r[3]));
+      out[((long long)y * H + x) * CO + co] = from_float<T>(tanhf(v + bb));
+    }
   }
 }
 
@@ -154,6 +168,8 @@ __device__ inline T c3_patch_value(const T* D, int q, int tap, int co) {
 }
 
 // ---- data gradient ---------------------------------------------------------------------------------------------------
+// One block per sample, the weights (transposed, rounded to T) in LDS once, the next patch's dout halo on its way while
+// the current patch is multiplied.
 template <typename T, int CIN>
 __global__ __launch_bounds__(256) void conv3_dgrad_kernel(Conv3Args a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -164,17 +180,30 @@ __global__ __launch_bounds__(256) void conv3_dgrad_kernel(Conv3Args a) {
   T* D = reinterpret_cast<T*>(lds);                                            // [100][4]
   unsigned char* PA = lds + ((C3_HALO * C3_HALO * C3_MAXCO * SZ + 15) & ~15);  // [64 pixels][prow]
   unsigned char* WT = PA + 64 * prow;                                          // [CIN][prow]: w transposed, (tap, co) fastest
-  unsigned char* OUT = PA;                                                     // epilogue: [64 pixels][orow], over PA and WT
-  static_assert(64 * orow <= (64 + CIN) * prow, "output staging fits");
-  const int j = blockIdx.y;
+  unsigned char* OUT = WT + CIN * prow;                                        // [64 pixels][orow]
+  const int j = blockIdx.x;
   if (j >= a.offs[a.L]) return;
   const int l = a.sample_model[j];
   const int H = a.H, CO = a.CO;
   const int tiles = (H + C3_TS - 1) / C3_TS;
-  const int y0 = (blockIdx.x / tiles) * C3_TS, x0 = (blockIdx.x % tiles) * C3_TS;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const T* dout = static_cast<const T*>(a.dout) + ((long long)a.out_seg * a.seg_samples + j) * H * H * CO;
-  c3_load_dout<T>(a, dout, y0, x0, D);
+  T* din = static_cast<T*>(a.din) + (long long)j * H * H * CIN;
+  constexpr int ND = (C3_HALO * C3_HALO * C3_MAXCO + 255) / 256;
+  T dreg[ND];
+  auto fetch = [&](int tile) {
+    const int y0 = (tile / tiles) * C3_TS, x0 = (tile % tiles) * C3_TS;
+#pragma unroll
+    for (int k = 0; k < ND; ++k) {
+      const int t = tid + 256 * k;
+      const int px = t >> 2, co = t & 3;
+      const int y = y0 - 1 + px / C3_HALO, x = x0 - 1 + px % C3_HALO;
+      dreg[k] = from_float<T>(0.f);
+      if (t < C3_HALO * C3_HALO * C3_MAXCO && co < CO && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)H)
+        dreg[k] = dout[((long long)y * H + x) * CO + co];
+    }
+  };
+  fetch(0);
   // zero the operand rows (K beyond 9 CO must multiply as zero), then the weights
   for (int t = tid; t < (64 + CIN) * prow / 16; t += 256) reinterpret_cast<uint4*>(PA)[t] = make_uint4(0, 0, 0, 0);
   __syncthreads();
@@ -183,48 +212,57 @@ __global__ __launch_bounds__(256) void conv3_dgrad_kernel(Conv3Args a) {
     const int k = i / CIN, ci = i - k * CIN;
     *reinterpret_cast<T*>(WT + ci * prow + k * SZ) = from_float<T>(w[i]);
   }
-  for (int i = tid; i < 64 * 9; i += 256) {
-    const int tap = i >> 6, q = i & 63;
-    for (int co = 0; co < CO; ++co) *reinterpret_cast<T*>(PA + q * prow + (tap * CO + co) * SZ) = c3_patch_value<T>(D, q, tap, co);
-  }
-  __syncthreads();
   // (row tile, column tile) pairs: 2 x CIN / 32, dealt to the four waves
   constexpr int NT = CIN / 32, PAIRS = 2 * NT / 4;
   static_assert(2 * NT % 4 == 0, "tile pairs per wave");
   const int r = lane & 31, h = lane >> 5;
   const int mt = wave & 1;
-  c3_f16 acc[PAIRS];
-#pragma unroll
-  for (int i = 0; i < PAIRS; ++i)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
   const int ksteps = (9 * CO * SZ + 31) / 32;
-  for (int ks = 0; ks < ksteps; ++ks) {
-    const uint4 av = *reinterpret_cast<const uint4*>(PA + (mt * 32 + r) * prow + h * 16 + ks * 32);
+  constexpr int cpr = CIN * SZ / 16;
+  for (int tile = 0; tile < tiles * tiles; ++tile) {
+    const int y0 = (tile / tiles) * C3_TS, x0 = (tile % tiles) * C3_TS;
+    __syncthreads();                                           // the previous patch: multiplied and written out
+#pragma unroll
+    for (int k = 0; k < ND; ++k) {
+      const int t = tid + 256 * k;
+      if (t < C3_HALO * C3_HALO * C3_MAXCO) D[t] = dreg[k];
+    }
+    if (tile + 1 < tiles * tiles) fetch(tile + 1);
+    __syncthreads();
+    for (int i = tid; i < 64 * 9; i += 256) {
+      const int tap = i >> 6, q = i & 63;
+      for (int co = 0; co < CO; ++co) *reinterpret_cast<T*>(PA + q * prow + (tap * CO + co) * SZ) = c3_patch_value<T>(D, q, tap, co);
+    }
+    __syncthreads();
+    c3_f16 acc[PAIRS];
+#pragma unroll
+    for (int i = 0; i < PAIRS; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int ks = 0; ks < ksteps; ++ks) {
+      const uint4 av = *reinterpret_cast<const uint4*>(PA + (mt * 32 + r) * prow + h * 16 + ks * 32);
+#pragma unroll
+      for (int i = 0; i < PAIRS; ++i) {
+        const int nt = (wave >> 1) + 2 * i;
+        const uint4 bv = *reinterpret_cast<const uint4*>(WT + (nt * 32 + r) * prow + h * 16 + ks * 32);
+        c3_mma(acc[i], av, bv, T());
+      }
+    }
 #pragma unroll
     for (int i = 0; i < PAIRS; ++i) {
       const int nt = (wave >> 1) + 2 * i;
-      const uint4 bv = *reinterpret_cast<const uint4*>(WT + (nt * 32 + r) * prow + h * 16 + ks * 32);
-      c3_mma(acc[i], av, bv, T());
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        *reinterpret_cast<T*>(OUT + (mt * 32 + c3_acc_row(e, h)) * orow + (nt * 32 + r) * SZ) = from_float<T>(acc[i][e]);
     }
-  }
-  __syncthreads();                                             // operands consumed: the area becomes the output stage
-#pragma unroll
-  for (int i = 0; i < PAIRS; ++i) {
-    const int nt = (wave >> 1) + 2 * i;
-#pragma unroll
-    for (int e = 0; e < 16; ++e)
-      *reinterpret_cast<T*>(OUT + (mt * 32 + c3_acc_row(e, h)) * orow + (nt * 32 + r) * SZ) = from_float<T>(acc[i][e]);
-  }
-  __syncthreads();
-  T* din = static_cast<T*>(a.din) + (long long)j * H * H * CIN;
-  constexpr int cpr = CIN * SZ / 16;
-  for (int i = tid; i < 64 * cpr; i += 256) {
-    const int q = i / cpr, ch = i - q * cpr;
-    const int y = y0 + q / C3_TS, x = x0 + q % C3_TS;
-    if (y >= H || x >= H) continue;
-    *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(din + ((long long)y * H + x) * CIN) + ch * 16) =
-        *reinterpret_cast<const uint4*>(OUT + q * orow + ch * 16);
+    __syncthreads();
+    for (int i = tid; i < 64 * cpr; i += 256) {
+      const int q = i / cpr, ch = i - q * cpr;
+      const int y = y0 + q / C3_TS, x = x0 + q % C3_TS;
+      if (y >= H || x >= H) continue;
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(din + ((long long)y * H + x) * CIN) + ch * 16) =
+          *reinterpret_cast<const uint4*>(OUT + q * orow + ch * 16);
+    }
   }
 }
 
@@ -239,7 +277,7 @@ __global__ __launch_bounds__(256) void conv3_wgrad_kernel(Conv3Args a, float* __
   T* D = reinterpret_cast<T*>(lds);                                            // [100][4]
   unsigned char* PT = lds + ((C3_HALO * C3_HALO * C3_MAXCO * SZ + 15) & ~15);  // [MT * 32 rows (tap, co)][krow]
   unsigned char* IT = PT + MT * 32 * krow;                                     // [CIN][krow]: the feature tile, pixel fastest
-  float* red = reinterpret_cast<float*>(IT + CIN * krow);                      // [MT * 32][CIN] sums over the waves
+  float* red = reinterpret_cast<float*>(PT);                                   // [MT * 32][CIN] sums over the waves, over the operands at the end
   const int l = blockIdx.y, split = blockIdx.x;
   const int s0 = a.offs[l], cnt = a.offs[l + 1] - s0;
   if (cnt == 0) return;
@@ -261,44 +299,74 @@ __global__ __launch_bounds__(256) void conv3_wgrad_kernel(Conv3Args a, float* __
   constexpr int cpr = CIN * SZ / 16, EPV = 16 / SZ;
   constexpr int ksteps = 64 * SZ / 32, kpw = ksteps / 4;       // each wave takes a quarter of the patch's pixels
   static_assert(ksteps % 4 == 0, "pixels per wave");
-  for (int n = n_lo; n < n_hi; ++n) {
+  // The global loads of patch i + 1 (dout halo and feature tile, into registers) are issued before patch i is
+  // multiplied: with three barriers and little arithmetic per patch the loop is otherwise a chain of load latencies.
+  constexpr int ND = (C3_HALO * C3_HALO * C3_MAXCO + 255) / 256, NI = 64 * cpr / 256;
+  static_assert(64 * cpr % 256 == 0, "feature tile chunks per thread");
+  T dreg[ND];
+  uint4 ireg[NI];
+  const int per_sample = tiles * tiles, npatch = (n_hi - n_lo) * per_sample;
+  auto fetch = [&](int idx) {
+    const int n = n_lo + idx / per_sample, tile = idx % per_sample;
+    const int y0 = (tile / tiles) * C3_TS, x0 = (tile % tiles) * C3_TS;
     const T* in = static_cast<const T*>(a.in) + (long long)(s0 + n) * H * H * CIN;
     const T* dout = static_cast<const T*>(a.dout) + ((long long)a.out_seg * a.seg_samples + s0 + n) * H * H * CO;
-    for (int tile = 0; tile < tiles * tiles; ++tile) {
-      const int y0 = (tile / tiles) * C3_TS, x0 = (tile % tiles) * C3_TS;
-      __syncthreads();                                         // the previous patch has been multiplied
-      c3_load_dout<T>(a, dout, y0, x0, D);
-      // a wave takes one 16-byte channel group of all 64 pixels: its lanes then write 64 consecutive elements of a
-      // row of IT (rows a multiple of 16 bytes apart would all fall into one bank if a lane's neighbours held the
-      // other channel groups of the same pixel); the tile's lines come out of the L1 for the other groups
-      for (int i = tid; i < 64 * cpr; i += 256) {
-        const int ch = i >> 6, q = i & 63;
-        const int y = y0 + q / C3_TS, x = x0 + q % C3_TS;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (y < H && x < H) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(in + ((long long)y * H + x) * CIN) + ch * 16);
-        const T* e = reinterpret_cast<const T*>(&v);
 #pragma unroll
-        for (int k = 0; k < EPV; ++k) *reinterpret_cast<T*>(IT + (ch * EPV + k) * krow + q * SZ) = e[k];
-      }
-      __syncthreads();
-      for (int i = tid; i < 64 * 9; i += 256) {
-        const int tap = i >> 6, q = i & 63;
-        for (int co = 0; co < CO; ++co) *reinterpret_cast<T*>(PT + (tap * CO + co) * krow + q * SZ) = c3_patch_value<T>(D, q, tap, co);
-      }
-      __syncthreads();
+    for (int k = 0; k < ND; ++k) {
+      const int t = tid + 256 * k;
+      const int px = t >> 2, co = t & 3;
+      const int y = y0 - 1 + px / C3_HALO, x = x0 - 1 + px % C3_HALO;
+      dreg[k] = from_float<T>(0.f);
+      if (t < C3_HALO * C3_HALO * C3_MAXCO && co < CO && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)H)
+        dreg[k] = dout[((long long)y * H + x) * CO + co];
+    }
+    // a wave takes one 16-byte channel group of all 64 pixels: its lanes then write 64 consecutive elements of a
+    // row of IT (rows a multiple of 16 bytes apart would all fall into one bank if a lane's neighbours held the
+    // other channel groups of the same pixel); the tile's lines come out of the L1 for the other groups
 #pragma unroll
-      for (int k = 0; k < kpw; ++k) {
-        const int koff = (wave * kpw + k) * 32 + h * 16;
-        uint4 bv[NT];
+    for (int k = 0; k < NI; ++k) {
+      const int i = tid + 256 * k;
+      const int ch = i >> 6, q = i & 63;
+      const int y = y0 + q / C3_TS, x = x0 + q % C3_TS;
+      ireg[k] = make_uint4(0, 0, 0, 0);
+      if (y < H && x < H) ireg[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(in + ((long long)y * H + x) * CIN) + ch * 16);
+    }
+  };
+  if (npatch > 0) fetch(0);
+  for (int idx = 0; idx < npatch; ++idx) {
+    __syncthreads();                                           // the previous patch has been multiplied
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bv[nt] = *reinterpret_cast<const uint4*>(IT + (nt * 32 + r) * krow + koff);
+    for (int k = 0; k < ND; ++k) {
+      const int t = tid + 256 * k;
+      if (t < C3_HALO * C3_HALO * C3_MAXCO) D[t] = dreg[k];
+    }
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-          if (m < mtiles) {
-            const uint4 av = *reinterpret_cast<const uint4*>(PT + (m * 32 + r) * krow + koff);
+    for (int k = 0; k < NI; ++k) {
+      const int i = tid + 256 * k;
+      const int ch = i >> 6, q = i & 63;
+      const T* e = reinterpret_cast<const T*>(&ireg[k]);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) c3_mma(acc[m][nt], av, bv[nt], T());
-          }
+      for (int kk = 0; kk < EPV; ++kk) *reinterpret_cast<T*>(IT + (ch * EPV + kk) * krow + q * SZ) = e[kk];
+    }
+    if (idx + 1 < npatch) fetch(idx + 1);
+    __syncthreads();
+    for (int i = tid; i < 64 * 9; i += 256) {
+      const int tap = i >> 6, q = i & 63;
+      for (int co = 0; co < CO; ++co) *reinterpret_cast<T*>(PT + (tap * CO + co) * krow + q * SZ) = c3_patch_value<T>(D, q, tap, co);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kpw; ++k) {
+      const int koff = (wave * kpw + k) * 32 + h * 16;
+      uint4 bv[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bv[nt] = *reinterpret_cast<const uint4*>(IT + (nt * 32 + r) * krow + koff);
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        if (m < mtiles) {
+          const uint4 av = *reinterpret_cast<const uint4*>(PT + (m * 32 + r) * krow + koff);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) c3_mma(acc[m][nt], av, bv[nt], T());
         }
       }
     }
@@ -334,7 +402,7 @@ __global__ void conv3_wgrad_final_kernel(Conv3Args a, const float* __restrict__ 
   dw[(long long)l * dw_stride + e] = s;
 }
 // row splits per model of the weight gradient: enough blocks to fill the chip, a function of the model count only
-int conv3_wgrad_splits(int L) { return min(max((1024 + L - 1) / L, 1), C3_MAX_SPLITS); }
+int conv3_wgrad_splits(int L) { return min(max((2048 + L - 1) / L, 1), C3_MAX_SPLITS); }
 
 static bool conv3_ok(const Conv3Args& a) {
   return a.CO >= 1 && a.CO <= C3_MAXCO && (a.Cin == 64 || a.Cin == 128) && a.H >= 1 && a.H <= 64 && a.w && a.offs && a.sample_model;
@@ -346,20 +414,18 @@ template <typename K> static void c3_allow_lds(K kernel, size_t lds) {
 template <typename T> void launch_conv3_fwd(const Conv3Args& a, hipStream_t st) {
   if (a.n == 0) return;
   if (!conv3_ok(a) || !a.in || !a.out || !a.bias) return launch_fail("image-side k3 convolution: unsupported shape or null operand");
-  const int tiles = (a.H + C3_TS - 1) / C3_TS;
-  const size_t lds = (size_t)(C3_HALO * C3_HALO + 9 * a.CO) * (a.Cin * sizeof(T) + 16);
-  const dim3 grid(tiles * tiles, a.n);
+  const size_t lds = (size_t)(C3_HALO * C3_HALO + 9 * C3_MAXCO) * (a.Cin * sizeof(T) + 16) + (size_t)4 * 64 * C3_MAXCO * 4;
+  const dim3 grid(a.n);
   if (a.Cin == 64) { c3_allow_lds(&conv3_fwd_kernel<T, 64>, lds); hipLaunchKernelGGL((conv3_fwd_kernel<T, 64>), grid, dim3(256), lds, st, a); }
   else { c3_allow_lds(&conv3_fwd_kernel<T, 128>, lds); hipLaunchKernelGGL((conv3_fwd_kernel<T, 128>), grid, dim3(256), lds, st, a); }
 }
 template <typename T> void launch_conv3_dgrad(const Conv3Args& a, hipStream_t st) {
   if (a.n == 0) return;
   if (!conv3_ok(a) || !a.dout || !a.din) return launch_fail("image-side k3 convolution: unsupported shape or null operand");
-  const int tiles = (a.H + C3_TS - 1) / C3_TS;
   const int SZ = (int)sizeof(T);
   const size_t prow = (size_t)(9 * C3_MAXCO * SZ + 31) / 32 * 32 + 16;
-  const size_t lds = (size_t)((C3_HALO * C3_HALO * C3_MAXCO * SZ + 15) & ~15) + (64 + a.Cin) * prow;
-  const dim3 grid(tiles * tiles, a.n);
+  const size_t lds = (size_t)((C3_HALO * C3_HALO * C3_MAXCO * SZ + 15) & ~15) + (64 + a.Cin) * prow + (size_t)64 * (a.Cin * SZ + 16);
+  const dim3 grid(a.n);
   if (a.Cin == 64) { c3_allow_lds(&conv3_dgrad_kernel<T, 64>, lds); hipLaunchKernelGGL((conv3_dgrad_kernel<T, 64>), grid, dim3(256), lds, st, a); }
   else { c3_allow_lds(&conv3_dgrad_kernel<T, 128>, lds); hipLaunchKernelGGL((conv3_dgrad_kernel<T, 128>), grid, dim3(256), lds, st, a); }
 }
@@ -370,7 +436,7 @@ template <typename T> void launch_conv3_wgrad(const Conv3Args& a, float* part, f
   const int SZ = (int)sizeof(T);
   const size_t krow = (size_t)64 * SZ + 16;
   const int MT = (9 * C3_MAXCO + 31) / 32;
-  const size_t lds = (size_t)((C3_HALO * C3_HALO * C3_MAXCO * SZ + 15) & ~15) + (MT * 32 + a.Cin) * krow + (size_t)MT * 32 * a.Cin * 4;
+  const size_t lds = (size_t)((C3_HALO * C3_HALO * C3_MAXCO * SZ + 15) & ~15) + std::max((MT * 32 + a.Cin) * krow, (size_t)MT * 32 * a.Cin * 4);
   const dim3 grid(splits, a.L);
   if (a.Cin == 64) { c3_allow_lds(&conv3_wgrad_kernel<T, 64>, lds); hipLaunchKernelGGL((conv3_wgrad_kernel<T, 64>), grid, dim3(256), lds, st, a, part, splits); }
   else { c3_allow_lds(&conv3_wgrad_kernel<T, 128>, lds); hipLaunchKernelGGL((conv3_wgrad_kernel<T, 128>), grid, dim3(256), lds, st, a, part, splits); }
