@@ -36,6 +36,12 @@ SPECS = {
                     d_ch=[16, 32, 64, 128]),
     "paper16": dict(family="paper", cond_g=0, cond_d=0, z_dim=24, img_c=3, img_hw=16, g_h0=4, g_ch=[64, 128, 64],
                     d_ch=[16, 32, 72]),
+    # the same family at shapes that reach the other paths of its image-side kernels: one image channel, a side that
+    # is not a multiple of the 8-pixel patches, 128 feature channels in front of the image; and four image channels
+    "paper28": dict(family="paper", cond_g=0, cond_d=0, z_dim=16, img_c=1, img_hw=28, g_h0=7, g_ch=[128, 64, 128],
+                    d_ch=[16, 32]),
+    "paper16c4": dict(family="paper", cond_g=0, cond_d=0, z_dim=16, img_c=4, img_hw=16, g_h0=4, g_ch=[64, 64, 64],
+                      d_ch=[16, 32]),
 }
 
 # name -> (spec, n_models, n_labels, per-label batch, precision)

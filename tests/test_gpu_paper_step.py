@@ -159,3 +159,18 @@ def test_paper_networks_at_the_printed_widths(prec):
         p.step(*batch(p.spec, lab, 400 + s))
         p.compare("step %d" % s)
     p.close()
+
+
+@pytest.mark.parametrize("prec", [binding.FP32, binding.BF16])
+@pytest.mark.parametrize("spec_name", ["paper28", "paper16c4"])
+def test_paper_networks_other_image_shapes(prec, spec_name):
+    """One image channel on a 28 x 28 image behind 128 feature channels (patches that hang over the border, the wider
+    instantiation of the image-side kernels), and four image channels (two row tiles of (tap, channel) in the weight
+    gradient of the last convolution); two ragged models, two iterations."""
+    p = PaperPair(spec_name, 2, 24, prec)
+    rng = np.random.default_rng(3)
+    for s, n in enumerate([19, 24]):
+        lab = np.concatenate([np.arange(2), rng.integers(0, 2, n - 2)])
+        p.step(*batch(p.spec, lab, 500 + s))
+        p.compare("step %d" % s)
+    p.close()
