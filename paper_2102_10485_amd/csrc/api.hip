@@ -1360,7 +1360,7 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     ok = ok && dev_alloc(c, &c->colD, (size_t)2 * NB * c1.Hs * c1.Hs * c->KcD * es) &&
          dev_alloc(c, &c->colG, c->paper ? 16 : (size_t)NB * gl.Hs * gl.Hs * c->KcG * es) && dev_alloc(c, &c->wpD, (size_t)L * d1 * es) &&
          dev_alloc(c, &c->wpG, (size_t)L * g1 * es) && dev_alloc(c, (void**)&c->dwp, (size_t)c->img_ksplit * L * (d1 > g1 ? d1 : g1) * 4) &&
-         dev_alloc(c, (void**)&c->bias_partial, (size_t)L * IMG_BIAS_CHUNKS * 4 * 4);
+         dev_alloc(c, (void**)&c->bias_partial, (size_t)L * img_bias_chunks(L) * 4 * 4);
   }
   {
     // partial blocks of the weight gradients that are split over rows (few models only)

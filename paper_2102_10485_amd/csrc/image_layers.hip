@@ -14,6 +14,8 @@
 // gradient GEMM returns the class sums and the bias gradient with no extra pass over the feature tensor.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace gan {
@@ -88,10 +90,11 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
   const int j = blockIdx.x;
   if (j >= a.offs[a.L]) return;
   const int g8 = a.Kc >> 3;
+  const int nt = blockDim.x;                                      // a multiple of g8 (the launcher's choice), at most 256
   const int rps = a.Hs * a.Hs, Hb = 2 * a.Hs, CB = a.CB;
   const int npix = Hb * Hb, Hp = Hb + 2;
   // the border: rows 0 and Hp - 1, columns 0 and Hp - 1
-  for (int t = threadIdx.x; t < 4 * Hp * CB; t += 256) {
+  for (int t = threadIdx.x; t < 4 * Hp * CB; t += nt) {
     const int side = t / (Hp * CB), r = t - side * (Hp * CB);
     const int q = r / CB, cb = r - q * CB;
     const int py = side == 0 ? 0 : (side == 1 ? Hp - 1 : q), px = side < 2 ? q : (side == 2 ? 0 : Hp - 1);
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
   }
   if (a.img) {
     const T* img = static_cast<const T*>(a.img) + ((long long)a.seg * a.seg_samples + j) * npix * CB;
-    for (int t = threadIdx.x; t < npix * CB; t += 256) {
+    for (int t = threadIdx.x; t < npix * CB; t += nt) {
       const int pxl = t / CB, cb = t - pxl * CB;
       const int py = pxl / Hb, px = pxl - py * Hb;
       tile[((py + 1) * Hp + px + 1) * CB + cb] = img[t];
@@ -108,13 +111,13 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
     const float* real = a.real + (long long)a.perm[j] * CB * npix;     // NCHW fp32; npix is a multiple of 4
     const int nq = npix >> 2;
     if ((reinterpret_cast<uintptr_t>(a.real) & 15) != 0) {             // caller's buffer not 16-byte aligned: scalar loads
-      for (int t = threadIdx.x; t < npix * CB; t += 256) {
+      for (int t = threadIdx.x; t < npix * CB; t += nt) {
         const int cb = t / npix, pxl = t - cb * npix;
         const int py = pxl / Hb, px = pxl - py * Hb;
         tile[((py + 1) * Hp + px + 1) * CB + cb] = from_float<T>(real[t]);
       }
     } else
-    for (int t = threadIdx.x; t < CB * nq; t += 256) {
+    for (int t = threadIdx.x; t < CB * nq; t += nt) {
       const int cb = t / nq, pxl = 4 * (t - cb * nq);
       const float4 v = reinterpret_cast<const float4*>(real)[t];
       const float vv[4] = {v.x, v.y, v.z, v.w};
@@ -132,7 +135,7 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
   // position class: their 9 possible rows are written once, behind the image tile.
   const int gtap = ntap >> 3, gsp = g8 - gtap;     // groups of tap columns, of the others
   T* special = tile + Hp * Hp * CB + ((16 - ((Hp * Hp * CB * (int)sizeof(T)) & 15)) & 15) / (int)sizeof(T);   // 16-byte aligned; [9][gsp * 8]
-  for (int t = threadIdx.x; t < 9 * gsp * 8; t += 256) {
+  for (int t = threadIdx.x; t < 9 * gsp * 8; t += nt) {
     const int cls = t / (gsp * 8), q = t - cls * (gsp * 8);          // q: column - ntap
     float val = 0.f;
     if (a.nslot > 0) {
@@ -142,10 +145,10 @@ __global__ __launch_bounds__(256) void im2col_sample_kernel(Im2colArgs a) {
     special[t] = from_float<T>(val);
   }
   __syncthreads();
-  // A thread keeps its group of 8 columns (256 is a multiple of the groups per row: the launcher checks) and walks
-  // down the patch rows in steps of 256 / g8; the row's (y, x) is carried along instead of divided out, and the values
+  // A thread keeps its group of 8 columns (the block's thread count is a multiple of the groups per row) and walks
+  // down the patch rows in steps of threads / g8; the row's (y, x) is carried along instead of divided out, and the values
   // travel as stored (no conversion): the kernel is bound by its vector instructions otherwise.
-  const int g = (int)threadIdx.x % g8, pstep = 256 / g8;
+  const int g = (int)threadIdx.x % g8, pstep = nt / g8;
   int off[8];                                      // tap columns: element offset from the patch's corner
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -191,10 +194,11 @@ template <typename T> void launch_im2col(const Im2colArgs& a, hipStream_t st) {
   if (tot == 0) return;
   // the zero-bordered image tile, then (16-byte aligned) the 9 possible rows of the columns behind the taps
   const size_t lds = (size_t)(2 * a.Hs + 2) * (2 * a.Hs + 2) * a.CB * sizeof(T) + 16 + (size_t)9 * (a.Kc - 16 * a.CB) * sizeof(T);
-  if (lds <= 64 * 1024 && 256 % (a.Kc / 8) == 0 && a.Kc >= 16 * a.CB) {
+  const int g8 = a.Kc / 8;
+  if (lds <= 64 * 1024 && g8 >= 1 && g8 <= 256 && a.Kc >= 16 * a.CB) {
     if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&im2col_sample_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((im2col_sample_kernel<T>), dim3((unsigned)a.n), dim3(256), lds, st, a);
+    hipLaunchKernelGGL((im2col_sample_kernel<T>), dim3((unsigned)a.n), dim3((unsigned)(256 / g8 * g8)), lds, st, a);
     return;
   }
   hipLaunchKernelGGL((im2col_kernel<T>), dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
@@ -344,18 +348,30 @@ __global__ __launch_bounds__(256) void img_bias_partial_kernel(ImgBiasArgs a) {
     __syncthreads();
   }
 }
-__global__ void img_bias_final_kernel(ImgBiasArgs a, int chunks) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= a.L * a.CB) return;
-  const int l = idx / a.CB, cb = idx - l * a.CB;
+// one block per model: thread t adds the chunks t, t + 256, ... in turn, then a fixed tree over the threads
+__global__ __launch_bounds__(256) void img_bias_final_kernel(ImgBiasArgs a, int chunks) {
+  __shared__ float red[256];
+  const int l = blockIdx.x;
   if (a.offs[l + 1] == a.offs[l]) return;
-  float s = 0.f;
-  for (int k = 0; k < chunks; ++k) s += a.partial[((long long)l * chunks + k) * 4 + cb];
-  a.dbias[(long long)l * a.pstride + cb] = s;
+  for (int cb = 0; cb < a.CB; ++cb) {
+    float s = 0.f;
+    for (int k = threadIdx.x; k < chunks; k += 256) s += a.partial[((long long)l * chunks + k) * 4 + cb];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+      if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) a.dbias[(long long)l * a.pstride + cb] = red[0];
+    __syncthreads();
+  }
 }
+// chunks of a model's pixels: enough blocks to fill the chip with few models; a function of the model count only
+int img_bias_chunks(int L) { return std::min(std::max(2048 / (L > 0 ? L : 1), 32), 256); }
 template <typename T> void launch_img_bias_grad(const ImgBiasArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((img_bias_partial_kernel<T>), dim3(IMG_BIAS_CHUNKS, a.L), dim3(256), 0, st, a);
-  hipLaunchKernelGGL(img_bias_final_kernel, dim3((a.L * a.CB + 255) / 256), dim3(256), 0, st, a, IMG_BIAS_CHUNKS);
+  const int chunks = img_bias_chunks(a.L);
+  hipLaunchKernelGGL((img_bias_partial_kernel<T>), dim3(chunks, a.L), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(img_bias_final_kernel, dim3(a.L), dim3(256), 0, st, a, chunks);
 }
 template void launch_img_bias_grad<float>(const ImgBiasArgs&, hipStream_t);
 template void launch_img_bias_grad<bf16_t>(const ImgBiasArgs&, hipStream_t);

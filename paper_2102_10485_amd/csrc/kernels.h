@@ -123,10 +123,10 @@ struct UpImgArgs {
 };
 template <typename T> void launch_up_img(const UpImgArgs& a, hipStream_t st);
 
-constexpr int IMG_BIAS_CHUNKS = 32;
+int img_bias_chunks(int L);          // pixel chunks per model of the image-side bias gradient
 struct ImgBiasArgs {
   const void* img;          // [pixels][CB] of segment 0
-  float* partial;           // [L][IMG_BIAS_CHUNKS][4]
+  float* partial;           // [L][img_bias_chunks(L)][4]
   float* dbias;             // model 0, stride pstride
   long long pstride;
   const int* offs;

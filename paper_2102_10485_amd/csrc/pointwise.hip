@@ -280,21 +280,26 @@ __device__ inline void storev(bf16_t* p, const float (&v)[8]) {
 // A block = 16 channels x RED_SLICES slices of the (phase, tile) sequence of one (segment, model): every thread
 // merges its contiguous slice in order, then the slices are merged in order.  The slicing depends on the model's own
 // tile count only.
-constexpr int RED_SLICES = 16;
+constexpr int RED_SLICES = 16;      // slices of the backward reduction's second stage
+// Threads of a block = SL slices x CX channels.  16 x 16 as a rule; 64 x 4 when a model has so many tiles (one pair
+// over the whole batch) that sixteen chains of dependent merges would be the whole kernel.  The choice follows from
+// the configuration (tile bound per model), never from a batch.
+template <int SL, int CX>
 __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict__ partial,
                                                                     const int* __restrict__ tpre, int ub_tiles, int nphase,
                                                                     int groups, int tile_rows, int gemm_rps) {
-  __shared__ float sh[RED_SLICES][16][3];
-  const int cx = threadIdx.x & 15, sl = threadIdx.x >> 4;
-  const int cblocks = (a.C + 15) / 16;
-  const int c = (blockIdx.x % cblocks) * 16 + cx;
+  static_assert(SL * CX == 256, "block shape");
+  __shared__ float sh[SL][CX][3];
+  const int cx = threadIdx.x % CX, sl = threadIdx.x / CX;
+  const int cblocks = (a.C + CX - 1) / CX;
+  const int c = (blockIdx.x % cblocks) * CX + cx;
   const int l = (blockIdx.x / cblocks) % a.L;
   const int sidx = blockIdx.x / (cblocks * a.L);
   const int cnt = a.offs[l + 1] - a.offs[l];
   if (cnt == 0) return;                                // block-uniform
   const int rows = cnt * gemm_rps;                     // rows of this model in the GEMM's row space (per phase)
   const int t0 = tpre[l], ntiles = tpre[l + 1] - t0;
-  const int seq = nphase * ntiles, per = (seq + RED_SLICES - 1) / RED_SLICES;
+  const int seq = nphase * ntiles, per = (seq + SL - 1) / SL;
   float n = 0.f, mean = 0.f, m2 = 0.f;
   if (c < a.C)
 #pragma unroll 4
@@ -313,7 +318,7 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
   sh[sl][cx][0] = n; sh[sl][cx][1] = mean; sh[sl][cx][2] = m2;
   __syncthreads();
   if (sl != 0 || c >= a.C) return;
-  for (int k = 1; k < RED_SLICES; ++k) {
+  for (int k = 1; k < SL; ++k) {
     const float nt = sh[k][cx][0];
     if (nt == 0.f) continue;                           // an empty slice
     const float d = sh[k][cx][1] - mean;
@@ -330,11 +335,18 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
 }
 void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
                                   int groups, int tile_rows, int gemm_rps, hipStream_t st) {
-  const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
-  if (tot == 0) return;
+  if ((long long)a.nseg * a.L * a.C == 0) return;
   if (!tpre || !partial) return launch_fail("BatchNorm statistics: no tile prefix array or no partial sums");
-  hipLaunchKernelGGL(bn_stats_from_partial_kernel, dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
-                     groups, tile_rows, gemm_rps);
+  const bool many = (long long)ub_tiles * nphase * groups > 512LL * a.L;       // tiles per model, by the launch's upper bound
+  if (many) {
+    const long long tot = (long long)a.nseg * a.L * ((a.C + 3) / 4);
+    hipLaunchKernelGGL((bn_stats_from_partial_kernel<64, 4>), dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
+                       groups, tile_rows, gemm_rps);
+  } else {
+    const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
+    hipLaunchKernelGGL((bn_stats_from_partial_kernel<16, 16>), dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
+                       groups, tile_rows, gemm_rps);
+  }
 }
 
 // running <- (1 - momentum) running + momentum * batch, once per segment in order; unbiased variance stored.
@@ -525,7 +537,8 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_final_kernel(NormArgs a, co
   const int per = (ntiles + RED_SLICES - 1) / RED_SLICES;
   float s0 = 0.f, s1 = 0.f;
   if (c < a.C)
-    for (int t = t0 + sl * per; t < t0 + min(ntiles, (sl + 1) * per); ++t) {
+#pragma unroll 8
+    for (int t = t0 + sl * per; t < t0 + min(ntiles, (sl + 1) * per); ++t) {     // (eight tiles' loads in flight, added in order)
       const long long o = (((long long)sidx * ub_tiles + t) * a.C + c) * 2;
       s0 += partial[o];
       s1 += partial[o + 1];
