@@ -2,15 +2,16 @@
 // channels onto the 1-4 image channels, + bias, tanh -- and its two gradients.  With so few output channels the layer
 // does not fit the grouped GEMM engine's tiles, but it is still a contraction, and direct loops over it were bound by
 // their vector instructions (4.9 ms of a 15.7 ms step).  Three small MFMA kernels on 8 x 8 pixel patches:
-//   forward : rows = the patch's 64 pixels, columns = the image channels (CO of the tile's 32), K = (neighbour of the
-//             3 x 3 window, feature channel); the patch with its one-pixel halo sits in LDS, the four waves share the
-//             feature channels and add their partial sums through LDS.
+//   forward : R[halo pixel][(tap, co)] = sum_ci F[halo pixel][ci] w[tap][co][ci] for the patch with its one-pixel halo
+//             (rows = the 100 halo pixels, 32 per wave; columns = the 9 CO pairs; K = the feature channels), then every
+//             output pixel adds the nine entries its neighbours hold for it.
 //   dgrad   : din[p][ci] = sum_{tap, co} P[p][(tap, co)] * w[tap][co][ci] with P[p][(ky, kx, co)] =
 //             dout[p - (ky - 1, kx - 1)][co]: rows = pixels, K = 9 CO (padded to whole MFMA steps), columns = Cin.
-//   wgrad   : dw[(tap, co)][ci] = sum_p P[p][(tap, co)] * in[p][ci]: K = pixels, so both operands are laid out in LDS
-//             with the pixel index fastest (P is built that way, the feature tile is transposed while it is written);
-//             a block walks the patches of its share of a model's samples, each wave taking a quarter of every
-//             patch's pixels, and the waves' sums are added in order at the end.
+//   wgrad   : dw[(tap, co)][ci] = sum_p P[p][(tap, co)] * in[p][ci]: K = pixels, the slow index of both operands in
+//             memory.  bf16: the feature tile goes to LDS as it is and the transposing LDS read delivers it pixel-fastest,
+//             P is read element by element out of the dout halo tile.  fp32 (no 32-bit transposing read): both operands
+//             are written to LDS pixel-fastest.  A block walks the patches of its share of a model's samples, each wave
+//             taking a quarter of every patch's pixels, and the waves' sums are added in order at the end.
 // Storage type T on the MFMA inputs (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32), fp32 sums; the
 // fp32 master weights are rounded to T on their way into LDS, as every other layer's weights are in their storage copy.
 #include <hip/hip_runtime.h>

@@ -12,66 +12,93 @@ namespace gan {
 
 __device__ inline int model_of_label(int y, int L) { return L == 1 ? 0 : y; }
 
-__global__ void route_count_kernel(const int* __restrict__ label_ids, int n, int L, int n_labels, int* cnt, int* flags) {
+// One block of ROUTE_CHUNKS threads does the whole partition: thread t owns the t-th run of consecutive samples.
+//   1. per-(chunk, model) counts;  2. per model, the exclusive scan over the chunks (a chunk's samples of a model follow
+//   those of the chunks before it: stable) and the model's total;  3. model offsets, the tile prefix of every geometry
+//   and the models' order by size, each a short serial loop on its own thread(s);  4. the scatter.
+// The count table lives in LDS when it fits (256 x L ints), the totals and offsets when L <= ROUTE_LDS_MODELS; otherwise
+// they are the global arrays, which one block may use the same way (barriers order its own global accesses).
+// Labels are loaded eight at a time so that their latencies overlap.
+constexpr int ROUTE_LDS_MODELS = 4096;
+constexpr int ROUTE_LDS_CNT_BYTES = 128 * 1024;
+__global__ __launch_bounds__(ROUTE_CHUNKS) void route_kernel(const int* __restrict__ label_ids, int n, int L, int n_labels,
+                                                              GeomTable geoms, RouteBuffers rb, int cnt_in_lds, int small) {
+  extern __shared__ int route_lds[];
   const int t = threadIdx.x;
+  int* cl = small ? route_lds : rb.counts;                     // [L]
+  int* ol = small ? route_lds + L : rb.offs;                   // [L + 1]
+  int* cnt = cnt_in_lds ? route_lds + (2 * L + 1) : rb.cnt;    // [ROUTE_CHUNKS][L]
+  for (int i = t; i < ROUTE_CHUNKS * L; i += ROUTE_CHUNKS) cnt[i] = 0;
+  __syncthreads();
   int* row = cnt + (long long)t * L;
-  for (int l = 0; l < L; ++l) row[l] = 0;
   const int chunk = (n + ROUTE_CHUNKS - 1) / ROUTE_CHUNKS;
-  const int i0 = t * chunk, i1 = min(n, i0 + chunk);
+  const int i0 = min(n, t * chunk), i1 = min(n, i0 + chunk);
   bool bad = false;
-  for (int i = i0; i < i1; ++i) {
-    const int y = label_ids[i];
-    if (y < 0 || y >= n_labels) { bad = true; continue; }
-    row[model_of_label(y, L)] += 1;
+  for (int i = i0; i < i1; i += 8) {
+    int ys[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ys[k] = i + k < i1 ? label_ids[i + k] : -1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (i + k >= i1) continue;
+      if (ys[k] < 0 || ys[k] >= n_labels) { bad = true; continue; }
+      row[model_of_label(ys[k], L)] += 1;
+    }
   }
-  if (bad) flags[0] = 1;
-}
-
-__global__ void route_scan_chunks_kernel(int* cnt, int* counts, int L) {
-  const int l = blockIdx.x * blockDim.x + threadIdx.x;
-  if (l >= L) return;
-  int run = 0;
-  for (int t = 0; t < ROUTE_CHUNKS; ++t) {
-    const int c = cnt[(long long)t * L + l];
-    cnt[(long long)t * L + l] = run;
-    run += c;
+  if (bad) rb.flags[0] = 1;
+  __syncthreads();
+  for (int l = t; l < L; l += ROUTE_CHUNKS) {
+    int run = 0;
+    for (int c = 0; c < ROUTE_CHUNKS; ++c) {
+      const int v = cnt[(long long)c * L + l];
+      cnt[(long long)c * L + l] = run;
+      run += v;
+    }
+    cl[l] = run;
+    rb.counts[l] = run;
   }
-  counts[l] = run;
-}
-
-__global__ void route_offsets_kernel(const int* counts, int* offs, int* tpre, int L, GeomTable geoms) {
-  const int t = threadIdx.x;
+  __syncthreads();
   if (t == 0) {
     int run = 0;
-    for (int l = 0; l < L; ++l) { offs[l] = run; run += counts[l]; }
-    offs[L] = run;
+    for (int l = 0; l < L; ++l) { ol[l] = run; rb.offs[l] = run; run += cl[l]; }
+    ol[L] = run;
+    rb.offs[L] = run;
   } else if (t - 1 < geoms.n) {
     const int g = t - 1;
-    int* tp = tpre + (long long)g * (L + 1);
+    int* tp = rb.tpre + (long long)g * (L + 1);
     int run = 0;
     for (int l = 0; l < L; ++l) {
       tp[l] = run;
-      run += (counts[l] * geoms.rps[g] + geoms.tile_rows[g] - 1) / geoms.tile_rows[g];
+      run += (cl[l] * geoms.rps[g] + geoms.tile_rows[g] - 1) / geoms.tile_rows[g];
     }
     tp[L] = run;
+  } else if (t >= 64 && rb.order) {
+    // order[rank of l] = l, rank = number of models with more samples, or as many and a smaller index
+    for (int l = t - 64; l < L; l += ROUTE_CHUNKS - 64) {
+      const int c = cl[l];
+      int rank = 0;
+      for (int j = 0; j < L; ++j) {
+        const int cj = cl[j];
+        rank += (cj > c || (cj == c && j < l)) ? 1 : 0;
+      }
+      rb.order[rank] = l;
+    }
   }
-}
-
-__global__ void route_scatter_kernel(const int* __restrict__ label_ids, int n, int L, int n_labels, int* cnt,
-                                     const int* offs, int* perm, int* sample_model, int* sample_slot) {
-  const int t = threadIdx.x;
-  int* row = cnt + (long long)t * L;
-  const int chunk = (n + ROUTE_CHUNKS - 1) / ROUTE_CHUNKS;
-  const int i0 = t * chunk, i1 = min(n, i0 + chunk);
-  for (int i = i0; i < i1; ++i) {
-    const int y = label_ids[i];
-    if (y < 0 || y >= n_labels) continue;
-    const int mdl = model_of_label(y, L);
-    const int pos = offs[mdl] + row[mdl];
-    row[mdl] += 1;
-    perm[pos] = i;
-    sample_model[pos] = mdl;
-    sample_slot[pos] = (L == 1) ? y : 0;
+  __syncthreads();
+  for (int i = i0; i < i1; i += 8) {
+    int ys[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ys[k] = i + k < i1 ? label_ids[i + k] : -1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (i + k >= i1 || ys[k] < 0 || ys[k] >= n_labels) continue;
+      const int mdl = model_of_label(ys[k], L);
+      const int pos = ol[mdl] + row[mdl];
+      row[mdl] += 1;
+      rb.perm[pos] = i + k;
+      rb.sample_model[pos] = mdl;
+      rb.sample_slot[pos] = (L == 1) ? ys[k] : 0;
+    }
   }
 }
 
@@ -115,27 +142,15 @@ void launch_tile_models(const int* tpre, int L, int* tmodel, int cap, hipStream_
   hipLaunchKernelGGL(tile_model_kernel, dim3((cap + 255) / 256, 1), dim3(256), 0, st, tpre, L, tmodel, cap);
 }
 
-// order[rank of l] = l, rank = number of models with more samples, or as many and a smaller index
-__global__ void model_order_kernel(const int* __restrict__ counts, int L, int* __restrict__ order) {
-  const int l = blockIdx.x * blockDim.x + threadIdx.x;
-  if (l >= L) return;
-  const int c = counts[l];
-  int rank = 0;
-  for (int j = 0; j < L; ++j) {
-    const int cj = counts[j];
-    rank += (cj > c || (cj == c && j < l)) ? 1 : 0;
-  }
-  order[rank] = l;
-}
-
 void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTable& geoms, const RouteBuffers& rb,
                   hipStream_t st) {
-  hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.flags);
-  hipLaunchKernelGGL(route_scan_chunks_kernel, dim3((L + 255) / 256), dim3(256), 0, st, rb.cnt, rb.counts, L);
-  hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(64), 0, st, rb.counts, rb.offs, rb.tpre, L, geoms);
-  hipLaunchKernelGGL(route_scatter_kernel, dim3(1), dim3(ROUTE_CHUNKS), 0, st, label_ids, n, L, n_labels, rb.cnt, rb.offs,
-                     rb.perm, rb.sample_model, rb.sample_slot);
-  if (rb.order) hipLaunchKernelGGL(model_order_kernel, dim3((L + 255) / 256), dim3(256), 0, st, rb.counts, L, rb.order);
+  if (geoms.n > 62) return launch_fail("routing: more tile geometries than the kernel has threads for");
+  const int small = L <= ROUTE_LDS_MODELS ? 1 : 0;
+  const int cnt_in_lds = small && (size_t)ROUTE_CHUNKS * L * 4 <= (size_t)ROUTE_LDS_CNT_BYTES ? 1 : 0;
+  const size_t lds = (small ? (size_t)(2 * L + 1) * 4 : 0) + (cnt_in_lds ? (size_t)ROUTE_CHUNKS * L * 4 : 0);
+  if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&route_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_CHUNKS), lds, st, label_ids, n, L, n_labels, geoms, rb, cnt_in_lds, small);
   if (rb.tmodel && geoms.n > 0)
     hipLaunchKernelGGL(tile_model_kernel, dim3((rb.tmodel_stride + 255) / 256, geoms.n), dim3(256), 0, st, rb.tpre, L, rb.tmodel,
                        rb.tmodel_stride);
