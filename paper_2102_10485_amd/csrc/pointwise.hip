@@ -16,18 +16,36 @@ __device__ inline int model_of_label(int y, int L) { return L == 1 ? 0 : y; }
 //   1. per-(chunk, model) counts;  2. per model, the exclusive scan over the chunks (a chunk's samples of a model follow
 //   those of the chunks before it: stable) and the model's total;  3. model offsets, the tile prefix of every geometry
 //   and the models' order by size, each a short serial loop on its own thread(s);  4. the scatter.
-// The count table lives in LDS when it fits (256 x L ints), the totals and offsets when L <= ROUTE_LDS_MODELS; otherwise
-// they are the global arrays, which one block may use the same way (barriers order its own global accesses).
-// Labels are loaded eight at a time so that their latencies overlap.
+// The count table lives in LDS when it fits (256 x L ints), the totals and offsets when L <= ROUTE_LDS_MODELS, the
+// labels (fetched once, coalesced) when there is room left; otherwise they are the global arrays, which one block may
+// use the same way (barriers order its own global accesses).  Every serial loop reads sixteen (labels: eight) values
+// ahead of using them: the loops are chains of memory latencies otherwise, because a load may not pass the store in
+// front of it.
 constexpr int ROUTE_LDS_MODELS = 4096;
-constexpr int ROUTE_LDS_CNT_BYTES = 128 * 1024;
+constexpr int ROUTE_LDS_CNT_BYTES = 112 * 1024;
+constexpr int ROUTE_LDS_BYTES = 152 * 1024;
+// (the three placements are template parameters so that every access is known to be an LDS or a global one: through
+// pointers that may be either, each LDS access took several times as long)
+template <bool small, bool cnt_in_lds, bool lab_in_lds>
 __global__ __launch_bounds__(ROUTE_CHUNKS) void route_kernel(const int* __restrict__ label_ids, int n, int L, int n_labels,
-                                                              GeomTable geoms, RouteBuffers rb, int cnt_in_lds, int small) {
+                                                              GeomTable geoms, RouteBuffers rb) {
   extern __shared__ int route_lds[];
+  static_assert(small || !cnt_in_lds, "the count table is in LDS only together with the totals");
   const int t = threadIdx.x;
   int* cl = small ? route_lds : rb.counts;                     // [L]
   int* ol = small ? route_lds + L : rb.offs;                   // [L + 1]
   int* cnt = cnt_in_lds ? route_lds + (2 * L + 1) : rb.cnt;    // [ROUTE_CHUNKS][L]
+  int* labl = route_lds + (small ? 2 * L + 1 : 0) + (cnt_in_lds ? ROUTE_CHUNKS * L : 0);   // [n]
+  const int* lab = lab_in_lds ? labl : label_ids;
+  if (lab_in_lds)
+    for (int i = t; i < n; i += 8 * ROUTE_CHUNKS) {
+      int ys[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ys[k] = i + k * ROUTE_CHUNKS < n ? label_ids[i + k * ROUTE_CHUNKS] : 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (i + k * ROUTE_CHUNKS < n) labl[i + k * ROUTE_CHUNKS] = ys[k];
+    }
   for (int i = t; i < ROUTE_CHUNKS * L; i += ROUTE_CHUNKS) cnt[i] = 0;
   __syncthreads();
   int* row = cnt + (long long)t * L;
@@ -37,7 +55,7 @@ __global__ __launch_bounds__(ROUTE_CHUNKS) void route_kernel(const int* __restri
   for (int i = i0; i < i1; i += 8) {
     int ys[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) ys[k] = i + k < i1 ? label_ids[i + k] : -1;
+    for (int k = 0; k < 8; ++k) ys[k] = i + k < i1 ? lab[i + k] : -1;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       if (i + k >= i1) continue;
@@ -49,29 +67,48 @@ __global__ __launch_bounds__(ROUTE_CHUNKS) void route_kernel(const int* __restri
   __syncthreads();
   for (int l = t; l < L; l += ROUTE_CHUNKS) {
     int run = 0;
-    for (int c = 0; c < ROUTE_CHUNKS; ++c) {
-      const int v = cnt[(long long)c * L + l];
-      cnt[(long long)c * L + l] = run;
-      run += v;
+    for (int c0 = 0; c0 < ROUTE_CHUNKS; c0 += 16) {
+      int v[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) v[k] = cnt[(long long)(c0 + k) * L + l];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        cnt[(long long)(c0 + k) * L + l] = run;
+        run += v[k];
+      }
     }
     cl[l] = run;
     rb.counts[l] = run;
   }
   __syncthreads();
-  if (t == 0) {
-    int run = 0;
-    for (int l = 0; l < L; ++l) { ol[l] = run; rb.offs[l] = run; run += cl[l]; }
-    ol[L] = run;
-    rb.offs[L] = run;
-  } else if (t - 1 < geoms.n) {
+  if (t <= geoms.n && t < 64) {
+    // t == 0: the model offsets; t - 1 = g: the tile prefix of geometry g
     const int g = t - 1;
-    int* tp = rb.tpre + (long long)g * (L + 1);
+    const int rps = t == 0 ? 1 : geoms.rps[g], tr = t == 0 ? 1 : geoms.tile_rows[g];
+    int* dst = t == 0 ? rb.offs : rb.tpre + (long long)g * (L + 1);
+    // tile heights are powers of two: a shift, not a division per model (two loops, so that the division is not
+    // computed and thrown away)
+    const int sh = (tr & (tr - 1)) == 0 ? __ffs(tr) - 1 : -1;
     int run = 0;
-    for (int l = 0; l < L; ++l) {
-      tp[l] = run;
-      run += (cl[l] * geoms.rps[g] + geoms.tile_rows[g] - 1) / geoms.tile_rows[g];
-    }
-    tp[L] = run;
+    auto prefix = [&](auto tiles_of) {
+      for (int l0 = 0; l0 < L; l0 += 16) {
+        int v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = l0 + k < L ? cl[l0 + k] : 0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          if (l0 + k >= L) continue;
+          dst[l0 + k] = run;
+          if (t == 0) ol[l0 + k] = run;
+          run += tiles_of(v[k]);
+        }
+      }
+    };
+    if (t == 0) prefix([](int c) { return c; });
+    else if (sh >= 0) prefix([=](int c) { return (c * rps + tr - 1) >> sh; });
+    else prefix([=](int c) { return (c * rps + tr - 1) / tr; });
+    dst[L] = run;
+    if (t == 0) ol[L] = run;
   } else if (t >= 64 && rb.order) {
     // order[rank of l] = l, rank = number of models with more samples, or as many and a smaller index
     for (int l = t - 64; l < L; l += ROUTE_CHUNKS - 64) {
@@ -88,7 +125,7 @@ __global__ __launch_bounds__(ROUTE_CHUNKS) void route_kernel(const int* __restri
   for (int i = i0; i < i1; i += 8) {
     int ys[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) ys[k] = i + k < i1 ? label_ids[i + k] : -1;
+    for (int k = 0; k < 8; ++k) ys[k] = i + k < i1 ? lab[i + k] : -1;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       if (i + k >= i1 || ys[k] < 0 || ys[k] >= n_labels) continue;
@@ -147,10 +184,17 @@ void launch_route(const int* label_ids, int n, int L, int n_labels, const GeomTa
   if (geoms.n > 62) return launch_fail("routing: more tile geometries than the kernel has threads for");
   const int small = L <= ROUTE_LDS_MODELS ? 1 : 0;
   const int cnt_in_lds = small && (size_t)ROUTE_CHUNKS * L * 4 <= (size_t)ROUTE_LDS_CNT_BYTES ? 1 : 0;
-  const size_t lds = (small ? (size_t)(2 * L + 1) * 4 : 0) + (cnt_in_lds ? (size_t)ROUTE_CHUNKS * L * 4 : 0);
-  if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&route_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_CHUNKS), lds, st, label_ids, n, L, n_labels, geoms, rb, cnt_in_lds, small);
+  size_t lds = (small ? (size_t)(2 * L + 1) * 4 : 0) + (cnt_in_lds ? (size_t)ROUTE_CHUNKS * L * 4 : 0);
+  const int lab_in_lds = lds + (size_t)n * 4 <= (size_t)ROUTE_LDS_BYTES ? 1 : 0;
+  if (lab_in_lds) lds += (size_t)n * 4;
+  auto go = [&](auto kernel) {
+    if (lds > 48 * 1024)   // above the default dynamic limit: ask for it (idempotent, cheap)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kernel, dim3(1), dim3(ROUTE_CHUNKS), lds, st, label_ids, n, L, n_labels, geoms, rb);
+  };
+  if (cnt_in_lds) { if (lab_in_lds) go(&route_kernel<true, true, true>); else go(&route_kernel<true, true, false>); }
+  else if (small) { if (lab_in_lds) go(&route_kernel<true, false, true>); else go(&route_kernel<true, false, false>); }
+  else { if (lab_in_lds) go(&route_kernel<false, false, true>); else go(&route_kernel<false, false, false>); }
   if (rb.tmodel && geoms.n > 0)
     hipLaunchKernelGGL(tile_model_kernel, dim3((rb.tmodel_stride + 255) / 256, geoms.n), dim3(256), 0, st, rb.tpre, L, rb.tmodel,
                        rb.tmodel_stride);
@@ -675,7 +719,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a) {
   const T* f = static_cast<const T*>(a.feat) + r * a.K;
   const float* w = a.w + (long long)l * a.pstride;
   float acc = 0.f;
-  for (int k = lane * 4; k < a.K; k += 256) {
+#pragma unroll 8
+  for (int k = lane * 4; k < a.K; k += 256) {     // (eight steps' loads in flight, added in order)
     float v[4];
     load4(f + k, v);
     const float4 ww = *reinterpret_cast<const float4*>(w + k);
@@ -775,7 +820,8 @@ __global__ __launch_bounds__(256) void head_bwd_w_kernel(HeadArgs a) {
   float acc[4] = {0, 0, 0, 0}, accb = 0.f;
   for (int s = 0; s < a.nseg; ++s) {
     const long long r0 = (long long)(a.seg_first + s) * a.seg_samples + s0;
-    for (int i = i0; i < i1; ++i) {
+#pragma unroll 8
+    for (int i = i0; i < i1; ++i) {               // (eight rows' loads in flight, added in order)
       const float d = a.dlogits[r0 + i];
       accb += d;
       if (k < a.K) {
