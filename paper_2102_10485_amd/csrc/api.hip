@@ -648,9 +648,10 @@ void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running
     launch_bn_from_running(a, c->st);
   } else {
     const int tr = layer_tile_rows(c, a.C * col_groups, gemm_rps);     // the tile height of the GEMM that left the partials (N = C * col_groups)
+    a.fold_running = update_running && a.nseg == 1 && a.run_mean && a.run_var;
     launch_bn_stats_from_partial(a, c->stat_partial, tpre_of(c, gemm_rps, tr), ub_tiles(c, a.n, gemm_rps, tr), gemm_phases, col_groups, tr,
                                  gemm_rps, c->st);
-    if (update_running) launch_bn_running(a, c->st);
+    if (update_running && !a.fold_running) launch_bn_running(a, c->st);
   }
   Scope s(c, "bn_apply", 0, 2 * elems * sizeof(T));
   launch_bn_apply<T>(a, c->st);
@@ -660,13 +661,14 @@ void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running
 template <typename T>
 void bn_backward(gan_ctx* c, NormArgs a, const void* x, const void* dy, void* dx, bool param_grads) {
   a.x = x; a.dy = dy; a.y = dx;
+  a.fold_grads = param_grads && a.nseg == 1;
   const double elems = (double)a.n * a.nseg * a.rps * a.C;
   {
     Scope s(c, "bn_bwd_reduce", 0, 2 * elems * sizeof(T));
     launch_bn_bwd_reduce<T>(a, tpre_of(c, a.rps, BN_RED_ROWS), tmodel_of(c, a.rps, BN_RED_ROWS), ub_tiles(c, a.n, a.rps, BN_RED_ROWS),
                             c->stat_partial, c->st);
   }
-  if (param_grads) launch_bn_param_grad(a, c->st);
+  if (param_grads && !a.fold_grads) launch_bn_param_grad(a, c->st);
   Scope s(c, "bn_bwd_apply", 0, 3 * elems * sizeof(T));
   launch_bn_bwd_apply<T>(a, c->st);
 }

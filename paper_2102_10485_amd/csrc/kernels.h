@@ -66,6 +66,8 @@ struct NormArgs {
   int n;                    // samples per segment passed by the caller (upper bound of offs[L])
   int act;                  // ACT_RELU / ACT_LRELU
   float slope, eps, momentum;
+  int fold_running;         // statistics from the GEMM's partials, one segment: that kernel also updates the running statistics
+  int fold_grads;           // backward reduction, one segment: its last stage also writes dgamma / dbeta
 };
 // statistics from the per-tile column sums a GEMM left behind (stat_partial of ConvArgs)
 void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,

@@ -391,6 +391,12 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
   a.mean[o] = mean;
   a.var[o] = var;
   a.rstd[o] = 1.0f / sqrtf(var + a.eps);
+  if (a.fold_running) {     // one segment: what bn_running_kernel would do next, without the launch
+    const long long S = (long long)cnt * a.rps;
+    const long long ro = (long long)l * a.rstride + c;
+    a.run_mean[ro] = (1.f - a.momentum) * a.run_mean[ro] + a.momentum * mean;
+    if (S > 1) a.run_var[ro] = (1.f - a.momentum) * a.run_var[ro] + a.momentum * var * ((float)S / (float)(S - 1));
+  }
 }
 void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
                                   int groups, int tile_rows, int gemm_rps, hipStream_t st) {
@@ -609,6 +615,10 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_final_kernel(NormArgs a, co
   const long long o = ((long long)((a.seg_first + sidx) * a.L + l) * a.C + c) * 2;
   a.sums[o] = s0;
   a.sums[o + 1] = s1;
+  if (a.fold_grads) {       // one segment: what bn_param_grad_kernel would do next, without the launch
+    a.dbeta[(long long)l * a.pstride + c] = 0.f + s0;
+    a.dgamma[(long long)l * a.pstride + c] = 0.f + s1;
+  }
 }
 template <typename T>
 void launch_bn_bwd_reduce(const NormArgs& a, const int* tpre, const int* tmodel, int ub_tiles, float* partial, hipStream_t st) {
