@@ -650,7 +650,7 @@ void bn_forward(gan_ctx* c, NormArgs a, const void* x, void* y, bool use_running
     const int tr = layer_tile_rows(c, a.C * col_groups, gemm_rps);     // the tile height of the GEMM that left the partials (N = C * col_groups)
     a.fold_running = update_running && a.nseg == 1 && a.run_mean && a.run_var;
     launch_bn_stats_from_partial(a, c->stat_partial, tpre_of(c, gemm_rps, tr), ub_tiles(c, a.n, gemm_rps, tr), gemm_phases, col_groups, tr,
-                                 gemm_rps, c->st);
+                                 gemm_rps, conv_stat_split(a.C * col_groups, tr), c->st);
     if (update_running && !a.fold_running) launch_bn_running(a, c->st);
   }
   Scope s(c, "bn_apply", 0, 2 * elems * sizeof(T));
@@ -1320,16 +1320,16 @@ gan_status gan_create(const gan_config* cfg, void* hip_stream, gan_ctx** out) {
     }
   }
   {
-    // per-tile column sums left by the GEMM in front of every BatchNorm: phases x segments x tiles x columns x 2
-    size_t mx = (size_t)ub_tiles(c, NB, 1, layer_tile_rows(c, c->G.J, 1)) * c->G.J;
+    // column sums left by the GEMM in front of every BatchNorm: phases x segments x tiles x sub-tiles (at most 4) x columns x 2
+    size_t mx = (size_t)4 * ub_tiles(c, NB, 1, layer_tile_rows(c, c->G.J, 1)) * c->G.J;
     for (size_t i = 0; i + 1 < c->G.conv.size(); ++i) {
       const ConvLayer& cl = c->G.conv[i];
-      const size_t v = (size_t)4 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs)) * cl.Cb;
+      const size_t v = (size_t)4 * 4 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cb, cl.Hs * cl.Hs)) * cl.Cb;
       mx = v > mx ? v : mx;
     }
     for (size_t j = 1; j < c->D.conv.size(); ++j) {
       const ConvLayer& cl = c->D.conv[j];
-      const size_t v = (size_t)2 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs)) * cl.Cs;
+      const size_t v = (size_t)4 * 2 * ub_tiles(c, NB, cl.Hs * cl.Hs, layer_tile_rows(c, cl.Cs, cl.Hs * cl.Hs)) * cl.Cs;
       mx = v > mx ? v : mx;
     }
     // and the BatchNorm backward reduction: segments x row blocks x channels x 2

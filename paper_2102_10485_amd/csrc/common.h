@@ -65,8 +65,9 @@ struct ConvArgs {
   const void* W;         // weights of model 0, K-contiguous: [tap][N][C] (storage type)
   void* Out;             // output activations (storage type)
   const void* Aux;       // EPI_ACT_BWD: saved forward output at the output position (storage type)
-  float* stat_partial;   // if set (wide tiles): per-tile column sums of the output and of its squared deviations from the tile's column mean,
-                         // [((phase * nseg + segment) * ub_tiles + tile) * N + col][2], for the BatchNorm that follows
+  float* stat_partial;   // if set: per sub-tile (the row block of one wave row of the tile; conv_stat_split of them per tile) the
+                         // column sums of the output and of its squared deviations from the sub-tile's column mean,
+                         // [(((phase * nseg + segment) * ub_tiles + tile) * split + block) * N + col][2], for the BatchNorm that follows
   int w_nstride;         // rows per tap in the weight block (>= N)
   const int* offs;       // [L+1] sample offsets of the models inside one segment
   const int* tpre;       // [L+1] prefix of M-tiles per model for this geometry
@@ -111,5 +112,7 @@ int wgrad_tiles_per_model(int ntaps, int Cb, int Cs);
 
 // rows per M-tile the forward-type kernel will use for n_out output channels and about rows_per_model rows
 int conv_tile_rows(int n_out, long long rows_per_model_hint, int n_models);
+// row blocks per tile with their own BatchNorm partial sums, for the tile the forward-type kernel uses for n_out channels
+int conv_stat_split(int n_out, int tile_rows);
 
 }  // namespace gan

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
   constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, PA = TL::PA, PB = TL::PB, RPP = TL::RPP;
   constexpr int KB = TL::KB, NST = TL::NST;
   constexpr int SMEM_RING = NST * (BM + BN) * KB;
-  constexpr int SMEM_EPI = BM * 8 + (TL::NT / 64) * 32 * (TN * 32 * 4 + 16) + TL::WM * BN * 8;   // see the epilogue
+  constexpr int SMEM_EPI = BM * 8 + (TL::NT / 64) * 32 * (TN * 32 * 4 + 16);   // see the epilogue
   constexpr int SMEM = SMEM_RING > SMEM_EPI ? SMEM_RING : SMEM_EPI;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
   unsigned char* const As = smem;                      // buffer s at As + s * BM * KB
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     constexpr int PSTRIDE = WCOLS * 4 + 16;                             // bytes per patch row
     constexpr int CPR = WCOLS / EPV;                                    // 16-byte output chunks per patch row
     unsigned char* patch = smem + BM * 8 + wave * (32 * PSTRIDE);       // after the row table
-    static_assert(SMEM >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8 && SMEM_EPI == BM * 8 + (TL::NT / 64) * 32 * PSTRIDE + TL::WM * BN * 8, "patch area");
+    static_assert(SMEM >= BM * 8 + (TL::NT / 64) * 32 * PSTRIDE && SMEM_EPI == BM * 8 + (TL::NT / 64) * 32 * PSTRIDE, "patch area");
     const int colw = nt * BN + wn * WCOLS;                              // first column of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -533,54 +533,50 @@ __global__ __launch_bounds__(TL::NT) void conv_gemm_kernel(ConvArgs p) {
     }
   }
   if (p.stat_partial) {
-    // For the BatchNorm that follows: per column of this tile, the sum of the fp32 results and the sum of squared
-    // deviations from the tile's own column mean (merged across tiles by the pairwise-update formula, which keeps
-    // the variance free of the E[x^2] - mean^2 cancellation).  Fixed order everywhere.
-    float* red = reinterpret_cast<float*>(smem + SMEM - TL::WM * BN * 8);   // [WM][BN][2], at the end of the buffers
-    const int valid_rows = min(BM, Mrows - m0);
+    // For the BatchNorm that follows.  Every wave's (TM*32)-row block of the tile is a sub-tile of its own: per column
+    // the sum of its fp32 results and the sum of their squared deviations from the sub-tile's column mean, which the
+    // statistics kernel merges across sub-tiles with the pairwise-update formula (no E[x^2] - mean^2 over a whole
+    // channel).  One pass over the accumulators with the sub-tile's first row as the shift K:
+    //   sum = K n + sum(x - K),   M2 = sum((x - K)^2) - (sum(x - K))^2 / n
+    // (a sample of the column is as good a shift as its mean up to a few units of the last place), no block-wide
+    // barrier and nothing shared between the waves, so a wave is done when its own stores and sums are.
+    constexpr int SUB = TM * 32;
+    const int nvalid = min(max(Mrows - m0 - wm * SUB, 0), SUB);          // valid rows of this wave's sub-tile: a prefix
+    const long long tix = (((long long)phase * p.nseg + sidx) * p.ub_tiles + mt) * TL::WM + wm;
+    if (nvalid > 0) {
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      float s1 = 0.f;
+      for (int tn = 0; tn < TN; ++tn) {
+        const float K = __shfl(acc[0][tn][0], lane & 31, 64);           // row 0 of the sub-tile, this lane's column
+        float s1 = 0.f, s2 = 0.f;
+        if (nvalid == SUB) {
 #pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
+          for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s1 += acc[tm][tn][e];             // rows past the model's end are exact zeros
-      s1 += __shfl_xor(s1, 32, 64);
-      if (lane < 32) red[(wm * BN + wn * TN * 32 + tn * 32 + lane) * 2] = s1;
-    }
-    __syncthreads();
+            for (int e = 0; e < 16; ++e) {
+              const float d = acc[tm][tn][e] - K;
+              s1 += d;
+              s2 += d * d;
+            }
+        } else {
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      const int c = wn * TN * 32 + tn * 32 + (lane & 31);
-      float tot = 0.f;
+          for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-      for (int w = 0; w < TL::WM; ++w) tot += red[(w * BN + c) * 2];
-      const float mean = tot / (float)valid_rows;
-      float s2 = 0.f;
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int rr = wm * TM * 32 + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          const float d = acc[tm][tn][e] - mean;
-          if (rr < valid_rows) s2 += d * d;
+            for (int e = 0; e < 16; ++e) {
+              const int rr = tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+              const float d = acc[tm][tn][e] - K;
+              if (rr < nvalid) { s1 += d; s2 += d * d; }
+            }
         }
-      s2 += __shfl_xor(s2, 32, 64);
-      if (lane < 32) red[(wm * BN + c) * 2 + 1] = s2;
+        s1 += __shfl_xor(s1, 32, 64);
+        s2 += __shfl_xor(s2, 32, 64);
+        const int col = nt * BN + wn * TN * 32 + tn * 32 + (lane & 31);
+        if (lane < 32 && col < N) {
+          const float nf = (float)nvalid;
+          p.stat_partial[(tix * N + col) * 2] = K * nf + s1;
+          p.stat_partial[(tix * N + col) * 2 + 1] = fmaxf(s2 - s1 * s1 / nf, 0.f);
+        }
+      }
     }
-    __syncthreads();
-    for (int c = tid; c < BN; c += TL::NT) {
-      const int col = nt * BN + c;
-      if (col >= N) continue;
-      float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-      for (int w = 0; w < TL::WM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
-      const long long t = ((long long)phase * p.nseg + sidx) * p.ub_tiles + mt;
-      p.stat_partial[(t * N + col) * 2] = s1;
-      p.stat_partial[(t * N + col) * 2 + 1] = s2;
-    }
-    // (the patches above sit after the row table, the sums at the end of the buffers: no barrier needed between them;
-    // the sums come last so that they are computed while the tile's stores are on their way)
   }
 }
 
@@ -602,6 +598,15 @@ static void launch_wide(const ConvArgs& a, hipStream_t st) {
   if (a.N <= TileNarrow::BN) return launch_one<T, MODE, EPI, TileNarrow>(a, st);
   if (a.N % 256 == 0) return launch_one<T, MODE, EPI, TileBig>(a, st);
   return launch_one<T, MODE, EPI, TileMid>(a, st);
+}
+
+// Row blocks per tile that leave their own BatchNorm partial sums (the WM of the tile launch_wide picks).
+int conv_stat_split(int n_out, int tile_rows) {
+  if (tile_rows == TileTiny::BM) return TileTiny::WM;
+  if (tile_rows == TileSmall::BM) return TileSmall::WM;
+  if (n_out <= TileNarrow::BN) return TileNarrow::WM;
+  if (n_out % 256 == 0) return TileBig::WM;
+  return TileMid::WM;
 }
 
 // The (mode, epilogue, tile) combinations the networks use.

@@ -70,8 +70,9 @@ struct NormArgs {
   int fold_grads;           // backward reduction, one segment: its last stage also writes dgamma / dbeta
 };
 // statistics from the per-tile column sums a GEMM left behind (stat_partial of ConvArgs)
+// (wsplit: sub-tiles per tile, conv_stat_split of the GEMM's tile)
 void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
-                                  int groups, int tile_rows, int gemm_rps, hipStream_t st);
+                                  int groups, int tile_rows, int gemm_rps, int wsplit, hipStream_t st);
 void launch_bn_running(const NormArgs& a, hipStream_t st);
 void launch_bn_from_running(const NormArgs& a, hipStream_t st);   // mean/rstd <- running statistics
 template <typename T> void launch_bn_apply(const NormArgs& a, hipStream_t st);

@@ -331,12 +331,13 @@ __device__ inline void storev(bf16_t* p, const float (&v)[8]) {
   __builtin_nontemporal_store(q, reinterpret_cast<u4*>(p));
 }
 
-// mean / var / rstd from what the producing GEMM left per tile and column: (sum, sum of squared deviations from the
-// tile's mean).  Tiles (and output phases, and column runs) of one (segment, model) are merged in a fixed order
-// with the pairwise update  mean += d n_t/(n+n_t),  M2 += M2_t + d^2 n n_t/(n+n_t),  d = mean_t - mean.
+// mean / var / rstd from what the producing GEMM left per sub-tile and column: (sum, sum of squared deviations from
+// the sub-tile's mean); a tile of tile_rows rows is wsplit sub-tiles of tile_rows / wsplit rows, the last ones of a
+// model's last tile possibly empty.  Sub-tiles (and output phases, and column runs) of one (segment, model) are merged
+// in a fixed order with the pairwise update  mean += d n_t/(n+n_t),  M2 += M2_t + d^2 n n_t/(n+n_t),  d = mean_t - mean.
 // The GEMM's N columns are `groups` runs of the C channels (the linear layer feeding G's first BatchNorm has one
 // run per pixel of the first feature map; the convolutions have one).
-// A block = 16 channels x RED_SLICES slices of the (phase, tile) sequence of one (segment, model): every thread
+// A block = 16 channels x RED_SLICES slices of the (phase, sub-tile) sequence of one (segment, model): every thread
 // merges its contiguous slice in order, then the slices are merged in order.  The slicing depends on the model's own
 // tile count only.
 constexpr int RED_SLICES = 16;      // slices of the backward reduction's second stage
@@ -346,7 +347,7 @@ constexpr int RED_SLICES = 16;      // slices of the backward reduction's second
 template <int SL, int CX>
 __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, const float* __restrict__ partial,
                                                                     const int* __restrict__ tpre, int ub_tiles, int nphase,
-                                                                    int groups, int tile_rows, int gemm_rps) {
+                                                                    int groups, int tile_rows, int gemm_rps, int wsplit) {
   static_assert(SL * CX == 256, "block shape");
   __shared__ float sh[SL][CX][3];
   const int cx = threadIdx.x % CX, sl = threadIdx.x / CX;
@@ -357,16 +358,18 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
   const int cnt = a.offs[l + 1] - a.offs[l];
   if (cnt == 0) return;                                // block-uniform
   const int rows = cnt * gemm_rps;                     // rows of this model in the GEMM's row space (per phase)
-  const int t0 = tpre[l], ntiles = tpre[l + 1] - t0;
-  const int seq = nphase * ntiles, per = (seq + SL - 1) / SL;
+  const int t0 = tpre[l], nsub = (tpre[l + 1] - t0) * wsplit, sub_rows = tile_rows / wsplit;
+  const int seq = nphase * nsub, per = (seq + SL - 1) / SL;
   float n = 0.f, mean = 0.f, m2 = 0.f;
   if (c < a.C)
 #pragma unroll 4
-    for (int q = sl * per; q < min(seq, (sl + 1) * per); ++q) {     // (unrolled: the loads of four tiles are in flight together)
-      const int ph = q / ntiles, t = q - ph * ntiles;
-      const float nt = (float)min(tile_rows, rows - t * tile_rows);
+    for (int q = sl * per; q < min(seq, (sl + 1) * per); ++q) {     // (unrolled: the loads of four sub-tiles are in flight together)
+      const int ph = q / nsub, t = q - ph * nsub;
+      const int left = rows - t * sub_rows;
+      if (left <= 0) continue;                         // an empty sub-tile at the end of the model's last tile: never written
+      const float nt = (float)min(sub_rows, left);
       for (int g = 0; g < groups; ++g) {
-        const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles + t0 + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
+        const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles * wsplit + (long long)t0 * wsplit + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
         const float d = partial[o] / nt - mean;
         const float nn = n + nt;
         mean += d * (nt / nn);
@@ -399,18 +402,19 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
   }
 }
 void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const int* tpre, int ub_tiles, int nphase,
-                                  int groups, int tile_rows, int gemm_rps, hipStream_t st) {
+                                  int groups, int tile_rows, int gemm_rps, int wsplit, hipStream_t st) {
   if ((long long)a.nseg * a.L * a.C == 0) return;
   if (!tpre || !partial) return launch_fail("BatchNorm statistics: no tile prefix array or no partial sums");
-  const bool many = (long long)ub_tiles * nphase * groups > 512LL * a.L;       // tiles per model, by the launch's upper bound
+  if (wsplit < 1 || tile_rows % wsplit) return launch_fail("BatchNorm statistics: the tile height is not a whole number of sub-tiles");
+  const bool many = (long long)ub_tiles * wsplit * nphase * groups > 1024LL * a.L;       // sub-tiles per model, by the launch's upper bound
   if (many) {
     const long long tot = (long long)a.nseg * a.L * ((a.C + 3) / 4);
     hipLaunchKernelGGL((bn_stats_from_partial_kernel<64, 4>), dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
-                       groups, tile_rows, gemm_rps);
+                       groups, tile_rows, gemm_rps, wsplit);
   } else {
     const long long tot = (long long)a.nseg * a.L * ((a.C + 15) / 16);
     hipLaunchKernelGGL((bn_stats_from_partial_kernel<16, 16>), dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
-                       groups, tile_rows, gemm_rps);
+                       groups, tile_rows, gemm_rps, wsplit);
   }
 }
 
