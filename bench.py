@@ -19,20 +19,20 @@ PEAK = {"mfma_bf16": 2500.0, "mfma_fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFL
 # the same counters read for the 1 GiB elementwise probe (fetch x 2.0, write x 1.0).  Valid only for the kernel sources they
 # were taken with: `sources` is the digest of csrc/ at that time, and the roofline reports null traffic when it differs.
 MEASURED_TRAFFIC = {
-    "sources": "4ff9f909d4d14562",
+    "sources": "3c14e561e968cad9",
     "workload": "config 2 bf16",
     "fetch_scale": 2.000, "write_scale": 1.000,
     "kib_per_launch": {
-        "gemm_dense<128x128>": (103307, 108800),
-        "gemm_up<256x256>": (453042, 274133),
-        "gemm_up<256x128>": (158415, 416000),
-        "gemm_dense+lrelu<256x128>": (154521, 614645),
-        "gemm_down<256x256>": (495881, 207200),
-        "wgrad<256x256>": (407418, 512048),
-        "gemm_up+actbwd<256x128>": (587737, 614400),
+        "gemm_dense<128x128>": (103311, 108800),
+        "gemm_up<256x256>": (453125, 275200),
+        "gemm_up<256x128>": (159004, 435200),
+        "gemm_dense+lrelu<256x128>": (154519, 614712),
+        "gemm_down<256x256>": (497429, 209600),
+        "wgrad<256x256>": (410032, 512070),
+        "gemm_up+actbwd<256x128>": (583434, 614400),
         "wgrad<64x128>": (460879, 25605),
-        "gemm_dense<256x128>": (103305, 409901),
-        "wgrad<256x128>": (52090, 409999),
+        "gemm_dense<256x128>": (103311, 409880),
+        "wgrad<256x128>": (52079, 410020),
     },
 }
 
