@@ -359,23 +359,26 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
   if (cnt == 0) return;                                // block-uniform
   const int rows = cnt * gemm_rps;                     // rows of this model in the GEMM's row space (per phase)
   const int t0 = tpre[l], nsub = (tpre[l + 1] - t0) * wsplit, sub_rows = tile_rows / wsplit;
-  const int seq = nphase * nsub, per = (seq + SL - 1) / SL;
+  // the sequence a slice is cut from: (phase, sub-tile, column run), the column runs fastest
+  const int seq = nphase * nsub * groups, per = (seq + SL - 1) / SL;
   float n = 0.f, mean = 0.f, m2 = 0.f;
+  const float inv_sub = 1.f / (float)sub_rows;
   if (c < a.C)
 #pragma unroll 4
-    for (int q = sl * per; q < min(seq, (sl + 1) * per); ++q) {     // (unrolled: the loads of four sub-tiles are in flight together)
+    for (int qg = sl * per; qg < min(seq, (sl + 1) * per); ++qg) {  // (unrolled: the loads of four entries are in flight together)
+      const int q = qg / groups, g = qg - q * groups;
       const int ph = q / nsub, t = q - ph * nsub;
       const int left = rows - t * sub_rows;
       if (left <= 0) continue;                         // an empty sub-tile at the end of the model's last tile: never written
       const float nt = (float)min(sub_rows, left);
-      for (int g = 0; g < groups; ++g) {
-        const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles * wsplit + (long long)t0 * wsplit + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
-        const float d = partial[o] / nt - mean;
-        const float nn = n + nt;
-        mean += d * (nt / nn);
-        m2 += partial[o + 1] + d * d * (n * nt / nn);
-        n = nn;
-      }
+      const long long o = ((((long long)ph * a.nseg + sidx) * ub_tiles * wsplit + (long long)t0 * wsplit + t) * ((long long)a.C * groups) + g * a.C + c) * 2;
+      // one division per merge: a full sub-tile's mean through the reciprocal of its height, the second weight from the first
+      const float d = (left >= sub_rows ? partial[o] * inv_sub : partial[o] / nt) - mean;
+      const float nn = n + nt;
+      const float w = nt / nn;
+      mean += d * w;
+      m2 += partial[o + 1] + d * d * (n * w);
+      n = nn;
     }
   sh[sl][cx][0] = n; sh[sl][cx][1] = mean; sh[sl][cx][2] = m2;
   __syncthreads();
@@ -385,8 +388,9 @@ __global__ __launch_bounds__(256) void bn_stats_from_partial_kernel(NormArgs a, 
     if (nt == 0.f) continue;                           // an empty slice
     const float d = sh[k][cx][1] - mean;
     const float nn = n + nt;
-    mean += d * (nt / nn);
-    m2 += sh[k][cx][2] + d * d * (n * nt / nn);
+    const float w = nt / nn;
+    mean += d * w;
+    m2 += sh[k][cx][2] + d * d * (n * w);
     n = nn;
   }
   const float var = m2 / n;
@@ -406,7 +410,7 @@ void launch_bn_stats_from_partial(const NormArgs& a, const float* partial, const
   if ((long long)a.nseg * a.L * a.C == 0) return;
   if (!tpre || !partial) return launch_fail("BatchNorm statistics: no tile prefix array or no partial sums");
   if (wsplit < 1 || tile_rows % wsplit) return launch_fail("BatchNorm statistics: the tile height is not a whole number of sub-tiles");
-  const bool many = (long long)ub_tiles * wsplit * nphase * groups > 1024LL * a.L;       // sub-tiles per model, by the launch's upper bound
+  const bool many = (long long)ub_tiles * wsplit * nphase * groups > 1024LL * a.L;       // entries per model, by the launch's upper bound
   if (many) {
     const long long tot = (long long)a.nseg * a.L * ((a.C + 3) / 4);
     hipLaunchKernelGGL((bn_stats_from_partial_kernel<64, 4>), dim3((unsigned)tot), dim3(256), 0, st, a, partial, tpre, ub_tiles, nphase,
