@@ -19,20 +19,20 @@ PEAK = {"mfma_bf16": 2500.0, "mfma_fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFL
 # the same counters read for the 1 GiB elementwise probe (fetch x 2.0, write x 1.0).  Valid only for the kernel sources they
 # were taken with: `sources` is the digest of csrc/ at that time, and the roofline reports null traffic when it differs.
 MEASURED_TRAFFIC = {
-    "sources": "3c14e561e968cad9",
+    "sources": "1272be6df4352ca9",
     "workload": "config 2 bf16",
     "fetch_scale": 2.000, "write_scale": 1.000,
     "kib_per_launch": {
         "gemm_dense<128x128>": (103311, 108800),
-        "gemm_up<256x256>": (453125, 275200),
-        "gemm_up<256x128>": (159004, 435200),
-        "gemm_dense+lrelu<256x128>": (154519, 614712),
-        "gemm_down<256x256>": (497429, 209600),
-        "wgrad<256x256>": (410032, 512070),
-        "gemm_up+actbwd<256x128>": (583434, 614400),
+        "gemm_up<256x256>": (453060, 275200),
+        "gemm_up<256x128>": (159017, 435200),
+        "gemm_dense+lrelu<256x128>": (154519, 614758),
+        "gemm_down<256x256>": (498161, 209600),
+        "wgrad<256x256>": (410476, 512076),
+        "gemm_up+actbwd<256x128>": (584743, 614400),
         "wgrad<64x128>": (460879, 25605),
-        "gemm_dense<256x128>": (103311, 409880),
-        "wgrad<256x128>": (52079, 410020),
+        "gemm_dense<256x128>": (103311, 409886),
+        "wgrad<256x128>": (52079, 410066),
     },
 }
 
